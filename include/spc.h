@@ -1,0 +1,200 @@
+/*
+ * spc.h — C ABI of the MI355X (gfx950) sparse-convolution (SpC) layer library.
+ *
+ * The library implements the two halves of an SpC layer as defined in Section 2
+ * of the Spira paper (arXiv 2511.20834):
+ *   voxel indexing   — packing, sorting, downsampling (Eq. 1) and kernel-map
+ *                      construction (Section 2.2, Sections 5.2, 5.3, 5.5);
+ *   feature computation — Eq. (2), in an output-stationary or a weight-stationary
+ *                      dataflow (Section 2.2, Section 5.4).
+ *
+ * Conventions
+ *   - Every function returns SPC_OK (0) or a negative SPC_ERR_* code; a message for
+ *     the calling thread's last error is available from spc_last_error().
+ *   - Pointers marked [device] are device (HBM) addresses on the current HIP device,
+ *     owned by the caller; [host] pointers are ordinary host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue work on it and return without waiting unless stated otherwise.
+ *   - Voxel indices are int32; a kernel map entry of -1 means "no input voxel".
+ *   - The offset index of a K x K x K kernel is k = (ix*K + iy)*K + iz (z fastest,
+ *     the group order of Section 5.2).  Per axis, index i stands for the offset
+ *     (i - (K-1)/2) * in_stride for odd K and i * in_stride for even K.
+ *   - No function may be called concurrently on the same spc_kmap from two threads.
+ */
+#ifndef SPC_H_
+#define SPC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPC_OK 0
+#define SPC_ERR_ARG (-1)         /* null pointer, bad size, bad enum, inconsistent descriptor */
+#define SPC_ERR_RANGE (-2)       /* a coordinate does not fit its packed field incl. guard band */
+#define SPC_ERR_DUP (-3)         /* duplicate voxel coordinates (only reported in validate mode) */
+#define SPC_ERR_UNSUPPORTED (-4) /* valid request this build has no kernel for */
+#define SPC_ERR_HIP (-5)         /* a HIP runtime call failed; message holds hipGetErrorString */
+#define SPC_ERR_NOMEM (-6)       /* device allocation failed */
+
+#define SPC_DTYPE_F16 0
+#define SPC_DTYPE_BF16 1
+#define SPC_DTYPE_F32 2
+
+#define SPC_LAYOUT_OS 1   /* |V_q| x K^3 matrix of input indices (Section 5.4, case I) */
+#define SPC_LAYOUT_WS 2   /* per-offset filtered (in,out) lists (Section 5.4, case II) */
+#define SPC_LAYOUT_BOTH 3
+
+#define SPC_DATAFLOW_OS 0 /* output-stationary: no atomics, bit-reproducible */
+#define SPC_DATAFLOW_WS 1 /* weight-stationary: fp32 atomic accumulation */
+
+#define SPC_PACK_VALIDATE 1 /* spc_pack_coords: check ranges and duplicates, wait, report */
+#define SPC_CONV_RELU 1     /* spc_conv_forward: apply max(x,0) before the output is stored */
+#define SPC_NET_SEQUENTIAL 1 /* spc_build_kmaps_network: one stream, level by level (for comparison) */
+
+/*
+ * Packing descriptor (Section 5.3).  A key holds, from the most significant bit
+ * down: bits_b bits of batch index, bits_x bits of x, bits_y of y, bits_z of z.
+ * A spatial field stores v - origin[a] + pad.  The guard band `pad` keeps every
+ * neighbour query q + delta inside its field, so that adding the packed offset to a
+ * packed coordinate never borrows or carries between fields (the paper's
+ * packed(q)+packed(delta)=packed(q+delta) holds only then).  For downsampling by
+ * masking to agree with floor() on the raw coordinates, origin[a] - pad must be a
+ * multiple of the largest output stride used.  key_bits is 32 or 64 and
+ * bits_b+bits_x+bits_y+bits_z must not exceed it.
+ */
+typedef struct spc_pack_desc {
+  int32_t key_bits;
+  int32_t bits_b, bits_x, bits_y, bits_z;
+  int32_t origin[3];
+  int32_t pad;
+} spc_pack_desc;
+
+/*
+ * Host helper: fills `out` for coordinates with lo[a] <= v <= hi[a] (inclusive, raw
+ * units), batch indices in [0, n_batch), the largest output stride `max_stride`
+ * (power of two) and the largest |offset component| `max_reach` of any layer.  Picks
+ * the smallest fields; key_bits = 32 if they fit, else 64 (or forces `key_bits` when
+ * it is 32 or 64).  Returns SPC_ERR_RANGE if even 64 bits do not suffice.
+ */
+int spc_pack_desc_fit(const int32_t lo[3], const int32_t hi[3], int32_t n_batch, int32_t max_stride,
+                      int32_t max_reach, int32_t key_bits, spc_pack_desc* out);
+
+/*
+ * Pack and sort (Sections 5.2-5.3; done once per network on the initial coordinates).
+ *   coords_bxyz [device] n rows of int32 (b, x, y, z), unique, any order.
+ *   keys_out    [device] n keys (uint32 or uint64 per d->key_bits), ascending.
+ *   perm_out    [device] n int32, may be NULL: keys_out[r] is the key of input row
+ *               perm_out[r]; the caller gathers feature rows with it once.
+ *   workspace   [device] scratch; call with workspace == NULL to get the size needed
+ *               in *workspace_bytes (nothing is enqueued then).
+ *   flags       SPC_PACK_VALIDATE: wait for the stream and return SPC_ERR_RANGE /
+ *               SPC_ERR_DUP if a row does not fit its field or occurs twice.  Without
+ *               it nothing is waited for and such input gives undefined keys.
+ */
+int spc_pack_coords(const int32_t* coords_bxyz, int64_t n, const spc_pack_desc* d, void* keys_out,
+                    int32_t* perm_out, void* workspace, size_t* workspace_bytes, int32_t flags,
+                    void* stream);
+
+/*
+ * One layer's voxel-indexing request.
+ *   K            kernel size per axis (1, 2, 3, 5 or 7).
+ *   in_stride    s_p: stride of the layer's input coordinates (power of two).
+ *   layer_stride s_l: 1 = submanifold (V_q = V_p); 2^m = strided, V_q from Eq. (1).
+ *   transposed   0/1.  1: the layer upsamples.  Its OUTPUT voxels are the level with
+ *                stride in_stride, its INPUT voxels that level downsampled by
+ *                layer_stride, and pair (in j, out i, offset k) exists iff
+ *                out_i = in_j + delta_k with delta_k from Delta(K, in_stride) — the
+ *                pairs of the strided layer with roles swapped.  (The paper does not
+ *                define transposed layers; this is the usual generalised-SpC reading.)
+ *   layout       SPC_LAYOUT_OS, _WS or _BOTH: which representation(s) to build.
+ */
+typedef struct spc_layer_desc {
+  int32_t K, in_stride, layer_stride, transposed, layout;
+} spc_layer_desc;
+
+typedef struct spc_kmap spc_kmap; /* opaque; owned by the library; release with spc_kmap_destroy */
+
+/*
+ * Build one kernel map with the one-shot search of Section 5.2 on packed keys
+ * (Section 5.3).  in_keys [device]: n_in sorted unique keys of the level with stride
+ * l->in_stride (all spatial components multiples of it).  For layer_stride > 1 the
+ * coarser level is produced first (mask, sort, unique: Section 5.3).  Nothing is
+ * waited for; the handle keeps device pointers into in_keys, which must stay alive
+ * and unchanged while the map is in use.
+ */
+int spc_build_kmap(const void* in_keys, int64_t n_in, const spc_pack_desc* d, const spc_layer_desc* l,
+                   spc_kmap** out, void* stream);
+
+/*
+ * Network-wide voxel indexing (Section 5.5).  v0_keys [device]: the n0 sorted keys of
+ * the stride-1 level.  Every coordinate level any layer needs is derived directly from
+ * v0_keys (closed form of Section 5.5), all levels concurrently over `streams`; then
+ * all distinct kernel maps are built concurrently.  Layers with equal (K, in_stride,
+ * layer_stride, transposed) receive the same handle (reference counted; call
+ * spc_kmap_destroy once per returned handle).  streams [host]: n_streams hipStream_t;
+ * on return streams[0] has been made to wait for all the work, nothing else is waited
+ * for.  out [host]: n_layers handles.
+ */
+int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc* d,
+                            const spc_layer_desc* layers, int32_t n_layers, spc_kmap** out,
+                            void* const* streams, int32_t n_streams, int32_t flags);
+
+/* Sizes.  For strided / transposed maps the counts are produced on the device; these
+ * calls wait for the build to finish the first time.  Return a negative SPC_ERR_* on failure. */
+int64_t spc_kmap_n_in(spc_kmap* m);
+int64_t spc_kmap_n_out(spc_kmap* m);
+int32_t spc_kmap_kvol(const spc_kmap* m); /* K^3 */
+/* [device] sorted keys of the layer's output (resp. input) voxels; valid while the map lives. */
+const void* spc_kmap_out_keys(const spc_kmap* m);
+const void* spc_kmap_in_keys(const spc_kmap* m);
+/* Copies the n_out sorted output keys to keys_host [host] (uint32 or uint64 per key_bits; `cap`
+ * keys of room).  Waits for the build. */
+int spc_kmap_copy_out_keys(spc_kmap* m, void* keys_host, int64_t cap);
+/* [device] OS layout: int32 [n_out][K^3], NULL if not built. */
+const int32_t* spc_kmap_os_map(const spc_kmap* m);
+/* [device] WS layout: list k occupies entries [k*ws_stride, k*ws_stride + nnz[k]) of both
+ * arrays, ordered by ascending output index; *nnz_dev [device] int32[K^3].  NULL if not built. */
+int spc_kmap_ws_lists(const spc_kmap* m, const int32_t** in_idx, const int32_t** out_idx,
+                      const int32_t** nnz_dev, int64_t* ws_stride);
+/* nnz_host [host] int64[K^3]: valid entries per offset.  Waits for the build. */
+int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host);
+/*
+ * Debug/test export: copies the map to the host as (k, in, out) int32 triples in the
+ * order offsets ascending, then output index ascending (which is the lexicographic
+ * order of the triples).  which = SPC_LAYOUT_OS or SPC_LAYOUT_WS selects the
+ * representation read.  triples [host] holds `cap` rows; *nnz_out receives the total.
+ * Waits for the build.
+ */
+int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_t cap, int64_t* nnz_out);
+void spc_kmap_destroy(spc_kmap* m);
+
+/*
+ * Feature computation, Eq. (2):  out[i,:] = sum_k feats_in[M[i,k],:] * W_k.
+ *   feats_in  [device] n_in rows of cin elements, row pitch ld_in elements.
+ *   weights   [device] [K^3][cin][cout] row-major, same dtype as the features.
+ *   feats_out [device] n_out rows of cout elements, row pitch ld_out (lets a caller
+ *             write straight into one half of a concatenated buffer).  Overwritten.
+ *   dtype     SPC_DTYPE_F16 / BF16: MFMA contraction, fp32 accumulation, output rounded
+ *             to nearest even.  SPC_DTYPE_F32: fp32 FMA arithmetic throughout.
+ *   dataflow  SPC_DATAFLOW_OS needs the OS layout, SPC_DATAFLOW_WS the WS layout
+ *             (Section 2.2).  OS results are bit-reproducible; WS uses fp32 atomics.
+ *   flags     SPC_CONV_RELU.
+ * Nothing is waited for.
+ */
+int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
+                     int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t dataflow,
+                     int32_t flags, void* stream);
+
+/* Releases the library's cached device blocks (maps still alive keep theirs). Waits for the device. */
+int spc_release_cache(void);
+
+const char* spc_last_error(void);
+const char* spc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPC_H_ */

@@ -1,0 +1,243 @@
+"""Thin ctypes binding of libspc.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+``include/spc.h``; PyTorch is used for device memory and streams.  There is no CPU
+fallback: loading fails loudly when the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspc.so")
+
+OK = 0
+DTYPE_F16, DTYPE_BF16, DTYPE_F32 = 0, 1, 2
+LAYOUT_OS, LAYOUT_WS, LAYOUT_BOTH = 1, 2, 3
+DATAFLOW_OS, DATAFLOW_WS = 0, 1
+PACK_VALIDATE = 1
+CONV_RELU = 1
+NET_SEQUENTIAL = 1
+ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -4, -5, -6
+
+EXPORTS = [
+    "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmaps_network", "spc_kmap_n_in",
+    "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
+    "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_export_triples", "spc_kmap_destroy", "spc_conv_forward",
+    "spc_release_cache", "spc_last_error", "spc_version",
+]
+
+
+class SpcError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("spc error %d: %s" % (code, msg))
+        self.code = code
+
+
+class PackDesc(ctypes.Structure):
+    _fields_ = [("key_bits", ctypes.c_int32), ("bits_b", ctypes.c_int32), ("bits_x", ctypes.c_int32),
+                ("bits_y", ctypes.c_int32), ("bits_z", ctypes.c_int32), ("origin", ctypes.c_int32 * 3),
+                ("pad", ctypes.c_int32)]
+
+    def as_dict(self):
+        return dict(key_bits=self.key_bits, bits_b=self.bits_b, bits_x=self.bits_x, bits_y=self.bits_y,
+                    bits_z=self.bits_z, origin=list(self.origin), pad=self.pad)
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_int32), ("in_stride", ctypes.c_int32), ("layer_stride", ctypes.c_int32),
+                ("transposed", ctypes.c_int32), ("layout", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("%s is missing: run `python -m paper_2511_20834_amd.build` (or __graft_entry__.build())"
+                               % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        L.spc_pack_desc_fit.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32), i32, i32, i32, i32, ctypes.POINTER(PackDesc)]
+        L.spc_pack_coords.argtypes = [vp, i64, ctypes.POINTER(PackDesc), vp, vp, vp, ctypes.POINTER(ctypes.c_size_t), i32, vp]
+        L.spc_build_kmap.argtypes = [vp, i64, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), ctypes.POINTER(vp), vp]
+        L.spc_build_kmaps_network.argtypes = [vp, i64, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), i32,
+                                              ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32]
+        for f in ("spc_kmap_n_in", "spc_kmap_n_out"):
+            getattr(L, f).argtypes = [vp]
+            getattr(L, f).restype = i64
+        L.spc_kmap_kvol.argtypes = [vp]
+        for f in ("spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map"):
+            getattr(L, f).argtypes = [vp]
+            getattr(L, f).restype = vp
+        L.spc_kmap_copy_out_keys.argtypes = [vp, vp, i64]
+        L.spc_kmap_ws_lists.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64)]
+        L.spc_kmap_nnz.argtypes = [vp, ctypes.POINTER(i64)]
+        L.spc_kmap_export_triples.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i64)]
+        L.spc_kmap_destroy.argtypes = [vp]
+        L.spc_kmap_destroy.restype = None
+        L.spc_conv_forward.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+        L.spc_last_error.restype = ctypes.c_char_p
+        L.spc_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise SpcError(rc, lib().spc_last_error().decode())
+
+
+def _stream(stream=None) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream) if hasattr(s, "cuda_stream") else int(s)
+
+
+def _dev_ptr(t: torch.Tensor) -> int:
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+_TORCH_DTYPE = {torch.float16: DTYPE_F16, torch.bfloat16: DTYPE_BF16, torch.float32: DTYPE_F32}
+
+
+def spc_version() -> str:
+    return lib().spc_version().decode()
+
+
+def spc_pack_desc_fit(lo, hi, n_batch: int = 1, max_stride: int = 1, max_reach: int = 1, key_bits: int = 0) -> PackDesc:
+    d = PackDesc()
+    a = (ctypes.c_int32 * 3)(*[int(v) for v in lo])
+    b = (ctypes.c_int32 * 3)(*[int(v) for v in hi])
+    _check(lib().spc_pack_desc_fit(a, b, n_batch, max_stride, max_reach, key_bits, ctypes.byref(d)))
+    return d
+
+
+def spc_pack_coords(coords: torch.Tensor, desc: PackDesc, want_perm: bool = True, flags: int = 0, stream=None,
+                    workspace: torch.Tensor | None = None):
+    """coords: int32 [N,4] device tensor (b,x,y,z).  Returns (keys, perm): sorted packed keys
+    (int32/int64 tensors holding the unsigned bit patterns) and the permutation (or None)."""
+    assert coords.dtype == torch.int32 and coords.dim() == 2 and coords.shape[1] == 4
+    n = coords.shape[0]
+    need = ctypes.c_size_t(0)
+    _check(lib().spc_pack_coords(None, n, ctypes.byref(desc), None, None, None, ctypes.byref(need), flags, None))
+    if workspace is None or workspace.numel() < need.value:
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=coords.device)
+    keys = torch.empty(n, dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device=coords.device)
+    perm = torch.empty(n, dtype=torch.int32, device=coords.device) if want_perm else None
+    size = ctypes.c_size_t(workspace.numel())
+    _check(lib().spc_pack_coords(_dev_ptr(coords), n, ctypes.byref(desc), _dev_ptr(keys),
+                                 _dev_ptr(perm) if want_perm else None, _dev_ptr(workspace), ctypes.byref(size), flags,
+                                 _stream(stream)))
+    return keys, perm
+
+
+class KMap:
+    """Owner of one spc_kmap handle (keeps the key tensor it points into alive)."""
+
+    def __init__(self, handle: int, keep=(), desc: PackDesc | None = None):
+        self.handle = ctypes.c_void_p(handle)
+        self._keep = keep
+        self.desc = desc
+
+    def destroy(self):
+        if self.handle:
+            lib().spc_kmap_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    @property
+    def n_in(self) -> int:
+        v = lib().spc_kmap_n_in(self.handle)
+        if v < 0:
+            _check(int(v))
+        return int(v)
+
+    @property
+    def n_out(self) -> int:
+        v = lib().spc_kmap_n_out(self.handle)
+        if v < 0:
+            _check(int(v))
+        return int(v)
+
+    @property
+    def kvol(self) -> int:
+        return int(lib().spc_kmap_kvol(self.handle))
+
+    def nnz(self):
+        import numpy as np
+        out = np.zeros(self.kvol, dtype=np.int64)
+        _check(lib().spc_kmap_nnz(self.handle, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))))
+        return out
+
+    def export_triples(self, which: int = LAYOUT_OS):
+        import numpy as np
+        nnz = ctypes.c_int64(0)
+        _check(lib().spc_kmap_export_triples(self.handle, which, None, 0, ctypes.byref(nnz)))
+        t = np.empty((nnz.value, 3), dtype=np.int32)
+        _check(lib().spc_kmap_export_triples(self.handle, which, t.ctypes.data_as(ctypes.c_void_p), nnz.value,
+                                             ctypes.byref(nnz)))
+        return t
+
+    def out_keys(self):
+        """Host copy of the layer's sorted output keys (as uint64)."""
+        import numpy as np
+        n = self.n_out
+        a = np.empty(n, dtype=np.uint32 if self.desc.key_bits == 32 else np.uint64)
+        _check(lib().spc_kmap_copy_out_keys(self.handle, a.ctypes.data_as(ctypes.c_void_p), n))
+        return a.astype(np.uint64)
+
+
+def spc_build_kmap(in_keys: torch.Tensor, desc: PackDesc, K: int, in_stride: int = 1, layer_stride: int = 1,
+                   transposed: int = 0, layout: int = LAYOUT_BOTH, stream=None) -> KMap:
+    l = LayerDesc(K, in_stride, layer_stride, transposed, layout)
+    h = ctypes.c_void_p()
+    _check(lib().spc_build_kmap(_dev_ptr(in_keys), in_keys.shape[0], ctypes.byref(desc), ctypes.byref(l), ctypes.byref(h),
+                                _stream(stream)))
+    return KMap(h.value, keep=(in_keys,), desc=desc)
+
+
+def spc_build_kmaps_network(v0_keys: torch.Tensor, desc: PackDesc, layers, streams=None, flags: int = 0):
+    """layers: sequence of (K, in_stride, layer_stride, transposed, layout).  Returns one KMap per layer
+    (layers with equal (K, in_stride, layer_stride, transposed) share the underlying map)."""
+    n = len(layers)
+    arr = (LayerDesc * n)(*[LayerDesc(*[int(v) for v in l]) for l in layers])
+    out = (ctypes.c_void_p * n)()
+    if streams is None:
+        streams = [torch.cuda.current_stream()]
+    sarr = (ctypes.c_void_p * len(streams))(*[_stream(s) for s in streams])
+    _check(lib().spc_build_kmaps_network(_dev_ptr(v0_keys), v0_keys.shape[0], ctypes.byref(desc), arr, n, out, sarr,
+                                         len(streams), flags))
+    return [KMap(out[i], keep=(v0_keys,), desc=desc) for i in range(n)]
+
+
+def spc_conv_forward(kmap: KMap, feats_in: torch.Tensor, weights: torch.Tensor, dataflow: int = DATAFLOW_OS,
+                     flags: int = 0, out: torch.Tensor | None = None, n_out: int | None = None, stream=None) -> torch.Tensor:
+    """feats_in [n_in, cin] (row pitch = stride(0)), weights [K^3, cin, cout] contiguous.  ``out`` may be a
+    column slice of a wider buffer (row pitch = stride(0)); it is allocated when None."""
+    assert feats_in.is_cuda and weights.is_cuda and weights.is_contiguous()
+    assert feats_in.dim() == 2 and feats_in.stride(1) == 1 and weights.dim() == 3
+    assert feats_in.dtype == weights.dtype and feats_in.dtype in _TORCH_DTYPE
+    cin, cout = weights.shape[1], weights.shape[2]
+    assert feats_in.shape[1] == cin and weights.shape[0] == kmap.kvol
+    if out is None:
+        out = torch.empty((n_out if n_out is not None else kmap.n_out, cout), dtype=feats_in.dtype, device=feats_in.device)
+    assert out.dim() == 2 and out.stride(1) == 1 and out.shape[1] == cout and out.dtype == feats_in.dtype
+    _check(lib().spc_conv_forward(kmap.handle, feats_in.data_ptr(), feats_in.stride(0), weights.data_ptr(), out.data_ptr(),
+                                  out.stride(0), cin, cout, _TORCH_DTYPE[feats_in.dtype], dataflow, flags, _stream(stream)))
+    return out
+
+
+def spc_release_cache() -> None:
+    _check(lib().spc_release_cache())

@@ -1,0 +1,399 @@
+// Feature computation, Eq. (2): out[i,:] = sum_k F[M[i,k],:] W_k, in the
+// output-stationary and the weight-stationary dataflow (Section 2.2, Section 5.4).
+//
+// fp16 / bf16: the per-offset contraction runs on 32x32x16 MFMA with fp32
+// accumulators.  A wave owns 32-row blocks of output voxels (OS) or of (in,out)
+// pairs (WS).  Gathered feature rows go straight from global memory (L2) into the
+// MFMA A-operand registers: lane l needs 8 consecutive channels of row l%32, which is
+// one 16-byte load, so no LDS round trip is needed for them.  The weight slice W_k is
+// re-laid once per call into B-operand order and staged through LDS, where all waves
+// of the workgroup read it with conflict-free 16-byte loads.
+// OS skips an offset for a whole workgroup tile (and a wave skips its MFMAs) when no
+// row has a valid entry — outputs are spatially sorted, so emptiness is coherent.
+// fp32 (and channel counts the MFMA tiling does not cover) use plain FMA kernels.
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include <algorithm>
+#include <type_traits>
+
+#include "spc_internal.h"
+
+namespace spc {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <typename T>
+struct Mfma;
+template <>
+struct Mfma<_Float16> {
+  using V8 = half8;
+  __device__ static inline floatx16 mma(V8 a, V8 b, floatx16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+};
+template <>
+struct Mfma<__bf16> {
+  using V8 = bf16x8;
+  __device__ static inline floatx16 mma(V8 a, V8 b, floatx16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+};
+
+template <typename T>
+__device__ inline float to_f32(T v) { return static_cast<float>(v); }
+template <typename T>
+__device__ inline T from_f32(float v) { return static_cast<T>(v); }  // round to nearest even
+
+constexpr int CONV_THREADS = 256;
+constexpr int CK = 64;  // input channels staged per step
+
+// W [K3][cin][cout]  ->  Wp [K3][cin/16][cout/32][64 lanes][8]: lane l holds channels
+// 16*kk + 8*(l/32) + 0..7 of output column 32*nb + l%32 (the B operand of one MFMA).
+template <typename T>
+__global__ __launch_bounds__(256) void prepack_weights_kernel(const T* __restrict__ W, T* __restrict__ Wp, int K3, int cin, int cout) {
+  const int KK = cin / 16, NB = cout / 32;
+  const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  const int64_t total = int64_t(K3) * KK * NB * 64;
+  if (gid >= total) return;
+  const int lane = gid & 63;
+  int64_t t = gid >> 6;
+  const int nb = t % NB;
+  t /= NB;
+  const int kk = t % KK;
+  const int k = t / KK;
+  const T* src = W + (int64_t(k) * cin + kk * 16 + 8 * (lane >> 5)) * cout + nb * 32 + (lane & 31);
+  T* dst = Wp + gid * 8;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) dst[j] = src[int64_t(j) * cout];
+}
+
+// Shared inner step: stage nkk*NB B-fragments of offset k, channels [c0, c0+16*nkk), then
+// multiply the wave's RB row blocks.  idx[rb] is the gathered input row (or -1) of lane%32.
+template <typename T, int NB, int RB>
+__device__ inline void contract_offset(const T* __restrict__ F, int64_t ld_in, const T* __restrict__ Wp_k, int cin,
+                                       const int (&idx)[RB], bool wave_has, typename Mfma<T>::V8* sB,
+                                       floatx16 (&acc)[RB][NB]) {
+  using V8 = typename Mfma<T>::V8;
+  const int tid = threadIdx.x, lane = tid & 63, lh = lane >> 5;
+  for (int c0 = 0; c0 < cin; c0 += CK) {
+    const int nkk = min(CK, cin - c0) / 16;
+    if (c0 > 0) __syncthreads();  // previous chunk fully consumed
+    const V8* src = reinterpret_cast<const V8*>(Wp_k) + int64_t(c0 / 16) * NB * 64;
+    for (int e = tid; e < nkk * NB * 64; e += CONV_THREADS) sB[e] = src[e];
+    __syncthreads();
+    if (wave_has) {
+      V8 a[RB][CK / 16];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int kk = 0; kk < CK / 16; ++kk) {
+          V8 v = {};
+          if (kk < nkk && idx[rb] >= 0) v = *reinterpret_cast<const V8*>(F + int64_t(idx[rb]) * ld_in + c0 + kk * 16 + 8 * lh);
+          a[rb][kk] = v;
+        }
+#pragma unroll
+      for (int kk = 0; kk < CK / 16; ++kk) {
+        if (kk < nkk) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            const V8 b = sB[(kk * NB + nb) * 64 + lane];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[rb][nb] = Mfma<T>::mma(a[rb][kk], b, acc[rb][nb]);
+          }
+        }
+      }
+    }
+  }
+}
+
+// Output-stationary: workgroup = 4 waves x RB blocks of 32 consecutive output voxels.
+template <typename T, int NB, int RB>
+__global__ __launch_bounds__(CONV_THREADS) void conv_os_mfma_kernel(const int32_t* __restrict__ M, int n_out_h,
+                                                                    const int* __restrict__ n_out_d, int K3,
+                                                                    const T* __restrict__ F, int64_t ld_in,
+                                                                    const T* __restrict__ Wp, T* __restrict__ out,
+                                                                    int64_t ld_out, int cin, int relu) {
+  using V8 = typename Mfma<T>::V8;
+  constexpr int WROWS = 32 * RB, TROWS = 4 * WROWS;
+  extern __shared__ __align__(16) unsigned char smem[];
+  V8* sB = reinterpret_cast<V8*>(smem);
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int i0 = blockIdx.x * TROWS;
+  if (i0 >= n_out) return;
+  const int rows = min(TROWS, n_out - i0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lh = lane >> 5;
+  floatx16 acc[RB][NB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
+  const int cout = NB * 32;
+  const int64_t w_stride = int64_t(cin) * cout;
+  for (int k = 0; k < K3; ++k) {
+    int idx[RB];
+    bool has = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const int r = wave * WROWS + rb * 32 + lr;
+      idx[rb] = r < rows ? M[int64_t(i0 + r) * K3 + k] : -1;
+      has |= idx[rb] >= 0;
+    }
+    if (!__syncthreads_or(has)) continue;  // nobody in the tile has this offset
+    const bool wave_has = __ballot(has) != 0ull;
+    contract_offset<T, NB, RB>(F, ld_in, Wp + k * w_stride, cin, idx, wave_has, sB, acc);
+  }
+  // D layout of the 32x32 MFMA: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = wave * WROWS + rb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+        if (row < rows) {
+          float v = acc[rb][nb][r];
+          if (relu) v = fmaxf(v, 0.f);
+          out[int64_t(i0 + row) * ld_out + nb * 32 + lr] = from_f32<T>(v);
+        }
+      }
+}
+
+// Weight-stationary: workgroup = one offset k and 4 x RB blocks of 32 (in,out) pairs;
+// partial sums are merged into an fp32 buffer with hardware float atomics.
+template <typename T, int NB, int RB>
+__global__ __launch_bounds__(CONV_THREADS) void conv_ws_mfma_kernel(const int32_t* __restrict__ ws_in,
+                                                                    const int32_t* __restrict__ ws_out,
+                                                                    const int32_t* __restrict__ nnz, int64_t ws_stride,
+                                                                    const T* __restrict__ F, int64_t ld_in,
+                                                                    const T* __restrict__ Wp, float* __restrict__ accum,
+                                                                    int cin) {
+  using V8 = typename Mfma<T>::V8;
+  constexpr int WROWS = 32 * RB, TROWS = 4 * WROWS;
+  extern __shared__ __align__(16) unsigned char smem[];
+  V8* sB = reinterpret_cast<V8*>(smem);
+  __shared__ int s_out[TROWS];
+  const int k = blockIdx.y;
+  const int cnt = nnz[k];
+  const int p0 = blockIdx.x * TROWS;
+  if (p0 >= cnt) return;
+  const int rows = min(TROWS, cnt - p0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lh = lane >> 5;
+  const int32_t* li = ws_in + int64_t(k) * ws_stride + p0;
+  const int32_t* lo = ws_out + int64_t(k) * ws_stride + p0;
+  for (int r = tid; r < TROWS; r += CONV_THREADS) s_out[r] = r < rows ? lo[r] : -1;
+  floatx16 acc[RB][NB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
+  int idx[RB];
+  bool has = false;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int r = wave * WROWS + rb * 32 + lr;
+    idx[rb] = r < rows ? li[r] : -1;
+    has |= idx[rb] >= 0;
+  }
+  const bool wave_has = __ballot(has) != 0ull;
+  const int cout = NB * 32;
+  contract_offset<T, NB, RB>(F, ld_in, Wp + int64_t(k) * cin * cout, cin, idx, wave_has, sB, acc);
+  if (!wave_has) return;  // s_out was published by the barriers inside contract_offset
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = wave * WROWS + rb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+      const int o = s_out[row];
+      if (o >= 0) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) unsafeAtomicAdd(accum + int64_t(o) * cout + nb * 32 + lr, acc[rb][nb][r]);
+      }
+    }
+}
+
+// ---------------------------------------------------------------- plain FMA kernels
+template <typename T>
+__global__ __launch_bounds__(256) void conv_os_simple_kernel(const int32_t* __restrict__ M, int n_out_h,
+                                                             const int* __restrict__ n_out_d, int K3,
+                                                             const T* __restrict__ F, int64_t ld_in,
+                                                             const T* __restrict__ W, T* __restrict__ out,
+                                                             int64_t ld_out, int cin, int cout, int relu) {
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  const int64_t i = gid / cout;
+  const int co = static_cast<int>(gid - i * cout);
+  if (i >= n_out) return;
+  float acc = 0.f;
+  for (int k = 0; k < K3; ++k) {
+    const int j = M[i * K3 + k];
+    if (j < 0) continue;
+    const T* f = F + int64_t(j) * ld_in;
+    const T* w = W + int64_t(k) * cin * cout + co;
+    for (int ci = 0; ci < cin; ++ci) acc = fmaf(to_f32(f[ci]), to_f32(w[int64_t(ci) * cout]), acc);
+  }
+  if (relu) acc = fmaxf(acc, 0.f);
+  out[i * ld_out + co] = from_f32<T>(acc);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void conv_ws_simple_kernel(const int32_t* __restrict__ ws_in,
+                                                             const int32_t* __restrict__ ws_out,
+                                                             const int32_t* __restrict__ nnz, int64_t ws_stride,
+                                                             const T* __restrict__ F, int64_t ld_in,
+                                                             const T* __restrict__ W, float* __restrict__ accum,
+                                                             int cin, int cout) {
+  const int k = blockIdx.y;
+  const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  const int64_t p = gid / cout;
+  const int co = static_cast<int>(gid - p * cout);
+  if (p >= nnz[k]) return;
+  const int j = ws_in[int64_t(k) * ws_stride + p], o = ws_out[int64_t(k) * ws_stride + p];
+  const T* f = F + int64_t(j) * ld_in;
+  const T* w = W + int64_t(k) * cin * cout + co;
+  float acc = 0.f;
+  for (int ci = 0; ci < cin; ++ci) acc = fmaf(to_f32(f[ci]), to_f32(w[int64_t(ci) * cout]), acc);
+  unsafeAtomicAdd(accum + int64_t(o) * cout + co, acc);
+}
+
+__global__ __launch_bounds__(256) void zero_f32_kernel(float4* __restrict__ p, int64_t n4) {
+  const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ accum, int n_out_h,
+                                                       const int* __restrict__ n_out_d, int cout, T* __restrict__ out,
+                                                       int64_t ld_out, int relu) {
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  const int64_t i = gid / cout;
+  const int co = static_cast<int>(gid - i * cout);
+  if (i >= n_out) return;
+  float v = accum[gid];
+  if (relu) v = fmaxf(v, 0.f);
+  out[i * ld_out + co] = from_f32<T>(v);
+}
+
+// ---------------------------------------------------------------- dispatch
+struct ConvArgs {
+  spc_kmap* m;
+  const void* F;
+  int64_t ld_in;
+  const void* W;
+  void* out;
+  int64_t ld_out;
+  int cin, cout, relu, dataflow;
+  int n_out_h;
+  const int* n_out_d;
+  int64_t rows_cap;
+  hipStream_t s;
+};
+
+template <typename T, int NB, int RB>
+static void launch_mfma(const ConvArgs& a, const T* Wp, float* accum) {
+  constexpr int TROWS = 128 * RB;
+  const size_t lds = size_t(CK / 16) * NB * 64 * 16;
+  if (a.dataflow == SPC_DATAFLOW_OS) {
+    const int grid = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
+    hipLaunchKernelGGL((conv_os_mfma_kernel<T, NB, RB>), dim3(grid), dim3(CONV_THREADS), lds, a.s, a.m->os_map, a.n_out_h,
+                       a.n_out_d, a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp, static_cast<T*>(a.out), a.ld_out, a.cin,
+                       a.relu);
+  } else {
+    const int gx = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
+    hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, a.m->K3), dim3(CONV_THREADS), lds, a.s, a.m->ws_in,
+                       a.m->ws_out, a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin);
+  }
+}
+
+template <typename T>
+static int conv_typed(const ConvArgs& a, bool allow_mfma) {
+  const int K3 = a.m->K3;
+  const int64_t out_elems = a.rows_cap * a.cout;
+  float* accum = nullptr;
+  if (a.dataflow == SPC_DATAFLOW_WS) {
+    accum = static_cast<float*>(pool_alloc(std::max<size_t>(size_t(out_elems) * 4 + 16, 256)));
+    if (!accum) return SPC_ERR_NOMEM;
+    const int64_t n4 = (out_elems + 3) / 4;
+    if (n4 > 0) hipLaunchKernelGGL(zero_f32_kernel, dim3((n4 + 255) / 256), dim3(256), 0, a.s, reinterpret_cast<float4*>(accum), n4);
+  }
+  int rc = SPC_OK;
+  const bool mfma_ok = allow_mfma && a.cin % 16 == 0 && (a.cout == 32 || a.cout == 64 || a.cout == 128 || a.cout == 256) &&
+                       a.ld_in % 8 == 0 && (reinterpret_cast<uintptr_t>(a.F) % 16 == 0);
+  if (a.rows_cap > 0) {
+    if constexpr (!std::is_same<T, float>::value) {
+     if (mfma_ok) {
+      T* Wp = static_cast<T*>(pool_alloc(size_t(K3) * a.cin * a.cout * sizeof(T)));
+      if (!Wp) {
+        pool_free(accum);
+        return SPC_ERR_NOMEM;
+      }
+      const int64_t total = int64_t(K3) * (a.cin / 16) * (a.cout / 32) * 64;
+      hipLaunchKernelGGL(prepack_weights_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, a.s, static_cast<const T*>(a.W), Wp,
+                         K3, a.cin, a.cout);
+      switch (a.cout) {
+        case 32: launch_mfma<T, 1, 2>(a, Wp, accum); break;
+        case 64: launch_mfma<T, 2, 2>(a, Wp, accum); break;
+        case 128: launch_mfma<T, 4, 1>(a, Wp, accum); break;
+        case 256: launch_mfma<T, 8, 1>(a, Wp, accum); break;
+      }
+      pool_free(Wp);  // reuse is ordered behind this stream's work
+     }
+    }
+    if (mfma_ok) {
+    } else if (a.dataflow == SPC_DATAFLOW_OS) {
+      const int64_t threads = out_elems;
+      hipLaunchKernelGGL(conv_os_simple_kernel<T>, dim3((threads + 255) / 256), dim3(256), 0, a.s, a.m->os_map, a.n_out_h,
+                         a.n_out_d, K3, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), static_cast<T*>(a.out),
+                         a.ld_out, a.cin, a.cout, a.relu);
+    } else {
+      const int64_t threads = out_elems;  // nnz[k] <= n_out for every offset
+      hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((threads + 255) / 256, K3), dim3(256), 0, a.s, a.m->ws_in, a.m->ws_out,
+                         a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), accum, a.cin,
+                         a.cout);
+    }
+    if (a.dataflow == SPC_DATAFLOW_WS)
+      hipLaunchKernelGGL(finalize_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, accum, a.n_out_h, a.n_out_d, a.cout,
+                         static_cast<T*>(a.out), a.ld_out, a.relu);
+  }
+  pool_free(accum);
+  if (hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "feature kernel launch failed");
+  return rc;
+}
+
+}  // namespace spc
+
+extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
+                                int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t dataflow, int32_t flags,
+                                void* stream) {
+  using namespace spc;
+  if (!m || !feats_in || !weights || !feats_out) return set_error(SPC_ERR_ARG, "NULL argument");
+  if (cin < 1 || cout < 1 || ld_in < cin || ld_out < cout) return set_error(SPC_ERR_ARG, "bad channel counts or row pitches");
+  if (dataflow != SPC_DATAFLOW_OS && dataflow != SPC_DATAFLOW_WS) return set_error(SPC_ERR_ARG, "bad dataflow");
+  if (dataflow == SPC_DATAFLOW_OS && !(m->desc.layout & SPC_LAYOUT_OS)) return set_error(SPC_ERR_ARG, "map has no OS layout");
+  if (dataflow == SPC_DATAFLOW_WS && !(m->desc.layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "map has no WS layout");
+  ConvArgs a{};
+  a.m = m;
+  a.F = feats_in;
+  a.ld_in = ld_in;
+  a.W = weights;
+  a.out = feats_out;
+  a.ld_out = ld_out;
+  a.cin = cin;
+  a.cout = cout;
+  a.relu = (flags & SPC_CONV_RELU) ? 1 : 0;
+  a.dataflow = dataflow;
+  const Level* ol = m->out_level;
+  a.n_out_h = static_cast<int>(ol->n_host < 0 ? 0 : ol->n_host);
+  a.n_out_d = ol->n_host < 0 ? ol->n_dev : nullptr;
+  a.rows_cap = ol->n_host < 0 ? m->out_cap : ol->n_host;
+  a.s = static_cast<hipStream_t>(stream);
+  switch (dtype) {
+    case SPC_DTYPE_F16: return conv_typed<_Float16>(a, true);
+    case SPC_DTYPE_BF16: return conv_typed<__bf16>(a, true);
+    case SPC_DTYPE_F32: return conv_typed<float>(a, false);
+  }
+  return set_error(SPC_ERR_ARG, "bad dtype");
+}

@@ -1,0 +1,670 @@
+// Kernel-map construction: the one-shot search over sorted packed keys
+// (Sections 5.2-5.3), the output-stationary |V_q| x K^3 layout, the filtered
+// weight-stationary lists (Section 5.4, cases I and II) and the network-wide
+// builder (Section 5.5).
+//
+// What is kept from the paper: no query structure is built; offsets are split into
+// K^2 groups that share (dx,dy); only the smallest-z query of a group is searched and
+// the other K-1 are resolved on consecutive positions; queries are formed by adding a
+// packed offset to a packed key.
+// What is different (CDNA4): a workgroup owns a contiguous tile of sorted output
+// voxels.  Because adding a constant keeps the order, all queries of a tile and group
+// fall into one contiguous window of the input array.  The 2 K^2 window bounds are found
+// by wave-wide 64-ary searches (three dependent loads for 2^18 keys instead of 18), the
+// windows are copied into LDS with coalesced loads, and every lane then searches in LDS.
+// Windows that do not fit the LDS budget are searched in global memory, restricted to
+// the window, with the same code.
+#include <algorithm>
+#include <map>
+#include <tuple>
+
+#include "spc_internal.h"
+
+namespace spc {
+
+constexpr int SEARCH_THREADS = 256;
+constexpr int WIN_CAP_BYTES = 48 * 1024;  // LDS budget for staged windows per workgroup
+constexpr int MAX_K = 7;
+
+template <typename KeyT>
+struct SearchParams {
+  KeyT X[MAX_K];  // packed x offsets per ix (wrapping arithmetic)
+  KeyT Y[MAX_K];  // packed y offsets per iy
+  KeyT zmin;      // packed smallest z offset
+  KeyT zstep;     // distance between consecutive z offsets (= input stride)
+  int zrev;       // 1: z offsets descend with iz (transposed maps)
+};
+
+__device__ inline int lanemask_lt_popc(unsigned long long m) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(m), 0));
+}
+
+// S simultaneous wave-wide searches over keys[0,n).  upper[s]=false: first index with
+// key >= q; true: first index with key > q.  All lanes get the results.  Each round
+// every lane probes the last key of its 1/64 slice; the ballot tells the slice that
+// holds the answer.
+template <typename KeyT, int S>
+__device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, const KeyT (&q)[S], const bool (&upper)[S],
+                                   int (&res)[S]) {
+  const int lane = threadIdx.x & 63;
+  int lo[S], hi[S];
+#pragma unroll
+  for (int s = 0; s < S; ++s) {
+    lo[s] = 0;
+    hi[s] = n;
+  }
+  while (true) {
+    int maxlen = 0;
+#pragma unroll
+    for (int s = 0; s < S; ++s) maxlen = max(maxlen, hi[s] - lo[s]);
+    if (maxlen == 0) break;
+    bool pred[S];
+    int chunk[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      const int len = hi[s] - lo[s];
+      chunk[s] = (len + 63) >> 6;
+      const long long first = (long long)lo[s] + (long long)lane * chunk[s];
+      pred[s] = false;
+      if (len > 0 && first < hi[s]) {
+        const long long idx = min(first + chunk[s] - 1, (long long)hi[s] - 1);
+        const KeyT v = keys[idx];
+        pred[s] = upper[s] ? (v <= q[s]) : (v < q[s]);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      const int len = hi[s] - lo[s];
+      if (len > 0) {
+        const int c = __popcll(__ballot(pred[s]));
+        const int n_chunks = (len + chunk[s] - 1) / chunk[s];
+        const int nlo = lo[s] + c * chunk[s];
+        if (c >= n_chunks) {
+          lo[s] = hi[s];
+        } else {
+          hi[s] = min(nlo + chunk[s] - 1, hi[s] - 1);
+          lo[s] = nlo;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < S; ++s) res[s] = lo[s];
+}
+
+// Per-lane lower bound in a window of wsz keys.
+template <typename KeyT, typename Ptr>
+__device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
+  int lo = 0, len = wsz;
+  while (len > 0) {
+    const int half = len >> 1;
+    const bool less = win[lo + half] < q;
+    lo = less ? lo + half + 1 : lo;
+    len = less ? len - half - 1 : half;
+  }
+  return lo;
+}
+
+// Resolves the K z-consecutive queries of one (output voxel, group) pair: one search
+// for the smallest z, then at most one comparison per further query on consecutive
+// positions (valid because keys are sorted integers whose z components are multiples
+// of the input stride, Section 5.2).
+template <typename KeyT, int K, typename Ptr>
+__device__ inline void resolve_group(Ptr win, int wsz, int wlo, KeyT q0, KeyT zstep, int zrev, int32_t (&res)[K]) {
+  int pos = lane_lower_bound<KeyT>(win, wsz, q0);
+#pragma unroll
+  for (int t = 0; t < K; ++t) {
+    const KeyT qt = q0 + KeyT(t) * zstep;
+    const bool hit = pos < wsz && win[pos] == qt;
+    const int iz = zrev ? K - 1 - t : t;
+    res[iz] = hit ? wlo + pos : -1;
+    pos += hit ? 1 : 0;
+  }
+}
+
+template <typename KeyT, int K>
+__global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
+    const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
+    int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
+    int32_t* __restrict__ tile_counts, int n_tiles_cap) {
+  constexpr int G = K * K, K3 = K * K * K;
+  constexpr int WIN_CAP = WIN_CAP_BYTES / sizeof(KeyT);
+  constexpr int NW = SEARCH_THREADS / 64;
+  extern __shared__ __align__(16) unsigned char smem[];
+  KeyT* okeys = reinterpret_cast<KeyT*>(smem);   // [tile]
+  KeyT* win = okeys + tile;                      // [WIN_CAP]
+  __shared__ int s_wlo[G], s_wsz[G], s_woff[G];
+  __shared__ int s_bound[2 * G];
+  __shared__ int s_cnt[K3];
+  __shared__ KeyT s_gd[G];  // packed (dx,dy,zmin) offset of every group
+
+  const int n_in = n_in_d ? *n_in_d : n_in_h;
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int i0 = blockIdx.x * tile;
+  if (i0 >= n_out) return;  // whole workgroup leaves together
+  const int rows = min(tile, n_out - i0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  for (int v = tid; v < rows; v += SEARCH_THREADS) okeys[v] = out_keys[i0 + v];
+  for (int k = tid; k < K3; k += SEARCH_THREADS) s_cnt[k] = 0;
+#pragma unroll
+  for (int g = 0; g < G; ++g)  // static indices keep the kernel arguments in scalar registers
+    if (tid == g) s_gd[g] = sp.X[g / K] + sp.Y[g % K] + sp.zmin;
+  __syncthreads();
+  const KeyT kfirst = okeys[0], klast = okeys[rows - 1];
+  const KeyT zspan = KeyT(K - 1) * sp.zstep;
+
+  // ---- window bounds: search s = 2*g + side, dealt round-robin to the waves, 4 at a time
+  constexpr int S = 4;
+  for (int s0 = wave * S; s0 < 2 * G; s0 += NW * S) {
+    KeyT q[S];
+    bool up[S];
+    int res[S];
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+      const int s = min(s0 + j, 2 * G - 1);
+      const int g = s >> 1;
+      const KeyT d = s_gd[g];
+      up[j] = (s & 1) != 0;
+      q[j] = up[j] ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
+    }
+    wave_bounds<KeyT, S>(in_keys, n_in, q, up, res);
+    if (lane < S && s0 + lane < 2 * G) {
+      int r = res[0];
+#pragma unroll
+      for (int j = 1; j < S; ++j) r = (lane == j) ? res[j] : r;
+      s_bound[s0 + lane] = r;
+    }
+  }
+  __syncthreads();
+
+  // ---- window placement in LDS (first fit in group order; the rest stay in global memory)
+  if (tid == 0) {
+    int used = 0;
+    for (int g = 0; g < G; ++g) {
+      const int lo = s_bound[2 * g], sz = max(0, s_bound[2 * g + 1] - lo);
+      s_wlo[g] = lo;
+      s_wsz[g] = sz;
+      if (used + sz <= WIN_CAP) {
+        s_woff[g] = used;
+        used += sz;
+      } else {
+        s_woff[g] = -1;
+      }
+    }
+  }
+  __syncthreads();
+  for (int g = 0; g < G; ++g) {
+    const int off = s_woff[g];
+    if (off < 0) continue;
+    const int lo = s_wlo[g], sz = s_wsz[g];
+    for (int e = tid; e < sz; e += SEARCH_THREADS) win[off + e] = in_keys[lo + e];
+  }
+  __syncthreads();
+
+  // ---- per-lane searches; work item w = v*G + g so that a wave writes one contiguous run of M
+  const int items = rows * G;
+  int32_t* Mt = M + int64_t(i0) * K3;
+  for (int w = tid; w < items; w += SEARCH_THREADS) {
+    const int v = w / G, g = w - v * G;
+    const KeyT q0 = okeys[v] + s_gd[g];
+    const int off = s_woff[g], wlo = s_wlo[g], wsz = s_wsz[g];
+    int32_t r[K];
+    if (off >= 0) resolve_group<KeyT, K>(win + off, wsz, wlo, q0, sp.zstep, sp.zrev, r);
+    else resolve_group<KeyT, K>(in_keys + wlo, wsz, wlo, q0, sp.zstep, sp.zrev, r);
+#pragma unroll
+    for (int t = 0; t < K; ++t) Mt[int64_t(w) * K + t] = r[t];
+    if (tile_counts) {
+#pragma unroll
+      for (int t = 0; t < K; ++t)
+        if (r[t] >= 0) atomicAdd(&s_cnt[g * K + t], 1);
+    }
+  }
+  if (tile_counts) {
+    __syncthreads();
+    for (int k = tid; k < K3; k += SEARCH_THREADS) tile_counts[int64_t(k) * n_tiles_cap + blockIdx.x] = s_cnt[k];
+  }
+}
+
+// One workgroup per offset k: exclusive scan of that offset's per-tile counts in place,
+// total into nnz[k].
+__global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile_counts, int n_tiles_cap, int tile,
+                                                      int n_out_h, const int* __restrict__ n_out_d,
+                                                      int32_t* __restrict__ nnz) {
+  __shared__ int wave_sum[4];
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int n_tiles = (n_out + tile - 1) / tile;
+  int32_t* c = tile_counts + int64_t(blockIdx.x) * n_tiles_cap;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int carry = 0;
+  for (int b0 = 0; b0 < n_tiles; b0 += 256) {
+    const int i = b0 + threadIdx.x;
+    const int v = i < n_tiles ? c[i] : 0;
+    int x = v;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int y = __shfl_up(x, d, 64);
+      if (lane >= d) x += y;
+    }
+    if (lane == 63) wave_sum[wave] = x;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int w = 0; w < 4; ++w) {
+      const int s = wave_sum[w];
+      if (w < wave) base += s;
+      tot += s;
+    }
+    __syncthreads();
+    if (i < n_tiles) c[i] = carry + base + x - v;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) nnz[blockIdx.x] = carry;
+}
+
+// One workgroup per tile: the tile's rows of the OS matrix are read once (coalesced)
+// into LDS; each wave then filters whole columns with ballots, so list k comes out
+// ordered by output index without atomics.
+__global__ __launch_bounds__(256) void ws_fill_kernel(const int32_t* __restrict__ M, int n_out_h,
+                                                      const int* __restrict__ n_out_d, int K3, int tile,
+                                                      const int32_t* __restrict__ tile_base, int n_tiles_cap,
+                                                      int32_t* __restrict__ ws_in, int32_t* __restrict__ ws_out,
+                                                      int64_t ws_stride) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  int32_t* sM = reinterpret_cast<int32_t*>(smem);
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int i0 = blockIdx.x * tile;
+  if (i0 >= n_out) return;
+  const int rows = min(tile, n_out - i0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t* Mt = M + int64_t(i0) * K3;
+  for (int e = tid; e < rows * K3; e += 256) sM[e] = Mt[e];
+  __syncthreads();
+  for (int k = wave; k < K3; k += 4) {
+    int base = tile_base[int64_t(k) * n_tiles_cap + blockIdx.x];
+    int32_t* li = ws_in + int64_t(k) * ws_stride;
+    int32_t* lo = ws_out + int64_t(k) * ws_stride;
+    for (int v0 = 0; v0 < rows; v0 += 64) {
+      const int v = v0 + lane;
+      const int j = v < rows ? sM[v * K3 + k] : -1;
+      const unsigned long long m = __ballot(j >= 0);
+      if (j >= 0) {
+        const int r = base + lanemask_lt_popc(m);
+        li[r] = j;
+        lo[r] = i0 + v;
+      }
+      base += __popcll(m);
+    }
+  }
+}
+
+__global__ void copy_int_kernel(const int* src, int* dst) { *dst = *src; }
+
+// ---------------------------------------------------------------- host side
+static int axis_offset(int K, int s, int i) { return (K % 2 == 1) ? (i - (K - 1) / 2) * s : i * s; }
+
+static int tile_for(int K) { return K <= 3 ? 128 : (K == 5 ? 64 : 32); }
+
+template <typename KeyT, int K>
+static int launch_search(spc_kmap* m, hipStream_t s) {
+  const PackInfo& pi = m->pi;
+  const int sp_stride = m->desc.in_stride;
+  const int sign = m->desc.transposed ? -1 : 1;
+  SearchParams<KeyT> sp{};
+  for (int i = 0; i < K; ++i) {
+    const int64_t o = int64_t(sign) * axis_offset(K, sp_stride, i);
+    sp.X[i] = static_cast<KeyT>(static_cast<uint64_t>(o) << pi.sh_x);
+    sp.Y[i] = static_cast<KeyT>(static_cast<uint64_t>(o) << pi.sh_y);
+  }
+  const int64_t z_a = int64_t(sign) * axis_offset(K, sp_stride, 0), z_b = int64_t(sign) * axis_offset(K, sp_stride, K - 1);
+  sp.zmin = static_cast<KeyT>(static_cast<uint64_t>(std::min(z_a, z_b)));
+  sp.zstep = static_cast<KeyT>(sp_stride);
+  sp.zrev = (K > 1 && z_a > z_b) ? 1 : 0;
+  const Level* in = m->in_level;
+  const Level* out = m->out_level;
+  const size_t lds = size_t(m->tile) * sizeof(KeyT) + WIN_CAP_BYTES;
+  if (m->n_tiles > 0)
+    hipLaunchKernelGGL((kmap_search_kernel<KeyT, K>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
+                       static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
+                       static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
+                       sp, m->tile, m->os_map, m->tile_counts, m->n_tiles);
+  return SPC_OK;
+}
+
+template <typename KeyT>
+static int launch_search_k(spc_kmap* m, hipStream_t s) {
+  switch (m->desc.K) {
+    case 1: return launch_search<KeyT, 1>(m, s);
+    case 2: return launch_search<KeyT, 2>(m, s);
+    case 3: return launch_search<KeyT, 3>(m, s);
+    case 5: return launch_search<KeyT, 5>(m, s);
+    case 7: return launch_search<KeyT, 7>(m, s);
+  }
+  return set_error(SPC_ERR_UNSUPPORTED, "kernel size %d not built (1,2,3,5,7 are)", m->desc.K);
+}
+
+static void kmap_free(spc_kmap* m) {
+  pool_free(m->os_map);
+  pool_free(m->ws_in);
+  pool_free(m->ws_out);
+  pool_free(m->nnz_dev);
+  pool_free(m->tile_counts);
+  level_unref(m->in_level);
+  level_unref(m->out_level);
+  if (m->ready) (void)hipEventDestroy(m->ready);
+  delete m;
+}
+
+static int check_layer(const spc_layer_desc* l) {
+  if (!l) return set_error(SPC_ERR_ARG, "layer descriptor is NULL");
+  auto pow2 = [](int v) { return v >= 1 && (v & (v - 1)) == 0; };
+  if (l->K != 1 && l->K != 2 && l->K != 3 && l->K != 5 && l->K != 7)
+    return set_error(SPC_ERR_UNSUPPORTED, "kernel size %d not built (1,2,3,5,7 are)", l->K);
+  if (!pow2(l->in_stride) || !pow2(l->layer_stride)) return set_error(SPC_ERR_ARG, "strides must be powers of two");
+  if (l->transposed != 0 && l->transposed != 1) return set_error(SPC_ERR_ARG, "transposed must be 0 or 1");
+  if (l->transposed && l->layer_stride == 1) return set_error(SPC_ERR_ARG, "a transposed layer needs layer_stride > 1");
+  if (l->layout < 1 || l->layout > 3) return set_error(SPC_ERR_ARG, "layout must be OS, WS or BOTH");
+  return SPC_OK;
+}
+
+static int ilog2(int v) {
+  int b = 0;
+  while ((1 << b) < v) ++b;
+  return b;
+}
+
+// Builds the map object for given input/output levels (references are taken).
+static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_layer_desc& l, hipStream_t s, spc_kmap** res) {
+  spc_kmap* m = new spc_kmap;
+  m->pi = pi;
+  m->desc = l;
+  m->K3 = l.K * l.K * l.K;
+  m->in_level = in;
+  in->refs++;
+  m->out_level = out;
+  out->refs++;
+  (void)hipGetDevice(&m->device);
+  m->out_cap = out->n_host >= 0 ? out->n_host : out->cap;
+  m->tile = tile_for(l.K);
+  m->n_tiles = static_cast<int>((m->out_cap + m->tile - 1) / m->tile);
+  const size_t cells = std::max<size_t>(size_t(m->out_cap) * m->K3, 64);
+  m->os_map = static_cast<int32_t*>(pool_alloc(cells * 4));
+  m->nnz_dev = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->K3) * 4, 256)));
+  bool ok = m->os_map && m->nnz_dev;
+  if (ok && (l.layout & SPC_LAYOUT_WS)) {
+    m->ws_in = static_cast<int32_t*>(pool_alloc(cells * 4));
+    m->ws_out = static_cast<int32_t*>(pool_alloc(cells * 4));
+    m->tile_counts = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->K3 * 4, 256)));
+    ok = m->ws_in && m->ws_out && m->tile_counts;
+  }
+  if (!ok) {
+    kmap_free(m);
+    return SPC_ERR_NOMEM;
+  }
+  int rc = pi.key_bits == 32 ? launch_search_k<uint32_t>(m, s) : launch_search_k<uint64_t>(m, s);
+  if (rc == SPC_OK && (l.layout & SPC_LAYOUT_WS)) {
+    const int n_out_h = static_cast<int>(out->n_host < 0 ? 0 : out->n_host);
+    hipLaunchKernelGGL(ws_scan_kernel, dim3(m->K3), dim3(256), 0, s, m->tile_counts, m->n_tiles, m->tile, n_out_h,
+                       out->n_dev, m->nnz_dev);
+    if (m->n_tiles > 0)
+      hipLaunchKernelGGL(ws_fill_kernel, dim3(m->n_tiles), dim3(256), size_t(m->tile) * m->K3 * 4, s, m->os_map, n_out_h,
+                         out->n_dev, m->K3, m->tile, m->tile_counts, m->n_tiles, m->ws_in, m->ws_out, m->out_cap);
+  }
+  if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "kernel-map launch failed");
+  if (rc == SPC_OK && (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||
+                       hipEventRecord(m->ready, s) != hipSuccess))
+    rc = set_error(SPC_ERR_HIP, "event record failed");
+  if (rc != SPC_OK) {
+    kmap_free(m);
+    return rc;
+  }
+  *res = m;
+  return SPC_OK;
+}
+
+static Level* borrowed_level(const void* keys, int64_t n, int stride) {
+  Level* lv = new Level;
+  lv->keys = const_cast<void*>(keys);
+  lv->owns_keys = false;
+  lv->cap = n;
+  lv->n_host = n;
+  lv->stride = stride;
+  return lv;
+}
+
+static int fetch_level_n(Level* lv) {
+  if (lv->n_host >= 0) return SPC_OK;
+  if (lv->ready) SPC_HIP_CHECK(hipEventSynchronize(lv->ready));
+  int v = 0;
+  SPC_HIP_CHECK(hipMemcpy(&v, lv->n_dev, sizeof(int), hipMemcpyDeviceToHost));
+  lv->n_host = v;
+  return SPC_OK;
+}
+
+}  // namespace spc
+
+using namespace spc;
+
+extern "C" {
+
+int spc_build_kmap(const void* in_keys, int64_t n_in, const spc_pack_desc* d, const spc_layer_desc* l, spc_kmap** out,
+                   void* stream) {
+  PackInfo pi;
+  SPC_RETURN_IF(check_desc(d, &pi));
+  SPC_RETURN_IF(check_layer(l));
+  if (!out) return set_error(SPC_ERR_ARG, "out is NULL");
+  if (n_in < 0 || n_in > 0x7fffffff || (!in_keys && n_in > 0)) return set_error(SPC_ERR_ARG, "bad in_keys / n_in");
+  if (int64_t(n_in) * l->K * l->K * l->K > (int64_t(1) << 40)) return set_error(SPC_ERR_ARG, "map too large");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Level* given = borrowed_level(in_keys, n_in, l->in_stride);
+  Level* derived = nullptr;
+  int rc = SPC_OK;
+  if (l->layer_stride > 1) rc = downsample_level(in_keys, n_in, nullptr, pi, ilog2(l->in_stride * l->layer_stride), &derived, s);
+  if (rc == SPC_OK) {
+    if (l->layer_stride == 1) rc = build_on_levels(given, given, pi, *l, s, out);
+    else if (!l->transposed) rc = build_on_levels(given, derived, pi, *l, s, out);
+    else rc = build_on_levels(derived, given, pi, *l, s, out);
+  }
+  level_unref(given);
+  level_unref(derived);
+  return rc;
+}
+
+int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc* d, const spc_layer_desc* layers,
+                            int32_t n_layers, spc_kmap** out, void* const* streams, int32_t n_streams, int32_t flags) {
+  PackInfo pi;
+  SPC_RETURN_IF(check_desc(d, &pi));
+  if (!layers || !out || n_layers < 1) return set_error(SPC_ERR_ARG, "layers/out NULL or n_layers < 1");
+  if (!streams || n_streams < 1) return set_error(SPC_ERR_ARG, "at least one stream is required");
+  if (n0 < 0 || n0 > 0x7fffffff || (!v0_keys && n0 > 0)) return set_error(SPC_ERR_ARG, "bad v0_keys / n0");
+  for (int i = 0; i < n_layers; ++i) SPC_RETURN_IF(check_layer(&layers[i]));
+  const int ns = (flags & SPC_NET_SEQUENTIAL) ? 1 : n_streams;
+  std::vector<hipStream_t> st(ns);
+  for (int i = 0; i < ns; ++i) st[i] = static_cast<hipStream_t>(streams[i]);
+
+  // fork: every other stream waits for what streams[0] has enqueued so far (the pack/sort)
+  hipEvent_t fork = nullptr;
+  if (ns > 1) {
+    SPC_HIP_CHECK(hipEventCreateWithFlags(&fork, hipEventDisableTiming));
+    SPC_HIP_CHECK(hipEventRecord(fork, st[0]));
+    for (int i = 1; i < ns; ++i) SPC_HIP_CHECK(hipStreamWaitEvent(st[i], fork, 0));
+  }
+
+  // ---- phase 1: all coordinate levels, each straight from V_0 (closed form, Section 5.5)
+  std::map<int, Level*> levels;          // stride -> level
+  std::map<int, int> level_stream;       // stride -> index of the stream that produces it
+  levels[1] = borrowed_level(v0_keys, n0, 1);
+  level_stream[1] = 0;
+  int rc = SPC_OK, next = 0;
+  for (int i = 0; i < n_layers && rc == SPC_OK; ++i) {
+    const int need[2] = {layers[i].in_stride, layers[i].in_stride * layers[i].layer_stride};
+    for (int j = 0; j < 2 && rc == SPC_OK; ++j) {
+      if (levels.count(need[j])) continue;
+      const int si = (next++) % ns;
+      Level* lv = nullptr;
+      rc = downsample_level(v0_keys, n0, nullptr, pi, ilog2(need[j]), &lv, st[si]);
+      if (rc == SPC_OK) {
+        levels[need[j]] = lv;
+        level_stream[need[j]] = si;
+      }
+    }
+  }
+
+  // ---- phase 2: one search per distinct (K, in_stride, layer_stride, transposed)
+  using Key = std::tuple<int, int, int, int>;
+  std::map<Key, spc_kmap*> maps;
+  std::map<Key, int> want;
+  for (int i = 0; i < n_layers; ++i) want[Key(layers[i].K, layers[i].in_stride, layers[i].layer_stride, layers[i].transposed)] |= layers[i].layout;
+  std::vector<hipEvent_t> joins;
+  next = 0;
+  for (auto& kv : want) {
+    if (rc != SPC_OK) break;
+    spc_layer_desc l{std::get<0>(kv.first), std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first), kv.second};
+    Level* fine = levels[l.in_stride];
+    Level* coarse = levels[l.in_stride * l.layer_stride];
+    Level* in = l.transposed ? coarse : fine;
+    Level* outl = l.transposed ? fine : coarse;
+    const int si = (next++) % ns;
+    for (Level* dep : {in, outl})  // the map's stream waits for the levels it reads
+      if (dep->ready && level_stream[dep->stride] != si) {
+        hipError_t e = hipStreamWaitEvent(st[si], dep->ready, 0);
+        if (e != hipSuccess) rc = set_error(SPC_ERR_HIP, "hipStreamWaitEvent: %s", hipGetErrorString(e));
+      }
+    spc_kmap* m = nullptr;
+    if (rc == SPC_OK) rc = build_on_levels(in, outl, pi, l, st[si], &m);
+    if (rc == SPC_OK) {
+      maps[kv.first] = m;
+      if (si != 0) (void)hipStreamWaitEvent(st[0], m->ready, 0);  // join into streams[0]
+    }
+  }
+  // levels produced on other streams but not consumed by any map still join
+  for (auto& kv : levels)
+    if (kv.second->ready && level_stream[kv.first] != 0) (void)hipStreamWaitEvent(st[0], kv.second->ready, 0);
+  if (fork) (void)hipEventDestroy(fork);
+
+  if (rc == SPC_OK) {
+    for (int i = 0; i < n_layers; ++i) {
+      spc_kmap* m = maps[Key(layers[i].K, layers[i].in_stride, layers[i].layer_stride, layers[i].transposed)];
+      m->refs++;
+      out[i] = m;
+    }
+  }
+  for (auto& kv : maps)  // drop the builder's own reference
+    if (kv.second->refs.fetch_sub(1) == 1) kmap_free(kv.second);
+  for (auto& kv : levels) level_unref(kv.second);
+  return rc;
+}
+
+void spc_kmap_destroy(spc_kmap* m) {
+  if (m && m->refs.fetch_sub(1) == 1) kmap_free(m);
+}
+
+int64_t spc_kmap_n_in(spc_kmap* m) {
+  if (!m) return set_error(SPC_ERR_ARG, "map is NULL");
+  int rc = fetch_level_n(m->in_level);
+  return rc != SPC_OK ? rc : m->in_level->n_host;
+}
+int64_t spc_kmap_n_out(spc_kmap* m) {
+  if (!m) return set_error(SPC_ERR_ARG, "map is NULL");
+  int rc = fetch_level_n(m->out_level);
+  return rc != SPC_OK ? rc : m->out_level->n_host;
+}
+int32_t spc_kmap_kvol(const spc_kmap* m) { return m ? m->K3 : SPC_ERR_ARG; }
+const void* spc_kmap_out_keys(const spc_kmap* m) { return m ? m->out_level->keys : nullptr; }
+const void* spc_kmap_in_keys(const spc_kmap* m) { return m ? m->in_level->keys : nullptr; }
+const int32_t* spc_kmap_os_map(const spc_kmap* m) { return (m && (m->desc.layout & SPC_LAYOUT_OS)) ? m->os_map : nullptr; }
+
+int spc_kmap_copy_out_keys(spc_kmap* m, void* keys_host, int64_t cap) {
+  if (!m || !keys_host) return set_error(SPC_ERR_ARG, "NULL argument");
+  if (m->ready) SPC_HIP_CHECK(hipEventSynchronize(m->ready));
+  SPC_RETURN_IF(fetch_level_n(m->out_level));
+  const int64_t n = m->out_level->n_host;
+  if (cap < n) return set_error(SPC_ERR_ARG, "room for %lld keys, map has %lld", (long long)cap, (long long)n);
+  if (n > 0) SPC_HIP_CHECK(hipMemcpy(keys_host, m->out_level->keys, size_t(n) * (m->pi.key_bits / 8), hipMemcpyDeviceToHost));
+  return SPC_OK;
+}
+
+int spc_kmap_ws_lists(const spc_kmap* m, const int32_t** in_idx, const int32_t** out_idx, const int32_t** nnz_dev,
+                      int64_t* ws_stride) {
+  if (!m) return set_error(SPC_ERR_ARG, "map is NULL");
+  if (!(m->desc.layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "map was built without the WS layout");
+  if (in_idx) *in_idx = m->ws_in;
+  if (out_idx) *out_idx = m->ws_out;
+  if (nnz_dev) *nnz_dev = m->nnz_dev;
+  if (ws_stride) *ws_stride = m->out_cap;
+  return SPC_OK;
+}
+
+int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_t cap, int64_t* nnz_out) {
+  if (!m || !nnz_out) return set_error(SPC_ERR_ARG, "NULL argument");
+  if (which != SPC_LAYOUT_OS && which != SPC_LAYOUT_WS) return set_error(SPC_ERR_ARG, "which must be OS or WS");
+  if (which == SPC_LAYOUT_WS && !(m->desc.layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "WS layout was not built");
+  if (which == SPC_LAYOUT_OS && !(m->desc.layout & SPC_LAYOUT_OS)) return set_error(SPC_ERR_ARG, "OS layout was not built");
+  SPC_HIP_CHECK(hipEventSynchronize(m->ready));
+  SPC_RETURN_IF(fetch_level_n(m->out_level));
+  const int64_t n_out = m->out_level->n_host;
+  const int K3 = m->K3;
+  int64_t nnz = 0;
+  if (which == SPC_LAYOUT_OS) {
+    std::vector<int32_t> M(size_t(n_out) * K3);
+    if (!M.empty()) SPC_HIP_CHECK(hipMemcpy(M.data(), m->os_map, M.size() * 4, hipMemcpyDeviceToHost));
+    for (int k = 0; k < K3; ++k)
+      for (int64_t i = 0; i < n_out; ++i) {
+        const int32_t j = M[i * K3 + k];
+        if (j < 0) continue;
+        if (nnz < cap && triples) {
+          triples[3 * nnz] = k;
+          triples[3 * nnz + 1] = j;
+          triples[3 * nnz + 2] = static_cast<int32_t>(i);
+        }
+        ++nnz;
+      }
+  } else {
+    std::vector<int32_t> cnt(K3);
+    SPC_HIP_CHECK(hipMemcpy(cnt.data(), m->nnz_dev, size_t(K3) * 4, hipMemcpyDeviceToHost));
+    std::vector<int32_t> a, b;
+    for (int k = 0; k < K3; ++k) {
+      const int c = cnt[k];
+      if (c < 0 || c > n_out) return set_error(SPC_ERR_HIP, "corrupt WS count %d at offset %d", c, k);
+      a.resize(c);
+      b.resize(c);
+      if (c) {
+        SPC_HIP_CHECK(hipMemcpy(a.data(), m->ws_in + int64_t(k) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
+        SPC_HIP_CHECK(hipMemcpy(b.data(), m->ws_out + int64_t(k) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
+      }
+      for (int e = 0; e < c; ++e) {
+        if (nnz < cap && triples) {
+          triples[3 * nnz] = k;
+          triples[3 * nnz + 1] = a[e];
+          triples[3 * nnz + 2] = b[e];
+        }
+        ++nnz;
+      }
+    }
+  }
+  *nnz_out = nnz;
+  return SPC_OK;
+}
+
+int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host) {
+  if (!m || !nnz_host) return set_error(SPC_ERR_ARG, "NULL argument");
+  if (m->nnz_host.empty()) {
+    SPC_HIP_CHECK(hipEventSynchronize(m->ready));
+    SPC_RETURN_IF(fetch_level_n(m->out_level));
+    std::vector<int64_t> cnt(m->K3, 0);
+    if (m->desc.layout & SPC_LAYOUT_WS) {
+      std::vector<int32_t> c(m->K3);
+      SPC_HIP_CHECK(hipMemcpy(c.data(), m->nnz_dev, size_t(m->K3) * 4, hipMemcpyDeviceToHost));
+      for (int k = 0; k < m->K3; ++k) cnt[k] = c[k];
+    } else {
+      const int64_t n_out = m->out_level->n_host;
+      std::vector<int32_t> M(size_t(n_out) * m->K3);
+      if (!M.empty()) SPC_HIP_CHECK(hipMemcpy(M.data(), m->os_map, M.size() * 4, hipMemcpyDeviceToHost));
+      for (int64_t i = 0; i < n_out; ++i)
+        for (int k = 0; k < m->K3; ++k) cnt[k] += M[i * m->K3 + k] >= 0;
+    }
+    m->nnz_host = cnt;
+  }
+  for (int k = 0; k < m->K3; ++k) nnz_host[k] = m->nnz_host[k];
+  return SPC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,292 @@
+// Coordinate packing (Section 5.3), the one-time sort (Section 5.2) and the
+// packed-native downsampling of a stride level (Eq. 1 via mask, sort, unique).
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+
+#include "spc_internal.h"
+
+namespace spc {
+
+// ---------------------------------------------------------------- sort wrappers
+template <typename KeyT>
+static int sort_pairs_t(const void* ki, void* ko, const int32_t* vi, int32_t* vo, int64_t n, int end_bit, void* temp,
+                        size_t& temp_bytes, hipStream_t s) {
+  hipError_t e = rocprim::radix_sort_pairs(temp, temp_bytes, static_cast<const KeyT*>(ki), static_cast<KeyT*>(ko), vi, vo,
+                                           static_cast<size_t>(n), 0u, static_cast<unsigned>(end_bit), s);
+  if (e != hipSuccess) return set_error(SPC_ERR_HIP, "radix_sort_pairs: %s", hipGetErrorString(e));
+  return SPC_OK;
+}
+template <typename KeyT>
+static int sort_keys_t(const void* ki, void* ko, int64_t n, int end_bit, void* temp, size_t& temp_bytes, hipStream_t s) {
+  hipError_t e = rocprim::radix_sort_keys(temp, temp_bytes, static_cast<const KeyT*>(ki), static_cast<KeyT*>(ko),
+                                          static_cast<size_t>(n), 0u, static_cast<unsigned>(end_bit), s);
+  if (e != hipSuccess) return set_error(SPC_ERR_HIP, "radix_sort_keys: %s", hipGetErrorString(e));
+  return SPC_OK;
+}
+
+size_t sort_pairs_temp_bytes(int key_bits, int64_t n) {
+  size_t b = 0;
+  if (key_bits == 32) sort_pairs_t<uint32_t>(nullptr, nullptr, nullptr, nullptr, n, 32, nullptr, b, nullptr);
+  else sort_pairs_t<uint64_t>(nullptr, nullptr, nullptr, nullptr, n, 64, nullptr, b, nullptr);
+  return b;
+}
+int sort_pairs(int key_bits, const void* ki, void* ko, const int32_t* vi, int32_t* vo, int64_t n, int end_bit, void* temp,
+               size_t temp_bytes, hipStream_t s) {
+  return key_bits == 32 ? sort_pairs_t<uint32_t>(ki, ko, vi, vo, n, end_bit, temp, temp_bytes, s)
+                        : sort_pairs_t<uint64_t>(ki, ko, vi, vo, n, end_bit, temp, temp_bytes, s);
+}
+size_t sort_keys_temp_bytes(int key_bits, int64_t n) {
+  size_t b = 0;
+  if (key_bits == 32) sort_keys_t<uint32_t>(nullptr, nullptr, n, 32, nullptr, b, nullptr);
+  else sort_keys_t<uint64_t>(nullptr, nullptr, n, 64, nullptr, b, nullptr);
+  return b;
+}
+int sort_keys(int key_bits, const void* ki, void* ko, int64_t n, int end_bit, void* temp, size_t temp_bytes, hipStream_t s) {
+  return key_bits == 32 ? sort_keys_t<uint32_t>(ki, ko, n, end_bit, temp, temp_bytes, s)
+                        : sort_keys_t<uint64_t>(ki, ko, n, end_bit, temp, temp_bytes, s);
+}
+
+// ---------------------------------------------------------------- kernels
+struct PackParams {
+  int sh_b, sh_x, sh_y;
+  int bits_b, bits_x, bits_y, bits_z;
+  int ox, oy, oz, pad;
+};
+
+// One thread per voxel: 16-byte coalesced load of (b,x,y,z), one key store.
+// status bit 0 is raised if a field (with its guard band on both sides) does not fit.
+template <typename KeyT>
+__global__ __launch_bounds__(256) void pack_kernel(const int4* __restrict__ coords, int64_t n, PackParams p,
+                                                   KeyT* __restrict__ keys, int32_t* __restrict__ iota,
+                                                   int32_t* __restrict__ status) {
+  const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (i >= n) return;
+  const int4 c = coords[i];
+  const int64_t fx = int64_t(c.y) - p.ox, fy = int64_t(c.z) - p.oy, fz = int64_t(c.w) - p.oz;
+  const bool ok = c.x >= 0 && (int64_t(c.x) < (int64_t(1) << p.bits_b)) && fx >= 0 && fy >= 0 && fz >= 0 &&
+                  fx + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_x) && fy + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_y) &&
+                  fz + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_z);
+  KeyT key;
+  if (ok) {
+    key = (KeyT(c.x) << p.sh_b) | (KeyT(fx + p.pad) << p.sh_x) | (KeyT(fy + p.pad) << p.sh_y) | KeyT(fz + p.pad);
+  } else {
+    key = ~KeyT(0);
+    atomicOr(status, 1);
+  }
+  keys[i] = key;
+  if (iota) iota[i] = static_cast<int32_t>(i);
+}
+
+template <typename KeyT>
+__global__ __launch_bounds__(256) void dup_check_kernel(const KeyT* __restrict__ keys, int64_t n, int32_t* __restrict__ status) {
+  const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (i + 1 < n && keys[i] == keys[i + 1] && keys[i] != ~KeyT(0)) atomicOr(status, 2);
+}
+
+__global__ void set_int_kernel(int32_t* p, int32_t v) { *p = v; }
+
+template <typename KeyT>
+__global__ __launch_bounds__(256) void mask_kernel(const KeyT* __restrict__ in, int64_t n, KeyT mask, KeyT* __restrict__ out) {
+  const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  if (i < n) out[i] = in[i] & mask;
+}
+
+// Order-preserving removal of repeated keys from a sorted array, in three launches:
+// heads per block, exclusive scan of the block counts, compacting write.
+constexpr int UQ_THREADS = 256;
+constexpr int UQ_ITEMS = 8;
+constexpr int UQ_BLOCK = UQ_THREADS * UQ_ITEMS;
+
+template <typename KeyT>
+__device__ inline bool is_head(const KeyT* keys, int64_t i) { return i == 0 || keys[i] != keys[i - 1]; }
+
+__device__ inline int block_exclusive_scan(int v, int* total) {
+  // 256 threads = 4 waves; wave scan by shuffles, then the 4 wave totals through LDS.
+  __shared__ int wave_sum[UQ_THREADS / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int x = v;
+  for (int d = 1; d < 64; d <<= 1) {
+    int y = __shfl_up(x, d, 64);
+    if (lane >= d) x += y;
+  }
+  if (lane == 63) wave_sum[wave] = x;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int w = 0; w < UQ_THREADS / 64; ++w) {
+    int s = wave_sum[w];
+    if (w < wave) base += s;
+    tot += s;
+  }
+  __syncthreads();
+  *total = tot;
+  return base + x - v;
+}
+
+template <typename KeyT>
+__global__ __launch_bounds__(UQ_THREADS) void unique_count_kernel(const KeyT* __restrict__ keys, int64_t n,
+                                                                  int32_t* __restrict__ block_counts) {
+  const int64_t base = int64_t(blockIdx.x) * UQ_BLOCK;
+  int c = 0;
+  for (int it = 0; it < UQ_ITEMS; ++it) {
+    const int64_t i = base + it * UQ_THREADS + threadIdx.x;
+    if (i < n && is_head(keys, i)) ++c;
+  }
+  int total;
+  block_exclusive_scan(c, &total);
+  if (threadIdx.x == 0) block_counts[blockIdx.x] = total;
+}
+
+// Single workgroup: exclusive scan of n_blocks counts in place; the grand total goes to *n_out.
+__global__ __launch_bounds__(UQ_THREADS) void scan_counts_kernel(int32_t* __restrict__ counts, int n_blocks,
+                                                                 int32_t* __restrict__ n_out) {
+  int carry = 0;
+  for (int b0 = 0; b0 < n_blocks; b0 += UQ_THREADS) {
+    const int i = b0 + threadIdx.x;
+    const int v = i < n_blocks ? counts[i] : 0;
+    int total;
+    const int ex = block_exclusive_scan(v, &total);
+    if (i < n_blocks) counts[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) *n_out = carry;
+}
+
+template <typename KeyT>
+__global__ __launch_bounds__(UQ_THREADS) void unique_write_kernel(const KeyT* __restrict__ keys, int64_t n,
+                                                                  const int32_t* __restrict__ block_base,
+                                                                  KeyT* __restrict__ out) {
+  const int64_t base = int64_t(blockIdx.x) * UQ_BLOCK;
+  int run = block_base[blockIdx.x];
+  for (int it = 0; it < UQ_ITEMS; ++it) {  // items are visited in array order, so ranks stay ordered
+    const int64_t i = base + it * UQ_THREADS + threadIdx.x;
+    const bool head = i < n && is_head(keys, i);
+    int total;
+    const int ex = block_exclusive_scan(head ? 1 : 0, &total);
+    if (head) out[run + ex] = keys[i];
+    run += total;
+  }
+}
+
+template <typename KeyT>
+static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, Level* lv, hipStream_t s) {
+  const size_t ksz = sizeof(KeyT);
+  const size_t tb = sort_keys_temp_bytes(pi.key_bits, n);
+  const int n_blocks = static_cast<int>((n + UQ_BLOCK - 1) / UQ_BLOCK);
+  // scratch: masked keys | sorted keys | block counts | sort temp
+  const size_t off_sorted = (n * ksz + 255) / 256 * 256;
+  const size_t off_counts = off_sorted * 2;
+  const size_t off_temp = off_counts + (size_t(n_blocks) * 4 + 255) / 256 * 256;
+  char* scratch = static_cast<char*>(pool_alloc(off_temp + tb + 256));
+  if (!scratch) return SPC_ERR_NOMEM;
+  KeyT* masked = reinterpret_cast<KeyT*>(scratch);
+  KeyT* sorted = reinterpret_cast<KeyT*>(scratch + off_sorted);
+  int32_t* counts = reinterpret_cast<int32_t*>(scratch + off_counts);
+  const KeyT mask = static_cast<KeyT>(level_mask(pi, m));
+  const int grid = static_cast<int>((n + 255) / 256);
+  int rc = SPC_OK;
+  if (n > 0) {
+    hipLaunchKernelGGL(mask_kernel<KeyT>, dim3(grid), dim3(256), 0, s, static_cast<const KeyT*>(src), n, mask, masked);
+    rc = sort_keys(pi.key_bits, masked, sorted, n, pi.used_bits, scratch + off_temp, tb, s);
+    if (rc == SPC_OK) {
+      hipLaunchKernelGGL(unique_count_kernel<KeyT>, dim3(n_blocks), dim3(UQ_THREADS), 0, s, sorted, n, counts);
+      hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(UQ_THREADS), 0, s, counts, n_blocks, lv->n_dev);
+      hipLaunchKernelGGL(unique_write_kernel<KeyT>, dim3(n_blocks), dim3(UQ_THREADS), 0, s, sorted, n, counts,
+                         static_cast<KeyT*>(lv->keys));
+    }
+  } else {
+    hipLaunchKernelGGL(set_int_kernel, dim3(1), dim3(1), 0, s, lv->n_dev, 0);
+  }
+  // The scratch block returns to the cache now; reuse is ordered behind these kernels
+  // as long as later library calls are ordered after this stream's work.
+  pool_free(scratch);
+  if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "downsample launch failed");
+  return rc;
+}
+
+int downsample_level(const void* src_keys, int64_t n_src, const int* /*n_src_dev*/, const PackInfo& pi, int m, Level** out,
+                     hipStream_t stream) {
+  Level* lv = new Level;
+  lv->cap = n_src;
+  lv->stride = 1 << m;
+  lv->owns_keys = true;
+  lv->keys = pool_alloc(std::max<size_t>(size_t(n_src) * (pi.key_bits / 8), 256));
+  lv->n_dev = static_cast<int*>(pool_alloc(256));
+  if (!lv->keys || !lv->n_dev) {
+    level_unref(lv);
+    return SPC_ERR_NOMEM;
+  }
+  int rc = pi.key_bits == 32 ? downsample_t<uint32_t>(src_keys, n_src, pi, m, lv, stream)
+                             : downsample_t<uint64_t>(src_keys, n_src, pi, m, lv, stream);
+  if (rc == SPC_OK) {
+    if (hipEventCreateWithFlags(&lv->ready, hipEventDisableTiming) != hipSuccess ||
+        hipEventRecord(lv->ready, stream) != hipSuccess)
+      rc = set_error(SPC_ERR_HIP, "event record failed");
+  }
+  if (rc != SPC_OK) {
+    level_unref(lv);
+    return rc;
+  }
+  *out = lv;
+  return SPC_OK;
+}
+
+}  // namespace spc
+
+// ---------------------------------------------------------------- C ABI
+extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_desc* d, void* keys_out, int32_t* perm_out,
+                               void* workspace, size_t* workspace_bytes, int32_t flags, void* stream) {
+  using namespace spc;
+  PackInfo pi;
+  SPC_RETURN_IF(check_desc(d, &pi));
+  if (n < 0 || n > 0x7fffffff) return set_error(SPC_ERR_ARG, "n out of range");
+  if (!workspace_bytes) return set_error(SPC_ERR_ARG, "workspace_bytes is NULL");
+  const size_t ksz = pi.key_bits / 8;
+  const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
+  const size_t off_iota = (nn * ksz + 255) / 256 * 256;
+  const size_t off_status = off_iota + (nn * 4 + 255) / 256 * 256;
+  const size_t off_temp = off_status + 256;
+  const size_t tb = std::max(sort_pairs_temp_bytes(pi.key_bits, nn), sort_keys_temp_bytes(pi.key_bits, nn));
+  const size_t need = off_temp + tb + 256;
+  if (!workspace) {
+    *workspace_bytes = need;
+    return SPC_OK;
+  }
+  if (*workspace_bytes < need) return set_error(SPC_ERR_ARG, "workspace too small: %zu < %zu", *workspace_bytes, need);
+  if (!coords || !keys_out) return set_error(SPC_ERR_ARG, "NULL coords or keys_out");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  void* keys_tmp = ws;
+  int32_t* iota = reinterpret_cast<int32_t*>(ws + off_iota);
+  int32_t* status = reinterpret_cast<int32_t*>(ws + off_status);
+  PackParams p{pi.sh_b, pi.sh_x, pi.sh_y, pi.bits_b, pi.bits_x, pi.bits_y, pi.bits_z, d->origin[0], d->origin[1], d->origin[2], d->pad};
+  hipLaunchKernelGGL(set_int_kernel, dim3(1), dim3(1), 0, s, status, 0);
+  if (n > 0) {
+    const int grid = static_cast<int>((n + 255) / 256);
+    if (pi.key_bits == 32)
+      hipLaunchKernelGGL(pack_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, reinterpret_cast<const int4*>(coords), n, p,
+                         static_cast<uint32_t*>(keys_tmp), perm_out ? iota : nullptr, status);
+    else
+      hipLaunchKernelGGL(pack_kernel<uint64_t>, dim3(grid), dim3(256), 0, s, reinterpret_cast<const int4*>(coords), n, p,
+                         static_cast<uint64_t*>(keys_tmp), perm_out ? iota : nullptr, status);
+    // all-ones keys of rejected rows must keep their place at the end: sort every key bit then
+    const int end_bit = (flags & SPC_PACK_VALIDATE) ? pi.key_bits : pi.used_bits;
+    if (perm_out) SPC_RETURN_IF(sort_pairs(pi.key_bits, keys_tmp, keys_out, iota, perm_out, n, end_bit, ws + off_temp, tb, s));
+    else SPC_RETURN_IF(sort_keys(pi.key_bits, keys_tmp, keys_out, n, end_bit, ws + off_temp, tb, s));
+    if (flags & SPC_PACK_VALIDATE) {
+      if (pi.key_bits == 32)
+        hipLaunchKernelGGL(dup_check_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint32_t*>(keys_out), n, status);
+      else
+        hipLaunchKernelGGL(dup_check_kernel<uint64_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint64_t*>(keys_out), n, status);
+    }
+  }
+  SPC_HIP_CHECK(hipGetLastError());
+  if (flags & SPC_PACK_VALIDATE) {
+    int32_t st = 0;
+    SPC_HIP_CHECK(hipMemcpyAsync(&st, status, sizeof(st), hipMemcpyDeviceToHost, s));
+    SPC_HIP_CHECK(hipStreamSynchronize(s));
+    if (st & 1) return set_error(SPC_ERR_RANGE, "a coordinate does not fit its packed field (guard band included)");
+    if (st & 2) return set_error(SPC_ERR_DUP, "duplicate voxel coordinates");
+  }
+  return SPC_OK;
+}

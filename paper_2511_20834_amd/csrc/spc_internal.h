@@ -1,0 +1,96 @@
+// Internal declarations shared by the translation units of libspc (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <mutex>
+#include <vector>
+
+#include "spc.h"
+
+namespace spc {
+
+// ---------------------------------------------------------------- errors
+int set_error(int code, const char* fmt, ...);
+#define SPC_HIP_CHECK(expr)                                                                       \
+  do {                                                                                            \
+    hipError_t e__ = (expr);                                                                      \
+    if (e__ != hipSuccess)                                                                        \
+      return ::spc::set_error(SPC_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), \
+                              __FILE__, __LINE__);                                                \
+  } while (0)
+#define SPC_RETURN_IF(expr)     \
+  do {                          \
+    int rc__ = (expr);          \
+    if (rc__ != SPC_OK) return rc__; \
+  } while (0)
+
+// ---------------------------------------------------------------- device block cache
+// hipMalloc costs tens of microseconds and synchronises; kernel maps are built per
+// frame, so freed blocks are kept (binned by rounded size) and handed out again.
+void* pool_alloc(size_t bytes);  // nullptr on failure (error set)
+void pool_free(void* p);
+int pool_release_all();
+
+// ---------------------------------------------------------------- packing
+struct PackInfo {
+  int key_bits;
+  int sh_b, sh_x, sh_y;  // left shifts of the batch/x/y fields (z has shift 0)
+  int bits_b, bits_x, bits_y, bits_z;
+  int used_bits;
+};
+int check_desc(const spc_pack_desc* d, PackInfo* pi);
+// Mask that clears the low m bits of every spatial field (Section 5.3).
+uint64_t level_mask(const PackInfo& pi, int m);
+
+// ---------------------------------------------------------------- coordinate levels
+// One sorted packed-key array (a stride level).  n is known on the host for the
+// caller's own array; for derived levels it lives on the device until the host asks.
+struct Level {
+  std::atomic<int> refs{1};
+  void* keys = nullptr;   // device
+  bool owns_keys = false;
+  int64_t cap = 0;        // rows allocated / upper bound of n
+  int64_t n_host = -1;    // -1: not yet fetched
+  int* n_dev = nullptr;   // device int (nullptr when n_host is authoritative from the start)
+  int stride = 1;
+  hipEvent_t ready = nullptr;  // recorded after the level's last kernel
+};
+void level_unref(Level* l);
+
+// Derive the level with stride 2^m of `src_keys` (mask, sort, unique).  Enqueues only.
+int downsample_level(const void* src_keys, int64_t n_src, const int* n_src_dev, const PackInfo& pi, int m,
+                     Level** out, hipStream_t stream);
+
+// ---------------------------------------------------------------- sort (rocPRIM radix sort)
+size_t sort_pairs_temp_bytes(int key_bits, int64_t n);
+int sort_pairs(int key_bits, const void* keys_in, void* keys_out, const int32_t* vals_in, int32_t* vals_out,
+               int64_t n, int end_bit, void* temp, size_t temp_bytes, hipStream_t s);
+size_t sort_keys_temp_bytes(int key_bits, int64_t n);
+int sort_keys(int key_bits, const void* keys_in, void* keys_out, int64_t n, int end_bit, void* temp,
+              size_t temp_bytes, hipStream_t s);
+
+}  // namespace spc
+
+// ---------------------------------------------------------------- kernel map object
+struct spc_kmap {
+  std::atomic<int> refs{1};
+  spc::PackInfo pi{};
+  spc_layer_desc desc{};
+  int K3 = 0;
+  spc::Level* in_level = nullptr;   // the layer's input voxels
+  spc::Level* out_level = nullptr;  // the layer's output voxels
+  int64_t out_cap = 0;              // rows allocated in os_map / ws lists
+  int32_t* os_map = nullptr;        // [out_cap][K3]
+  int32_t* ws_in = nullptr;         // [K3][out_cap]
+  int32_t* ws_out = nullptr;        // [K3][out_cap]
+  int32_t* nnz_dev = nullptr;       // [K3]
+  int32_t* tile_counts = nullptr;   // [n_tiles][K3] scratch of the two-pass compaction
+  int tile = 0, n_tiles = 0;
+  std::vector<int64_t> nnz_host;    // filled lazily
+  hipEvent_t ready = nullptr;       // recorded after the last build kernel
+  int device = 0;
+};

@@ -1,0 +1,234 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+Kernel maps must be bit-exact (sorted (offset, in, out) triples); features within
+max|y - yhat| / max|yhat| <= 1e-2 for fp16/bf16 inputs with fp32 accumulation and
+1e-5 in fp32 mode."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_20834_amd import binding as B
+from paper_2511_20834_amd import synth
+
+from gpu_common import (fit_desc, gpu_pack, keys_to_u64, oracle_keys, oracle_layer, rel_err, to_torch)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float16: 1e-2, torch.bfloat16: 1e-2, torch.float32: 1e-5}
+
+
+def _cloud(name):
+    if name == "tiny":
+        return synth.tiny_cloud()
+    if name == "tiny_neg":
+        c = synth.tiny_cloud()
+        c[:, 1:] -= 33
+        return c
+    if name == "rand_b3":
+        c = synth.random_cloud(5000, (37, 29, 23), seed=3, batch=3)
+        c[:, 1:] -= 7
+        return c
+    if name == "grid":
+        return synth.full_grid(12, batch=2)
+    if name == "ragged":
+        return synth.random_cloud(128 * 5 + 1, (30, 30, 30), seed=4)
+    if name == "one":
+        return np.array([[0, 5, 6, 7]], np.int32)
+    raise KeyError(name)
+
+
+def _check_map(c0_sorted, keys_t, desc, K, s_p, s_l, transposed, kmap):
+    cin, cout, M = oracle_layer(c0_sorted, K, s_p, s_l, transposed)
+    assert kmap.n_in == len(cin) and kmap.n_out == len(cout)
+    assert np.array_equal(kmap.out_keys(), oracle_keys(cout, desc))
+    ref = oracle.triples(M)
+    got_os = kmap.export_triples(B.LAYOUT_OS)
+    got_ws = kmap.export_triples(B.LAYOUT_WS)
+    assert np.array_equal(got_os, ref)
+    assert np.array_equal(got_ws, ref)
+    assert np.array_equal(kmap.nnz(), np.bincount(ref[:, 0], minlength=K ** 3))
+    return cin, cout, M
+
+
+# ----------------------------------------------------------------------------- pack + sort
+@pytest.mark.parametrize("name,key_bits", [("tiny", 0), ("tiny_neg", 0), ("rand_b3", 0), ("rand_b3", 64), ("one", 0)])
+def test_pack_sort_matches_oracle(name, key_bits):
+    c = _cloud(name)
+    desc = fit_desc(c, [(3, 1, 2)], key_bits)
+    keys, perm = gpu_pack(c, desc, B.PACK_VALIDATE)
+    cs, operm = oracle.sort_coords(c)
+    assert np.array_equal(keys_to_u64(keys), oracle_keys(cs, desc))
+    assert np.array_equal(perm.cpu().numpy().astype(np.int64), operm)
+
+
+def test_pack_validate_errors():
+    c = _cloud("tiny")
+    desc = fit_desc(c, [(3, 1, 1)])
+    bad = c.copy()
+    bad[5, 1] = 10_000
+    with pytest.raises(B.SpcError) as e:
+        gpu_pack(bad, desc, B.PACK_VALIDATE)
+    assert e.value.code == B.ERR_RANGE
+    dup = np.concatenate([c, c[7:8]])
+    with pytest.raises(B.SpcError) as e:
+        gpu_pack(dup, desc, B.PACK_VALIDATE)
+    assert e.value.code == B.ERR_DUP
+    desc.bits_x = 31
+    with pytest.raises(B.SpcError) as e:
+        gpu_pack(c, desc)
+    assert e.value.code == B.ERR_ARG
+
+
+# ----------------------------------------------------------------------------- kernel maps
+@pytest.mark.parametrize("name,K,s_l,transposed,key_bits", [
+    ("tiny", 3, 1, 0, 0), ("tiny_neg", 3, 1, 0, 0), ("tiny", 5, 1, 0, 0), ("tiny", 7, 1, 0, 0), ("tiny", 1, 1, 0, 0),
+    ("tiny", 3, 2, 0, 0), ("tiny_neg", 2, 2, 0, 0), ("tiny_neg", 2, 2, 1, 0), ("tiny", 3, 2, 1, 0),
+    ("rand_b3", 3, 1, 0, 0), ("rand_b3", 3, 2, 0, 64), ("rand_b3", 5, 1, 0, 64), ("rand_b3", 2, 2, 1, 64),
+    ("grid", 3, 1, 0, 0), ("ragged", 3, 1, 0, 0), ("ragged", 5, 1, 0, 0), ("one", 3, 1, 0, 0), ("one", 2, 2, 1, 0),
+])
+def test_kmap_bit_exact(name, K, s_l, transposed, key_bits):
+    c = _cloud(name)
+    desc = fit_desc(c, [(K, 1, s_l)], key_bits)
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, transposed, B.LAYOUT_BOTH)
+    _check_map(cs, keys, desc, K, 1, s_l, transposed, km)
+    km.destroy()
+
+
+def test_kmap_on_coarse_level():
+    """A layer whose input is already a strided level (s_p = 2 and 4)."""
+    c = _cloud("tiny_neg")
+    desc = fit_desc(c, [(3, 4, 2)])
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    down = B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS)
+    k2 = torch.from_numpy(down.out_keys().astype(np.uint32).view(np.int32)).cuda()
+    for K, s_l in ((3, 1), (3, 2), (2, 2)):
+        km = B.spc_build_kmap(k2, desc, K, 2, s_l, 0, B.LAYOUT_BOTH)
+        _check_map(cs, k2, desc, K, 2, s_l, 0, km)
+        km.destroy()
+    down.destroy()
+
+
+def test_kmap_empty_input():
+    desc = B.spc_pack_desc_fit([0, 0, 0], [10, 10, 10], 1, 2, 1)
+    keys = torch.empty(0, dtype=torch.int32, device="cuda")
+    for s_l in (1, 2):
+        km = B.spc_build_kmap(keys, desc, 3, 1, s_l, 0, B.LAYOUT_BOTH)
+        assert km.n_out == 0 and km.export_triples(B.LAYOUT_OS).shape == (0, 3) and km.nnz().sum() == 0
+        km.destroy()
+
+
+def test_kmap_bad_arguments():
+    desc = B.spc_pack_desc_fit([0, 0, 0], [10, 10, 10], 1, 2, 1)
+    keys = torch.zeros(4, dtype=torch.int32, device="cuda")
+    for args, code in (((4, 1, 1, 0, 3), B.ERR_UNSUPPORTED), ((3, 3, 1, 0, 3), B.ERR_ARG), ((3, 1, 1, 1, 3), B.ERR_ARG),
+                       ((3, 1, 1, 0, 0), B.ERR_ARG)):
+        with pytest.raises(B.SpcError) as e:
+            B.spc_build_kmap(keys, desc, *args)
+        assert e.value.code == code
+
+
+# ----------------------------------------------------------------------------- features
+def _run_conv(c, K, s_l, transposed, cin, cout, dtype, seed=0, relu=False):
+    desc = fit_desc(c, [(K, 1, s_l)])
+    keys, perm = gpu_pack(c, desc)
+    cs, operm = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, transposed, B.LAYOUT_BOTH)
+    ci, co, M = oracle_layer(cs, K, 1, s_l, transposed)
+    np_dt = np.float32 if dtype == torch.float32 else np.float16
+    F = synth.features(len(ci), cin, np_dt, seed=seed + 1)
+    W = synth.weights(K ** 3, cin, cout, np_dt, seed=seed + 2)
+    Ft, F64 = to_torch(F, dtype)
+    Wt, W64 = to_torch(W, dtype)
+    ref = oracle.conv(M, F64, W64)
+    if relu:
+        ref = np.maximum(ref, 0)
+    outs = {}
+    for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
+        y = B.spc_conv_forward(km, Ft, Wt, df, B.CONV_RELU if relu else 0)
+        torch.cuda.synchronize()
+        outs[df] = y.cpu().to(torch.float64).numpy()
+        assert outs[df].shape == ref.shape
+        err = rel_err(outs[df], ref)
+        assert err <= TOL[dtype], (df, err)
+    km.destroy()
+    return outs, ref
+
+
+@pytest.mark.parametrize("dtype,cin,cout", [
+    (torch.float16, 64, 64), (torch.float16, 32, 32), (torch.float16, 64, 128), (torch.float16, 128, 256),
+    (torch.float16, 16, 32), (torch.float16, 80, 64), (torch.bfloat16, 64, 64), (torch.bfloat16, 32, 128),
+    (torch.float32, 16, 16), (torch.float32, 5, 7), (torch.float16, 4, 32), (torch.float16, 16, 16), (torch.float16, 24, 40),
+])
+def test_conv_submanifold_k3(dtype, cin, cout):
+    _run_conv(_cloud("tiny"), 3, 1, 0, cin, cout, dtype)
+
+
+@pytest.mark.parametrize("K,s_l,transposed", [(5, 1, 0), (3, 2, 0), (2, 2, 0), (2, 2, 1), (1, 1, 0), (7, 1, 0)])
+def test_conv_other_layers(K, s_l, transposed):
+    _run_conv(_cloud("tiny_neg"), K, s_l, transposed, 32, 64, torch.float16, relu=(K == 5))
+    _run_conv(_cloud("ragged"), K, s_l, transposed, 6, 10, torch.float32)
+
+
+def test_conv_selector_weight_checks_map_through_features():
+    """W_k = I for one offset: the output must be the gathered input rows exactly."""
+    c = _cloud("tiny")
+    desc = fit_desc(c, [(3, 1, 1)])
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, 3)
+    M = oracle.kernel_map(cs, cs, 3, 1)
+    F = synth.features(len(cs), 32, np.float16, seed=5)
+    Ft = torch.from_numpy(F).cuda()
+    for k in (0, 13, 22):
+        W = np.zeros((27, 32, 32), np.float16)
+        W[k] = np.eye(32, dtype=np.float16)
+        for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
+            y = B.spc_conv_forward(km, Ft, torch.from_numpy(W).cuda(), df).cpu().numpy()
+            ref = np.where(M[:, k:k + 1] >= 0, F[np.maximum(M[:, k], 0)], np.float16(0))
+            assert np.array_equal(y, ref)
+    km.destroy()
+
+
+def test_conv_os_is_bit_reproducible_and_ws_stable():
+    c = _cloud("rand_b3")
+    outs1, _ = _run_conv(c, 3, 1, 0, 64, 64, torch.float16, seed=7)
+    outs2, _ = _run_conv(c, 3, 1, 0, 64, 64, torch.float16, seed=7)
+    assert np.array_equal(outs1[B.DATAFLOW_OS], outs2[B.DATAFLOW_OS])
+    assert rel_err(outs1[B.DATAFLOW_WS], outs2[B.DATAFLOW_WS]) <= 1e-2
+
+
+def test_conv_strided_rows_concat_buffer():
+    """ld_in / ld_out: read from and write into column slices of wider buffers."""
+    c = _cloud("tiny")
+    desc = fit_desc(c, [(3, 1, 1)])
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, 3)
+    M = oracle.kernel_map(cs, cs, 3, 1)
+    n = len(cs)
+    wide_in = torch.from_numpy(synth.features(n, 96, np.float16, seed=8)).cuda()
+    W = torch.from_numpy(synth.weights(27, 32, 64, np.float16, seed=9)).cuda()
+    wide_out = torch.full((n, 160), 7.0, dtype=torch.float16, device="cuda")
+    fin = wide_in[:, 32:64]
+    for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
+        B.spc_conv_forward(km, fin, W, df, out=wide_out[:, 64:128])
+        ref = oracle.conv(M, fin.cpu().double().numpy(), W.cpu().double().numpy())
+        assert rel_err(wide_out[:, 64:128].cpu().double().numpy(), ref) <= 1e-2
+        assert bool((wide_out[:, :64] == 7).all()) and bool((wide_out[:, 128:] == 7).all())
+    km.destroy()
+
+
+def test_conv_bad_arguments():
+    c = _cloud("one")
+    desc = fit_desc(c, [(3, 1, 1)])
+    keys, _ = gpu_pack(c, desc)
+    km = B.spc_build_kmap(keys, desc, 3, layout=B.LAYOUT_OS)
+    F = torch.zeros((1, 16), dtype=torch.float16, device="cuda")
+    W = torch.zeros((27, 16, 16), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.SpcError) as e:
+        B.spc_conv_forward(km, F, W, B.DATAFLOW_WS)
+    assert e.value.code == B.ERR_ARG
+    km.destroy()
