@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""One-GPU benchmark of the SpC layer hot path (pack+sort -> feature-row permutation ->
+kernel-map build -> weight re-layout -> feature computation) on synthetic clouds.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--dataflow os|ws]
+
+A "step" is one pass of the whole path over one cloud, inputs already resident in HBM.
+Prints ONE JSON line (see the keys below); `value` is whole-path throughput in
+Mvoxel-offsets/s = |V_q| * K^3 / step time.  Per-phase numbers, the roofline of the
+dominant kernel and the CPU oracle timed on the host cores ride along.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16/bf16 MFMA
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
+PEAK_FP32_TFLOPS = 157.3
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
+    ap.add_argument("--dataflow", default="auto", choices=["auto", "os", "ws"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2511_20834_amd import binding as B
+    from paper_2511_20834_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    B.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    K, s_l, cin, cout = cfg["K"], cfg["layer_stride"], cfg["cin"], cfg["cout"]
+    K3 = K ** 3
+    tdt = {"f32": torch.float32, "f16": torch.float16}[cfg["dtype"]]
+    coords_np = synth.cloud(cfg["cloud"])
+    n = coords_np.shape[0]
+    F_np, W_np = synth.layer_tensors(args.config, n)
+    dataflow = {"os": B.DATAFLOW_OS, "ws": B.DATAFLOW_WS}.get(args.dataflow)
+    if dataflow is None:
+        dataflow = B.DATAFLOW_WS if args.config == 3 else B.DATAFLOW_OS
+    layout = B.LAYOUT_OS if dataflow == B.DATAFLOW_OS else B.LAYOUT_WS
+
+    lo, hi = coords_np[:, 1:].min(0), coords_np[:, 1:].max(0)
+    reach = ((K - 1) // 2) if K % 2 else (K - 1)
+    desc = B.spc_pack_desc_fit(lo, hi, int(coords_np[:, 0].max()) + 1, s_l, reach)
+
+    dev = torch.device("cuda:0")
+    coords = torch.from_numpy(coords_np).to(dev)
+    F_raw = torch.from_numpy(F_np).to(dev)
+    W = torch.from_numpy(W_np).to(dev)
+    ws = torch.empty(B.spc_pack_workspace_bytes(n, desc), dtype=torch.uint8, device=dev)
+    keys = torch.empty(n, dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device=dev)
+    perm = torch.empty(n, dtype=torch.int32, device=dev)
+    F = torch.empty_like(F_raw)
+    use_packed = tdt != torch.float32 and cin % 16 == 0 and cout in (32, 64, 128, 256)
+    Wp = torch.empty_like(W)
+
+    # sizes that only exist after a first build (strided layers produce |V_q| on the device)
+    B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+    km0 = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout)
+    n_out = km0.n_out
+    nnz = int(km0.nnz().sum())
+    km0.destroy()
+    out = torch.empty((n_out, cout), dtype=tdt, device=dev)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    phases = ("pack_sort", "permute", "kmap_build", "weights", "conv")
+
+    def step(marks=None):
+        if marks is not None:
+            marks[0].record()
+        B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+        if marks is not None:
+            marks[1].record()
+        B.spc_permute_rows(F_raw, perm, F)
+        if marks is not None:
+            marks[2].record()
+        km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout)
+        if marks is not None:
+            marks[3].record()
+        if use_packed:
+            B.spc_conv_prepare_weights(W, Wp)
+        if marks is not None:
+            marks[4].record()
+        B.spc_conv_forward(km, F, Wp if use_packed else W, dataflow, B.CONV_PACKED_WEIGHTS if use_packed else 0, out=out)
+        if marks is not None:
+            marks[5].record()
+        km.destroy()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps, no per-phase events inside
+    t0 = time.perf_counter()
+    e_start, e_end = ev(), ev()
+    e_start.record()
+    for _ in range(args.steps):
+        step()
+    e_end.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = max(e_start.elapsed_time(e_end), 0.0) / args.steps
+    ms_per_step_wall = wall * 1e3 / args.steps
+
+    # ---- per-phase durations (separate pass: events between the calls, same stream)
+    n_prof = min(args.steps, 50)
+    marks = [[ev() for _ in range(6)] for _ in range(n_prof)]
+    for i in range(n_prof):
+        step(marks[i])
+    torch.cuda.synchronize()
+    phase_ms = {p: float(np.mean([marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(n_prof)]))
+                for j, p in enumerate(phases)}
+
+    voxel_offsets = n_out * K3
+    flops = 2.0 * nnz * cin * cout
+    value = voxel_offsets / (ms_per_step * 1e-3) / 1e6
+    conv_tflops = flops / (phase_ms["conv"] * 1e-3) / 1e12
+    key_b = desc.key_bits // 8
+    if layout == B.LAYOUT_OS:
+        map_bytes = n * key_b + n_out * key_b + n_out * K3 * 4
+    else:
+        map_bytes = n * key_b + n_out * key_b + nnz * 8 + K3 * 4
+    kmap_gbs = map_bytes / (phase_ms["kmap_build"] * 1e-3) / 1e9
+    if tdt == torch.float32:
+        roof = {"kernel": "conv_%s_simple_kernel" % ("os" if dataflow == B.DATAFLOW_OS else "ws"), "bound": "alu",
+                "achieved": conv_tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+                "frac": conv_tflops / PEAK_FP32_TFLOPS, "traffic": None}
+    else:
+        roof = {"kernel": "conv_%s_mfma_kernel" % ("os" if dataflow == B.DATAFLOW_OS else "ws"), "bound": "mfma",
+                "achieved": conv_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                "frac": conv_tflops / PEAK_MFMA_F16_TFLOPS, "traffic": None}
+
+    result = {
+        "metric": "SpC layer hot path (pack+sort, kmap build, feature computation) Mvoxel-offsets/s",
+        "value": value, "unit": "Mvoxel-offsets/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "ms_per_step_wall": ms_per_step_wall, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": "cfg%d: %s cloud, %d voxels -> %d outputs, K=%d, layer stride %d, C %d->%d, %s, dataflow %s"
+                   % (args.config, cfg["cloud"], n, n_out, K, s_l, cin, cout, cfg["dtype"],
+                      "OS" if dataflow == B.DATAFLOW_OS else "WS"),
+                   "n_voxels": n, "n_out": n_out, "K": K, "cin": cin, "cout": cout, "nnz": nnz,
+                   "key_bits": desc.key_bits},
+        "parts": {"phase_ms": phase_ms,
+                  "kmap_build_Mvoxel_offsets_per_s": voxel_offsets / (phase_ms["kmap_build"] * 1e-3) / 1e6,
+                  "kmap_build_algorithmic_GBps": kmap_gbs, "kmap_build_frac_of_hbm_peak": kmap_gbs / PEAK_HBM_GBS,
+                  "conv_useful_TFLOPs": conv_tflops, "conv_frac_of_mfma_peak": conv_tflops / PEAK_MFMA_F16_TFLOPS},
+        "roofline": roof,
+    }
+
+    if not args.no_check:
+        import oracle
+        cs, operm = oracle.sort_coords(coords_np)
+        oc, M = oracle.layer(cs, K, 1, s_l)
+        rows = np.random.default_rng(0).choice(n_out, size=min(n_out, 512), replace=False)
+        ref = oracle.conv(M[rows], F_np[operm].astype(np.float64), W_np.astype(np.float64))
+        got = out[torch.from_numpy(rows).to(dev)].cpu().double().numpy()
+        err = float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+        result["check"] = {"rows": int(len(rows)), "max_rel_err": err, "ok": bool(err <= (1e-5 if tdt == torch.float32 else 1e-2))}
+
+    if not args.no_cpu_baseline:
+        import oracle
+        F64, W64 = F_np.astype(np.float64), W_np.astype(np.float64)
+        best = None
+        t_all = time.perf_counter()
+        reps = 0
+        while reps < 3 or (time.perf_counter() - t_all < 10.0 and reps < 20):
+            t = time.perf_counter()
+            cs, operm = oracle.sort_coords(coords_np)
+            oc, M = oracle.layer(cs, K, 1, s_l)
+            oracle.conv(M, F64[operm], W64)
+            dt = time.perf_counter() - t
+            best = dt if best is None else min(best, dt)
+            reps += 1
+        result["cpu_baseline"] = {"value": len(oc) * K3 / best / 1e6, "unit": "Mvoxel-offsets/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": "whole workload (sort + hash-map kernel map + fp64 features), best of %d runs" % reps,
+                                  "seconds": best}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

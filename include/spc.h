@@ -52,6 +52,7 @@ extern "C" {
 
 #define SPC_PACK_VALIDATE 1 /* spc_pack_coords: check ranges and duplicates, wait, report */
 #define SPC_CONV_RELU 1     /* spc_conv_forward: apply max(x,0) before the output is stored */
+#define SPC_CONV_PACKED_WEIGHTS 2 /* spc_conv_forward: `weights` came from spc_conv_prepare_weights */
 #define SPC_NET_SEQUENTIAL 1 /* spc_build_kmaps_network: one stream, level by level (for comparison) */
 
 /*
@@ -187,6 +188,24 @@ void spc_kmap_destroy(spc_kmap* m);
 int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
                      int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t dataflow,
                      int32_t flags, void* stream);
+
+/*
+ * Weights are constant during inference, so their re-layout into MFMA operand order can
+ * be hoisted out of the layer call.  Writes K^3*cin*cout elements to packed_out [device]
+ * (same dtype) for use with SPC_CONV_PACKED_WEIGHTS.  Returns SPC_ERR_UNSUPPORTED for the
+ * shapes/dtypes that do not run on the MFMA kernels (fp32, cin % 16 != 0, cout not in
+ * {32,64,128,256}); those layers take the plain [K^3][cin][cout] weights only.
+ */
+int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32_t cin, int32_t cout, int32_t dtype,
+                             void* packed_out, void* stream);
+
+/*
+ * Row gather used once per cloud after spc_pack_coords (Section 5.2: one initial sort):
+ * dst[r, :] = src[perm[r], :] for r < n; rows of `row_bytes` bytes (a multiple of 4), row
+ * pitches in bytes.  All pointers [device].
+ */
+int spc_permute_rows(const void* src, int64_t src_pitch, const int32_t* perm, int64_t n, int64_t row_bytes,
+                     void* dst, int64_t dst_pitch, void* stream);
 
 /* Releases the library's cached device blocks (maps still alive keep theirs). Waits for the device. */
 int spc_release_cache(void);

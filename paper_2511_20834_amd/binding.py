@@ -20,6 +20,7 @@ LAYOUT_OS, LAYOUT_WS, LAYOUT_BOTH = 1, 2, 3
 DATAFLOW_OS, DATAFLOW_WS = 0, 1
 PACK_VALIDATE = 1
 CONV_RELU = 1
+CONV_PACKED_WEIGHTS = 2
 NET_SEQUENTIAL = 1
 ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -4, -5, -6
 
@@ -27,6 +28,7 @@ EXPORTS = [
     "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
     "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_export_triples", "spc_kmap_destroy", "spc_conv_forward",
+    "spc_conv_prepare_weights", "spc_permute_rows",
     "spc_release_cache", "spc_last_error", "spc_version",
 ]
 
@@ -83,6 +85,8 @@ def lib():
         L.spc_kmap_destroy.argtypes = [vp]
         L.spc_kmap_destroy.restype = None
         L.spc_conv_forward.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+        L.spc_conv_prepare_weights.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.spc_permute_rows.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp]
         L.spc_last_error.restype = ctypes.c_char_p
         L.spc_version.restype = ctypes.c_char_p
         _lib = L
@@ -119,18 +123,28 @@ def spc_pack_desc_fit(lo, hi, n_batch: int = 1, max_stride: int = 1, max_reach: 
     return d
 
 
+def spc_pack_workspace_bytes(n: int, desc: PackDesc) -> int:
+    need = ctypes.c_size_t(0)
+    _check(lib().spc_pack_coords(None, n, ctypes.byref(desc), None, None, None, ctypes.byref(need), 0, None))
+    return int(need.value)
+
+
 def spc_pack_coords(coords: torch.Tensor, desc: PackDesc, want_perm: bool = True, flags: int = 0, stream=None,
-                    workspace: torch.Tensor | None = None):
+                    workspace: torch.Tensor | None = None, keys_out: torch.Tensor | None = None,
+                    perm_out: torch.Tensor | None = None):
     """coords: int32 [N,4] device tensor (b,x,y,z).  Returns (keys, perm): sorted packed keys
     (int32/int64 tensors holding the unsigned bit patterns) and the permutation (or None)."""
     assert coords.dtype == torch.int32 and coords.dim() == 2 and coords.shape[1] == 4
     n = coords.shape[0]
-    need = ctypes.c_size_t(0)
-    _check(lib().spc_pack_coords(None, n, ctypes.byref(desc), None, None, None, ctypes.byref(need), flags, None))
-    if workspace is None or workspace.numel() < need.value:
-        workspace = torch.empty(need.value, dtype=torch.uint8, device=coords.device)
-    keys = torch.empty(n, dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device=coords.device)
-    perm = torch.empty(n, dtype=torch.int32, device=coords.device) if want_perm else None
+    if workspace is None:
+        workspace = torch.empty(spc_pack_workspace_bytes(n, desc), dtype=torch.uint8, device=coords.device)
+    kdt = torch.int32 if desc.key_bits == 32 else torch.int64
+    keys = keys_out if keys_out is not None else torch.empty(n, dtype=kdt, device=coords.device)
+    assert keys.dtype == kdt and keys.numel() == n
+    perm = None
+    if want_perm:
+        perm = perm_out if perm_out is not None else torch.empty(n, dtype=torch.int32, device=coords.device)
+        assert perm.dtype == torch.int32 and perm.numel() == n
     size = ctypes.c_size_t(workspace.numel())
     _check(lib().spc_pack_coords(_dev_ptr(coords), n, ctypes.byref(desc), _dev_ptr(keys),
                                  _dev_ptr(perm) if want_perm else None, _dev_ptr(workspace), ctypes.byref(size), flags,
@@ -236,6 +250,27 @@ def spc_conv_forward(kmap: KMap, feats_in: torch.Tensor, weights: torch.Tensor, 
     assert out.dim() == 2 and out.stride(1) == 1 and out.shape[1] == cout and out.dtype == feats_in.dtype
     _check(lib().spc_conv_forward(kmap.handle, feats_in.data_ptr(), feats_in.stride(0), weights.data_ptr(), out.data_ptr(),
                                   out.stride(0), cin, cout, _TORCH_DTYPE[feats_in.dtype], dataflow, flags, _stream(stream)))
+    return out
+
+
+def spc_conv_prepare_weights(weights: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """weights [K^3, cin, cout] fp16/bf16 -> the MFMA operand layout expected with CONV_PACKED_WEIGHTS."""
+    assert weights.is_cuda and weights.is_contiguous() and weights.dim() == 3 and weights.dtype in _TORCH_DTYPE
+    if out is None:
+        out = torch.empty_like(weights)
+    _check(lib().spc_conv_prepare_weights(weights.data_ptr(), weights.shape[0], weights.shape[1], weights.shape[2],
+                                          _TORCH_DTYPE[weights.dtype], out.data_ptr(), _stream(stream)))
+    return out
+
+
+def spc_permute_rows(src: torch.Tensor, perm: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """out[r] = src[perm[r]] (feature rows into sorted-voxel order)."""
+    assert src.is_cuda and src.dim() == 2 and src.stride(1) == 1 and perm.dtype == torch.int32
+    if out is None:
+        out = torch.empty((perm.shape[0], src.shape[1]), dtype=src.dtype, device=src.device)
+    es = src.element_size()
+    _check(lib().spc_permute_rows(src.data_ptr(), src.stride(0) * es, perm.data_ptr(), perm.shape[0], src.shape[1] * es,
+                                  out.data_ptr(), out.stride(0) * es, _stream(stream)))
     return out
 
 

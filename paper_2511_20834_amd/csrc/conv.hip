@@ -279,6 +279,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
 
 // ---------------------------------------------------------------- dispatch
 struct ConvArgs {
+  int packed;
   spc_kmap* m;
   const void* F;
   int64_t ld_in;
@@ -320,26 +321,35 @@ static int conv_typed(const ConvArgs& a, bool allow_mfma) {
     if (n4 > 0) hipLaunchKernelGGL(zero_f32_kernel, dim3((n4 + 255) / 256), dim3(256), 0, a.s, reinterpret_cast<float4*>(accum), n4);
   }
   int rc = SPC_OK;
+  if (a.packed && !(allow_mfma && a.cin % 16 == 0 && (a.cout == 32 || a.cout == 64 || a.cout == 128 || a.cout == 256)))
+    return set_error(SPC_ERR_ARG, "packed weights given for a shape the MFMA kernels do not run");
+  if (a.packed && (a.ld_in % 8 != 0 || reinterpret_cast<uintptr_t>(a.F) % 16 != 0))
+    return set_error(SPC_ERR_ARG, "packed weights need 16-byte aligned feature rows");
   const bool mfma_ok = allow_mfma && a.cin % 16 == 0 && (a.cout == 32 || a.cout == 64 || a.cout == 128 || a.cout == 256) &&
                        a.ld_in % 8 == 0 && (reinterpret_cast<uintptr_t>(a.F) % 16 == 0);
   if (a.rows_cap > 0) {
     if constexpr (!std::is_same<T, float>::value) {
      if (mfma_ok) {
-      T* Wp = static_cast<T*>(pool_alloc(size_t(K3) * a.cin * a.cout * sizeof(T)));
-      if (!Wp) {
-        pool_free(accum);
-        return SPC_ERR_NOMEM;
+      const T* Wp = static_cast<const T*>(a.W);
+      T* Wtmp = nullptr;
+      if (!a.packed) {
+        Wtmp = static_cast<T*>(pool_alloc(size_t(K3) * a.cin * a.cout * sizeof(T)));
+        if (!Wtmp) {
+          pool_free(accum);
+          return SPC_ERR_NOMEM;
+        }
+        const int64_t total = int64_t(K3) * (a.cin / 16) * (a.cout / 32) * 64;
+        hipLaunchKernelGGL(prepack_weights_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, a.s, static_cast<const T*>(a.W),
+                           Wtmp, K3, a.cin, a.cout);
+        Wp = Wtmp;
       }
-      const int64_t total = int64_t(K3) * (a.cin / 16) * (a.cout / 32) * 64;
-      hipLaunchKernelGGL(prepack_weights_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, a.s, static_cast<const T*>(a.W), Wp,
-                         K3, a.cin, a.cout);
       switch (a.cout) {
         case 32: launch_mfma<T, 1, 2>(a, Wp, accum); break;
         case 64: launch_mfma<T, 2, 2>(a, Wp, accum); break;
         case 128: launch_mfma<T, 4, 1>(a, Wp, accum); break;
         case 256: launch_mfma<T, 8, 1>(a, Wp, accum); break;
       }
-      pool_free(Wp);  // reuse is ordered behind this stream's work
+      pool_free(Wtmp);  // reuse is ordered behind this stream's work
      }
     }
     if (mfma_ok) {
@@ -384,6 +394,7 @@ extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in
   a.cin = cin;
   a.cout = cout;
   a.relu = (flags & SPC_CONV_RELU) ? 1 : 0;
+  a.packed = (flags & SPC_CONV_PACKED_WEIGHTS) ? 1 : 0;
   a.dataflow = dataflow;
   const Level* ol = m->out_level;
   a.n_out_h = static_cast<int>(ol->n_host < 0 ? 0 : ol->n_host);
@@ -396,4 +407,45 @@ extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in
     case SPC_DTYPE_F32: return conv_typed<float>(a, false);
   }
   return set_error(SPC_ERR_ARG, "bad dtype");
+}
+
+extern "C" int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32_t cin, int32_t cout, int32_t dtype,
+                                        void* packed_out, void* stream) {
+  using namespace spc;
+  if (!weights || !packed_out || kvol < 1) return set_error(SPC_ERR_ARG, "NULL argument or kvol < 1");
+  if ((dtype != SPC_DTYPE_F16 && dtype != SPC_DTYPE_BF16) || cin < 16 || cin % 16 != 0 ||
+      !(cout == 32 || cout == 64 || cout == 128 || cout == 256))
+    return set_error(SPC_ERR_UNSUPPORTED, "no MFMA kernel for dtype %d, cin %d, cout %d", dtype, cin, cout);
+  const int64_t total = int64_t(kvol) * (cin / 16) * (cout / 32) * 64;
+  // both 16-bit types move as raw 2-byte elements
+  hipLaunchKernelGGL(prepack_weights_kernel<_Float16>, dim3((total + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const _Float16*>(weights), static_cast<_Float16*>(packed_out), kvol, cin, cout);
+  SPC_HIP_CHECK(hipGetLastError());
+  return SPC_OK;
+}
+
+namespace spc {
+__global__ __launch_bounds__(256) void permute_rows_kernel(const uint32_t* __restrict__ src, int64_t src_pitch_w,
+                                                           const int32_t* __restrict__ perm, int64_t n, int row_w,
+                                                           uint32_t* __restrict__ dst, int64_t dst_pitch_w) {
+  const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  const int64_t r = gid / row_w;
+  const int w = static_cast<int>(gid - r * row_w);
+  if (r < n) dst[r * dst_pitch_w + w] = src[int64_t(perm[r]) * src_pitch_w + w];
+}
+}  // namespace spc
+
+extern "C" int spc_permute_rows(const void* src, int64_t src_pitch, const int32_t* perm, int64_t n, int64_t row_bytes, void* dst,
+                                int64_t dst_pitch, void* stream) {
+  using namespace spc;
+  if (!src || !perm || !dst) return set_error(SPC_ERR_ARG, "NULL argument");
+  if (n < 0 || row_bytes < 4 || row_bytes % 4 || src_pitch % 4 || dst_pitch % 4 || src_pitch < row_bytes || dst_pitch < row_bytes)
+    return set_error(SPC_ERR_ARG, "rows and pitches must be multiples of 4 bytes, pitch >= row");
+  const int64_t total = n * (row_bytes / 4);
+  if (total > 0)
+    hipLaunchKernelGGL(permute_rows_kernel, dim3((total + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint32_t*>(src), src_pitch / 4, perm, n, static_cast<int>(row_bytes / 4),
+                       static_cast<uint32_t*>(dst), dst_pitch / 4);
+  SPC_HIP_CHECK(hipGetLastError());
+  return SPC_OK;
 }

@@ -1,0 +1,55 @@
+"""Parity at the full sizes of the benchmark configurations (single layers 0-3),
+through the same calls and launch configuration bench.py times."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_20834_amd import binding as B
+from paper_2511_20834_amd import synth
+
+from gpu_common import oracle_keys, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_config_full_size(cfg):
+    c = synth.CONFIGS[cfg]
+    K, s_l, cin, cout = c["K"], c["layer_stride"], c["cin"], c["cout"]
+    coords = synth.cloud(c["cloud"])
+    n = len(coords)
+    F, W = synth.layer_tensors(cfg, n)
+    reach = (K - 1) // 2
+    desc = B.spc_pack_desc_fit(coords[:, 1:].min(0), coords[:, 1:].max(0), int(coords[:, 0].max()) + 1, s_l, reach)
+    assert desc.key_bits == 32
+    keys, perm = B.spc_pack_coords(torch.from_numpy(coords).cuda(), desc, True, B.PACK_VALIDATE)
+    cs, operm = oracle.sort_coords(coords)
+    assert np.array_equal(perm.cpu().numpy(), operm)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_BOTH)
+    oc, M = oracle.layer(cs, K, 1, s_l)
+    assert km.n_out == len(oc)
+    assert np.array_equal(km.out_keys(), oracle_keys(oc, desc))
+    ref_t = oracle.triples(M)
+    assert np.array_equal(km.export_triples(B.LAYOUT_OS), ref_t)
+    assert np.array_equal(km.export_triples(B.LAYOUT_WS), ref_t)
+    Fs = B.spc_permute_rows(torch.from_numpy(F).cuda(), perm)
+    assert np.array_equal(Fs.cpu().numpy(), F[operm])
+    Wt = torch.from_numpy(W).cuda()
+    ref = oracle.conv(M, F[operm].astype(np.float64), W.astype(np.float64))
+    tol = 1e-5 if c["dtype"] == "f32" else 1e-2
+    packed = B.spc_conv_prepare_weights(Wt) if c["dtype"] != "f32" else None
+    for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
+        y = B.spc_conv_forward(km, Fs, Wt, df).cpu().double().numpy()
+        err = rel_err(y, ref)
+        assert err <= tol, (cfg, df, err)
+        # element-wise form: |y - yhat| <= tol * (|yhat| + rms(yhat)) everywhere
+        rms = np.sqrt((ref ** 2).mean())
+        assert np.all(np.abs(y - ref) <= tol * (np.abs(ref) + rms))
+        if packed is not None:
+            y2 = B.spc_conv_forward(km, Fs, packed, df, B.CONV_PACKED_WEIGHTS).cpu().double().numpy()
+            if df == B.DATAFLOW_OS:
+                assert np.array_equal(y2, y)
+            else:
+                assert rel_err(y2, ref) <= tol
+    km.destroy()
