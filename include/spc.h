@@ -154,7 +154,10 @@ const void* spc_kmap_in_keys(const spc_kmap* m);
 /* Copies the n_out sorted output keys to keys_host [host] (uint32 or uint64 per key_bits; `cap`
  * keys of room).  Waits for the build. */
 int spc_kmap_copy_out_keys(spc_kmap* m, void* keys_host, int64_t cap);
-/* [device] OS layout: int32 [n_out][K^3], NULL if not built. */
+/* [device] OS layout, NULL if not built.  The |V_q| x K^3 matrix is stored in blocks of 32
+ * consecutive output voxels, offset-major inside a block: entry (i, k) sits at
+ * ((i/32)*K^3 + k)*32 + i%32, so the 32 entries an MFMA row block needs for one offset are one
+ * 128-byte line.  Rows past n_out in the last block hold -1. */
 const int32_t* spc_kmap_os_map(const spc_kmap* m);
 /* [device] WS layout: list k occupies entries [k*ws_stride, k*ws_stride + nnz[k]) of both
  * arrays, ordered by ascending output index; *nnz_dev [device] int32[K^3].  NULL if not built. */

@@ -8,8 +8,8 @@
 // one 16-byte load, so no LDS round trip is needed for them.  The weight slice W_k is
 // re-laid once per call into B-operand order and staged through LDS, where all waves
 // of the workgroup read it with conflict-free 16-byte loads.
-// OS skips an offset for a whole workgroup tile (and a wave skips its MFMAs) when no
-// row has a valid entry — outputs are spatially sorted, so emptiness is coherent.
+// OS skips an offset for a 32-row block when no row has a valid entry — outputs are
+// spatially sorted, so emptiness is coherent (the map builder records it per block).
 // fp32 (and channel counts the MFMA tiling does not cover) use plain FMA kernels.
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
@@ -105,22 +105,104 @@ __device__ inline void contract_offset(const T* __restrict__ F, int64_t ld_in, c
   }
 }
 
-// Output-stationary: workgroup = 4 waves x RB blocks of 32 consecutive output voxels.
-template <typename T, int NB, int RB>
-__global__ __launch_bounds__(CONV_THREADS) void conv_os_mfma_kernel(const int32_t* __restrict__ M, int n_out_h,
-                                                                    const int* __restrict__ n_out_d, int K3,
-                                                                    const T* __restrict__ F, int64_t ld_in,
-                                                                    const T* __restrict__ Wp, T* __restrict__ out,
-                                                                    int64_t ld_out, int cin, int relu) {
+// Output-stationary kernel: waves are autonomous, weights are staged through LDS in phases.
+//
+// A workgroup of WAVES waves walks the weight tensor once, in phases of up to HALF_BYTES.
+// The phases alternate between two halves of the LDS buffer: while a phase is being
+// consumed, every thread already holds its share of the next phase in registers (loaded
+// before the compute started) and drops it into the other half afterwards — one barrier
+// per phase, and the L2 latency of the weights is off the critical path.
+// Each wave owns RB adjacent blocks of 32 consecutive output voxels and processes — on its
+// own, without further synchronisation — those of its steps whose weights are resident.
+// A step is one offset k with at least one valid row in the wave's blocks (the map
+// builder's block masks say which) and one chunk of CKS input channels:
+//   A operand: 32 gathered feature rows per block, straight from global memory into
+//              registers (lane l reads 16 bytes: channels 8*(l/32)..+7 of row l%32 per
+//              16-channel slab), kept in a ring of D buffers so that D-1 gathers are in
+//              flight behind the one being multiplied; rows without an input voxel gather
+//              from a zero row (selecting the address, not the data, keeps the loaded
+//              registers untouched until use, so nothing waits on a prefetch);
+//   B operand: 16-byte conflict-free LDS reads, each reused for the RB blocks;
+//   MFMA 32x32x16 into fp32 accumulators that stay in registers for the whole kernel
+//   (no atomics; the offset order is ascending, so results are bit-reproducible).
+// Blocks are dealt to workgroups round-robin inside an XCD-contiguous range: a workgroup's
+// waves sit in different parts of the cloud (dense and sparse regions mix, which balances
+// the CUs), while neighbouring blocks, which gather the same feature rows, run on the same
+// XCD and share its L2.
+constexpr int HALF_BYTES = 72 * 1024;  // 9 offsets of 64x64 fp16: one x-slab of a 3x3x3 kernel per phase
+constexpr int KLIST_CAP = 352;  // >= 7^3
+__device__ __align__(16) uint32_t g_zero_row[64];  // zero-initialised, never written
+
+template <typename T, int NB, int RB, int WAVES, int NKK, int D>
+__global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t* __restrict__ M,
+                                                                   const uint32_t* __restrict__ block_masks,
+                                                                   int mask_words, int n_out_h,
+                                                                   const int* __restrict__ n_out_d, int K3,
+                                                                   const T* __restrict__ F, int64_t ld_in,
+                                                                   const T* __restrict__ Wp, T* __restrict__ out,
+                                                                   int64_t ld_out, int cin, int relu, int chunks_per_phase,
+                                                                   int n_wg_per_xcd) {
   using V8 = typename Mfma<T>::V8;
-  constexpr int WROWS = 32 * RB, TROWS = 4 * WROWS;
+  constexpr int CKS = 16 * NKK;
+  constexpr int THREADS = 64 * WAVES;
+  constexpr int cout = NB * 32;
+  constexpr int SV = HALF_BYTES / 16 / THREADS;  // staging vectors per thread per phase
   extern __shared__ __align__(16) unsigned char smem[];
-  V8* sB = reinterpret_cast<V8*>(smem);
+  V8* sW = reinterpret_cast<V8*>(smem);
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int16_t* klist = reinterpret_cast<int16_t*>(smem + 2 * HALF_BYTES) + wave * KLIST_CAP;
   const int n_out = n_out_d ? *n_out_d : n_out_h;
-  const int i0 = blockIdx.x * TROWS;
-  if (i0 >= n_out) return;
-  const int rows = min(TROWS, n_out - i0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lh = lane >> 5;
+  const int64_t n_blocks = (int64_t(n_out) + 31) >> 5;
+  // tile = RB adjacent blocks; tile t -> (XCD range, workgroup within the XCD, wave)
+  const int n_wg = n_wg_per_xcd * 8;
+  const int wg = (blockIdx.x & 7) * n_wg_per_xcd + (blockIdx.x >> 3);
+  const int64_t n_tiles = (n_blocks + RB - 1) / RB;
+  const int64_t tiles_per_xcd = (n_tiles + 7) / 8;
+  const int xcd = wg / n_wg_per_xcd, wg_in_xcd = wg - xcd * n_wg_per_xcd;
+  const int64_t t_in_xcd = int64_t(wave) * n_wg_per_xcd + wg_in_xcd;
+  const int64_t tile = xcd * tiles_per_xcd + t_in_xcd;
+  const bool active = t_in_xcd < tiles_per_xcd && tile < n_tiles;
+  const int64_t blk0 = tile * RB;
+  const int nch = cin / CKS;
+  (void)n_wg;
+
+  // phase 0 of the weights is requested first, so that its latency overlaps the set-up below
+  const int n_chunks = K3 * nch;
+  V8 st[SV];
+  auto stage_load = [&](int c_lo) {
+    const int hi = min(n_chunks, c_lo + chunks_per_phase);
+    const int n_vec = static_cast<int>(int64_t(hi - c_lo) * CKS * cout / 8);
+    const V8* src = reinterpret_cast<const V8*>(Wp + int64_t(c_lo) * CKS * cout);
+#pragma unroll
+    for (int i = 0; i < SV; ++i) st[i] = src[min(i * THREADS + tid, n_vec - 1)];
+  };
+  auto stage_store = [&](int c_lo, V8* half) {
+    const int hi = min(n_chunks, c_lo + chunks_per_phase);
+    const int n_vec = static_cast<int>(int64_t(hi - c_lo) * CKS * cout / 8);
+#pragma unroll
+    for (int i = 0; i < SV; ++i)
+      if (i * THREADS + tid < n_vec) half[i * THREADS + tid] = st[i];
+  };
+  stage_load(0);
+
+  // offsets present in this wave's blocks, ascending
+  int nk = 0;
+  if (active) {
+    for (int wd = 0; wd < mask_words; ++wd) {
+      unsigned m = 0;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        if (blk0 + rb < n_blocks) m |= block_masks[(blk0 + rb) * mask_words + wd];
+      const bool bit = lane < 32 && ((m >> lane) & 1u);
+      const unsigned long long bal = __ballot(bit);
+      if (bit) klist[nk + __builtin_amdgcn_mbcnt_lo(unsigned(bal), 0)] = static_cast<int16_t>(wd * 32 + lane);
+      nk += __popcll(bal);
+    }
+  }
+  nk = __builtin_amdgcn_readfirstlane(nk);
+  __builtin_amdgcn_wave_barrier();
+
   floatx16 acc[RB][NB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
@@ -128,35 +210,152 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_os_mfma_kernel(const int32_
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
-  const int cout = NB * 32;
-  const int64_t w_stride = int64_t(cin) * cout;
-  for (int k = 0; k < K3; ++k) {
-    int idx[RB];
-    bool has = false;
+
+  // A position is (index into klist, channel chunk); positions past the end are clamped so that
+  // the pipeline issues the same loads every step (the surplus ones are never consumed).
+  struct Pos {
+    int ki, ch;
+  };
+  auto advance = [&](Pos& p) {
+    if (++p.ch == nch) {
+      p.ch = 0;
+      ++p.ki;
+    }
+  };
+  auto k_at = [&](const Pos& p) -> int {
+    return nk > 0 ? __builtin_amdgcn_readfirstlane(int(klist[min(p.ki, nk - 1)])) : 0;
+  };
+  // a block past the end (odd tail) reads block 0's map rows; its results are never stored
+  const int32_t* Mb[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) Mb[rb] = M + ((active && blk0 + rb < n_blocks) ? blk0 + rb : 0) * int64_t(K3) * 32 + lr;
+  auto load_idx = [&](const Pos& p, int (&dst)[RB]) {
+    const int k32 = k_at(p) * 32;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) dst[rb] = Mb[rb][k32];
+  };
+  const T* zero_row = reinterpret_cast<const T*>(g_zero_row) + 8 * lh;
+  auto gather = [&](const Pos& p, const int (&j)[RB], V8 (&dst)[RB][NKK]) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      const int r = wave * WROWS + rb * 32 + lr;
-      idx[rb] = r < rows ? M[int64_t(i0 + r) * K3 + k] : -1;
-      has |= idx[rb] >= 0;
+      const T* src = j[rb] < 0 ? zero_row : F + int64_t(j[rb]) * ld_in + p.ch * CKS + 8 * lh;
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) dst[rb][kk] = *reinterpret_cast<const V8*>(src + kk * 16);
     }
-    if (!__syncthreads_or(has)) continue;  // nobody in the tile has this offset
-    const bool wave_has = __ballot(has) != 0ull;
-    contract_offset<T, NB, RB>(F, ld_in, Wp + k * w_stride, cin, idx, wave_has, sB, acc);
+  };
+
+  // ring of D A-operand buffers: step u lives in buffer u % D and is refilled, once consumed,
+  // with step u + D; jj[b] holds the map indices for that refill, themselves loaded D steps earlier
+  V8 a[D][RB][NKK];
+  int jj[D][RB];
+  Pos pc{0, 0};  // current step
+  Pos pg{0, 0};  // next step to gather
+  Pos pi{0, 0};  // next step whose map indices are loaded
+#pragma unroll
+  for (int b = 0; b < D; ++b) {
+    load_idx(pg, jj[b]);
+    gather(pg, jj[b], a[b]);
+    advance(pg);
+  }
+  pi = pg;
+#pragma unroll
+  for (int b = 0; b < D; ++b) {
+    load_idx(pi, jj[b]);
+    advance(pi);
+  }
+
+  int c_hi = 0;
+  int64_t e_lo = 0;
+  const V8* sWp = sW;  // LDS half of the current phase
+  int k_cur = k_at(pc);
+  auto can_step = [&]() -> bool { return pc.ki < nk && k_cur * nch + pc.ch < c_hi; };
+  auto step = [&](auto B_) {
+    constexpr int B = decltype(B_)::value;
+    const V8* Bk = sWp + ((int64_t(k_cur) * cin + pc.ch * CKS) * cout - e_lo) / 8 + lane;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      V8 bw[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) bw[nb] = Bk[(kk * NB + nb) * 64];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) acc[rb][nb] = Mfma<T>::mma(a[B][rb][kk], bw[nb], acc[rb][nb]);
+    }
+    gather(pg, jj[B], a[B]);
+    advance(pg);
+    load_idx(pi, jj[B]);
+    advance(pi);
+    advance(pc);
+    k_cur = k_at(pc);
+  };
+  auto rotate_ring = [&]() {  // buffer 1 becomes buffer 0 (used when a phase ends off-phase; rare)
+    V8 t[RB][NKK];
+    int tj[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      tj[rb] = jj[0][rb];
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) t[rb][kk] = a[0][rb][kk];
+    }
+#pragma unroll
+    for (int b = 0; b + 1 < D; ++b)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        jj[b][rb] = jj[b + 1][rb];
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) a[b][rb][kk] = a[b + 1][rb][kk];
+      }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      jj[D - 1][rb] = tj[rb];
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) a[D - 1][rb][kk] = t[rb][kk];
+    }
+  };
+
+  stage_store(0, sW);
+  __syncthreads();
+  int half = 0;
+  for (int c_lo = 0; c_lo < n_chunks; c_lo += chunks_per_phase) {
+    c_hi = min(n_chunks, c_lo + chunks_per_phase);
+    e_lo = int64_t(c_lo) * CKS * cout;
+    sWp = sW + half * (HALF_BYTES / 16);
+    const bool more = c_hi < n_chunks;
+    if (more) stage_load(c_hi);
+    for (;;) {  // the current step always sits in buffer 0 here
+      if (!can_step()) break;
+      step(std::integral_constant<int, 0>{});
+      if (!can_step()) { rotate_ring(); break; }
+      step(std::integral_constant<int, 1>{});
+      if constexpr (D == 3) {
+        if (!can_step()) { rotate_ring(); rotate_ring(); break; }
+        step(std::integral_constant<int, 2>{});
+      }
+    }
+    half ^= 1;
+    if (more) stage_store(c_hi, sW + half * (HALF_BYTES / 16));
+    __syncthreads();  // next phase visible; everybody is done with the half it will overwrite next
   }
   // D layout of the 32x32 MFMA: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+  if (active) {
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+    for (int rb = 0; rb < RB; ++rb) {
+      const int64_t i0 = (blk0 + rb) * 32;
+      const int rows = static_cast<int>(max<int64_t>(0, min<int64_t>(32, n_out - i0)));
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = wave * WROWS + rb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-        if (row < rows) {
-          float v = acc[rb][nb][r];
-          if (relu) v = fmaxf(v, 0.f);
-          out[int64_t(i0 + row) * ld_out + nb * 32 + lr] = from_f32<T>(v);
+        for (int r = 0; r < 16; ++r) {
+          const int row = 8 * (r / 4) + 4 * lh + (r % 4);
+          if (row < rows) {
+            float v = acc[rb][nb][r];
+            if (relu) v = fmaxf(v, 0.f);
+            out[(i0 + row) * ld_out + nb * 32 + lr] = from_f32<T>(v);
+          }
         }
-      }
+    }
+  }
 }
 
 // Weight-stationary: workgroup = one offset k and 4 x RB blocks of 32 (in,out) pairs;
@@ -228,7 +427,7 @@ __global__ __launch_bounds__(256) void conv_os_simple_kernel(const int32_t* __re
   if (i >= n_out) return;
   float acc = 0.f;
   for (int k = 0; k < K3; ++k) {
-    const int j = M[i * K3 + k];
+    const int j = M[((i >> 5) * K3 + k) * 32 + (i & 31)];
     if (j < 0) continue;
     const T* f = F + int64_t(j) * ld_in;
     const T* w = W + int64_t(k) * cin * cout + co;
@@ -298,10 +497,30 @@ static void launch_mfma(const ConvArgs& a, const T* Wp, float* accum) {
   constexpr int TROWS = 128 * RB;
   const size_t lds = size_t(CK / 16) * NB * 64 * 16;
   if (a.dataflow == SPC_DATAFLOW_OS) {
-    const int grid = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
-    hipLaunchKernelGGL((conv_os_mfma_kernel<T, NB, RB>), dim3(grid), dim3(CONV_THREADS), lds, a.s, a.m->os_map, a.n_out_h,
-                       a.n_out_d, a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp, static_cast<T*>(a.out), a.ld_out, a.cin,
-                       a.relu);
+    constexpr int WAVES = 8;
+    constexpr int RBK = NB <= 2 ? 2 : 1;  // blocks per wave
+    constexpr int DEPTH = 2;
+    const int64_t n_blocks = (a.rows_cap + 31) / 32;
+    const int64_t n_tiles = (n_blocks + RBK - 1) / RBK;
+    const int64_t tiles_per_xcd = (n_tiles + 7) / 8;
+    const int per_xcd = static_cast<int>((tiles_per_xcd + WAVES - 1) / WAVES);
+    const size_t lds = 2 * HALF_BYTES + size_t(WAVES) * KLIST_CAP * 2;
+    auto go = [&](auto NKK_) {
+      constexpr int NKK = decltype(NKK_)::value;
+      const int cpp = std::max(1, HALF_BYTES / (16 * NKK * NB * 32 * int(sizeof(T))));
+      static bool attr_set = false;  // one per instantiation
+      if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        attr_set = true;
+      }
+      hipLaunchKernelGGL((conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>), dim3(per_xcd * 8), dim3(64 * WAVES), lds, a.s,
+                         a.m->os_map, a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3,
+                         static_cast<const T*>(a.F), a.ld_in, Wp, static_cast<T*>(a.out), a.ld_out, a.cin, a.relu, cpp, per_xcd);
+    };
+    if (a.cin % 64 == 0) go(std::integral_constant<int, 4>{});
+    else if (a.cin % 32 == 0) go(std::integral_constant<int, 2>{});
+    else go(std::integral_constant<int, 1>{});
   } else {
     const int gx = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
     hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, a.m->K3), dim3(CONV_THREADS), lds, a.s, a.m->ws_in,

@@ -126,8 +126,10 @@ template <typename KeyT, int K>
 __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
     int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
-    int32_t* __restrict__ tile_counts, int n_tiles_cap) {
+    uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap) {
   constexpr int G = K * K, K3 = K * K * K;
+  constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
+  constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
   constexpr int WIN_CAP = WIN_CAP_BYTES / sizeof(KeyT);
   constexpr int NW = SEARCH_THREADS / 64;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -136,6 +138,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   __shared__ int s_wlo[G], s_wsz[G], s_woff[G];
   __shared__ int s_bound[2 * G];
   __shared__ int s_cnt[K3];
+  __shared__ unsigned s_mask[MAX_BLOCKS * MW];
   __shared__ KeyT s_gd[G];  // packed (dx,dy,zmin) offset of every group
 
   const int n_in = n_in_d ? *n_in_d : n_in_h;
@@ -147,6 +150,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 
   for (int v = tid; v < rows; v += SEARCH_THREADS) okeys[v] = out_keys[i0 + v];
   for (int k = tid; k < K3; k += SEARCH_THREADS) s_cnt[k] = 0;
+  for (int k = tid; k < MAX_BLOCKS * MW; k += SEARCH_THREADS) s_mask[k] = 0u;
 #pragma unroll
   for (int g = 0; g < G; ++g)  // static indices keep the kernel arguments in scalar registers
     if (tid == g) s_gd[g] = sp.X[g / K] + sp.Y[g % K] + sp.zmin;
@@ -202,28 +206,37 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   }
   __syncthreads();
 
-  // ---- per-lane searches; work item w = v*G + g so that a wave writes one contiguous run of M
-  const int items = rows * G;
-  int32_t* Mt = M + int64_t(i0) * K3;
-  for (int w = tid; w < items; w += SEARCH_THREADS) {
-    const int v = w / G, g = w - v * G;
-    const KeyT q0 = okeys[v] + s_gd[g];
-    const int off = s_woff[g], wlo = s_wlo[g], wsz = s_wsz[g];
+  // ---- per-lane searches.  Work item w = g*tile + v: a wave holds 64 consecutive output
+  // voxels of ONE group, so all its lanes search the same window and every store of the
+  // blocked map M[block][k][32] is two full 128-byte segments.
+  const int64_t b0 = int64_t(i0) >> 5;
+  const int rows32 = (rows + 31) & ~31;
+  for (int w = tid; w < G * tile; w += SEARCH_THREADS) {
+    const int g = w / tile, v = w - g * tile;  // g is uniform in the wave (tile is a multiple of 64)
+    const bool act = v < rows;
+    const KeyT q0 = act ? KeyT(okeys[v] + s_gd[g]) : KeyT(0);
+    const int off = s_woff[g], wlo = s_wlo[g], wsz = act ? s_wsz[g] : 0;
     int32_t r[K];
     if (off >= 0) resolve_group<KeyT, K>(win + off, wsz, wlo, q0, sp.zstep, sp.zrev, r);
     else resolve_group<KeyT, K>(in_keys + wlo, wsz, wlo, q0, sp.zstep, sp.zrev, r);
+    const int bl = v >> 5;
 #pragma unroll
-    for (int t = 0; t < K; ++t) Mt[int64_t(w) * K + t] = r[t];
-    if (tile_counts) {
-#pragma unroll
-      for (int t = 0; t < K; ++t)
-        if (r[t] >= 0) atomicAdd(&s_cnt[g * K + t], 1);
+    for (int t = 0; t < K; ++t) {
+      const int k = g * K + t;
+      if (v < rows32) M[((b0 + bl) * K3 + k) * 32 + (v & 31)] = r[t];  // rows past the end hold -1
+      const unsigned long long hit = __ballot(r[t] >= 0);
+      if (hit) {
+        if (lane == 0 && unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
+        if (lane == 32 && unsigned(hit >> 32)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
+        if (tile_counts && lane == 0) atomicAdd(&s_cnt[k], __popcll(hit));
+      }
     }
   }
-  if (tile_counts) {
-    __syncthreads();
+  __syncthreads();
+  const int n_bl = rows32 >> 5;
+  for (int e = tid; e < n_bl * MW; e += SEARCH_THREADS) block_masks[b0 * MW + e] = s_mask[e];
+  if (tile_counts)
     for (int k = tid; k < K3; k += SEARCH_THREADS) tile_counts[int64_t(k) * n_tiles_cap + blockIdx.x] = s_cnt[k];
-  }
 }
 
 // One workgroup per offset k: exclusive scan of that offset's per-tile counts in place,
@@ -260,31 +273,27 @@ __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile
   if (threadIdx.x == 0) nnz[blockIdx.x] = carry;
 }
 
-// One workgroup per tile: the tile's rows of the OS matrix are read once (coalesced)
-// into LDS; each wave then filters whole columns with ballots, so list k comes out
-// ordered by output index without atomics.
+// One workgroup per tile of the search kernel.  In the blocked map a column (fixed k) of a
+// 32-row block is contiguous, so a wave filters two blocks of one offset per step with a
+// coalesced load and a ballot; list k comes out ordered by output index without atomics.
 __global__ __launch_bounds__(256) void ws_fill_kernel(const int32_t* __restrict__ M, int n_out_h,
                                                       const int* __restrict__ n_out_d, int K3, int tile,
                                                       const int32_t* __restrict__ tile_base, int n_tiles_cap,
                                                       int32_t* __restrict__ ws_in, int32_t* __restrict__ ws_out,
                                                       int64_t ws_stride) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  int32_t* sM = reinterpret_cast<int32_t*>(smem);
   const int n_out = n_out_d ? *n_out_d : n_out_h;
   const int i0 = blockIdx.x * tile;
   if (i0 >= n_out) return;
   const int rows = min(tile, n_out - i0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int32_t* Mt = M + int64_t(i0) * K3;
-  for (int e = tid; e < rows * K3; e += 256) sM[e] = Mt[e];
-  __syncthreads();
+  const int64_t b0 = int64_t(i0) >> 5;
   for (int k = wave; k < K3; k += 4) {
     int base = tile_base[int64_t(k) * n_tiles_cap + blockIdx.x];
     int32_t* li = ws_in + int64_t(k) * ws_stride;
     int32_t* lo = ws_out + int64_t(k) * ws_stride;
     for (int v0 = 0; v0 < rows; v0 += 64) {
       const int v = v0 + lane;
-      const int j = v < rows ? sM[v * K3 + k] : -1;
+      const int j = v < rows ? M[((b0 + (v >> 5)) * K3 + k) * 32 + (v & 31)] : -1;
       const unsigned long long m = __ballot(j >= 0);
       if (j >= 0) {
         const int r = base + lanemask_lt_popc(m);
@@ -301,7 +310,7 @@ __global__ void copy_int_kernel(const int* src, int* dst) { *dst = *src; }
 // ---------------------------------------------------------------- host side
 static int axis_offset(int K, int s, int i) { return (K % 2 == 1) ? (i - (K - 1) / 2) * s : i * s; }
 
-static int tile_for(int K) { return K <= 3 ? 128 : (K == 5 ? 64 : 32); }
+static int tile_for(int K) { return K <= 3 ? 128 : 64; }
 
 template <typename KeyT, int K>
 static int launch_search(spc_kmap* m, hipStream_t s) {
@@ -325,7 +334,7 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
     hipLaunchKernelGGL((kmap_search_kernel<KeyT, K>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
-                       sp, m->tile, m->os_map, m->tile_counts, m->n_tiles);
+                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles);
   return SPC_OK;
 }
 
@@ -343,6 +352,7 @@ static int launch_search_k(spc_kmap* m, hipStream_t s) {
 
 static void kmap_free(spc_kmap* m) {
   pool_free(m->os_map);
+  pool_free(m->block_masks);
   pool_free(m->ws_in);
   pool_free(m->ws_out);
   pool_free(m->nnz_dev);
@@ -385,10 +395,13 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->out_cap = out->n_host >= 0 ? out->n_host : out->cap;
   m->tile = tile_for(l.K);
   m->n_tiles = static_cast<int>((m->out_cap + m->tile - 1) / m->tile);
-  const size_t cells = std::max<size_t>(size_t(m->out_cap) * m->K3, 64);
+  m->n_blocks_cap = (m->out_cap + 31) / 32;
+  m->mask_words = (m->K3 + 31) / 32;
+  const size_t cells = std::max<size_t>(size_t(m->n_blocks_cap) * 32 * m->K3, 64);
   m->os_map = static_cast<int32_t*>(pool_alloc(cells * 4));
+  m->block_masks = static_cast<uint32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * m->mask_words * 4, 256)));
   m->nnz_dev = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->K3) * 4, 256)));
-  bool ok = m->os_map && m->nnz_dev;
+  bool ok = m->os_map && m->nnz_dev && m->block_masks;
   if (ok && (l.layout & SPC_LAYOUT_WS)) {
     m->ws_in = static_cast<int32_t*>(pool_alloc(cells * 4));
     m->ws_out = static_cast<int32_t*>(pool_alloc(cells * 4));
@@ -405,7 +418,7 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
     hipLaunchKernelGGL(ws_scan_kernel, dim3(m->K3), dim3(256), 0, s, m->tile_counts, m->n_tiles, m->tile, n_out_h,
                        out->n_dev, m->nnz_dev);
     if (m->n_tiles > 0)
-      hipLaunchKernelGGL(ws_fill_kernel, dim3(m->n_tiles), dim3(256), size_t(m->tile) * m->K3 * 4, s, m->os_map, n_out_h,
+      hipLaunchKernelGGL(ws_fill_kernel, dim3(m->n_tiles), dim3(256), 0, s, m->os_map, n_out_h,
                          out->n_dev, m->K3, m->tile, m->tile_counts, m->n_tiles, m->ws_in, m->ws_out, m->out_cap);
   }
   if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "kernel-map launch failed");
@@ -604,11 +617,11 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
   const int K3 = m->K3;
   int64_t nnz = 0;
   if (which == SPC_LAYOUT_OS) {
-    std::vector<int32_t> M(size_t(n_out) * K3);
+    std::vector<int32_t> M(size_t((n_out + 31) / 32) * 32 * K3);
     if (!M.empty()) SPC_HIP_CHECK(hipMemcpy(M.data(), m->os_map, M.size() * 4, hipMemcpyDeviceToHost));
     for (int k = 0; k < K3; ++k)
       for (int64_t i = 0; i < n_out; ++i) {
-        const int32_t j = M[i * K3 + k];
+        const int32_t j = M[((i >> 5) * K3 + k) * 32 + (i & 31)];
         if (j < 0) continue;
         if (nnz < cap && triples) {
           triples[3 * nnz] = k;
@@ -656,10 +669,10 @@ int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host) {
       for (int k = 0; k < m->K3; ++k) cnt[k] = c[k];
     } else {
       const int64_t n_out = m->out_level->n_host;
-      std::vector<int32_t> M(size_t(n_out) * m->K3);
+      std::vector<int32_t> M(size_t((n_out + 31) / 32) * 32 * m->K3);
       if (!M.empty()) SPC_HIP_CHECK(hipMemcpy(M.data(), m->os_map, M.size() * 4, hipMemcpyDeviceToHost));
       for (int64_t i = 0; i < n_out; ++i)
-        for (int k = 0; k < m->K3; ++k) cnt[k] += M[i * m->K3 + k] >= 0;
+        for (int k = 0; k < m->K3; ++k) cnt[k] += M[((i >> 5) * m->K3 + k) * 32 + (i & 31)] >= 0;
     }
     m->nnz_host = cnt;
   }

@@ -84,7 +84,10 @@ struct spc_kmap {
   spc::Level* in_level = nullptr;   // the layer's input voxels
   spc::Level* out_level = nullptr;  // the layer's output voxels
   int64_t out_cap = 0;              // rows allocated in os_map / ws lists
-  int32_t* os_map = nullptr;        // [out_cap][K3]
+  int64_t n_blocks_cap = 0;         // 32-row blocks allocated
+  int mask_words = 0;               // ceil(K3/32)
+  int32_t* os_map = nullptr;        // blocked OS layout [n_blocks][K3][32]: entry (i,k) at ((i/32)*K3+k)*32 + i%32
+  uint32_t* block_masks = nullptr;  // [n_blocks][mask_words]: bit k set iff some row of the block has offset k
   int32_t* ws_in = nullptr;         // [K3][out_cap]
   int32_t* ws_out = nullptr;        // [K3][out_cap]
   int32_t* nnz_dev = nullptr;       // [K3]
