@@ -129,3 +129,41 @@ def layer(coords_sorted, K: int, s_p: int, s_l: int):
     """Output coordinates and kernel map of one layer on sorted input coordinates."""
     out = coords_sorted if s_l == 1 else downsample(coords_sorted, s_p * s_l)
     return out, kernel_map(coords_sorted, out, K, s_p)
+
+
+def network_forward(coords_sorted, F0, layers, weights, act_dtype=np.float16, inputs_override=None):
+    """Layer stack on the CPU: every layer is Eq. (2) in fp64, followed by ReLU (where the
+    layer says so) and rounding of the activations to ``act_dtype`` (round to nearest
+    even), because activations are stored in that type between layers.  ``layers`` is a
+    list of dicts (K, in_stride, layer_stride, transposed, src, skip, save, relu).
+    Returns (dict of saved tensors as float64 arrays holding act_dtype values, list of
+    per-layer kernel maps)."""
+    levels = {1: coords_sorted}
+
+    def level(s):
+        if s not in levels:
+            levels[s] = downsample(coords_sorted, s)
+        return levels[s]
+
+    T = {"input": np.asarray(F0, dtype=np.float64)}
+    maps = []
+    for j, l in enumerate(layers):
+        K, sp, sl = l["K"], l["in_stride"], l["layer_stride"]
+        fine = level(sp)
+        if sl == 1:
+            M = kernel_map(fine, fine, K, sp)
+        elif not l["transposed"]:
+            M = kernel_map(fine, level(sp * sl), K, sp)
+        else:
+            M = kernel_map_transposed(level(sp * sl), fine, K, sp)
+        maps.append(M)
+        if inputs_override is not None:
+            x = inputs_override[j]
+        else:
+            x = T[l["src"]] if l["skip"] is None else np.concatenate([T[l["src"]], T[l["skip"]]], axis=1)
+        y = conv(M, x, np.asarray(weights[j], dtype=np.float64))
+        if l["relu"]:
+            y = np.maximum(y, 0.0)
+        T[l["save"]] = y.astype(act_dtype).astype(np.float64)
+        T["_raw_%d" % j] = y
+    return T, maps

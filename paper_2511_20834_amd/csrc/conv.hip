@@ -534,7 +534,7 @@ static int conv_typed(const ConvArgs& a, bool allow_mfma) {
   const int64_t out_elems = a.rows_cap * a.cout;
   float* accum = nullptr;
   if (a.dataflow == SPC_DATAFLOW_WS) {
-    accum = static_cast<float*>(pool_alloc(std::max<size_t>(size_t(out_elems) * 4 + 16, 256)));
+    accum = static_cast<float*>(pool_alloc(std::max<size_t>(size_t(out_elems) * 4 + 16, 256), a.s));
     if (!accum) return SPC_ERR_NOMEM;
     const int64_t n4 = (out_elems + 3) / 4;
     if (n4 > 0) hipLaunchKernelGGL(zero_f32_kernel, dim3((n4 + 255) / 256), dim3(256), 0, a.s, reinterpret_cast<float4*>(accum), n4);
@@ -552,9 +552,9 @@ static int conv_typed(const ConvArgs& a, bool allow_mfma) {
       const T* Wp = static_cast<const T*>(a.W);
       T* Wtmp = nullptr;
       if (!a.packed) {
-        Wtmp = static_cast<T*>(pool_alloc(size_t(K3) * a.cin * a.cout * sizeof(T)));
+        Wtmp = static_cast<T*>(pool_alloc(size_t(K3) * a.cin * a.cout * sizeof(T), a.s));
         if (!Wtmp) {
-          pool_free(accum);
+          pool_free(accum, a.s);
           return SPC_ERR_NOMEM;
         }
         const int64_t total = int64_t(K3) * (a.cin / 16) * (a.cout / 32) * 64;
@@ -568,7 +568,7 @@ static int conv_typed(const ConvArgs& a, bool allow_mfma) {
         case 128: launch_mfma<T, 4, 1>(a, Wp, accum); break;
         case 256: launch_mfma<T, 8, 1>(a, Wp, accum); break;
       }
-      pool_free(Wtmp);  // reuse is ordered behind this stream's work
+      pool_free(Wtmp, a.s);  // reuse is ordered behind this stream's work
      }
     }
     if (mfma_ok) {
@@ -587,7 +587,7 @@ static int conv_typed(const ConvArgs& a, bool allow_mfma) {
       hipLaunchKernelGGL(finalize_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, accum, a.n_out_h, a.n_out_d, a.cout,
                          static_cast<T*>(a.out), a.ld_out, a.relu);
   }
-  pool_free(accum);
+  pool_free(accum, a.s);
   if (hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "feature kernel launch failed");
   return rc;
 }

@@ -351,12 +351,12 @@ static int launch_search_k(spc_kmap* m, hipStream_t s) {
 }
 
 static void kmap_free(spc_kmap* m) {
-  pool_free(m->os_map);
-  pool_free(m->block_masks);
-  pool_free(m->ws_in);
-  pool_free(m->ws_out);
-  pool_free(m->nnz_dev);
-  pool_free(m->tile_counts);
+  pool_free(m->os_map, m->stream);
+  pool_free(m->block_masks, m->stream);
+  pool_free(m->ws_in, m->stream);
+  pool_free(m->ws_out, m->stream);
+  pool_free(m->nnz_dev, m->stream);
+  pool_free(m->tile_counts, m->stream);
   level_unref(m->in_level);
   level_unref(m->out_level);
   if (m->ready) (void)hipEventDestroy(m->ready);
@@ -387,6 +387,7 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->pi = pi;
   m->desc = l;
   m->K3 = l.K * l.K * l.K;
+  m->stream = s;
   m->in_level = in;
   in->refs++;
   m->out_level = out;
@@ -398,14 +399,14 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->n_blocks_cap = (m->out_cap + 31) / 32;
   m->mask_words = (m->K3 + 31) / 32;
   const size_t cells = std::max<size_t>(size_t(m->n_blocks_cap) * 32 * m->K3, 64);
-  m->os_map = static_cast<int32_t*>(pool_alloc(cells * 4));
-  m->block_masks = static_cast<uint32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * m->mask_words * 4, 256)));
-  m->nnz_dev = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->K3) * 4, 256)));
+  m->os_map = static_cast<int32_t*>(pool_alloc(cells * 4, s));
+  m->block_masks = static_cast<uint32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * m->mask_words * 4, 256), s));
+  m->nnz_dev = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->K3) * 4, 256), s));
   bool ok = m->os_map && m->nnz_dev && m->block_masks;
   if (ok && (l.layout & SPC_LAYOUT_WS)) {
-    m->ws_in = static_cast<int32_t*>(pool_alloc(cells * 4));
-    m->ws_out = static_cast<int32_t*>(pool_alloc(cells * 4));
-    m->tile_counts = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->K3 * 4, 256)));
+    m->ws_in = static_cast<int32_t*>(pool_alloc(cells * 4, s));
+    m->ws_out = static_cast<int32_t*>(pool_alloc(cells * 4, s));
+    m->tile_counts = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->K3 * 4, 256), s));
     ok = m->ws_in && m->ws_out && m->tile_counts;
   }
   if (!ok) {

@@ -177,7 +177,7 @@ static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, L
   const size_t off_sorted = (n * ksz + 255) / 256 * 256;
   const size_t off_counts = off_sorted * 2;
   const size_t off_temp = off_counts + (size_t(n_blocks) * 4 + 255) / 256 * 256;
-  char* scratch = static_cast<char*>(pool_alloc(off_temp + tb + 256));
+  char* scratch = static_cast<char*>(pool_alloc(off_temp + tb + 256, s));
   if (!scratch) return SPC_ERR_NOMEM;
   KeyT* masked = reinterpret_cast<KeyT*>(scratch);
   KeyT* sorted = reinterpret_cast<KeyT*>(scratch + off_sorted);
@@ -199,7 +199,7 @@ static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, L
   }
   // The scratch block returns to the cache now; reuse is ordered behind these kernels
   // as long as later library calls are ordered after this stream's work.
-  pool_free(scratch);
+  pool_free(scratch, s);
   if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "downsample launch failed");
   return rc;
 }
@@ -210,8 +210,9 @@ int downsample_level(const void* src_keys, int64_t n_src, const int* /*n_src_dev
   lv->cap = n_src;
   lv->stride = 1 << m;
   lv->owns_keys = true;
-  lv->keys = pool_alloc(std::max<size_t>(size_t(n_src) * (pi.key_bits / 8), 256));
-  lv->n_dev = static_cast<int*>(pool_alloc(256));
+  lv->stream = stream;
+  lv->keys = pool_alloc(std::max<size_t>(size_t(n_src) * (pi.key_bits / 8), 256), stream);
+  lv->n_dev = static_cast<int*>(pool_alloc(256, stream));
   if (!lv->keys || !lv->n_dev) {
     level_unref(lv);
     return SPC_ERR_NOMEM;

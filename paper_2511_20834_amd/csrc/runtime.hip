@@ -4,6 +4,8 @@
 #include <cstring>
 #include <map>
 #include <unordered_map>
+#include <utility>
+#include <vector>
 
 #include "spc_internal.h"
 
@@ -20,11 +22,15 @@ int set_error(int code, const char* fmt, ...) {
 }
 
 // ---------------------------------------------------------------- block cache
+// Freed blocks are kept for reuse, binned by rounded size AND by the stream whose work
+// last touched them: a block is handed out again only to work enqueued on that same
+// stream, so stream order alone guarantees that the previous user has finished (blocks
+// are returned right after the kernels that use them were enqueued, not after they ran).
 namespace {
 struct Pool {
   std::mutex mu;
-  std::multimap<size_t, void*> free_blocks;       // rounded size -> block
-  std::unordered_map<void*, size_t> live;         // block -> rounded size
+  std::map<std::pair<size_t, hipStream_t>, std::vector<void*>> free_blocks;
+  std::unordered_map<void*, size_t> live;  // block -> rounded size
 };
 Pool& pool() {
   static Pool* p = new Pool;  // never destroyed: device memory is reclaimed by the driver at exit
@@ -42,15 +48,15 @@ size_t round_size(size_t b) {
 }
 }  // namespace
 
-void* pool_alloc(size_t bytes) {
+void* pool_alloc(size_t bytes, hipStream_t stream) {
   const size_t r = round_size(bytes);
   Pool& P = pool();
   {
     std::lock_guard<std::mutex> lk(P.mu);
-    auto it = P.free_blocks.find(r);
-    if (it != P.free_blocks.end()) {
-      void* p = it->second;
-      P.free_blocks.erase(it);
+    auto it = P.free_blocks.find({r, stream});
+    if (it != P.free_blocks.end() && !it->second.empty()) {
+      void* p = it->second.back();
+      it->second.pop_back();
       P.live[p] = r;
       return p;
     }
@@ -71,13 +77,13 @@ void* pool_alloc(size_t bytes) {
   return p;
 }
 
-void pool_free(void* p) {
+void pool_free(void* p, hipStream_t stream) {
   if (!p) return;
   Pool& P = pool();
   std::lock_guard<std::mutex> lk(P.mu);
   auto it = P.live.find(p);
   if (it == P.live.end()) return;
-  P.free_blocks.emplace(it->second, p);
+  P.free_blocks[{it->second, stream}].push_back(p);
   P.live.erase(it);
 }
 
@@ -86,7 +92,8 @@ int pool_release_all() {
   std::vector<void*> blocks;
   {
     std::lock_guard<std::mutex> lk(P.mu);
-    for (auto& kv : P.free_blocks) blocks.push_back(kv.second);
+    for (auto& kv : P.free_blocks)
+      for (void* b : kv.second) blocks.push_back(b);
     P.free_blocks.clear();
   }
   if (!blocks.empty()) (void)hipDeviceSynchronize();
@@ -136,8 +143,8 @@ uint64_t level_mask(const PackInfo& pi, int m) {
 void level_unref(Level* l) {
   if (!l) return;
   if (l->refs.fetch_sub(1) == 1) {
-    if (l->owns_keys) pool_free(l->keys);
-    pool_free(l->n_dev);
+    if (l->owns_keys) pool_free(l->keys, l->stream);
+    pool_free(l->n_dev, l->stream);
     if (l->ready) (void)hipEventDestroy(l->ready);
     delete l;
   }

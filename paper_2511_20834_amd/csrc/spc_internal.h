@@ -30,9 +30,10 @@ int set_error(int code, const char* fmt, ...);
 
 // ---------------------------------------------------------------- device block cache
 // hipMalloc costs tens of microseconds and synchronises; kernel maps are built per
-// frame, so freed blocks are kept (binned by rounded size) and handed out again.
-void* pool_alloc(size_t bytes);  // nullptr on failure (error set)
-void pool_free(void* p);
+// frame, so freed blocks are kept and handed out again — only to work on the stream
+// that last used them, which makes stream order the only synchronisation needed.
+void* pool_alloc(size_t bytes, hipStream_t stream);  // nullptr on failure (error set)
+void pool_free(void* p, hipStream_t stream);
 int pool_release_all();
 
 // ---------------------------------------------------------------- packing
@@ -58,6 +59,7 @@ struct Level {
   int* n_dev = nullptr;   // device int (nullptr when n_host is authoritative from the start)
   int stride = 1;
   hipEvent_t ready = nullptr;  // recorded after the level's last kernel
+  hipStream_t stream = nullptr;  // stream the level was produced on
 };
 void level_unref(Level* l);
 
@@ -95,5 +97,6 @@ struct spc_kmap {
   int tile = 0, n_tiles = 0;
   std::vector<int64_t> nnz_host;    // filled lazily
   hipEvent_t ready = nullptr;       // recorded after the last build kernel
+  hipStream_t stream = nullptr;     // stream the map was built on
   int device = 0;
 };

@@ -256,3 +256,50 @@ def layer_tensors(cfg: int, n_in: int):
     f = features(n_in, c["cin"], dt, seed=SEED_BASE + 100 + cfg)
     w = weights(k3, c["cin"], c["cout"], dt, seed=SEED_BASE + 200 + cfg, std=std)
     return f, w
+
+
+# ----------------------------------------------------------------------------
+# config 4: UNet-style layer stack (a workload description, no arithmetic)
+# ----------------------------------------------------------------------------
+def unet_layers(cin: int = 4, widths=(32, 64, 128, 256)):
+    """The 25 SpC layers of benchmark configuration 4 as dicts with keys
+    name, K, in_stride, layer_stride, transposed, cin, cout, relu, src, skip, save.
+
+    ``src`` / ``skip`` name the tensors a layer reads (``skip`` is concatenated after
+    ``src`` along channels), ``save`` the name under which its output is kept.  Encoder:
+    a 3x3x3 stem, then per stage a 2x2x2 stride-2 layer and two 3x3x3 submanifold
+    layers.  Decoder: per stage a 2x2x2 transposed layer, concatenation with the encoder
+    tensor of that level, and two 3x3x3 submanifold layers.  ReLU after every layer but
+    the last; batch norm is folded into the weights (weights only, no bias)."""
+    L = []
+    w0 = widths[0]
+    L.append(dict(name="stem", K=3, in_stride=1, layer_stride=1, transposed=0, cin=cin, cout=w0, src="input", skip=None,
+                  save="enc0"))
+    prev, c_prev = "enc0", w0
+    for i, w in enumerate(widths):
+        s = 2 ** i
+        L.append(dict(name="down%d" % (i + 1), K=2, in_stride=s, layer_stride=2, transposed=0, cin=c_prev, cout=w, src=prev,
+                      skip=None, save="d%d" % (i + 1)))
+        L.append(dict(name="enc%da" % (i + 1), K=3, in_stride=2 * s, layer_stride=1, transposed=0, cin=w, cout=w,
+                      src="d%d" % (i + 1), skip=None, save="e%da" % (i + 1)))
+        L.append(dict(name="enc%db" % (i + 1), K=3, in_stride=2 * s, layer_stride=1, transposed=0, cin=w, cout=w,
+                      src="e%da" % (i + 1), skip=None, save="enc%d" % (i + 1)))
+        prev, c_prev = "enc%d" % (i + 1), w
+    skip_w = [w0] + list(widths[:-1])  # widths of enc0 .. enc3
+    for i in range(len(widths) - 1, -1, -1):
+        s = 2 ** i  # stride of the finer level this stage produces
+        c_up = skip_w[i]
+        L.append(dict(name="up%d" % (i + 1), K=2, in_stride=s, layer_stride=2, transposed=1, cin=c_prev, cout=c_up, src=prev,
+                      skip=None, save="u%d" % (i + 1)))
+        L.append(dict(name="dec%da" % (i + 1), K=3, in_stride=s, layer_stride=1, transposed=0, cin=2 * c_up, cout=c_up,
+                      src="u%d" % (i + 1), skip="enc%d" % i, save="g%da" % (i + 1)))
+        L.append(dict(name="dec%db" % (i + 1), K=3, in_stride=s, layer_stride=1, transposed=0, cin=c_up, cout=c_up,
+                      src="g%da" % (i + 1), skip=None, save="dec%d" % (i + 1)))
+        prev, c_prev = "dec%d" % (i + 1), c_up
+    for j, l in enumerate(L):
+        l["relu"] = j != len(L) - 1
+    return L
+
+
+def unet_weights(layers, dtype=np.float16, seed: int = SEED_BASE + 400):
+    return [weights(l["K"] ** 3, l["cin"], l["cout"], dtype, seed=seed + j) for j, l in enumerate(layers)]

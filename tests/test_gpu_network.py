@@ -1,0 +1,98 @@
+"""Configuration 4: the 25-layer UNet-style stack on the LiDAR-like cloud, with all kernel
+maps built up front by the network-wide builder on several HIP streams."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_20834_amd import binding as B
+from paper_2511_20834_amd import synth
+from paper_2511_20834_amd.network import SpcNetwork
+
+from gpu_common import oracle_keys, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(cloud_name):
+    coords = synth.cloud(cloud_name)
+    layers = synth.unet_layers()
+    W = synth.unet_weights(layers)
+    desc = B.spc_pack_desc_fit(coords[:, 1:].min(0), coords[:, 1:].max(0), 1, 16, 16)
+    assert desc.key_bits == 32
+    keys, perm = B.spc_pack_coords(torch.from_numpy(coords).cuda(), desc, True, B.PACK_VALIDATE)
+    cs, operm = oracle.sort_coords(coords)
+    assert np.array_equal(perm.cpu().numpy(), operm)
+    F0 = synth.features(len(coords), 4, np.float16, seed=synth.SEED_BASE + 300)
+    Fs = B.spc_permute_rows(torch.from_numpy(F0).cuda(), perm)
+    return coords, cs, operm, layers, W, desc, keys, F0, Fs
+
+
+@pytest.mark.parametrize("cloud_name,mode", [("tiny", "streams"), ("lidar", "streams"), ("lidar", "sequential")])
+def test_network_maps_bit_exact_and_shared(cloud_name, mode):
+    coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup(cloud_name)
+    net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W],
+                     dataflow=[B.DATAFLOW_OS if j % 2 == 0 else B.DATAFLOW_WS for j in range(len(layers))])
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
+    maps = net.build_maps(keys, desc, streams, B.NET_SEQUENTIAL if mode == "sequential" else 0)
+    torch.cuda.synchronize()
+    handles = {}
+    for j, (l, m) in enumerate(zip(layers, maps)):
+        key = (l["K"], l["in_stride"], l["layer_stride"], l["transposed"])
+        handles.setdefault(key, set()).add(m.handle.value)
+    assert len(handles) == 13 and all(len(v) == 1 for v in handles.values())  # one map per distinct layer geometry
+    T, omaps = oracle.network_forward(cs, F0[operm], layers[:0], [])
+    seen = set()
+    for j, (l, m) in enumerate(zip(layers, maps)):
+        key = (l["K"], l["in_stride"], l["layer_stride"], l["transposed"])
+        if key in seen:
+            continue
+        seen.add(key)
+        fine = cs if l["in_stride"] == 1 else oracle.downsample(cs, l["in_stride"])
+        if l["layer_stride"] == 1:
+            oc, M = fine, oracle.kernel_map(fine, fine, l["K"], l["in_stride"])
+        elif not l["transposed"]:
+            oc = oracle.downsample(cs, l["in_stride"] * 2)
+            M = oracle.kernel_map(fine, oc, l["K"], l["in_stride"])
+        else:
+            oc = fine
+            M = oracle.kernel_map_transposed(oracle.downsample(cs, l["in_stride"] * 2), fine, l["K"], l["in_stride"])
+        assert m.n_out == len(oc), l["name"]
+        assert np.array_equal(m.out_keys(), oracle_keys(oc, desc)), l["name"]
+        ref = oracle.triples(M)
+        # the shared map carries the union of the layouts its layers asked for
+        for which in (B.LAYOUT_OS, B.LAYOUT_WS):
+            try:
+                got = m.export_triples(which)
+            except B.SpcError:
+                continue
+            assert np.array_equal(got, ref), (l["name"], which)
+    net.destroy_maps()
+
+
+@pytest.mark.parametrize("cloud_name,dataflow", [("tiny", "os"), ("lidar", "os"), ("lidar", "mixed")])
+def test_network_forward_matches_oracle(cloud_name, dataflow):
+    coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup(cloud_name)
+    df = B.DATAFLOW_OS if dataflow == "os" else [B.DATAFLOW_WS if l["K"] == 2 or l["in_stride"] >= 8 else B.DATAFLOW_OS
+                                                 for l in layers]
+    net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W], dataflow=df)
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
+    net.build_maps(keys, desc, streams)
+    y, T = net.forward(Fs, keep=True)
+    torch.cuda.synchronize()
+    # (a) layer by layer: the oracle is fed the GPU's own (fp16) inputs, which isolates each layer's error
+    gpu_in = []
+    for l in layers:
+        x = T[l["src"]].cpu().double().numpy()
+        if l["skip"] is not None:
+            x = np.concatenate([x, T[l["skip"]].cpu().double().numpy()], axis=1)
+        gpu_in.append(x)
+    Tl, _ = oracle.network_forward(cs, F0[operm], layers, W, inputs_override=gpu_in)
+    for j, l in enumerate(layers):
+        err = rel_err(T[l["save"]].cpu().double().numpy(), Tl[l["save"]])
+        assert err <= 1e-2, (l["name"], err)
+    # (b) end to end against the oracle's own chain
+    To, _ = oracle.network_forward(cs, F0[operm], layers, W)
+    err = rel_err(y.cpu().double().numpy(), To[layers[-1]["save"]])
+    assert err <= 1e-2, err
+    net.destroy_maps()
