@@ -186,21 +186,18 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   };
   stage_load(0);
 
-  // offsets present in this wave's blocks, ascending
-  int nk = 0;
-  if (active) {
-    for (int wd = 0; wd < mask_words; ++wd) {
-      unsigned m = 0;
+  // offsets present in this wave's blocks: union of the blocks' masks, one word per 32 offsets,
+  // parked in LDS; the positions below walk its set bits in ascending order with scalar ops
+  unsigned* smask = reinterpret_cast<unsigned*>(klist);
+  for (int wd = lane; wd < mask_words; wd += 64) {
+    unsigned m = 0;
+    if (active) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
         if (blk0 + rb < n_blocks) m |= block_masks[(blk0 + rb) * mask_words + wd];
-      const bool bit = lane < 32 && ((m >> lane) & 1u);
-      const unsigned long long bal = __ballot(bit);
-      if (bit) klist[nk + __builtin_amdgcn_mbcnt_lo(unsigned(bal), 0)] = static_cast<int16_t>(wd * 32 + lane);
-      nk += __popcll(bal);
     }
+    smask[wd] = m;
   }
-  nk = __builtin_amdgcn_readfirstlane(nk);
   __builtin_amdgcn_wave_barrier();
 
   floatx16 acc[RB][NB];
@@ -211,26 +208,38 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
 
-  // A position is (index into klist, channel chunk); positions past the end are clamped so that
-  // the pipeline issues the same loads every step (the surplus ones are never consumed).
+  // A position is (mask word, remaining bits of that word, channel chunk, current offset k).
+  // Positions past the end keep their last k, so that the pipeline issues the same loads every
+  // step (the surplus ones are never consumed).
   struct Pos {
-    int ki, ch;
+    int wd;
+    unsigned rem;
+    int ch, k;
+    bool valid;
+  };
+  auto settle = [&](Pos& p) {
+    while (p.rem == 0 && p.wd + 1 < mask_words) {
+      ++p.wd;
+      p.rem = __builtin_amdgcn_readfirstlane(smask[p.wd]);
+    }
+    if (p.rem != 0) p.k = p.wd * 32 + __builtin_ctz(p.rem);
+    else p.valid = false;
   };
   auto advance = [&](Pos& p) {
     if (++p.ch == nch) {
       p.ch = 0;
-      ++p.ki;
+      p.rem &= p.rem - 1;
+      settle(p);
     }
   };
-  auto k_at = [&](const Pos& p) -> int {
-    return nk > 0 ? __builtin_amdgcn_readfirstlane(int(klist[min(p.ki, nk - 1)])) : 0;
-  };
+  Pos p0{0, static_cast<unsigned>(__builtin_amdgcn_readfirstlane(smask[0])), 0, 0, true};
+  settle(p0);
   // a block past the end (odd tail) reads block 0's map rows; its results are never stored
   const int32_t* Mb[RB];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) Mb[rb] = M + ((active && blk0 + rb < n_blocks) ? blk0 + rb : 0) * int64_t(K3) * 32 + lr;
   auto load_idx = [&](const Pos& p, int (&dst)[RB]) {
-    const int k32 = k_at(p) * 32;
+    const int k32 = p.k * 32;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) dst[rb] = Mb[rb][k32];
   };
@@ -248,9 +257,9 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   // with step u + D; jj[b] holds the map indices for that refill, themselves loaded D steps earlier
   V8 a[D][RB][NKK];
   int jj[D][RB];
-  Pos pc{0, 0};  // current step
-  Pos pg{0, 0};  // next step to gather
-  Pos pi{0, 0};  // next step whose map indices are loaded
+  Pos pc = p0;  // current step
+  Pos pg = p0;  // next step to gather
+  Pos pi = p0;  // next step whose map indices are loaded
 #pragma unroll
   for (int b = 0; b < D; ++b) {
     load_idx(pg, jj[b]);
@@ -267,27 +276,26 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   int c_hi = 0;
   int64_t e_lo = 0;
   const V8* sWp = sW;  // LDS half of the current phase
-  int k_cur = k_at(pc);
-  auto can_step = [&]() -> bool { return pc.ki < nk && k_cur * nch + pc.ch < c_hi; };
+  auto can_step = [&]() -> bool { return pc.valid && pc.k * nch + pc.ch < c_hi; };
   auto step = [&](auto B_) {
     constexpr int B = decltype(B_)::value;
-    const V8* Bk = sWp + ((int64_t(k_cur) * cin + pc.ch * CKS) * cout - e_lo) / 8 + lane;
+    const V8* Bk = sWp + ((int64_t(pc.k) * cin + pc.ch * CKS) * cout - e_lo) / 8 + lane;
+    V8 bw[NKK][NB];
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) {
-      V8 bw[NB];
+    for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) bw[nb] = Bk[(kk * NB + nb) * 64];
+      for (int nb = 0; nb < NB; ++nb) bw[kk][nb] = Bk[(kk * NB + nb) * 64];
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) acc[rb][nb] = Mfma<T>::mma(a[B][rb][kk], bw[nb], acc[rb][nb]);
-    }
+        for (int rb = 0; rb < RB; ++rb) acc[rb][nb] = Mfma<T>::mma(a[B][rb][kk], bw[kk][nb], acc[rb][nb]);
     gather(pg, jj[B], a[B]);
     advance(pg);
     load_idx(pi, jj[B]);
     advance(pi);
     advance(pc);
-    k_cur = k_at(pc);
   };
   auto rotate_ring = [&]() {  // buffer 1 becomes buffer 0 (used when a phase ends off-phase; rare)
     V8 t[RB][NKK];

@@ -23,7 +23,7 @@
 namespace spc {
 
 constexpr int SEARCH_THREADS = 256;
-constexpr int WIN_CAP_BYTES = 48 * 1024;  // LDS budget for staged windows per workgroup
+constexpr int WIN_CAP_BYTES = 20 * 1024;  // LDS budget for staged windows per workgroup (several workgroups share a CU)
 constexpr int MAX_K = 7;
 
 template <typename KeyT>
@@ -42,16 +42,29 @@ __device__ inline int lanemask_lt_popc(unsigned long long m) {
 // S simultaneous wave-wide searches over keys[0,n).  upper[s]=false: first index with
 // key >= q; true: first index with key > q.  All lanes get the results.  Each round
 // every lane probes the last key of its 1/64 slice; the ballot tells the slice that
-// holds the answer.
+// holds the answer.  The first round probes the same 64 keys for every search of every
+// workgroup, so the caller loads them once (`probe`, one per lane) and that round costs no
+// memory access; 2^18 keys then need two dependent loads per search, all S searches of a
+// wave in flight together.
 template <typename KeyT, int S>
-__device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, const KeyT (&q)[S], const bool (&upper)[S],
-                                   int (&res)[S]) {
+__device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, KeyT probe, const KeyT (&q)[S],
+                                   const bool (&upper)[S], int (&res)[S]) {
   const int lane = threadIdx.x & 63;
   int lo[S], hi[S];
+  const int chunk0 = (n + 63) >> 6;
+  const int n_chunks0 = chunk0 > 0 ? (n + chunk0 - 1) / chunk0 : 0;
 #pragma unroll
   for (int s = 0; s < S; ++s) {
-    lo[s] = 0;
-    hi[s] = n;
+    // lanes past the last slice hold no probe; their predicate is false
+    const bool pr = lane < n_chunks0 && (upper[s] ? (probe <= q[s]) : (probe < q[s]));
+    const int c = __popcll(__ballot(pr));
+    if (n == 0 || c >= n_chunks0) {
+      lo[s] = n;
+      hi[s] = n;
+    } else {
+      lo[s] = c * chunk0;
+      hi[s] = min(lo[s] + chunk0 - 1, n - 1);
+    }
   }
   while (true) {
     int maxlen = 0;
@@ -65,12 +78,10 @@ __device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, const K
       const int len = hi[s] - lo[s];
       chunk[s] = (len + 63) >> 6;
       const long long first = (long long)lo[s] + (long long)lane * chunk[s];
-      pred[s] = false;
-      if (len > 0 && first < hi[s]) {
-        const long long idx = min(first + chunk[s] - 1, (long long)hi[s] - 1);
-        const KeyT v = keys[idx];
-        pred[s] = upper[s] ? (v <= q[s]) : (v < q[s]);
-      }
+      // clamped, unconditional load: all S loads of a round are issued back to back
+      const long long idx = max(0ll, min(min(first + chunk[s] - 1, (long long)hi[s] - 1), (long long)n - 1));
+      const KeyT v = keys[idx];
+      pred[s] = len > 0 && first < hi[s] && (upper[s] ? (v <= q[s]) : (v < q[s]));
     }
 #pragma unroll
     for (int s = 0; s < S; ++s) {
@@ -92,7 +103,7 @@ __device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, const K
   for (int s = 0; s < S; ++s) res[s] = lo[s];
 }
 
-// Per-lane lower bound in a window of wsz keys.
+// Per-lane lower bound in a window of wsz keys (used for windows that stay in global memory).
 template <typename KeyT, typename Ptr>
 __device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
   int lo = 0, len = wsz;
@@ -105,22 +116,7 @@ __device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
   return lo;
 }
 
-// Resolves the K z-consecutive queries of one (output voxel, group) pair: one search
-// for the smallest z, then at most one comparison per further query on consecutive
-// positions (valid because keys are sorted integers whose z components are multiples
-// of the input stride, Section 5.2).
-template <typename KeyT, int K, typename Ptr>
-__device__ inline void resolve_group(Ptr win, int wsz, int wlo, KeyT q0, KeyT zstep, int zrev, int32_t (&res)[K]) {
-  int pos = lane_lower_bound<KeyT>(win, wsz, q0);
-#pragma unroll
-  for (int t = 0; t < K; ++t) {
-    const KeyT qt = q0 + KeyT(t) * zstep;
-    const bool hit = pos < wsz && win[pos] == qt;
-    const int iz = zrev ? K - 1 - t : t;
-    res[iz] = hit ? wlo + pos : -1;
-    pos += hit ? 1 : 0;
-  }
-}
+constexpr int SEARCH_GB = 5;  // groups whose LDS searches one lane keeps in flight together
 
 template <typename KeyT, int K>
 __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
@@ -135,7 +131,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   extern __shared__ __align__(16) unsigned char smem[];
   KeyT* okeys = reinterpret_cast<KeyT*>(smem);   // [tile]
   KeyT* win = okeys + tile;                      // [WIN_CAP]
-  __shared__ int s_wlo[G], s_wsz[G], s_woff[G];
+  __shared__ int s_wlo[G], s_wsz[G], s_woff[G], s_wend[G + 1];
   __shared__ int s_bound[2 * G];
   __shared__ int s_cnt[K3];
   __shared__ unsigned s_mask[MAX_BLOCKS * MW];
@@ -148,6 +144,11 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const int rows = min(tile, n_out - i0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
+  // first-round probes of the wave-wide searches (the same 64 keys for everybody: L2-resident)
+  const int chunk0 = (n_in + 63) >> 6;
+  KeyT probe = 0;
+  if (n_in > 0 && (long long)lane * chunk0 < n_in) probe = in_keys[min((long long)(lane + 1) * chunk0 - 1, (long long)n_in - 1)];
+
   for (int v = tid; v < rows; v += SEARCH_THREADS) okeys[v] = out_keys[i0 + v];
   for (int k = tid; k < K3; k += SEARCH_THREADS) s_cnt[k] = 0;
   for (int k = tid; k < MAX_BLOCKS * MW; k += SEARCH_THREADS) s_mask[k] = 0u;
@@ -158,8 +159,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const KeyT kfirst = okeys[0], klast = okeys[rows - 1];
   const KeyT zspan = KeyT(K - 1) * sp.zstep;
 
-  // ---- window bounds: search s = 2*g + side, dealt round-robin to the waves, 4 at a time
-  constexpr int S = 4;
+  // ---- window bounds: search s = 2*g + side, dealt round-robin to the waves, S at a time
+  constexpr int S = (2 * G + NW - 1) / NW < 5 ? (2 * G + NW - 1) / NW : 5;
   for (int s0 = wave * S; s0 < 2 * G; s0 += NW * S) {
     KeyT q[S];
     bool up[S];
@@ -167,12 +168,11 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
     for (int j = 0; j < S; ++j) {
       const int s = min(s0 + j, 2 * G - 1);
-      const int g = s >> 1;
-      const KeyT d = s_gd[g];
+      const KeyT d = s_gd[s >> 1];
       up[j] = (s & 1) != 0;
       q[j] = up[j] ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
     }
-    wave_bounds<KeyT, S>(in_keys, n_in, q, up, res);
+    wave_bounds<KeyT, S>(in_keys, n_in, probe, q, up, res);
     if (lane < S && s0 + lane < 2 * G) {
       int r = res[0];
 #pragma unroll
@@ -182,53 +182,119 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   }
   __syncthreads();
 
-  // ---- window placement in LDS (first fit in group order; the rest stay in global memory)
-  if (tid == 0) {
-    int used = 0;
-    for (int g = 0; g < G; ++g) {
-      const int lo = s_bound[2 * g], sz = max(0, s_bound[2 * g + 1] - lo);
-      s_wlo[g] = lo;
-      s_wsz[g] = sz;
-      if (used + sz <= WIN_CAP) {
-        s_woff[g] = used;
-        used += sz;
-      } else {
-        s_woff[g] = -1;
-      }
+  // ---- window placement in LDS: a prefix sum over the groups by wave 0; groups whose window
+  // ends beyond the LDS budget stay in global memory
+  if (wave == 0) {
+    const int lo = lane < G ? s_bound[2 * lane] : 0;
+    const int sz = lane < G ? max(0, s_bound[2 * lane + 1] - lo) : 0;
+    int incl = sz;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int y = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += y;
     }
-  }
-  __syncthreads();
-  for (int g = 0; g < G; ++g) {
-    const int off = s_woff[g];
-    if (off < 0) continue;
-    const int lo = s_wlo[g], sz = s_wsz[g];
-    for (int e = tid; e < sz; e += SEARCH_THREADS) win[off + e] = in_keys[lo + e];
+    if (lane < G) {
+      const bool fits = incl <= WIN_CAP;
+      s_wlo[lane] = lo;
+      s_wsz[lane] = sz;
+      s_woff[lane] = fits ? incl - sz : -1;
+      s_wend[lane + 1] = fits ? incl : -1;
+    }
+    if (lane == 0) s_wend[0] = 0;
   }
   __syncthreads();
 
-  // ---- per-lane searches.  Work item w = g*tile + v: a wave holds 64 consecutive output
-  // voxels of ONE group, so all its lanes search the same window and every store of the
-  // blocked map M[block][k][32] is two full 128-byte segments.
+  // ---- staging, flattened over all windows that fit: element e of the concatenation belongs to
+  // the group g with wend[g] <= e < wend[g+1]; loads are issued four at a time per thread
+  int total = 0;
+  for (int g = 0; g < G; ++g) total = max(total, s_wend[g + 1]);
+  for (int e0 = 0; e0 < total; e0 += 4 * SEARCH_THREADS) {
+    KeyT tmp[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = e0 + i * SEARCH_THREADS + tid;
+      tmp[i] = 0;
+      if (e < total) {
+        int g = 0;
+        while (g + 1 < G && s_wend[g + 1] >= 0 && e >= s_wend[g + 1]) ++g;
+        tmp[i] = in_keys[s_wlo[g] + (e - s_woff[g])];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = e0 + i * SEARCH_THREADS + tid;
+      if (e < total) win[e] = tmp[i];
+    }
+  }
+  __syncthreads();
+
+  // ---- per-lane searches.  A wave holds 64 consecutive output voxels; a lane runs the lower
+  // bounds of up to SEARCH_GB groups interleaved (independent LDS chains hide each other's
+  // latency) with the branch-free bit-stepping form, whose trip count depends only on the window
+  // sizes.  Every store into the blocked map M[block][k][32] is two full 128-byte segments.
   const int64_t b0 = int64_t(i0) >> 5;
   const int rows32 = (rows + 31) & ~31;
-  for (int w = tid; w < G * tile; w += SEARCH_THREADS) {
-    const int g = w / tile, v = w - g * tile;  // g is uniform in the wave (tile is a multiple of 64)
-    const bool act = v < rows;
-    const KeyT q0 = act ? KeyT(okeys[v] + s_gd[g]) : KeyT(0);
-    const int off = s_woff[g], wlo = s_wlo[g], wsz = act ? s_wsz[g] : 0;
-    int32_t r[K];
-    if (off >= 0) resolve_group<KeyT, K>(win + off, wsz, wlo, q0, sp.zstep, sp.zrev, r);
-    else resolve_group<KeyT, K>(in_keys + wlo, wsz, wlo, q0, sp.zstep, sp.zrev, r);
-    const int bl = v >> 5;
+  const int parts = SEARCH_THREADS / tile;         // threads per output voxel
+  const int v = tid % tile, part = tid / tile;     // part is uniform in a wave (tile is a multiple of 64)
+  const bool act = v < rows;
+  const KeyT okey = act ? okeys[v] : KeyT(0);
+  const int bl = v >> 5;
+  for (int gb = part; gb < G; gb += parts * SEARCH_GB) {
+    int pos[SEARCH_GB], gidx[SEARCH_GB], wsz[SEARCH_GB], woff[SEARCH_GB];
+    KeyT q0[SEARCH_GB];
+    int maxw = 0;
+#pragma unroll
+    for (int j = 0; j < SEARCH_GB; ++j) {
+      const int g = gb + j * parts;
+      gidx[j] = g < G ? g : -1;
+      const int gc = g < G ? g : 0;
+      woff[j] = s_woff[gc];
+      wsz[j] = (g < G && act) ? s_wsz[gc] : 0;
+      q0[j] = okey + s_gd[gc];
+      pos[j] = 0;
+      if (g < G && woff[j] >= 0) maxw = max(maxw, s_wsz[gc]);
+    }
+    // lower bounds in LDS: pos += bit while the key before pos+bit is smaller than the query
+    for (int bit = maxw > 0 ? 1 << (31 - __clz(maxw)) : 0; bit > 0; bit >>= 1) {
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j) {
+        const int p = pos[j] + bit;
+        if (woff[j] >= 0 && p <= wsz[j] && win[woff[j] + p - 1] < q0[j]) pos[j] = p;
+      }
+    }
+    // global-memory windows (rare): plain per-lane lower bound
+#pragma unroll
+    for (int j = 0; j < SEARCH_GB; ++j)
+      if (gidx[j] >= 0 && woff[j] < 0) pos[j] = lane_lower_bound<KeyT>(in_keys + s_wlo[gidx[j]], wsz[j], q0[j]);
+    // the K z-consecutive queries of each group, from the position of the smallest-z one: at most
+    // one comparison per query on consecutive positions (keys are sorted integers whose z
+    // components are multiples of the input stride, Section 5.2); the groups' reads interleave
+    int32_t r[SEARCH_GB][K];
 #pragma unroll
     for (int t = 0; t < K; ++t) {
-      const int k = g * K + t;
-      if (v < rows32) M[((b0 + bl) * K3 + k) * 32 + (v & 31)] = r[t];  // rows past the end hold -1
-      const unsigned long long hit = __ballot(r[t] >= 0);
-      if (hit) {
-        if (lane == 0 && unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
-        if (lane == 32 && unsigned(hit >> 32)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
-        if (tile_counts && lane == 0) atomicAdd(&s_cnt[k], __popcll(hit));
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j) {
+        const int g = gidx[j] < 0 ? 0 : gidx[j];
+        const KeyT qt = q0[j] + KeyT(t) * sp.zstep;
+        bool hit = false;
+        if (pos[j] < wsz[j]) hit = (woff[j] >= 0 ? win[woff[j] + pos[j]] : in_keys[s_wlo[g] + pos[j]]) == qt;
+        r[j][sp.zrev ? K - 1 - t : t] = hit ? s_wlo[g] + pos[j] : -1;
+        pos[j] += hit ? 1 : 0;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < SEARCH_GB; ++j) {
+      const int g = gidx[j];
+      if (g < 0) continue;  // uniform in the wave
+#pragma unroll
+      for (int t = 0; t < K; ++t) {
+        const int k = g * K + t;
+        if (v < rows32) M[((b0 + bl) * K3 + k) * 32 + (v & 31)] = r[j][t];  // rows past the end hold -1
+        const unsigned long long hit = __ballot(r[j][t] >= 0);
+        if (hit) {
+          if (lane == 0 && unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
+          if (lane == 32 && unsigned(hit >> 32)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
+          if (tile_counts && lane == 0) atomicAdd(&s_cnt[k], __popcll(hit));
+        }
       }
     }
   }
