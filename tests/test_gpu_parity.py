@@ -34,6 +34,15 @@ def _cloud(name):
         return synth.random_cloud(128 * 5 + 1, (30, 30, 30), seed=4)
     if name == "one":
         return np.array([[0, 5, 6, 7]], np.int32)
+    if name in ("slab_3k", "slab_12k"):
+        # a dense two-voxel-thick slab in a wide scene: thousands of keys share the sort's top bits
+        ny = 25 if name == "slab_3k" else 100
+        g = np.stack(np.meshgrid(np.arange(500, 502), np.arange(ny), np.arange(60), indexing="ij"), -1).reshape(-1, 3)
+        far = np.array([[0, 0, 0], [1000, 3, 7], [250, 90, 59]])
+        c = np.concatenate([g, far]).astype(np.int32)
+        c = np.concatenate([np.zeros((len(c), 1), np.int32), c], 1)
+        np.random.default_rng(12).shuffle(c, axis=0)
+        return c
     raise KeyError(name)
 
 
@@ -51,7 +60,8 @@ def _check_map(c0_sorted, keys_t, desc, K, s_p, s_l, transposed, kmap):
 
 
 # ----------------------------------------------------------------------------- pack + sort
-@pytest.mark.parametrize("name,key_bits", [("tiny", 0), ("tiny_neg", 0), ("rand_b3", 0), ("rand_b3", 64), ("one", 0)])
+@pytest.mark.parametrize("name,key_bits", [("tiny", 0), ("tiny_neg", 0), ("rand_b3", 0), ("rand_b3", 64), ("one", 0),
+                                           ("slab_3k", 0), ("slab_12k", 0), ("slab_12k", 64), ("ragged", 64)])
 def test_pack_sort_matches_oracle(name, key_bits):
     c = _cloud(name)
     desc = fit_desc(c, [(3, 1, 2)], key_bits)
