@@ -27,6 +27,21 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 PEAK_FP32_TFLOPS = 157.3
 
 
+def _recorded_traffic(cfg: int, kernel: str):
+    """HBM bytes per launch of the dominant kernel, as measured by the rocprofv3 --pmc runs whose
+    summary is kept under profiles/ (a line 'traffic_bytes_per_launch <kernel> <bytes>')."""
+    path = os.path.join(ROOT, "profiles", "cfg%d_pmc_traffic.txt" % cfg)
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) == 3 and t[0] == "traffic_bytes_per_launch" and t[1] == kernel:
+                    return float(t[2])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -36,6 +51,8 @@ def main() -> int:
     ap.add_argument("--dataflow", default="auto", choices=["auto", "os", "ws"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--copy-probe-mb", type=int, default=0,
+                    help="run one plain device copy of this many MiB before the warm-up (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -109,6 +126,15 @@ def main() -> int:
             marks[5].record()
         km.destroy()
 
+    if args.copy_probe_mb > 0:
+        # plain copy kernel (spc_permute_rows with the identity permutation): reads and writes a known byte count
+        rows = args.copy_probe_mb * 1024 * 1024 // 256
+        src = torch.ones((rows, 128), dtype=torch.float16, device=dev)
+        ident = torch.arange(rows, dtype=torch.int32, device=dev)
+        B.spc_permute_rows(src, ident)
+        torch.cuda.synchronize()
+        del src, ident
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -149,9 +175,11 @@ def main() -> int:
                 "achieved": conv_tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
                 "frac": conv_tflops / PEAK_FP32_TFLOPS, "traffic": None}
     else:
-        roof = {"kernel": "conv_%s_mfma_kernel" % ("os" if dataflow == B.DATAFLOW_OS else "ws"), "bound": "mfma",
+        roof = {"kernel": "conv_os_phase_kernel" if dataflow == B.DATAFLOW_OS else "conv_ws_mfma_kernel", "bound": "mfma",
                 "achieved": conv_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                 "frac": conv_tflops / PEAK_MFMA_F16_TFLOPS, "traffic": None}
+
+    roof["traffic"] = _recorded_traffic(args.config, roof["kernel"])
 
     result = {
         "metric": "SpC layer hot path (pack+sort, kmap build, feature computation) Mvoxel-offsets/s",
