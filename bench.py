@@ -42,12 +42,93 @@ def _recorded_traffic(cfg: int, kernel: str):
     return None
 
 
+def bench_network(args, torch, B, synth) -> int:
+    """Configuration 4: the 25-layer UNet-style stack.  A step = pack+sort, feature-row permutation,
+    network-wide kernel-map build on four HIP streams, and the 25 feature computations."""
+    from paper_2511_20834_amd.network import SpcNetwork
+    dev = torch.device("cuda:0")
+    coords_np = synth.cloud("lidar")
+    n = coords_np.shape[0]
+    layers = synth.unet_layers()
+    W_np = synth.unet_weights(layers)
+    F_np = synth.features(n, 4, np.float16, seed=synth.SEED_BASE + 300)
+    desc = B.spc_pack_desc_fit(coords_np[:, 1:].min(0), coords_np[:, 1:].max(0), 1, 16, 16)
+    coords = torch.from_numpy(coords_np).to(dev)
+    F_raw = torch.from_numpy(F_np).to(dev)
+    net = SpcNetwork(layers, [torch.from_numpy(w).to(dev) for w in W_np], dataflow=B.DATAFLOW_OS)
+    ws = torch.empty(B.spc_pack_workspace_bytes(n, desc), dtype=torch.uint8, device=dev)
+    keys = torch.empty(n, dtype=torch.int32, device=dev)
+    perm = torch.empty(n, dtype=torch.int32, device=dev)
+    F = torch.empty_like(F_raw)
+    streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(flags=0, marks=None, forward=True):
+        if marks:
+            marks[0].record()
+        B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+        B.spc_permute_rows(F_raw, perm, F)
+        if marks:
+            marks[1].record()
+        net.build_maps(keys, desc, streams, flags)
+        if marks:
+            marks[2].record()
+        y = net.forward(F) if forward else None
+        if marks:
+            marks[3].record()
+        net.destroy_maps()
+        return y
+
+    # sizes (fetched once; they do not change between steps)
+    B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+    maps = net.build_maps(keys, desc, streams)
+    vo = sum(m.n_out * m.kvol for m in maps)
+    flops = sum(2.0 * float(m.nnz().sum()) * l["cin"] * l["cout"] for m, l in zip(maps, layers))
+    level_sizes = sorted({(l["in_stride"], m.n_in if not l["transposed"] else m.n_out) for m, l in zip(maps, layers)})
+    net.destroy_maps()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    part = {}
+    for name, flags in (("streams", 0), ("sequential", B.NET_SEQUENTIAL)):
+        marks = [[ev() for _ in range(4)] for _ in range(min(args.steps, 30))]
+        for m in marks:
+            step(flags, m)
+        torch.cuda.synchronize()
+        part["build_ms_" + name] = float(np.mean([m[1].elapsed_time(m[2]) for m in marks]))
+        part["forward_ms"] = float(np.mean([m[2].elapsed_time(m[3]) for m in marks]))
+        part["pack_sort_permute_ms"] = float(np.mean([m[0].elapsed_time(m[1]) for m in marks]))
+    part["build_speedup_streams_over_sequential"] = part["build_ms_sequential"] / part["build_ms_streams"]
+    part["forward_useful_TFLOPs"] = flops / (part["forward_ms"] * 1e-3) / 1e12
+    result = {
+        "metric": "SpC UNet-style stack (pack+sort, network-wide kmap build, 25 feature layers) Mvoxel-offsets/s",
+        "value": vo / (ms_per_step * 1e-3) / 1e6, "unit": "Mvoxel-offsets/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "cfg4: lidar cloud, %d voxels, 25-layer UNet-style stack, 13 kernel maps on 4 streams, OS dataflow" % n,
+                   "n_voxels": n, "levels": level_sizes, "voxel_offsets": vo, "useful_flops": flops},
+        "parts": part,
+        "roofline": {"kernel": "conv_os_phase_kernel", "bound": "mfma", "achieved": part["forward_useful_TFLOPs"],
+                     "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": part["forward_useful_TFLOPs"] / PEAK_MFMA_F16_TFLOPS,
+                     "traffic": None},
+    }
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--dataflow", default="auto", choices=["auto", "os", "ws"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -67,6 +148,8 @@ def main() -> int:
         return 3
     B.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    if args.config == 4:
+        return bench_network(args, torch, B, synth)
     cfg = synth.CONFIGS[args.config]
     K, s_l, cin, cout = cfg["K"], cfg["layer_stride"], cfg["cin"], cfg["cout"]
     K3 = K ** 3
@@ -76,7 +159,7 @@ def main() -> int:
     F_np, W_np = synth.layer_tensors(args.config, n)
     dataflow = {"os": B.DATAFLOW_OS, "ws": B.DATAFLOW_WS}.get(args.dataflow)
     if dataflow is None:
-        dataflow = B.DATAFLOW_WS if args.config == 3 else B.DATAFLOW_OS
+        dataflow = B.DATAFLOW_OS  # with per-block offset skipping OS wins on all four single-layer configurations
     layout = B.LAYOUT_OS if dataflow == B.DATAFLOW_OS else B.LAYOUT_WS
 
     lo, hi = coords_np[:, 1:].min(0), coords_np[:, 1:].max(0)

@@ -53,6 +53,9 @@ extern "C" {
 #define SPC_PACK_VALIDATE 1 /* spc_pack_coords: check ranges and duplicates, wait, report */
 #define SPC_CONV_RELU 1     /* spc_conv_forward: apply max(x,0) before the output is stored */
 #define SPC_CONV_PACKED_WEIGHTS 2 /* spc_conv_forward: `weights` came from spc_conv_prepare_weights */
+#define SPC_CONV_OS_PHASE 4  /* spc_conv_forward, OS, 16-bit types: force the LDS-staged phase kernel */
+#define SPC_CONV_OS_SPLITK 8 /* spc_conv_forward, OS, 16-bit types: force the split-k kernel */
+#define SPC_CONV_SPLITK_RB(rb) ((rb) << 8) /* with SPC_CONV_OS_SPLITK: 32-row blocks per workgroup (1, 2, 4; 0 = by size) */
 #define SPC_NET_SEQUENTIAL 1 /* spc_build_kmaps_network: one stream, level by level (for comparison) */
 
 /*
@@ -185,7 +188,13 @@ void spc_kmap_destroy(spc_kmap* m);
  *             to nearest even.  SPC_DTYPE_F32: fp32 FMA arithmetic throughout.
  *   dataflow  SPC_DATAFLOW_OS needs the OS layout, SPC_DATAFLOW_WS the WS layout
  *             (Section 2.2).  OS results are bit-reproducible; WS uses fp32 atomics.
- *   flags     SPC_CONV_RELU.
+ *   flags     SPC_CONV_RELU; SPC_CONV_PACKED_WEIGHTS (see spc_conv_prepare_weights);
+ *             SPC_CONV_OS_PHASE or SPC_CONV_OS_SPLITK pick one of the two OS MFMA kernels
+ *             (default: chosen from the layer's size; both give the same result up to the
+ *             fp32 summation order, and each one alone is bit-reproducible).
+ * 16-bit layers with cout % 32 == 0 (OS) or cout in {32,64,128,256} (WS) run on MFMA; input
+ * channel counts that are not a multiple of 16, and rows that are not 16-byte aligned, are
+ * first copied into a zero-padded scratch buffer.  Everything else runs plain FMA kernels.
  * Nothing is waited for.
  */
 int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
@@ -196,8 +205,9 @@ int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const voi
  * Weights are constant during inference, so their re-layout into MFMA operand order can
  * be hoisted out of the layer call.  Writes K^3*cin*cout elements to packed_out [device]
  * (same dtype) for use with SPC_CONV_PACKED_WEIGHTS.  Returns SPC_ERR_UNSUPPORTED for the
- * shapes/dtypes that do not run on the MFMA kernels (fp32, cin % 16 != 0, cout not in
- * {32,64,128,256}); those layers take the plain [K^3][cin][cout] weights only.
+ * shapes/dtypes that do not take prepacked weights (fp32, cin % 16 != 0, cout % 32 != 0);
+ * those layers take the plain [K^3][cin][cout] weights only.  The WS dataflow accepts
+ * prepacked weights for cout in {32,64,128,256}.
  */
 int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32_t cin, int32_t cout, int32_t dtype,
                              void* packed_out, void* stream);

@@ -21,6 +21,8 @@ DATAFLOW_OS, DATAFLOW_WS = 0, 1
 PACK_VALIDATE = 1
 CONV_RELU = 1
 CONV_PACKED_WEIGHTS = 2
+CONV_OS_PHASE = 4
+CONV_OS_SPLITK = 8
 NET_SEQUENTIAL = 1
 ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -4, -5, -6
 

@@ -16,6 +16,7 @@
 
 #include <algorithm>
 #include <type_traits>
+#include <utility>
 
 #include "spc_internal.h"
 
@@ -43,13 +44,26 @@ __device__ inline float to_f32(T v) { return static_cast<float>(v); }
 template <typename T>
 __device__ inline T from_f32(float v) { return static_cast<T>(v); }  // round to nearest even
 
+// f(integral_constant<int,0>) ... f(integral_constant<int,N-1>): loops whose index must be a
+// compile-time constant (register arrays that are never indexed dynamically)
+template <int... S, typename Fn>
+__device__ inline void static_for_impl(std::integer_sequence<int, S...>, Fn&& f) {
+  (f(std::integral_constant<int, S>{}), ...);
+}
+template <int N, typename Fn>
+__device__ inline void static_for(Fn&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
 constexpr int CONV_THREADS = 256;
 constexpr int CK = 64;  // input channels staged per step
 
 // W [K3][cin][cout]  ->  Wp [K3][cin/16][cout/32][64 lanes][8]: lane l holds channels
 // 16*kk + 8*(l/32) + 0..7 of output column 32*nb + l%32 (the B operand of one MFMA).
+// Input channels cin_src..cin-1 (padding up to a multiple of 16) are written as zeros.
 template <typename T>
-__global__ __launch_bounds__(256) void prepack_weights_kernel(const T* __restrict__ W, T* __restrict__ Wp, int K3, int cin, int cout) {
+__global__ __launch_bounds__(256) void prepack_weights_kernel(const T* __restrict__ W, T* __restrict__ Wp, int K3, int cin_src,
+                                                              int cin, int cout) {
   const int KK = cin / 16, NB = cout / 32;
   const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   const int64_t total = int64_t(K3) * KK * NB * 64;
@@ -60,10 +74,22 @@ __global__ __launch_bounds__(256) void prepack_weights_kernel(const T* __restric
   t /= NB;
   const int kk = t % KK;
   const int k = t / KK;
-  const T* src = W + (int64_t(k) * cin + kk * 16 + 8 * (lane >> 5)) * cout + nb * 32 + (lane & 31);
+  const int c0 = kk * 16 + 8 * (lane >> 5);
+  const T* src = W + (int64_t(k) * cin_src + c0) * cout + nb * 32 + (lane & 31);
   T* dst = Wp + gid * 8;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) dst[j] = src[int64_t(j) * cout];
+  for (int j = 0; j < 8; ++j) dst[j] = c0 + j < cin_src ? src[int64_t(j) * cout] : T(0);
+}
+
+// Feature rows padded with zeros to a multiple of 16 channels (layers such as a 4-channel stem).
+template <typename T>
+__global__ __launch_bounds__(256) void pad_rows_kernel(const T* __restrict__ F, int64_t ld_in, int n_h, const int* __restrict__ n_d,
+                                                       int cin, int cin_pad, T* __restrict__ out) {
+  const int n = n_d ? *n_d : n_h;
+  const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+  const int64_t r = gid / cin_pad;
+  const int c = static_cast<int>(gid - r * cin_pad);
+  if (r < n) out[gid] = c < cin ? F[r * ld_in + c] : T(0);
 }
 
 // Shared inner step: stage nkk*NB B-fragments of offset k, channels [c0, c0+16*nkk), then
@@ -141,7 +167,7 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
                                                                    const T* __restrict__ F, int64_t ld_in,
                                                                    const T* __restrict__ Wp, T* __restrict__ out,
                                                                    int64_t ld_out, int cin, int relu, int chunks_per_phase,
-                                                                   int n_wg_per_xcd) {
+                                                                   int n_wg_per_xcd, int nb_total) {
   using V8 = typename Mfma<T>::V8;
   constexpr int CKS = 16 * NKK;
   constexpr int THREADS = 64 * WAVES;
@@ -154,6 +180,10 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   int16_t* klist = reinterpret_cast<int16_t*>(smem + 2 * HALF_BYTES) + wave * KLIST_CAP;
   const int n_out = n_out_d ? *n_out_d : n_out_h;
   const int64_t n_blocks = (int64_t(n_out) + 31) >> 5;
+  // blockIdx.y selects a slab of NB*32 output channels; the staged weights and everything below
+  // then look exactly like a layer with that many output channels
+  const int slab = blockIdx.y;
+  out += slab * (NB * 32);
   // tile = RB adjacent blocks; tile t -> (XCD range, workgroup within the XCD, wave)
   const int n_wg = n_wg_per_xcd * 8;
   const int wg = (blockIdx.x & 7) * n_wg_per_xcd + (blockIdx.x >> 3);
@@ -173,9 +203,14 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   auto stage_load = [&](int c_lo) {
     const int hi = min(n_chunks, c_lo + chunks_per_phase);
     const int n_vec = static_cast<int>(int64_t(hi - c_lo) * CKS * cout / 8);
-    const V8* src = reinterpret_cast<const V8*>(Wp + int64_t(c_lo) * CKS * cout);
+    // vector v of the phase, in slab view [chunk][kk][nb][lane], comes from [.][.][nb_total][lane] in memory
+    const V8* src = reinterpret_cast<const V8*>(Wp);
 #pragma unroll
-    for (int i = 0; i < SV; ++i) st[i] = src[min(i * THREADS + tid, n_vec - 1)];
+    for (int i = 0; i < SV; ++i) {
+      const int v = min(i * THREADS + tid, n_vec - 1);
+      const int t = v >> 6, nbs = t % NB, kkg = t / NB;
+      st[i] = src[((int64_t(c_lo) * NKK + kkg) * nb_total + slab * NB + nbs) * 64 + (v & 63)];
+    }
   };
   auto stage_store = [&](int c_lo, V8* half) {
     const int hi = min(n_chunks, c_lo + chunks_per_phase);
@@ -366,6 +401,186 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   }
 }
 
+// Output-stationary kernel for layers whose weight traffic is small next to the chip's L2
+// bandwidth (few output voxels, or few channels): one workgroup per block of 32 output voxels
+// and slab of NB*32 output channels, and the offsets present in the block are dealt round-robin
+// to the workgroup's four waves (a split of the reduction over k, Eq. (2)).  Nothing is staged
+// through LDS and no barrier sits inside the loop: a wave reads the B fragments of its offsets
+// straight from the prepacked weights (1 KB coalesced per fragment, L2-resident) next to the
+// gathered A rows, D (offset, 16-channel slab) entries ahead of the MFMA that consumes them.
+// The four partial accumulators meet in LDS and are summed in wave order, so results stay
+// bit-reproducible; the sum leaves LDS transposed, each thread storing consecutive channels of
+// one row.  Compared with the phase kernel this trades redundant weight reads (every block
+// re-reads its offsets' weights) for many more, much shorter dependency chains, which is what
+// the coarse levels of a network need: there a layer has fewer row blocks than the chip has
+// compute units.
+constexpr int SPLITK_WAVES = 4;
+constexpr int SPLITK_KL_CAP = 96;  // >= ceil(7^3 / 4) + 1
+
+template <typename T, int NB, int RB, int D>
+__global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const int32_t* __restrict__ M,
+                                                                          const uint32_t* __restrict__ block_masks,
+                                                                          int mask_words, int n_out_h,
+                                                                          const int* __restrict__ n_out_d, int K3,
+                                                                          const T* __restrict__ F, int64_t ld_in,
+                                                                          const T* __restrict__ Wp, T* __restrict__ out,
+                                                                          int64_t ld_out, int cin, int relu, int nb_total,
+                                                                          int vec_store) {
+  using V8 = typename Mfma<T>::V8;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int64_t n_blocks = (int64_t(n_out) + 31) >> 5;
+  const int64_t blk0 = int64_t(blockIdx.x) * RB;
+  if (blk0 >= n_blocks) return;  // whole workgroup
+  const int slab = blockIdx.y;
+  const int KK = cin / 16;
+  const int idx_rows = (K3 + SPLITK_WAVES - 1) / SPLITK_WAVES + 1;  // per wave, with the all-invalid row at the end
+  int32_t* sIdx = reinterpret_cast<int32_t*>(smem) + wave * idx_rows * (RB * 32);
+  int16_t* kl = reinterpret_cast<int16_t*>(smem + size_t(SPLITK_WAVES) * idx_rows * (RB * 128)) + wave * SPLITK_KL_CAP;
+
+  // this wave's offsets: those present in the tile (union of the builder's block masks) whose
+  // rank is wave mod 4
+  int cnt = 0;
+  for (int wd = 0; wd < mask_words; ++wd) {
+    unsigned m = 0;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      if (blk0 + rb < n_blocks) m |= block_masks[(blk0 + rb) * mask_words + wd];
+    m = __builtin_amdgcn_readfirstlane(m);
+    if (lane < 32 && ((m >> lane) & 1u)) {
+      const int rank = cnt + __builtin_popcount(m & ((1u << lane) - 1u));
+      if ((rank & (SPLITK_WAVES - 1)) == wave) kl[rank / SPLITK_WAVES] = static_cast<int16_t>(wd * 32 + lane);
+    }
+    cnt += __builtin_popcount(m);
+  }
+  const int n_i = cnt > wave ? (cnt - wave + SPLITK_WAVES - 1) / SPLITK_WAVES : 0;
+  if (lane == 0) kl[n_i] = 0;  // entries past the end read offset 0's weights (never multiplied)
+  __builtin_amdgcn_wave_barrier();
+  // their map rows (32 input indices per block), eight (offset, block) pairs per pass:
+  // lane -> (pair, 4 rows); blocks past the end of the level count as all-invalid
+  {
+    const int part = lane & 7;
+    for (int p = lane >> 3; p < n_i * RB; p += 8) {
+      const int i = p / RB, rb = p % RB;
+      int4 v = {-1, -1, -1, -1};
+      if (blk0 + rb < n_blocks)
+        v = *reinterpret_cast<const int4*>(M + ((blk0 + rb) * int64_t(K3) + kl[i]) * 32 + part * 4);
+      *reinterpret_cast<int4*>(sIdx + p * 32 + part * 4) = v;
+    }
+    for (int q = lane; q < RB * 32; q += 64) sIdx[n_i * RB * 32 + q] = -1;
+  }
+  __builtin_amdgcn_wave_barrier();
+
+  floatx16 acc[RB][NB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
+
+  // entry e = (i-th offset of this wave, 16-channel slab kk), kk fastest
+  const int n_entries = n_i * KK;
+  const T* zero_row = reinterpret_cast<const T*>(g_zero_row) + 8 * lh;
+  const V8* Wv = reinterpret_cast<const V8*>(Wp) + int64_t(slab) * NB * 64 + lane;
+  V8 a[D][RB];
+  V8 b[D][NB];
+  int i_n = 0, kk_n = 0;
+  int idx_n[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) idx_n[rb] = sIdx[rb * 32 + lr];
+  int k_n = __builtin_amdgcn_readfirstlane(static_cast<int>(kl[0]));
+  auto issue = [&](auto S_) {
+    constexpr int S = decltype(S_)::value;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const T* src = idx_n[rb] < 0 ? zero_row : F + int64_t(idx_n[rb]) * ld_in + kk_n * 16 + 8 * lh;
+      a[S][rb] = *reinterpret_cast<const V8*>(src);
+    }
+    const V8* wsrc = Wv + (int64_t(k_n) * KK + kk_n) * nb_total * 64;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) b[S][nb] = wsrc[nb * 64];
+    if (++kk_n == KK) {
+      kk_n = 0;
+      i_n = min(i_n + 1, n_i);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) idx_n[rb] = sIdx[(i_n * RB + rb) * 32 + lr];
+      k_n = __builtin_amdgcn_readfirstlane(static_cast<int>(kl[i_n]));
+    }
+  };
+  static_for<D>([&](auto S_) { issue(S_); });
+  for (int e0 = 0; e0 < n_entries; e0 += D) {
+    static_for<D>([&](auto S_) {
+      constexpr int S = decltype(S_)::value;
+      if (e0 + S < n_entries) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) acc[rb][nb] = Mfma<T>::mma(a[S][rb], b[S][nb], acc[rb][nb]);
+      }
+      issue(S_);
+    });
+  }
+
+  // The four partial sums meet in one LDS tile (the index area is dead by now): the waves add
+  // theirs in turn, last wave first.  Value (rb, nb, r, lane) sits at float
+  // (((rb*NB + nb)*4 + r/4)*64 + lane)*4 + r%4, so a lane moves four registers per access.
+  float4* red4 = reinterpret_cast<float4*>(smem);
+  for (int w = SPLITK_WAVES - 1; w >= 0; --w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float4* p = red4 + ((rb * NB + nb) * 4 + q) * 64 + lane;
+            float4 t = {acc[rb][nb][4 * q], acc[rb][nb][4 * q + 1], acc[rb][nb][4 * q + 2], acc[rb][nb][4 * q + 3]};
+            if (w != SPLITK_WAVES - 1) {
+              const float4 u = *p;
+              t.x += u.x;
+              t.y += u.y;
+              t.z += u.z;
+              t.w += u.w;
+            }
+            *p = t;
+          }
+    }
+  }
+  __syncthreads();
+  // D layout of the 32x32 MFMA: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+  // Thread t stores EPT consecutive channels of row t/8 of every block.
+  constexpr int EPT = NB * 4;
+  const float* red = reinterpret_cast<const float*>(smem);
+  const int row = tid >> 3, c0 = (tid & 7) * EPT;
+  const int nb = c0 >> 5, cc = c0 & 31;
+  const int q = row >> 3, h = (row & 7) >> 2, rr = row & 3;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int64_t i = (blk0 + rb) * 32 + row;
+    const float* p = red + ((((rb * NB + nb) * 4 + q) * 64) + h * 32 + cc) * 4 + rr;
+    T o[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+      const float v = p[4 * j];
+      o[j] = from_f32<T>(relu ? fmaxf(v, 0.f) : v);
+    }
+    if (i < n_out) {
+      T* dst = out + i * ld_out + slab * (NB * 32) + c0;
+      if (vec_store) {
+        if constexpr (EPT == 8) *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(o);
+        else *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o);
+      } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) dst[j] = o[j];
+      }
+    }
+  }
+}
+
 // Weight-stationary: workgroup = one offset k and 4 x RB blocks of 32 (in,out) pairs;
 // partial sums are merged into an fp32 buffer with hardware float atomics.
 template <typename T, int NB, int RB>
@@ -494,107 +709,210 @@ struct ConvArgs {
   void* out;
   int64_t ld_out;
   int cin, cout, relu, dataflow;
+  int os_variant;  // 0: chosen from the layer's size, 1: phase kernel, 2: split-k kernel
+  int splitk_rb;   // 0: chosen from the layer's size, else row blocks per workgroup (1, 2, 4)
   int n_out_h;
   const int* n_out_d;
   int64_t rows_cap;
   hipStream_t s;
 };
 
+// OS: one grid row of workgroups per slab of NB*32 output channels (NB = 2, or 1 when cout is an
+// odd multiple of 32).  Small slabs keep the accumulators of two row blocks in registers and give
+// the coarse, wide layers of a network enough workgroups to fill the chip.
+template <typename T, int NB>
+static void launch_os_mfma(const ConvArgs& a, const T* Wp) {
+  constexpr int WAVES = 8;
+  constexpr int RBK = 2;  // row blocks per wave
+  constexpr int DEPTH = 2;
+  const int nb_total = a.cout / 32, n_slabs = nb_total / NB;
+  const int64_t n_blocks = (a.rows_cap + 31) / 32;
+  const int64_t n_tiles = (n_blocks + RBK - 1) / RBK;
+  const int64_t tiles_per_xcd = (n_tiles + 7) / 8;
+  const int per_xcd = static_cast<int>((tiles_per_xcd + WAVES - 1) / WAVES);
+  const size_t lds = 2 * HALF_BYTES + size_t(WAVES) * KLIST_CAP * 2;
+  auto go = [&](auto NKK_) {
+    constexpr int NKK = decltype(NKK_)::value;
+    const int cpp = std::max(1, HALF_BYTES / (16 * NKK * NB * 32 * int(sizeof(T))));
+    static bool attr_set = false;  // one per instantiation
+    if (!attr_set) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      attr_set = true;
+    }
+    hipLaunchKernelGGL((conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>), dim3(per_xcd * 8, n_slabs), dim3(64 * WAVES), lds,
+                       a.s, a.m->os_map, a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3,
+                       static_cast<const T*>(a.F), a.ld_in, Wp, static_cast<T*>(a.out), a.ld_out, a.cin, a.relu, cpp, per_xcd,
+                       nb_total);
+  };
+  if (a.cin % 64 == 0) go(std::integral_constant<int, 4>{});
+  else if (a.cin % 32 == 0) go(std::integral_constant<int, 2>{});
+  else go(std::integral_constant<int, 1>{});
+}
+
+static size_t splitk_lds_bytes(int K3, int NB, int RB) {
+  const int idx_rows = (K3 + SPLITK_WAVES - 1) / SPLITK_WAVES + 1;
+  return std::max(size_t(SPLITK_WAVES) * idx_rows * RB * 128 + size_t(SPLITK_WAVES) * SPLITK_KL_CAP * 2,
+                  size_t(RB) * NB * 16 * 64 * 4);
+}
+
 template <typename T, int NB, int RB>
-static void launch_mfma(const ConvArgs& a, const T* Wp, float* accum) {
-  constexpr int TROWS = 128 * RB;
-  const size_t lds = size_t(CK / 16) * NB * 64 * 16;
-  if (a.dataflow == SPC_DATAFLOW_OS) {
-    constexpr int WAVES = 8;
-    constexpr int RBK = NB <= 2 ? 2 : 1;  // blocks per wave
-    constexpr int DEPTH = 2;
-    const int64_t n_blocks = (a.rows_cap + 31) / 32;
-    const int64_t n_tiles = (n_blocks + RBK - 1) / RBK;
-    const int64_t tiles_per_xcd = (n_tiles + 7) / 8;
-    const int per_xcd = static_cast<int>((tiles_per_xcd + WAVES - 1) / WAVES);
-    const size_t lds = 2 * HALF_BYTES + size_t(WAVES) * KLIST_CAP * 2;
-    auto go = [&](auto NKK_) {
-      constexpr int NKK = decltype(NKK_)::value;
-      const int cpp = std::max(1, HALF_BYTES / (16 * NKK * NB * 32 * int(sizeof(T))));
-      static bool attr_set = false;  // one per instantiation
-      if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        attr_set = true;
-      }
-      hipLaunchKernelGGL((conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>), dim3(per_xcd * 8), dim3(64 * WAVES), lds, a.s,
-                         a.m->os_map, a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3,
-                         static_cast<const T*>(a.F), a.ld_in, Wp, static_cast<T*>(a.out), a.ld_out, a.cin, a.relu, cpp, per_xcd);
-    };
-    if (a.cin % 64 == 0) go(std::integral_constant<int, 4>{});
-    else if (a.cin % 32 == 0) go(std::integral_constant<int, 2>{});
-    else go(std::integral_constant<int, 1>{});
-  } else {
-    const int gx = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
-    hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, a.m->K3), dim3(CONV_THREADS), lds, a.s, a.m->ws_in,
-                       a.m->ws_out, a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin);
+static void launch_os_splitk(const ConvArgs& a, const T* Wp) {
+  // about 96 registers of loads in flight per lane; the largest tile keeps two waves per SIMD
+  constexpr int D = (RB == 4 && NB == 2) ? 3 : 24 / (RB + NB);
+  const int nb_total = a.cout / 32, n_slabs = nb_total / NB;
+  const int64_t n_blocks = (a.rows_cap + 31) / 32;
+  const size_t lds = splitk_lds_bytes(a.m->K3, NB, RB);
+  static size_t lds_attr = 64 * 1024;  // one per instantiation
+  if (lds > lds_attr) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    lds_attr = lds;
+  }
+  constexpr int EPT = NB * 4;
+  T* out = static_cast<T*>(a.out);
+  const int vec = a.ld_out % EPT == 0 && reinterpret_cast<uintptr_t>(out) % (EPT * sizeof(T)) == 0;
+  hipLaunchKernelGGL((conv_os_splitk_kernel<T, NB, RB, D>), dim3(static_cast<unsigned>((n_blocks + RB - 1) / RB), n_slabs),
+                     dim3(64 * SPLITK_WAVES), lds, a.s, a.m->os_map, a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d,
+                     a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp, out, a.ld_out, a.cin, a.relu, nb_total, vec);
+}
+
+// Row blocks per workgroup of the split-k kernel: more blocks share each weight fragment read
+// (less L2 traffic) but leave fewer workgroups; small levels need the workgroups.
+static int splitk_rb(const ConvArgs& a, int NB) {
+  const int64_t n_blocks = (a.rows_cap + 31) / 32;
+  int rb = a.splitk_rb ? a.splitk_rb : (n_blocks >= 1024 ? 2 : 1);
+  while (rb > 1 && splitk_lds_bytes(a.m->K3, NB, rb) > 80 * 1024) rb >>= 1;
+  return rb;
+}
+
+template <typename T, int NB>
+static void launch_os_splitk_any(const ConvArgs& a, const T* Wp) {
+  switch (splitk_rb(a, NB)) {
+    case 4: launch_os_splitk<T, NB, 4>(a, Wp); break;
+    case 2: launch_os_splitk<T, NB, 2>(a, Wp); break;
+    default: launch_os_splitk<T, NB, 1>(a, Wp); break;
   }
 }
 
+// Measured crossover on MI355X (3x3x3 layers, 16..256 channels): below about 80k output voxels
+// the phase kernel has too few workgroups to fill the chip and the split-k kernel wins by 1.3-4x;
+// above, the redundant weight reads of the split-k kernel cost more than the phase kernel's
+// barriers.  Large kernels (5x5x5 and up) favour the split-k kernel at every size measured.
+static bool prefer_splitk(const ConvArgs& a) {
+  const int64_t n_blocks = (a.rows_cap + 31) / 32;
+  return n_blocks < 2560 || a.m->K3 > 64;
+}
+
+template <typename T, int NB, int RB>
+static void launch_ws_mfma(const ConvArgs& a, const T* Wp, float* accum) {
+  constexpr int TROWS = 128 * RB;
+  const size_t lds = size_t(CK / 16) * NB * 64 * 16;
+  const int gx = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
+  hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, a.m->K3), dim3(CONV_THREADS), lds, a.s, a.m->ws_in, a.m->ws_out,
+                     a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin);
+}
+
+// Shapes the MFMA kernels run (16-bit types): input channels a multiple of 16 (smaller or ragged
+// counts are zero-padded by the caller below), output channels a multiple of 32 for the OS
+// dataflow and one of 32/64/128/256 for the WS dataflow.
+static bool mfma_shape(int cin, int cout, int dataflow) {
+  if (cin % 16 != 0 || cout % 32 != 0) return false;
+  return dataflow == SPC_DATAFLOW_OS ? true : (cout == 32 || cout == 64 || cout == 128 || cout == 256);
+}
+
 template <typename T>
-static int conv_typed(const ConvArgs& a, bool allow_mfma) {
+static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
+  ConvArgs a = a0;
   const int K3 = a.m->K3;
   const int64_t out_elems = a.rows_cap * a.cout;
+  const bool aligned = a.ld_in % 8 == 0 && reinterpret_cast<uintptr_t>(a.F) % 16 == 0;
+  if (a.packed && !(allow_mfma && mfma_shape(a.cin, a.cout, a.dataflow)))
+    return set_error(SPC_ERR_ARG, "packed weights given for a shape the MFMA kernels do not run");
+  if (a.packed && !aligned) return set_error(SPC_ERR_ARG, "packed weights need 16-byte aligned feature rows");
+  if (a.rows_cap <= 0) return SPC_OK;
+  const int cin_pad = (a.cin + 15) / 16 * 16;
+  // ragged input channel counts and unaligned rows go through a zero-padded copy of the features
+  const bool repack_rows = !a.packed && (cin_pad != a.cin || !aligned);
+  const bool use_mfma = allow_mfma && mfma_shape(cin_pad, a.cout, a.dataflow);
   float* accum = nullptr;
   if (a.dataflow == SPC_DATAFLOW_WS) {
     accum = static_cast<float*>(pool_alloc(std::max<size_t>(size_t(out_elems) * 4 + 16, 256), a.s));
     if (!accum) return SPC_ERR_NOMEM;
     const int64_t n4 = (out_elems + 3) / 4;
-    if (n4 > 0) hipLaunchKernelGGL(zero_f32_kernel, dim3((n4 + 255) / 256), dim3(256), 0, a.s, reinterpret_cast<float4*>(accum), n4);
+    hipLaunchKernelGGL(zero_f32_kernel, dim3((n4 + 255) / 256), dim3(256), 0, a.s, reinterpret_cast<float4*>(accum), n4);
   }
   int rc = SPC_OK;
-  if (a.packed && !(allow_mfma && a.cin % 16 == 0 && (a.cout == 32 || a.cout == 64 || a.cout == 128 || a.cout == 256)))
-    return set_error(SPC_ERR_ARG, "packed weights given for a shape the MFMA kernels do not run");
-  if (a.packed && (a.ld_in % 8 != 0 || reinterpret_cast<uintptr_t>(a.F) % 16 != 0))
-    return set_error(SPC_ERR_ARG, "packed weights need 16-byte aligned feature rows");
-  const bool mfma_ok = allow_mfma && a.cin % 16 == 0 && (a.cout == 32 || a.cout == 64 || a.cout == 128 || a.cout == 256) &&
-                       a.ld_in % 8 == 0 && (reinterpret_cast<uintptr_t>(a.F) % 16 == 0);
-  if (a.rows_cap > 0) {
-    if constexpr (!std::is_same<T, float>::value) {
-     if (mfma_ok) {
-      const T* Wp = static_cast<const T*>(a.W);
-      T* Wtmp = nullptr;
-      if (!a.packed) {
-        Wtmp = static_cast<T*>(pool_alloc(size_t(K3) * a.cin * a.cout * sizeof(T), a.s));
-        if (!Wtmp) {
+  if constexpr (!std::is_same<T, float>::value) {
+    if (use_mfma) {
+      T* Fpad = nullptr;
+      if (repack_rows) {
+        const Level* il = a.m->in_level;
+        const int64_t rows_in = il->n_host < 0 ? il->cap : il->n_host;
+        Fpad = static_cast<T*>(pool_alloc(std::max<size_t>(size_t(rows_in) * cin_pad * sizeof(T), 256), a.s));
+        if (!Fpad) {
           pool_free(accum, a.s);
           return SPC_ERR_NOMEM;
         }
-        const int64_t total = int64_t(K3) * (a.cin / 16) * (a.cout / 32) * 64;
+        const int64_t total = rows_in * cin_pad;
+        if (total > 0)
+          hipLaunchKernelGGL(pad_rows_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, a.s, static_cast<const T*>(a.F), a.ld_in,
+                             static_cast<int>(il->n_host < 0 ? 0 : il->n_host), il->n_host < 0 ? il->n_dev : nullptr, a.cin, cin_pad,
+                             Fpad);
+        a.F = Fpad;
+        a.ld_in = cin_pad;
+      }
+      const T* Wp = static_cast<const T*>(a.W);
+      T* Wtmp = nullptr;
+      if (!a.packed) {
+        Wtmp = static_cast<T*>(pool_alloc(size_t(K3) * cin_pad * a.cout * sizeof(T), a.s));
+        if (!Wtmp) {
+          pool_free(accum, a.s);
+          pool_free(Fpad, a.s);
+          return SPC_ERR_NOMEM;
+        }
+        const int64_t total = int64_t(K3) * (cin_pad / 16) * (a.cout / 32) * 64;
         hipLaunchKernelGGL(prepack_weights_kernel<T>, dim3((total + 255) / 256), dim3(256), 0, a.s, static_cast<const T*>(a.W),
-                           Wtmp, K3, a.cin, a.cout);
+                           Wtmp, K3, a.cin, cin_pad, a.cout);
         Wp = Wtmp;
       }
-      switch (a.cout) {
-        case 32: launch_mfma<T, 1, 2>(a, Wp, accum); break;
-        case 64: launch_mfma<T, 2, 2>(a, Wp, accum); break;
-        case 128: launch_mfma<T, 4, 1>(a, Wp, accum); break;
-        case 256: launch_mfma<T, 8, 1>(a, Wp, accum); break;
+      a.cin = cin_pad;
+      if (a.dataflow == SPC_DATAFLOW_OS) {
+        const bool splitk = a.os_variant == 2 || (a.os_variant == 0 && prefer_splitk(a));
+        if (splitk) {
+          if (a.cout % 64 == 0) launch_os_splitk_any<T, 2>(a, Wp);
+          else launch_os_splitk_any<T, 1>(a, Wp);
+        } else {
+          if (a.cout % 64 == 0) launch_os_mfma<T, 2>(a, Wp);
+          else launch_os_mfma<T, 1>(a, Wp);
+        }
+      } else {
+        switch (a.cout) {
+          case 32: launch_ws_mfma<T, 1, 2>(a, Wp, accum); break;
+          case 64: launch_ws_mfma<T, 2, 2>(a, Wp, accum); break;
+          case 128: launch_ws_mfma<T, 4, 1>(a, Wp, accum); break;
+          case 256: launch_ws_mfma<T, 8, 1>(a, Wp, accum); break;
+        }
       }
-      pool_free(Wtmp, a.s);  // reuse is ordered behind this stream's work
-     }
+      // reuse of these blocks is ordered behind this stream's work
+      pool_free(Wtmp, a.s);
+      pool_free(Fpad, a.s);
     }
-    if (mfma_ok) {
-    } else if (a.dataflow == SPC_DATAFLOW_OS) {
-      const int64_t threads = out_elems;
-      hipLaunchKernelGGL(conv_os_simple_kernel<T>, dim3((threads + 255) / 256), dim3(256), 0, a.s, a.m->os_map, a.n_out_h,
-                         a.n_out_d, K3, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), static_cast<T*>(a.out),
-                         a.ld_out, a.cin, a.cout, a.relu);
-    } else {
-      const int64_t threads = out_elems;  // nnz[k] <= n_out for every offset
-      hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((threads + 255) / 256, K3), dim3(256), 0, a.s, a.m->ws_in, a.m->ws_out,
-                         a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), accum, a.cin,
-                         a.cout);
-    }
-    if (a.dataflow == SPC_DATAFLOW_WS)
-      hipLaunchKernelGGL(finalize_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, accum, a.n_out_h, a.n_out_d, a.cout,
-                         static_cast<T*>(a.out), a.ld_out, a.relu);
   }
+  if (use_mfma) {
+  } else if (a.dataflow == SPC_DATAFLOW_OS) {
+    hipLaunchKernelGGL(conv_os_simple_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, a.m->os_map, a.n_out_h,
+                       a.n_out_d, K3, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), static_cast<T*>(a.out),
+                       a.ld_out, a.cin, a.cout, a.relu);
+  } else {
+    // nnz[k] <= n_out for every offset
+    hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((out_elems + 255) / 256, K3), dim3(256), 0, a.s, a.m->ws_in, a.m->ws_out,
+                       a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), accum, a.cin,
+                       a.cout);
+  }
+  if (a.dataflow == SPC_DATAFLOW_WS)
+    hipLaunchKernelGGL(finalize_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, accum, a.n_out_h, a.n_out_d, a.cout,
+                       static_cast<T*>(a.out), a.ld_out, a.relu);
   pool_free(accum, a.s);
   if (hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "feature kernel launch failed");
   return rc;
@@ -622,6 +940,11 @@ extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in
   a.cout = cout;
   a.relu = (flags & SPC_CONV_RELU) ? 1 : 0;
   a.packed = (flags & SPC_CONV_PACKED_WEIGHTS) ? 1 : 0;
+  if ((flags & SPC_CONV_OS_PHASE) && (flags & SPC_CONV_OS_SPLITK)) return set_error(SPC_ERR_ARG, "two OS kernel variants requested");
+  a.os_variant = (flags & SPC_CONV_OS_PHASE) ? 1 : (flags & SPC_CONV_OS_SPLITK) ? 2 : 0;
+  a.splitk_rb = (flags >> 8) & 7;  // tuning aid: SPC_CONV_OS_SPLITK | (rb << 8)
+  if (a.splitk_rb != 0 && a.splitk_rb != 1 && a.splitk_rb != 2 && a.splitk_rb != 4)
+    return set_error(SPC_ERR_ARG, "row blocks per workgroup must be 1, 2 or 4");
   a.dataflow = dataflow;
   const Level* ol = m->out_level;
   a.n_out_h = static_cast<int>(ol->n_host < 0 ? 0 : ol->n_host);
@@ -640,13 +963,12 @@ extern "C" int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32
                                         void* packed_out, void* stream) {
   using namespace spc;
   if (!weights || !packed_out || kvol < 1) return set_error(SPC_ERR_ARG, "NULL argument or kvol < 1");
-  if ((dtype != SPC_DTYPE_F16 && dtype != SPC_DTYPE_BF16) || cin < 16 || cin % 16 != 0 ||
-      !(cout == 32 || cout == 64 || cout == 128 || cout == 256))
+  if ((dtype != SPC_DTYPE_F16 && dtype != SPC_DTYPE_BF16) || cin < 16 || cin % 16 != 0 || cout < 32 || cout % 32 != 0)
     return set_error(SPC_ERR_UNSUPPORTED, "no MFMA kernel for dtype %d, cin %d, cout %d", dtype, cin, cout);
   const int64_t total = int64_t(kvol) * (cin / 16) * (cout / 32) * 64;
   // both 16-bit types move as raw 2-byte elements
   hipLaunchKernelGGL(prepack_weights_kernel<_Float16>, dim3((total + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const _Float16*>(weights), static_cast<_Float16*>(packed_out), kvol, cin, cout);
+                     static_cast<const _Float16*>(weights), static_cast<_Float16*>(packed_out), kvol, cin, cin, cout);
   SPC_HIP_CHECK(hipGetLastError());
   return SPC_OK;
 }

@@ -21,6 +21,7 @@ class SpcNetwork:
             dataflow = B.DATAFLOW_OS
         self.dataflow = [dataflow] * n if isinstance(dataflow, int) else list(dataflow)
         self.maps = None
+        self._packed = None  # per layer: weights in the MFMA operand layout, or None
         # concat plan: tensor name -> (buffer name, column offset); a buffer holds [src | skip]
         self._placement = {}
         for l in layers:
@@ -44,10 +45,23 @@ class SpcNetwork:
                 m.destroy()
         self.maps = None
 
+    def prepare_weights(self):
+        """Re-orders every layer's weights once into the layout the MFMA kernels read (layers whose
+        shape those kernels do not take directly keep their plain weights)."""
+        self._packed = []
+        for w, df in zip(self.weights, self.dataflow):
+            cin, cout = w.shape[1], w.shape[2]
+            ok = w.dtype in (torch.float16, torch.bfloat16) and cin % 16 == 0 and cout % 32 == 0
+            if df == B.DATAFLOW_WS:
+                ok = ok and cout in (32, 64, 128, 256)
+            self._packed.append(B.spc_conv_prepare_weights(w) if ok else None)
+
     def forward(self, feats, keep=False):
         """feats: [n0, cin] device tensor in sorted-voxel order.  Returns the last layer's output
         (and, with keep=True, the dict of all saved tensors)."""
         assert self.maps is not None, "call build_maps first"
+        if self._packed is None:
+            self.prepare_weights()
         T = {"input": feats}
         bufs = {}
         y = None
@@ -64,7 +78,10 @@ class SpcNetwork:
                 if buf not in bufs:
                     bufs[buf] = torch.empty((n_out, width), dtype=feats.dtype, device=feats.device)
                 out = bufs[buf][:, col:col + l["cout"]]
-            y = B.spc_conv_forward(m, x, self.weights[j], self.dataflow[j], B.CONV_RELU if l["relu"] else 0, out=out,
-                                   n_out=n_out)
+            flags = B.CONV_RELU if l["relu"] else 0
+            w = self.weights[j]
+            if self._packed[j] is not None and x.stride(0) % 8 == 0 and x.data_ptr() % 16 == 0:
+                w, flags = self._packed[j], flags | B.CONV_PACKED_WEIGHTS
+            y = B.spc_conv_forward(m, x, w, self.dataflow[j], flags, out=out, n_out=n_out)
             T[l["save"]] = y
         return (y, T) if keep else y

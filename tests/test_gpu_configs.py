@@ -50,6 +50,11 @@ def test_config_full_size(cfg):
             y2 = B.spc_conv_forward(km, Fs, packed, df, B.CONV_PACKED_WEIGHTS).cpu().double().numpy()
             if df == B.DATAFLOW_OS:
                 assert np.array_equal(y2, y)
+                # both OS kernels at full size, whichever one the size-based choice picked above
+                for variant in (B.CONV_OS_PHASE, B.CONV_OS_SPLITK):
+                    y3 = B.spc_conv_forward(km, Fs, packed, df, B.CONV_PACKED_WEIGHTS | variant).cpu().double().numpy()
+                    assert rel_err(y3, ref) <= tol, (cfg, variant)
+                    assert np.all(np.abs(y3 - ref) <= tol * (np.abs(ref) + rms))
             else:
                 assert rel_err(y2, ref) <= tol
     km.destroy()

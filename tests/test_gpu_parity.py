@@ -156,13 +156,17 @@ def _run_conv(c, K, s_l, transposed, cin, cout, dtype, seed=0, relu=False):
     if relu:
         ref = np.maximum(ref, 0)
     outs = {}
-    for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
-        y = B.spc_conv_forward(km, Ft, Wt, df, B.CONV_RELU if relu else 0)
+    # both OS kernels are forced in turn (the flags are ignored where no MFMA kernel runs)
+    for df, variant in ((B.DATAFLOW_OS, B.CONV_OS_PHASE), (B.DATAFLOW_OS, B.CONV_OS_SPLITK), (B.DATAFLOW_OS, 0),
+                        (B.DATAFLOW_WS, 0)):
+        y = B.spc_conv_forward(km, Ft, Wt, df, (B.CONV_RELU if relu else 0) | variant)
         torch.cuda.synchronize()
-        outs[df] = y.cpu().to(torch.float64).numpy()
-        assert outs[df].shape == ref.shape
-        err = rel_err(outs[df], ref)
-        assert err <= TOL[dtype], (df, err)
+        o = y.cpu().to(torch.float64).numpy()
+        assert o.shape == ref.shape
+        err = rel_err(o, ref)
+        assert err <= TOL[dtype], (df, variant, err)
+        outs[df] = o
+        outs[(df, variant)] = o
     km.destroy()
     return outs, ref
 
@@ -171,6 +175,9 @@ def _run_conv(c, K, s_l, transposed, cin, cout, dtype, seed=0, relu=False):
     (torch.float16, 64, 64), (torch.float16, 32, 32), (torch.float16, 64, 128), (torch.float16, 128, 256),
     (torch.float16, 16, 32), (torch.float16, 80, 64), (torch.bfloat16, 64, 64), (torch.bfloat16, 32, 128),
     (torch.float32, 16, 16), (torch.float32, 5, 7), (torch.float16, 4, 32), (torch.float16, 16, 16), (torch.float16, 24, 40),
+    # output-channel slabs (several 64- or 32-wide slabs per layer) and zero-padded input channels
+    (torch.float16, 32, 96), (torch.float16, 64, 192), (torch.bfloat16, 16, 320), (torch.float16, 4, 64),
+    (torch.float16, 20, 128), (torch.bfloat16, 3, 96), (torch.float16, 1, 32),
 ])
 def test_conv_submanifold_k3(dtype, cin, cout):
     _run_conv(_cloud("tiny"), 3, 1, 0, cin, cout, dtype)
@@ -207,6 +214,8 @@ def test_conv_os_is_bit_reproducible_and_ws_stable():
     outs1, _ = _run_conv(c, 3, 1, 0, 64, 64, torch.float16, seed=7)
     outs2, _ = _run_conv(c, 3, 1, 0, 64, 64, torch.float16, seed=7)
     assert np.array_equal(outs1[B.DATAFLOW_OS], outs2[B.DATAFLOW_OS])
+    for v in (B.CONV_OS_PHASE, B.CONV_OS_SPLITK):
+        assert np.array_equal(outs1[(B.DATAFLOW_OS, v)], outs2[(B.DATAFLOW_OS, v)])
     assert rel_err(outs1[B.DATAFLOW_WS], outs2[B.DATAFLOW_WS]) <= 1e-2
 
 
@@ -228,6 +237,24 @@ def test_conv_strided_rows_concat_buffer():
         ref = oracle.conv(M, fin.cpu().double().numpy(), W.cpu().double().numpy())
         assert rel_err(wide_out[:, 64:128].cpu().double().numpy(), ref) <= 1e-2
         assert bool((wide_out[:, :64] == 7).all()) and bool((wide_out[:, 128:] == 7).all())
+    km.destroy()
+
+
+def test_conv_unaligned_feature_rows():
+    """Rows that do not start on 16-byte boundaries (odd column offset) still give the right result."""
+    c = _cloud("tiny")
+    desc = fit_desc(c, [(3, 1, 1)])
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, 3)
+    M = oracle.kernel_map(cs, cs, 3, 1)
+    wide_in = torch.from_numpy(synth.features(len(cs), 53, np.float16, seed=18)).cuda()
+    W = torch.from_numpy(synth.weights(27, 32, 64, np.float16, seed=19)).cuda()
+    fin = wide_in[:, 3:35]
+    ref = oracle.conv(M, fin.cpu().double().numpy(), W.cpu().double().numpy())
+    for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
+        y = B.spc_conv_forward(km, fin, W, df)
+        assert rel_err(y.cpu().double().numpy(), ref) <= 1e-2
     km.destroy()
 
 
