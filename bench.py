@@ -63,7 +63,7 @@ def bench_network(args, torch, B, synth) -> int:
     streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def step(flags=0, marks=None, forward=True):
+    def step(flags=0, marks=None, forward=True, keep=False):
         if marks:
             marks[0].record()
         B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
@@ -76,6 +76,7 @@ def bench_network(args, torch, B, synth) -> int:
         y = net.forward(F) if forward else None
         if marks:
             marks[3].record()
+        y = y.clone() if keep else None
         net.destroy_maps()
         return y
 
@@ -86,36 +87,56 @@ def bench_network(args, torch, B, synth) -> int:
     flops = sum(2.0 * float(m.nnz().sum()) * l["cin"] * l["cout"] for m, l in zip(maps, layers))
     level_sizes = sorted({(l["in_stride"], m.n_in if not l["transposed"] else m.n_out) for m, l in zip(maps, layers)})
     net.destroy_maps()
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # ---- eager launches: the host enqueues ~150 kernels and as many event operations per step
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-    e0, e1 = ev(), ev()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
-    part = {}
+    part = {"eager_ms_per_step": timed(step, args.steps)}
     for name, flags in (("streams", 0), ("sequential", B.NET_SEQUENTIAL)):
         marks = [[ev() for _ in range(4)] for _ in range(min(args.steps, 30))]
         for m in marks:
             step(flags, m)
         torch.cuda.synchronize()
-        part["build_ms_" + name] = float(np.mean([m[1].elapsed_time(m[2]) for m in marks]))
-        part["forward_ms"] = float(np.mean([m[2].elapsed_time(m[3]) for m in marks]))
+        part["eager_build_ms_" + name] = float(np.mean([m[1].elapsed_time(m[2]) for m in marks]))
+        part["eager_forward_ms"] = float(np.mean([m[2].elapsed_time(m[3]) for m in marks]))
         part["pack_sort_permute_ms"] = float(np.mean([m[0].elapsed_time(m[1]) for m in marks]))
-    part["build_speedup_streams_over_sequential"] = part["build_ms_sequential"] / part["build_ms_streams"]
-    part["forward_useful_TFLOPs"] = flops / (part["forward_ms"] * 1e-3) / 1e12
+
+    # ---- the same step recorded once into a HIP graph and replayed (the timed configuration)
+    caps = {}
+    for name, flags in (("streams", 0), ("sequential", B.NET_SEQUENTIAL)):
+        caps[name] = net.capture_step(coords, F_raw, desc, streams[1:], flags)
+        for _ in range(args.warmup):
+            caps[name].replay()
+        part["graph_ms_per_step_" + name] = timed(caps[name].replay, args.steps)
+    ms_per_step = part["graph_ms_per_step_streams"]
+    part["graph_speedup_streams_over_sequential"] = part["graph_ms_per_step_sequential"] / ms_per_step
+    # the replayed step must reproduce the eager step bit for bit
+    y_eager = step(keep=True)
+    torch.cuda.synchronize()
+    caps["streams"].replay()
+    torch.cuda.synchronize()
+    part["graph_equals_eager"] = bool(torch.equal(caps["streams"].output[:caps["streams"].n_out()], y_eager))
+    part["forward_useful_TFLOPs"] = flops / (part["eager_forward_ms"] * 1e-3) / 1e12
     result = {
         "metric": "SpC UNet-style stack (pack+sort, network-wide kmap build, 25 feature layers) Mvoxel-offsets/s",
         "value": vo / (ms_per_step * 1e-3) / 1e6, "unit": "Mvoxel-offsets/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "cfg4: lidar cloud, %d voxels, 25-layer UNet-style stack, 13 kernel maps on 4 streams, OS dataflow" % n,
+        "config": {"workload": "cfg4: lidar cloud, %d voxels, 25-layer UNet-style stack, 13 kernel maps on 4 streams, OS dataflow, "
+                               "step replayed from a HIP graph" % n,
                    "n_voxels": n, "levels": level_sizes, "voxel_offsets": vo, "useful_flops": flops},
         "parts": part,
-        "roofline": {"kernel": "conv_os_phase_kernel", "bound": "mfma", "achieved": part["forward_useful_TFLOPs"],
+        "roofline": {"kernel": "conv_os_splitk_kernel + conv_os_phase_kernel (all 25 layers)", "bound": "mfma",
+                     "achieved": part["forward_useful_TFLOPs"],
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": part["forward_useful_TFLOPs"] / PEAK_MFMA_F16_TFLOPS,
                      "traffic": None},
     }

@@ -57,6 +57,7 @@ extern "C" {
 #define SPC_CONV_OS_SPLITK 8 /* spc_conv_forward, OS, 16-bit types: force the split-k kernel */
 #define SPC_CONV_SPLITK_RB(rb) ((rb) << 8) /* with SPC_CONV_OS_SPLITK: 32-row blocks per workgroup (1, 2, 4; 0 = by size) */
 #define SPC_NET_SEQUENTIAL 1 /* spc_build_kmaps_network: one stream, level by level (for comparison) */
+#define SPC_NET_PHASE_BARRIER 2 /* spc_build_kmaps_network: all levels join streams[0] before any map search starts */
 
 /*
  * Packing descriptor (Section 5.3).  A key holds, from the most significant bit
@@ -176,6 +177,16 @@ int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host);
  * Waits for the build.
  */
 int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_t cap, int64_t* nnz_out);
+/*
+ * A strided layer's output count exists only on the device until somebody waits for it.
+ * spc_conv_forward picks its kernel from the output count; while the host does not know it
+ * (nobody called spc_kmap_n_out, or the map was built under stream capture and is rewritten by
+ * every replay) it assumes the upper bound n_in.  This sets a better estimate, e.g. the count a
+ * previous cloud of the same scene produced.  The estimate steers kernel selection and launch
+ * shape only: every kernel reads the true count on the device, so any value gives a correct
+ * result.
+ */
+int spc_kmap_set_size_hint(spc_kmap* m, int64_t n_out_hint);
 void spc_kmap_destroy(spc_kmap* m);
 
 /*
@@ -195,7 +206,13 @@ void spc_kmap_destroy(spc_kmap* m);
  * 16-bit layers with cout % 32 == 0 (OS) or cout in {32,64,128,256} (WS) run on MFMA; input
  * channel counts that are not a multiple of 16, and rows that are not 16-byte aligned, are
  * first copied into a zero-padded scratch buffer.  Everything else runs plain FMA kernels.
- * Nothing is waited for.
+ * Nothing is waited for, and nothing is allocated with hipMalloc once the library's block
+ * cache holds the scratch sizes of this call (i.e. after one call of the same shape on the same
+ * stream), so a warmed-up call sequence can be captured into a HIP graph: spc_pack_coords
+ * (without SPC_PACK_VALIDATE), spc_build_kmap(s_network), spc_conv_forward and
+ * spc_permute_rows only enqueue kernels, event records and event waits.  Maps built under
+ * capture must stay alive as long as the graph; their accessors that wait (n_out, nnz,
+ * export) drain the device and read the values of the latest replay.
  */
 int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
                      int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t dataflow,

@@ -24,12 +24,14 @@ CONV_PACKED_WEIGHTS = 2
 CONV_OS_PHASE = 4
 CONV_OS_SPLITK = 8
 NET_SEQUENTIAL = 1
+NET_PHASE_BARRIER = 2
 ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
-    "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_export_triples", "spc_kmap_destroy", "spc_conv_forward",
+    "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
+    "spc_conv_forward",
     "spc_conv_prepare_weights", "spc_permute_rows",
     "spc_release_cache", "spc_last_error", "spc_version",
 ]
@@ -84,6 +86,7 @@ def lib():
         L.spc_kmap_ws_lists.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.spc_kmap_nnz.argtypes = [vp, ctypes.POINTER(i64)]
         L.spc_kmap_export_triples.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i64)]
+        L.spc_kmap_set_size_hint.argtypes = [vp, i64]
         L.spc_kmap_destroy.argtypes = [vp]
         L.spc_kmap_destroy.restype = None
         L.spc_conv_forward.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
@@ -186,6 +189,9 @@ class KMap:
         if v < 0:
             _check(int(v))
         return int(v)
+
+    def set_size_hint(self, n_out_hint: int) -> None:
+        _check(lib().spc_kmap_set_size_hint(self.handle, int(n_out_hint)))
 
     @property
     def kvol(self) -> int:

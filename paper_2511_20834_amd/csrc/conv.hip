@@ -432,10 +432,11 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_out = n_out_d ? *n_out_d : n_out_h;
   const int64_t n_blocks = (int64_t(n_out) + 31) >> 5;
-  const int64_t blk0 = int64_t(blockIdx.x) * RB;
-  if (blk0 >= n_blocks) return;  // whole workgroup
   const int slab = blockIdx.y;
   const int KK = cin / 16;
+  // tiles of RB blocks, walked with a grid stride (uniform per workgroup, so the barriers below
+  // are reached by all of its waves or by none)
+  for (int64_t blk0 = int64_t(blockIdx.x) * RB; blk0 < n_blocks; blk0 += int64_t(gridDim.x) * RB) {
   const int idx_rows = (K3 + SPLITK_WAVES - 1) / SPLITK_WAVES + 1;  // per wave, with the all-invalid row at the end
   int32_t* sIdx = reinterpret_cast<int32_t*>(smem) + wave * idx_rows * (RB * 32);
   int16_t* kl = reinterpret_cast<int16_t*>(smem + size_t(SPLITK_WAVES) * idx_rows * (RB * 128)) + wave * SPLITK_KL_CAP;
@@ -579,6 +580,8 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
       }
     }
   }
+  __syncthreads();  // the LDS tile is reused as the next tile's index area
+  }
 }
 
 // Weight-stationary: workgroup = one offset k and 4 x RB blocks of 32 (in,out) pairs;
@@ -713,7 +716,8 @@ struct ConvArgs {
   int splitk_rb;   // 0: chosen from the layer's size, else row blocks per workgroup (1, 2, 4)
   int n_out_h;
   const int* n_out_d;
-  int64_t rows_cap;
+  int64_t rows_cap;  // upper bound of the output rows (exact when the host knows the count)
+  int64_t rows_sel;  // best host-side estimate of the output rows: kernel selection and launch shape only
   hipStream_t s;
 };
 
@@ -761,7 +765,8 @@ static void launch_os_splitk(const ConvArgs& a, const T* Wp) {
   // about 96 registers of loads in flight per lane; the largest tile keeps two waves per SIMD
   constexpr int D = (RB == 4 && NB == 2) ? 3 : 24 / (RB + NB);
   const int nb_total = a.cout / 32, n_slabs = nb_total / NB;
-  const int64_t n_blocks = (a.rows_cap + 31) / 32;
+  // the kernel walks tiles with a grid stride, so a grid sized from the estimate stays correct
+  const int64_t n_blocks = std::max<int64_t>((a.rows_sel + 31) / 32, 1);
   const size_t lds = splitk_lds_bytes(a.m->K3, NB, RB);
   static size_t lds_attr = 64 * 1024;  // one per instantiation
   if (lds > lds_attr) {
@@ -780,7 +785,7 @@ static void launch_os_splitk(const ConvArgs& a, const T* Wp) {
 // Row blocks per workgroup of the split-k kernel: more blocks share each weight fragment read
 // (less L2 traffic) but leave fewer workgroups; small levels need the workgroups.
 static int splitk_rb(const ConvArgs& a, int NB) {
-  const int64_t n_blocks = (a.rows_cap + 31) / 32;
+  const int64_t n_blocks = (a.rows_sel + 31) / 32;
   int rb = a.splitk_rb ? a.splitk_rb : (n_blocks >= 1024 ? 2 : 1);
   while (rb > 1 && splitk_lds_bytes(a.m->K3, NB, rb) > 80 * 1024) rb >>= 1;
   return rb;
@@ -800,7 +805,7 @@ static void launch_os_splitk_any(const ConvArgs& a, const T* Wp) {
 // above, the redundant weight reads of the split-k kernel cost more than the phase kernel's
 // barriers.  Large kernels (5x5x5 and up) favour the split-k kernel at every size measured.
 static bool prefer_splitk(const ConvArgs& a) {
-  const int64_t n_blocks = (a.rows_cap + 31) / 32;
+  const int64_t n_blocks = (a.rows_sel + 31) / 32;
   return n_blocks < 2560 || a.m->K3 > 64;
 }
 
@@ -950,6 +955,7 @@ extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in
   a.n_out_h = static_cast<int>(ol->n_host < 0 ? 0 : ol->n_host);
   a.n_out_d = ol->n_host < 0 ? ol->n_dev : nullptr;
   a.rows_cap = ol->n_host < 0 ? m->out_cap : ol->n_host;
+  a.rows_sel = (ol->n_host < 0 && m->n_out_hint >= 0) ? std::min(m->n_out_hint, a.rows_cap) : a.rows_cap;
   a.s = static_cast<hipStream_t>(stream);
   switch (dtype) {
     case SPC_DTYPE_F16: return conv_typed<_Float16>(a, true);

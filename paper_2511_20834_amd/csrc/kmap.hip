@@ -16,6 +16,7 @@
 // the window, with the same code.
 #include <algorithm>
 #include <map>
+#include <set>
 #include <tuple>
 
 #include "spc_internal.h"
@@ -426,6 +427,7 @@ static void kmap_free(spc_kmap* m) {
   level_unref(m->in_level);
   level_unref(m->out_level);
   if (m->ready) (void)hipEventDestroy(m->ready);
+  for (hipEvent_t e : m->aux_events) (void)hipEventDestroy(e);
   delete m;
 }
 
@@ -454,6 +456,7 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->desc = l;
   m->K3 = l.K * l.K * l.K;
   m->stream = s;
+  m->captured = stream_is_capturing(s);
   m->in_level = in;
   in->refs++;
   m->out_level = out;
@@ -510,12 +513,27 @@ static Level* borrowed_level(const void* keys, int64_t n, int stride) {
   return lv;
 }
 
+// Host copy of a level's voxel count in lv->n_fetched.  A level built under stream capture is
+// rewritten by every replay of the graph: its events cannot be waited for (they belong to the
+// capture), so the whole device is drained instead, and the value is never cached.
 static int fetch_level_n(Level* lv) {
-  if (lv->n_host >= 0) return SPC_OK;
-  if (lv->ready) SPC_HIP_CHECK(hipEventSynchronize(lv->ready));
+  if (lv->n_host >= 0) {
+    lv->n_fetched = lv->n_host;
+    return SPC_OK;
+  }
+  if (lv->captured) SPC_HIP_CHECK(hipDeviceSynchronize());
+  else if (lv->ready) SPC_HIP_CHECK(hipEventSynchronize(lv->ready));
   int v = 0;
   SPC_HIP_CHECK(hipMemcpy(&v, lv->n_dev, sizeof(int), hipMemcpyDeviceToHost));
-  lv->n_host = v;
+  lv->n_fetched = v;
+  if (!lv->captured) lv->n_host = v;
+  return SPC_OK;
+}
+
+// Waits until the map's arrays are complete (see fetch_level_n for captured builds).
+static int wait_map(const spc_kmap* m) {
+  if (m->captured) SPC_HIP_CHECK(hipDeviceSynchronize());
+  else if (m->ready) SPC_HIP_CHECK(hipEventSynchronize(m->ready));
   return SPC_OK;
 }
 
@@ -588,12 +606,38 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
     }
   }
 
+  std::vector<hipEvent_t> aux;
+  if (fork) aux.push_back(fork);
+  // Under stream capture the two-phase shape is forced: recording the free-form dependency
+  // pattern (streams waiting for each other's levels) has crashed the runtime's capture on
+  // ROCm 7.2, while fork / join / fork / join through streams[0] records fine.
+  const bool barrier = ns > 1 && ((flags & SPC_NET_PHASE_BARRIER) || stream_is_capturing(st[0]));
+  if (barrier && rc == SPC_OK) {
+    // all levels complete on streams[0], then every stream continues from there
+    for (int i = 1; i < ns; ++i) {
+      hipEvent_t j = nullptr;
+      if (hipEventCreateWithFlags(&j, hipEventDisableTiming) != hipSuccess || hipEventRecord(j, st[i]) != hipSuccess ||
+          hipStreamWaitEvent(st[0], j, 0) != hipSuccess)
+        rc = set_error(SPC_ERR_HIP, "joining stream %d failed", i);
+      if (j) aux.push_back(j);
+    }
+    hipEvent_t f2 = nullptr;
+    if (hipEventCreateWithFlags(&f2, hipEventDisableTiming) != hipSuccess || hipEventRecord(f2, st[0]) != hipSuccess)
+      rc = set_error(SPC_ERR_HIP, "fork failed");
+    if (f2) aux.push_back(f2);
+    for (int i = 1; i < ns && rc == SPC_OK; ++i)
+      if (hipStreamWaitEvent(st[i], f2, 0) != hipSuccess) rc = set_error(SPC_ERR_HIP, "fork failed");
+  }
+
   // ---- phase 2: one search per distinct (K, in_stride, layer_stride, transposed)
   using Key = std::tuple<int, int, int, int>;
   std::map<Key, spc_kmap*> maps;
   std::map<Key, int> want;
   for (int i = 0; i < n_layers; ++i) want[Key(layers[i].K, layers[i].in_stride, layers[i].layer_stride, layers[i].transposed)] |= layers[i].layout;
-  std::vector<hipEvent_t> joins;
+  // A stream waits for each foreign event at most once (stream order covers everything it
+  // enqueues later), and the other streams join streams[0] once, at the end: few, distinct
+  // cross-stream edges, which is also what a graph capture of this call records.
+  std::vector<std::set<hipEvent_t>> waited(ns);
   next = 0;
   for (auto& kv : want) {
     if (rc != SPC_OK) break;
@@ -604,21 +648,26 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
     Level* outl = l.transposed ? fine : coarse;
     const int si = (next++) % ns;
     for (Level* dep : {in, outl})  // the map's stream waits for the levels it reads
-      if (dep->ready && level_stream[dep->stride] != si) {
+      if (!barrier && dep->ready && level_stream[dep->stride] != si && waited[si].insert(dep->ready).second) {
         hipError_t e = hipStreamWaitEvent(st[si], dep->ready, 0);
         if (e != hipSuccess) rc = set_error(SPC_ERR_HIP, "hipStreamWaitEvent: %s", hipGetErrorString(e));
       }
     spc_kmap* m = nullptr;
     if (rc == SPC_OK) rc = build_on_levels(in, outl, pi, l, st[si], &m);
-    if (rc == SPC_OK) {
-      maps[kv.first] = m;
-      if (si != 0) (void)hipStreamWaitEvent(st[0], m->ready, 0);  // join into streams[0]
-    }
+    if (rc == SPC_OK) maps[kv.first] = m;
   }
-  // levels produced on other streams but not consumed by any map still join
-  for (auto& kv : levels)
-    if (kv.second->ready && level_stream[kv.first] != 0) (void)hipStreamWaitEvent(st[0], kv.second->ready, 0);
-  if (fork) (void)hipEventDestroy(fork);
+  // join: streams[0] continues only after everything the other streams were given
+  for (int i = 1; i < ns; ++i) {
+    hipEvent_t j = nullptr;
+    if (hipEventCreateWithFlags(&j, hipEventDisableTiming) != hipSuccess || hipEventRecord(j, st[i]) != hipSuccess ||
+        hipStreamWaitEvent(st[0], j, 0) != hipSuccess)
+      rc = set_error(SPC_ERR_HIP, "joining stream %d failed", i);
+    if (j) aux.push_back(j);
+  }
+  // these events live as long as the maps (a capture of this call refers to them): the first map owns them
+  if (rc == SPC_OK && !maps.empty()) maps.begin()->second->aux_events = aux;
+  else
+    for (hipEvent_t e : aux) (void)hipEventDestroy(e);
 
   if (rc == SPC_OK) {
     for (int i = 0; i < n_layers; ++i) {
@@ -633,6 +682,12 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
   return rc;
 }
 
+int spc_kmap_set_size_hint(spc_kmap* m, int64_t n_out_hint) {
+  if (!m || n_out_hint < 0) return set_error(SPC_ERR_ARG, "map is NULL or hint < 0");
+  m->n_out_hint = n_out_hint;
+  return SPC_OK;
+}
+
 void spc_kmap_destroy(spc_kmap* m) {
   if (m && m->refs.fetch_sub(1) == 1) kmap_free(m);
 }
@@ -640,12 +695,12 @@ void spc_kmap_destroy(spc_kmap* m) {
 int64_t spc_kmap_n_in(spc_kmap* m) {
   if (!m) return set_error(SPC_ERR_ARG, "map is NULL");
   int rc = fetch_level_n(m->in_level);
-  return rc != SPC_OK ? rc : m->in_level->n_host;
+  return rc != SPC_OK ? rc : m->in_level->n_fetched;
 }
 int64_t spc_kmap_n_out(spc_kmap* m) {
   if (!m) return set_error(SPC_ERR_ARG, "map is NULL");
   int rc = fetch_level_n(m->out_level);
-  return rc != SPC_OK ? rc : m->out_level->n_host;
+  return rc != SPC_OK ? rc : m->out_level->n_fetched;
 }
 int32_t spc_kmap_kvol(const spc_kmap* m) { return m ? m->K3 : SPC_ERR_ARG; }
 const void* spc_kmap_out_keys(const spc_kmap* m) { return m ? m->out_level->keys : nullptr; }
@@ -654,9 +709,9 @@ const int32_t* spc_kmap_os_map(const spc_kmap* m) { return (m && (m->desc.layout
 
 int spc_kmap_copy_out_keys(spc_kmap* m, void* keys_host, int64_t cap) {
   if (!m || !keys_host) return set_error(SPC_ERR_ARG, "NULL argument");
-  if (m->ready) SPC_HIP_CHECK(hipEventSynchronize(m->ready));
+  SPC_RETURN_IF(wait_map(m));
   SPC_RETURN_IF(fetch_level_n(m->out_level));
-  const int64_t n = m->out_level->n_host;
+  const int64_t n = m->out_level->n_fetched;
   if (cap < n) return set_error(SPC_ERR_ARG, "room for %lld keys, map has %lld", (long long)cap, (long long)n);
   if (n > 0) SPC_HIP_CHECK(hipMemcpy(keys_host, m->out_level->keys, size_t(n) * (m->pi.key_bits / 8), hipMemcpyDeviceToHost));
   return SPC_OK;
@@ -678,9 +733,9 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
   if (which != SPC_LAYOUT_OS && which != SPC_LAYOUT_WS) return set_error(SPC_ERR_ARG, "which must be OS or WS");
   if (which == SPC_LAYOUT_WS && !(m->desc.layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "WS layout was not built");
   if (which == SPC_LAYOUT_OS && !(m->desc.layout & SPC_LAYOUT_OS)) return set_error(SPC_ERR_ARG, "OS layout was not built");
-  SPC_HIP_CHECK(hipEventSynchronize(m->ready));
+  SPC_RETURN_IF(wait_map(m));
   SPC_RETURN_IF(fetch_level_n(m->out_level));
-  const int64_t n_out = m->out_level->n_host;
+  const int64_t n_out = m->out_level->n_fetched;
   const int K3 = m->K3;
   int64_t nnz = 0;
   if (which == SPC_LAYOUT_OS) {
@@ -726,8 +781,8 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
 
 int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host) {
   if (!m || !nnz_host) return set_error(SPC_ERR_ARG, "NULL argument");
-  if (m->nnz_host.empty()) {
-    SPC_HIP_CHECK(hipEventSynchronize(m->ready));
+  if (m->nnz_host.empty() || m->captured) {
+    SPC_RETURN_IF(wait_map(m));
     SPC_RETURN_IF(fetch_level_n(m->out_level));
     std::vector<int64_t> cnt(m->K3, 0);
     if (m->desc.layout & SPC_LAYOUT_WS) {
@@ -735,7 +790,7 @@ int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host) {
       SPC_HIP_CHECK(hipMemcpy(c.data(), m->nnz_dev, size_t(m->K3) * 4, hipMemcpyDeviceToHost));
       for (int k = 0; k < m->K3; ++k) cnt[k] = c[k];
     } else {
-      const int64_t n_out = m->out_level->n_host;
+      const int64_t n_out = m->out_level->n_fetched;
       std::vector<int32_t> M(size_t((n_out + 31) / 32) * 32 * m->K3);
       if (!M.empty()) SPC_HIP_CHECK(hipMemcpy(M.data(), m->os_map, M.size() * 4, hipMemcpyDeviceToHost));
       for (int64_t i = 0; i < n_out; ++i)

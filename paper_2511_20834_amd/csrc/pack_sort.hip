@@ -211,6 +211,7 @@ int downsample_level(const void* src_keys, int64_t n_src, const int* /*n_src_dev
   lv->stride = 1 << m;
   lv->owns_keys = true;
   lv->stream = stream;
+  lv->captured = stream_is_capturing(stream);
   lv->keys = pool_alloc(std::max<size_t>(size_t(n_src) * (pi.key_bits / 8), 256), stream);
   lv->n_dev = static_cast<int*>(pool_alloc(256, stream));
   if (!lv->keys || !lv->n_dev) {

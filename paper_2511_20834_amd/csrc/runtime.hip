@@ -140,6 +140,15 @@ uint64_t level_mask(const PackInfo& pi, int m) {
   return mask;
 }
 
+bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return st != hipStreamCaptureStatusNone;
+}
+
 void level_unref(Level* l) {
   if (!l) return;
   if (l->refs.fetch_sub(1) == 1) {

@@ -56,12 +56,15 @@ struct Level {
   bool owns_keys = false;
   int64_t cap = 0;        // rows allocated / upper bound of n
   int64_t n_host = -1;    // -1: not yet fetched
+  int64_t n_fetched = -1; // last value read back from n_dev (equals n_host unless the level was built under capture)
+  bool captured = false;  // produced while its stream was being captured into a graph: every replay rewrites it
   int* n_dev = nullptr;   // device int (nullptr when n_host is authoritative from the start)
   int stride = 1;
   hipEvent_t ready = nullptr;  // recorded after the level's last kernel
   hipStream_t stream = nullptr;  // stream the level was produced on
 };
 void level_unref(Level* l);
+bool stream_is_capturing(hipStream_t s);
 
 // Derive the level with stride 2^m of `src_keys` (mask, sort, unique).  Enqueues only.
 int downsample_level(const void* src_keys, int64_t n_src, const int* n_src_dev, const PackInfo& pi, int m,
@@ -86,6 +89,8 @@ struct spc_kmap {
   spc::Level* in_level = nullptr;   // the layer's input voxels
   spc::Level* out_level = nullptr;  // the layer's output voxels
   int64_t out_cap = 0;              // rows allocated in os_map / ws lists
+  int64_t n_out_hint = -1;          // caller's estimate of n_out for kernel selection while n_host is unknown
+  bool captured = false;            // built while its stream was being captured into a graph
   int64_t n_blocks_cap = 0;         // 32-row blocks allocated
   int mask_words = 0;               // ceil(K3/32)
   int32_t* os_map = nullptr;        // blocked OS layout [n_blocks][K3][32]: entry (i,k) at ((i/32)*K3+k)*32 + i%32
@@ -97,6 +102,7 @@ struct spc_kmap {
   int tile = 0, n_tiles = 0;
   std::vector<int64_t> nnz_host;    // filled lazily
   hipEvent_t ready = nullptr;       // recorded after the last build kernel
+  std::vector<hipEvent_t> aux_events;  // fork/join events of the network build that made this map
   hipStream_t stream = nullptr;     // stream the map was built on
   int device = 0;
 };

@@ -2,7 +2,12 @@
 ``synth.unet_layers``) through the C-ABI binding: all kernel maps are built up front by
 ``spc_build_kmaps_network`` (network-wide voxel indexing, Section 5.5), then every layer
 is one ``spc_conv_forward`` call.  Skip connections are realised without a copy: the two
-producers write into the two column halves of one buffer (row pitch arguments)."""
+producers write into the two column halves of one buffer (row pitch arguments).
+
+``SpcNetwork.capture_step`` records the whole step of one cloud size (pack + sort, feature
+permutation, map build on several streams, all feature layers) into one HIP graph: a step
+enqueues some 150 small kernels and as many event operations, which costs the host about as
+much time as the GPU needs to run them; replaying the graph removes the host from the loop."""
 from __future__ import annotations
 
 import torch
@@ -21,6 +26,7 @@ class SpcNetwork:
             dataflow = B.DATAFLOW_OS
         self.dataflow = [dataflow] * n if isinstance(dataflow, int) else list(dataflow)
         self.maps = None
+        self.size_hints = None  # per layer: n_out seen by the last learn_sizes()
         self._packed = None  # per layer: weights in the MFMA operand layout, or None
         # concat plan: tensor name -> (buffer name, column offset); a buffer holds [src | skip]
         self._placement = {}
@@ -31,13 +37,23 @@ class SpcNetwork:
                 self._placement[l["src"]] = (buf, 0, l["cin"])
                 self._placement[l["skip"]] = (buf, src_w, l["cin"])
 
-    def build_maps(self, v0_keys, desc, streams=None, flags=0):
+    def build_maps(self, v0_keys, desc, streams=None, flags=0, use_hints=False):
+        """use_hints: hand the level sizes of the last learn_sizes() to the new maps, so that the feature
+        kernels are chosen for those sizes without anybody waiting for the true counts."""
         req = []
         for l, df in zip(self.layers, self.dataflow):
             layout = B.LAYOUT_OS if df == B.DATAFLOW_OS else B.LAYOUT_WS
             req.append((l["K"], l["in_stride"], l["layer_stride"], l["transposed"], layout))
         self.maps = B.spc_build_kmaps_network(v0_keys, desc, req, streams, flags)
+        if use_hints and self.size_hints is not None:
+            for m, h in zip(self.maps, self.size_hints):
+                m.set_size_hint(h)
         return self.maps
+
+    def learn_sizes(self):
+        """Remembers every layer's output count of the current maps (waits for the build)."""
+        self.size_hints = [m.n_out for m in self.maps]
+        return self.size_hints
 
     def destroy_maps(self):
         if self.maps:
@@ -56,9 +72,13 @@ class SpcNetwork:
                 ok = ok and cout in (32, 64, 128, 256)
             self._packed.append(B.spc_conv_prepare_weights(w) if ok else None)
 
-    def forward(self, feats, keep=False):
+    def forward(self, feats, keep=False, static_rows=None):
         """feats: [n0, cin] device tensor in sorted-voxel order.  Returns the last layer's output
-        (and, with keep=True, the dict of all saved tensors)."""
+        (and, with keep=True, the dict of all saved tensors).
+        static_rows: None -> every tensor has exactly its level's voxel count, which the host waits
+        for once per level.  An int (an upper bound of every level's count, e.g. n0) -> every tensor
+        gets that many rows, of which the first n_out are written; nothing waits, so the call can be
+        captured into a graph."""
         assert self.maps is not None, "call build_maps first"
         if self._packed is None:
             self.prepare_weights()
@@ -67,7 +87,7 @@ class SpcNetwork:
         y = None
         for j, l in enumerate(self.layers):
             m = self.maps[j]
-            n_out = m.n_out
+            n_out = m.n_out if static_rows is None else int(static_rows)
             x = T[l["src"]]
             if l["skip"] is not None:
                 buf, _, _ = self._placement[l["src"]]
@@ -85,3 +105,58 @@ class SpcNetwork:
             y = B.spc_conv_forward(m, x, w, self.dataflow[j], flags, out=out, n_out=n_out)
             T[l["save"]] = y
         return (y, T) if keep else y
+
+    def capture_step(self, coords, feats_raw, desc, streams=None, flags=0):
+        """Records one full step for clouds of coords.shape[0] voxels into a HIP graph and returns a
+        CapturedStep.  Runs the step once eagerly first: that fills the library's block cache on the
+        streams used (so the capture allocates nothing) and learns the level sizes the kernels are
+        chosen for.  `coords` [n0,4] int32 and `feats_raw` [n0,cin] are the graph's input buffers:
+        overwrite them in place, then replay."""
+        return CapturedStep(self, coords, feats_raw, desc, streams, flags)
+
+
+class CapturedStep:
+    def __init__(self, net, coords, feats_raw, desc, streams, flags):
+        n0 = coords.shape[0]
+        dev = coords.device
+        self.net, self.coords, self.feats_raw = net, coords, feats_raw
+        self.ws = torch.empty(B.spc_pack_workspace_bytes(n0, desc), dtype=torch.uint8, device=dev)
+        self.keys = torch.empty(n0, dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device=dev)
+        self.perm = torch.empty(n0, dtype=torch.int32, device=dev)
+        self.feats = torch.empty_like(feats_raw)
+        self.stream = torch.cuda.Stream(device=dev)
+        side = list(streams) if streams else []
+
+        def step(static):
+            B.spc_pack_coords(coords, desc, True, 0, None, self.ws, self.keys, self.perm)
+            B.spc_permute_rows(feats_raw, self.perm, self.feats)
+            net.build_maps(self.keys, desc, [torch.cuda.current_stream()] + side, flags, use_hints=static)
+            if not static:
+                net.learn_sizes()
+            return net.forward(self.feats, static_rows=n0 if static else None)
+
+        self.stream.wait_stream(torch.cuda.current_stream(dev))
+        with torch.cuda.stream(self.stream):
+            step(False)
+            net.destroy_maps()
+            step(True)  # same allocation pattern as the capture
+            net.destroy_maps()
+        torch.cuda.synchronize(dev)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph, stream=self.stream, capture_error_mode="relaxed"):
+            self.output = step(True)
+        self.maps = net.maps  # alive as long as the graph
+        net.maps = None
+
+    def replay(self):
+        self.graph.replay()
+
+    def n_out(self) -> int:
+        """Valid rows of `output` after the latest replay (drains the device)."""
+        return self.maps[-1].n_out
+
+    def destroy(self):
+        self.graph = None
+        for m in self.maps or []:
+            m.destroy()
+        self.maps = None
