@@ -55,7 +55,7 @@ extern "C" {
 #define SPC_CONV_PACKED_WEIGHTS 2 /* spc_conv_forward: `weights` came from spc_conv_prepare_weights */
 #define SPC_CONV_OS_PHASE 4  /* spc_conv_forward, OS, 16-bit types: force the LDS-staged phase kernel */
 #define SPC_CONV_OS_SPLITK 8 /* spc_conv_forward, OS, 16-bit types: force the split-k kernel */
-#define SPC_CONV_SPLITK_RB(rb) ((rb) << 8) /* with SPC_CONV_OS_SPLITK: 32-row blocks per workgroup (1, 2, 4; 0 = by size) */
+#define SPC_CONV_SPLITK_RB(rb) ((rb) << 8) /* with SPC_CONV_OS_SPLITK: 32-row blocks per workgroup (1, 2; 0 = by size) */
 #define SPC_NET_SEQUENTIAL 1 /* spc_build_kmaps_network: one stream, level by level (for comparison) */
 #define SPC_NET_PHASE_BARRIER 2 /* spc_build_kmaps_network: all levels join streams[0] before any map search starts */
 

@@ -417,7 +417,9 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
 constexpr int SPLITK_WAVES = 4;
 constexpr int SPLITK_KL_CAP = 96;  // >= ceil(7^3 / 4) + 1
 
-template <typename T, int NB, int RB, int D>
+// LOOP: the grid was sized from an estimate of the output count and tiles are walked with a grid
+// stride; otherwise one tile per workgroup (the loop costs about 30 registers per lane).
+template <typename T, int NB, int RB, int D, bool LOOP>
 __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const int32_t* __restrict__ M,
                                                                           const uint32_t* __restrict__ block_masks,
                                                                           int mask_words, int n_out_h,
@@ -434,9 +436,9 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
   const int64_t n_blocks = (int64_t(n_out) + 31) >> 5;
   const int slab = blockIdx.y;
   const int KK = cin / 16;
-  // tiles of RB blocks, walked with a grid stride (uniform per workgroup, so the barriers below
-  // are reached by all of its waves or by none)
-  for (int64_t blk0 = int64_t(blockIdx.x) * RB; blk0 < n_blocks; blk0 += int64_t(gridDim.x) * RB) {
+  // tiles of RB blocks; the trip count is uniform per workgroup, so the barriers below are
+  // reached by all of its waves or by none
+  for (int64_t blk0 = int64_t(blockIdx.x) * RB; blk0 < n_blocks; blk0 += LOOP ? int64_t(gridDim.x) * RB : n_blocks) {
   const int idx_rows = (K3 + SPLITK_WAVES - 1) / SPLITK_WAVES + 1;  // per wave, with the all-invalid row at the end
   int32_t* sIdx = reinterpret_cast<int32_t*>(smem) + wave * idx_rows * (RB * 32);
   int16_t* kl = reinterpret_cast<int16_t*>(smem + size_t(SPLITK_WAVES) * idx_rows * (RB * 128)) + wave * SPLITK_KL_CAP;
@@ -580,7 +582,7 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
       }
     }
   }
-  __syncthreads();  // the LDS tile is reused as the next tile's index area
+  if constexpr (LOOP) __syncthreads();  // the LDS tile is reused as the next tile's index area
   }
 }
 
@@ -713,7 +715,7 @@ struct ConvArgs {
   int64_t ld_out;
   int cin, cout, relu, dataflow;
   int os_variant;  // 0: chosen from the layer's size, 1: phase kernel, 2: split-k kernel
-  int splitk_rb;   // 0: chosen from the layer's size, else row blocks per workgroup (1, 2, 4)
+  int splitk_rb;   // 0: chosen from the layer's size, else row blocks per workgroup (1, 2)
   int n_out_h;
   const int* n_out_d;
   int64_t rows_cap;  // upper bound of the output rows (exact when the host knows the count)
@@ -762,24 +764,32 @@ static size_t splitk_lds_bytes(int K3, int NB, int RB) {
 
 template <typename T, int NB, int RB>
 static void launch_os_splitk(const ConvArgs& a, const T* Wp) {
-  // about 96 registers of loads in flight per lane; the largest tile keeps two waves per SIMD
-  constexpr int D = (RB == 4 && NB == 2) ? 3 : 24 / (RB + NB);
+  constexpr int D = 24 / (RB + NB);  // about 96 registers of loads in flight per lane
   const int nb_total = a.cout / 32, n_slabs = nb_total / NB;
-  // the kernel walks tiles with a grid stride, so a grid sized from the estimate stays correct
+  // an estimated output count sizes the grid of the variant that walks tiles with a grid stride
+  const bool loop = a.rows_sel != a.rows_cap;
   const int64_t n_blocks = std::max<int64_t>((a.rows_sel + 31) / 32, 1);
   const size_t lds = splitk_lds_bytes(a.m->K3, NB, RB);
   static size_t lds_attr = 64 * 1024;  // one per instantiation
   if (lds > lds_attr) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D, true>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     lds_attr = lds;
   }
   constexpr int EPT = NB * 4;
   T* out = static_cast<T*>(a.out);
   const int vec = a.ld_out % EPT == 0 && reinterpret_cast<uintptr_t>(out) % (EPT * sizeof(T)) == 0;
-  hipLaunchKernelGGL((conv_os_splitk_kernel<T, NB, RB, D>), dim3(static_cast<unsigned>((n_blocks + RB - 1) / RB), n_slabs),
-                     dim3(64 * SPLITK_WAVES), lds, a.s, a.m->os_map, a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d,
-                     a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp, out, a.ld_out, a.cin, a.relu, nb_total, vec);
+  const dim3 grid(static_cast<unsigned>((n_blocks + RB - 1) / RB), n_slabs);
+  if (loop)
+    hipLaunchKernelGGL((conv_os_splitk_kernel<T, NB, RB, D, true>), grid, dim3(64 * SPLITK_WAVES), lds, a.s, a.m->os_map,
+                       a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp,
+                       out, a.ld_out, a.cin, a.relu, nb_total, vec);
+  else
+    hipLaunchKernelGGL((conv_os_splitk_kernel<T, NB, RB, D, false>), grid, dim3(64 * SPLITK_WAVES), lds, a.s, a.m->os_map,
+                       a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp,
+                       out, a.ld_out, a.cin, a.relu, nb_total, vec);
 }
 
 // Row blocks per workgroup of the split-k kernel: more blocks share each weight fragment read
@@ -794,7 +804,6 @@ static int splitk_rb(const ConvArgs& a, int NB) {
 template <typename T, int NB>
 static void launch_os_splitk_any(const ConvArgs& a, const T* Wp) {
   switch (splitk_rb(a, NB)) {
-    case 4: launch_os_splitk<T, NB, 4>(a, Wp); break;
     case 2: launch_os_splitk<T, NB, 2>(a, Wp); break;
     default: launch_os_splitk<T, NB, 1>(a, Wp); break;
   }
@@ -948,8 +957,8 @@ extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in
   if ((flags & SPC_CONV_OS_PHASE) && (flags & SPC_CONV_OS_SPLITK)) return set_error(SPC_ERR_ARG, "two OS kernel variants requested");
   a.os_variant = (flags & SPC_CONV_OS_PHASE) ? 1 : (flags & SPC_CONV_OS_SPLITK) ? 2 : 0;
   a.splitk_rb = (flags >> 8) & 7;  // tuning aid: SPC_CONV_OS_SPLITK | (rb << 8)
-  if (a.splitk_rb != 0 && a.splitk_rb != 1 && a.splitk_rb != 2 && a.splitk_rb != 4)
-    return set_error(SPC_ERR_ARG, "row blocks per workgroup must be 1, 2 or 4");
+  if (a.splitk_rb != 0 && a.splitk_rb != 1 && a.splitk_rb != 2)
+    return set_error(SPC_ERR_ARG, "row blocks per workgroup must be 1 or 2");
   a.dataflow = dataflow;
   const Level* ol = m->out_level;
   a.n_out_h = static_cast<int>(ol->n_host < 0 ? 0 : ol->n_host);
