@@ -134,6 +134,18 @@ int spc_build_kmap(const void* in_keys, int64_t n_in, const spc_pack_desc* d, co
                    spc_kmap** out, void* stream);
 
 /*
+ * Same, with the sort permutation folded into the map: in_perm [device] int32[n_in] is the
+ * perm_out of spc_pack_coords (sorted position -> caller's row), and every input index the
+ * map stores is in_perm[j] instead of j.  spc_conv_forward on such a map reads the caller's
+ * feature matrix in its original row order, so the first layer of a network needs no
+ * spc_permute_rows; its output rows are in sorted order like any other layer's.  in_perm
+ * is read by the build only (a build captured into a graph reads it on every replay).
+ * NULL in_perm = spc_build_kmap.  Not available for transposed layers.
+ */
+int spc_build_kmap_perm(const void* in_keys, int64_t n_in, const int32_t* in_perm, const spc_pack_desc* d,
+                        const spc_layer_desc* l, spc_kmap** out, void* stream);
+
+/*
  * Network-wide voxel indexing (Section 5.5).  v0_keys [device]: the n0 sorted keys of
  * the stride-1 level.  Every coordinate level any layer needs is derived directly from
  * v0_keys (closed form of Section 5.5), all levels concurrently over `streams`; then

@@ -28,7 +28,7 @@ NET_PHASE_BARRIER = 2
 ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmaps_network", "spc_kmap_n_in",
+    "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmap_perm", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
     "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
     "spc_conv_forward",
@@ -73,6 +73,7 @@ def lib():
         L.spc_pack_desc_fit.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32), i32, i32, i32, i32, ctypes.POINTER(PackDesc)]
         L.spc_pack_coords.argtypes = [vp, i64, ctypes.POINTER(PackDesc), vp, vp, vp, ctypes.POINTER(ctypes.c_size_t), i32, vp]
         L.spc_build_kmap.argtypes = [vp, i64, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), ctypes.POINTER(vp), vp]
+        L.spc_build_kmap_perm.argtypes = [vp, i64, vp, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), ctypes.POINTER(vp), vp]
         L.spc_build_kmaps_network.argtypes = [vp, i64, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), i32,
                                               ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32]
         for f in ("spc_kmap_n_in", "spc_kmap_n_out"):
@@ -222,12 +223,19 @@ class KMap:
 
 
 def spc_build_kmap(in_keys: torch.Tensor, desc: PackDesc, K: int, in_stride: int = 1, layer_stride: int = 1,
-                   transposed: int = 0, layout: int = LAYOUT_BOTH, stream=None) -> KMap:
+                   transposed: int = 0, layout: int = LAYOUT_BOTH, stream=None, in_perm: torch.Tensor | None = None) -> KMap:
+    """in_perm: the permutation returned by spc_pack_coords; the map then addresses the caller's unsorted
+    feature rows (spc_build_kmap_perm)."""
     l = LayerDesc(K, in_stride, layer_stride, transposed, layout)
     h = ctypes.c_void_p()
-    _check(lib().spc_build_kmap(_dev_ptr(in_keys), in_keys.shape[0], ctypes.byref(desc), ctypes.byref(l), ctypes.byref(h),
-                                _stream(stream)))
-    return KMap(h.value, keep=(in_keys,), desc=desc)
+    if in_perm is None:
+        _check(lib().spc_build_kmap(_dev_ptr(in_keys), in_keys.shape[0], ctypes.byref(desc), ctypes.byref(l), ctypes.byref(h),
+                                    _stream(stream)))
+        return KMap(h.value, keep=(in_keys,), desc=desc)
+    assert in_perm.dtype == torch.int32 and in_perm.shape[0] == in_keys.shape[0]
+    _check(lib().spc_build_kmap_perm(_dev_ptr(in_keys), in_keys.shape[0], _dev_ptr(in_perm), ctypes.byref(desc), ctypes.byref(l),
+                                     ctypes.byref(h), _stream(stream)))
+    return KMap(h.value, keep=(in_keys, in_perm), desc=desc)
 
 
 def spc_build_kmaps_network(v0_keys: torch.Tensor, desc: PackDesc, layers, streams=None, flags: int = 0):

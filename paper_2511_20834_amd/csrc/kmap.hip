@@ -123,7 +123,8 @@ template <typename KeyT, int K>
 __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
     int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
-    uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap) {
+    uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
+    const int32_t* __restrict__ in_perm) {
   constexpr int G = K * K, K3 = K * K * K;
   constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
@@ -289,7 +290,10 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
       for (int t = 0; t < K; ++t) {
         const int k = g * K + t;
-        if (v < rows32) M[((b0 + bl) * K3 + k) * 32 + (v & 31)] = r[j][t];  // rows past the end hold -1
+        // found positions are stored as they are, or mapped to the caller's row numbering
+        int32_t jv = r[j][t];
+        if (in_perm && jv >= 0) jv = in_perm[jv];
+        if (v < rows32) M[((b0 + bl) * K3 + k) * 32 + (v & 31)] = jv;  // rows past the end hold -1
         const unsigned long long hit = __ballot(r[j][t] >= 0);
         if (hit) {
           if (lane == 0 && unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
@@ -401,7 +405,7 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
     hipLaunchKernelGGL((kmap_search_kernel<KeyT, K>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
-                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles);
+                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm);
   return SPC_OK;
 }
 
@@ -450,8 +454,10 @@ static int ilog2(int v) {
 }
 
 // Builds the map object for given input/output levels (references are taken).
-static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_layer_desc& l, hipStream_t s, spc_kmap** res) {
+static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_layer_desc& l, hipStream_t s, spc_kmap** res,
+                           const int32_t* in_perm = nullptr) {
   spc_kmap* m = new spc_kmap;
+  m->in_perm = in_perm;
   m->pi = pi;
   m->desc = l;
   m->K3 = l.K * l.K * l.K;
@@ -545,6 +551,11 @@ extern "C" {
 
 int spc_build_kmap(const void* in_keys, int64_t n_in, const spc_pack_desc* d, const spc_layer_desc* l, spc_kmap** out,
                    void* stream) {
+  return spc_build_kmap_perm(in_keys, n_in, nullptr, d, l, out, stream);
+}
+
+int spc_build_kmap_perm(const void* in_keys, int64_t n_in, const int32_t* in_perm, const spc_pack_desc* d,
+                        const spc_layer_desc* l, spc_kmap** out, void* stream) {
   PackInfo pi;
   SPC_RETURN_IF(check_desc(d, &pi));
   SPC_RETURN_IF(check_layer(l));
@@ -557,8 +568,9 @@ int spc_build_kmap(const void* in_keys, int64_t n_in, const spc_pack_desc* d, co
   int rc = SPC_OK;
   if (l->layer_stride > 1) rc = downsample_level(in_keys, n_in, nullptr, pi, ilog2(l->in_stride * l->layer_stride), &derived, s);
   if (rc == SPC_OK) {
-    if (l->layer_stride == 1) rc = build_on_levels(given, given, pi, *l, s, out);
-    else if (!l->transposed) rc = build_on_levels(given, derived, pi, *l, s, out);
+    if (in_perm && l->transposed) rc = set_error(SPC_ERR_ARG, "in_perm applies to the given level, which a transposed layer writes");
+    else if (l->layer_stride == 1) rc = build_on_levels(given, given, pi, *l, s, out, in_perm);
+    else if (!l->transposed) rc = build_on_levels(given, derived, pi, *l, s, out, in_perm);
     else rc = build_on_levels(derived, given, pi, *l, s, out);
   }
   level_unref(given);

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const int4* __restrict__ coor
     key = (KeyT(c.x) << p.sh_b) | (KeyT(fx + p.pad) << p.sh_x) | (KeyT(fy + p.pad) << p.sh_y) | KeyT(fz + p.pad);
   } else {
     key = ~KeyT(0);
-    atomicOr(status, 1);
+    if (status) atomicOr(status, 1);
   }
   keys[i] = key;
   if (iota) iota[i] = static_cast<int32_t>(i);
@@ -260,9 +260,10 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   char* ws = static_cast<char*>(workspace);
   void* keys_tmp = ws;
   int32_t* iota = reinterpret_cast<int32_t*>(ws + off_iota);
-  int32_t* status = reinterpret_cast<int32_t*>(ws + off_status);
+  // the status word is only kept when somebody is going to read it
+  int32_t* status = (flags & SPC_PACK_VALIDATE) ? reinterpret_cast<int32_t*>(ws + off_status) : nullptr;
   PackParams p{pi.sh_b, pi.sh_x, pi.sh_y, pi.bits_b, pi.bits_x, pi.bits_y, pi.bits_z, d->origin[0], d->origin[1], d->origin[2], d->pad};
-  hipLaunchKernelGGL(set_int_kernel, dim3(1), dim3(1), 0, s, status, 0);
+  if (status) hipLaunchKernelGGL(set_int_kernel, dim3(1), dim3(1), 0, s, status, 0);
   if (n > 0) {
     const int grid = static_cast<int>((n + 255) / 256);
     if (pi.key_bits == 32)

@@ -88,6 +88,7 @@ struct spc_kmap {
   int K3 = 0;
   spc::Level* in_level = nullptr;   // the layer's input voxels
   spc::Level* out_level = nullptr;  // the layer's output voxels
+  const int32_t* in_perm = nullptr; // caller's row number of every input voxel (borrowed), or NULL
   int64_t out_cap = 0;              // rows allocated in os_map / ws lists
   int64_t n_out_hint = -1;          // caller's estimate of n_out for kernel selection while n_host is unknown
   bool captured = false;            // built while its stream was being captured into a graph

@@ -240,6 +240,33 @@ def test_conv_strided_rows_concat_buffer():
     km.destroy()
 
 
+@pytest.mark.parametrize("K,s_l", [(3, 1), (2, 2), (3, 2), (5, 1)])
+def test_kmap_with_sort_permutation_folded_in(K, s_l):
+    """spc_build_kmap_perm: the stored input indices are the caller's row numbers, so the layer runs on
+    the unsorted feature matrix and gives the result of the sorted pipeline."""
+    c = _cloud("rand_b3")
+    desc = fit_desc(c, [(K, 1, s_l)])
+    keys, perm = gpu_pack(c, desc)
+    cs, operm = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_BOTH, in_perm=perm)
+    ci, co, M = oracle_layer(cs, K, 1, s_l, 0)
+    ref_t = oracle.triples(M)
+    ref_t[:, 1] = operm[ref_t[:, 1]]  # sorted position -> original row
+    ref_t = ref_t[np.lexsort((ref_t[:, 2], ref_t[:, 0]))]
+    for which in (B.LAYOUT_OS, B.LAYOUT_WS):
+        got = km.export_triples(which)
+        assert np.array_equal(got[np.lexsort((got[:, 2], got[:, 0]))], ref_t), which
+    F = synth.features(len(c), 32, np.float16, seed=31)  # rows in the cloud's original order
+    W = synth.weights(K ** 3, 32, 64, np.float16, seed=32)
+    ref = oracle.conv(M, F[operm].astype(np.float64), W.astype(np.float64))
+    for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
+        y = B.spc_conv_forward(km, torch.from_numpy(F).cuda(), torch.from_numpy(W).cuda(), df)
+        assert rel_err(y.cpu().double().numpy(), ref) <= 1e-2, df
+    km.destroy()
+    with pytest.raises(B.SpcError):
+        B.spc_build_kmap(keys, desc, 2, 1, 2, 1, B.LAYOUT_OS, in_perm=perm)
+
+
 def test_conv_unaligned_feature_rows():
     """Rows that do not start on 16-byte boundaries (odd column offset) still give the right result."""
     c = _cloud("tiny")
