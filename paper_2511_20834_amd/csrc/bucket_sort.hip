@@ -1,0 +1,503 @@
+// Sort of packed voxel keys for the cloud sizes of this workload (thousands to about half a
+// million keys): one most-significant-digit split, then every bucket is sorted inside LDS by
+// one workgroup.  Four short launches, no look-back spinning, no global atomics:
+//
+//   count    each workgroup produces its share of the keys (packing coordinates, Section 5.3,
+//            or masking the keys of a finer level, Section 5.5), histograms the top `fb` used
+//            key bits ("fine bins") in LDS and writes one row of the table [workgroup][bin];
+//   colscan  exclusive prefixes down the table's columns: where a workgroup's keys of a bin go
+//            inside the bin, and the bin totals;
+//   scatter  each workgroup scans the bin totals (where every bin starts) and moves its keys,
+//            with their source index, to their bin's range; workgroup 0 also cuts the bin
+//            sequence into buckets of about BS_TARGET keys: the buckets adapt to the key
+//            distribution (a LiDAR sweep is many times denser near the sensor), so the sort
+//            workgroups get equal work;
+//   sort     one workgroup per bucket: bitonic network over (key, index) in LDS, three
+//            stages per barrier (a thread holds the 8 elements that three consecutive
+//            compare distances connect).  With variant UNIQUE the bucket's distinct keys are
+//            counted and left at the start of the bucket's range (the caller compacts the
+//            ranges with `gather`).
+//
+// x is the most significant spatial field, so a bucket is a slab of the scene.  A single bin
+// that outgrows the LDS tile (a dense slab) is sorted straight in global memory by the
+// all-ascending form of the network (first step of every merge compares mirrored positions),
+// which sorts any length when the missing tail is taken as +infinity: comparators that touch
+// the tail are skipped.  Correct for any input, slow only for degenerate ones.
+// Comparing (key, source index) pairs makes the result the stable order, independent of how
+// the scatter raced.
+#include <algorithm>
+
+#include "spc_internal.h"
+
+namespace spc {
+
+constexpr int BS_THREADS = 256;   // sort / gather workgroups
+constexpr int BS_WIDE = 1024;     // count / scan / scatter workgroups
+// keys per LDS tile (32 KB of (key, index) elements either way)
+template <typename KeyT>
+constexpr int bs_cap() { return sizeof(KeyT) == 4 ? 4096 : 2048; }
+
+__device__ inline int bs_bin(uint64_t key, int shift, int n_bin) {
+  const uint64_t b = key >> shift;
+  return b < uint64_t(n_bin) ? static_cast<int>(b) : n_bin - 1;  // all-ones keys of rejected rows go last
+}
+
+// ---------------------------------------------------------------- key sources
+template <typename KeyT>
+struct SrcPack {
+  const int4* coords;
+  PackParams p;
+  int32_t* status;
+  __device__ KeyT operator()(int64_t i) const { return pack_key<KeyT>(coords[i], p, status); }
+  __device__ bool skip(int64_t, KeyT) const { return false; }
+};
+template <typename KeyT>
+struct SrcMask {
+  const KeyT* keys;
+  KeyT mask;
+  __device__ KeyT operator()(int64_t i) const { return keys[i] & mask; }
+  // The finer level is sorted, so runs along z collapse to runs of equal masked keys: only the
+  // first key of a run takes part (the result is the set of distinct keys either way).
+  __device__ bool skip(int64_t i, KeyT key) const { return i > 0 && (keys[i - 1] & mask) == key; }
+};
+
+// ---------------------------------------------------------------- count
+template <typename KeyT, typename Src>
+__global__ __launch_bounds__(BS_WIDE) void bs_count_kernel(Src src, int64_t n, int per, int shift, int n_bin,
+                                                           KeyT* __restrict__ keys0, int32_t* __restrict__ table) {
+  __shared__ int hist[BS_MAX_BIN];
+  for (int b = threadIdx.x; b < n_bin; b += BS_WIDE) hist[b] = 0;
+  __syncthreads();
+  const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
+  for (int64_t i = lo + threadIdx.x; i < hi; i += BS_WIDE) {
+    const KeyT key = src(i);
+    keys0[i] = key;
+    if (!src.skip(i, key)) atomicAdd(&hist[bs_bin(key, shift, n_bin)], 1);
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < n_bin; b += BS_WIDE) table[int64_t(blockIdx.x) * n_bin + b] = hist[b];
+}
+
+// ---------------------------------------------------------------- column scan
+// One thread per four bins: before[w][f] receives the number of keys of bin f held by workgroups
+// < w, tot[f] the bin's total.  The loads of 16 table rows are in flight together.
+constexpr int BS_COL_THREADS = 64;
+__global__ __launch_bounds__(BS_COL_THREADS) void bs_colscan_kernel(const int32_t* __restrict__ table,
+                                                                    int32_t* __restrict__ before, int n_wg, int n_bin,
+                                                                    int32_t* __restrict__ tot) {
+  constexpr int ROWS = 16;
+  const int f0 = (blockIdx.x * BS_COL_THREADS + threadIdx.x) * 4;
+  if (f0 >= n_bin) return;  // n_bin is a multiple of 4
+  int4 run = make_int4(0, 0, 0, 0);
+  for (int w0 = 0; w0 < n_wg; w0 += ROWS) {
+    int4 c[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) c[r] = *reinterpret_cast<const int4*>(table + int64_t(min(w0 + r, n_wg - 1)) * n_bin + f0);
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+      if (w0 + r < n_wg) {
+        *reinterpret_cast<int4*>(before + int64_t(w0 + r) * n_bin + f0) = run;
+        run.x += c[r].x;
+        run.y += c[r].y;
+        run.z += c[r].z;
+        run.w += c[r].w;
+      }
+  }
+  *reinterpret_cast<int4*>(tot + f0) = run;
+}
+
+// ---------------------------------------------------------------- scatter
+// Every workgroup scans the bin totals on its own (16 KB; cheaper than one more launch): start
+// of bin f, then the workgroup's first position in the bin.  Workgroup 0 also cuts the bin
+// sequence into buckets: bucket j starts at the first bin whose start is >= j * target
+// (bstart[n_bucket] = n).
+template <typename KeyT, bool DEDUP>
+__global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restrict__ keys0, int64_t n, int per, int shift,
+                                                             int n_bin, const int32_t* __restrict__ before,
+                                                             const int32_t* __restrict__ tot, int target, int n_bucket,
+                                                             KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
+                                                             int32_t* __restrict__ bstart) {
+  __shared__ int pos[BS_MAX_BIN + 1];  // bin starts, then this workgroup's running position in every bin
+  __shared__ int wave_tot[BS_WIDE / 64];
+  static_assert(BS_MAX_BIN == 4 * BS_WIDE, "one int4 of bins per thread");
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int f0 = t * 4;
+  int4 c = make_int4(0, 0, 0, 0), bef = c;
+  if (f0 < n_bin) {
+    c = *reinterpret_cast<const int4*>(tot + f0);
+    bef = *reinterpret_cast<const int4*>(before + int64_t(blockIdx.x) * n_bin + f0);
+  }
+  const int sum = c.x + c.y + c.z + c.w;
+  int x = sum;
+  for (int d = 1; d < 64; d <<= 1) {
+    const int y = __shfl_up(x, d, 64);
+    if (lane >= d) x += y;
+  }
+  if (lane == 63) wave_tot[wave] = x;
+  __syncthreads();
+  int base = x - sum, total = 0;  // total: keys that take part (all of them unless DEDUP)
+  for (int w = 0; w < BS_WIDE / 64; ++w) {
+    if (w < wave) base += wave_tot[w];
+    total += wave_tot[w];
+  }
+  const int4 st = make_int4(base, base + c.x, base + c.x + c.y, base + c.x + c.y + c.z);
+  if (blockIdx.x == 0) {
+    if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = st;
+    if (t == 0) pos[n_bin] = total;
+    __syncthreads();
+    // bin f opens every bucket j with start(f-1) < j * target <= start(f); bucket 0 opens at bin 0
+    for (int f = t; f < n_bin; f += BS_WIDE) {
+      const int s1 = pos[f];
+      const int j0 = f == 0 ? 0 : pos[f - 1] / target + 1;
+      for (int j = j0; j <= s1 / target && j < n_bucket; ++j) bstart[j] = s1;
+    }
+    // buckets whose threshold lies beyond the last bin's start are empty
+    for (int j = pos[n_bin - 1] / target + 1 + t; j < n_bucket; j += BS_WIDE) bstart[j] = total;
+    if (t == 0) bstart[n_bucket] = total;
+    __syncthreads();
+  }
+  if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = make_int4(st.x + bef.x, st.y + bef.y, st.z + bef.z, st.w + bef.w);
+  __syncthreads();
+  const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
+  for (int64_t i = lo + threadIdx.x; i < hi; i += BS_WIDE) {
+    const KeyT key = keys0[i];
+    if (DEDUP && i > 0 && keys0[i - 1] == key) continue;
+    const int p = atomicAdd(&pos[bs_bin(key, shift, n_bin)], 1);
+    keys1[p] = key;
+    vals1[p] = static_cast<int32_t>(i);
+  }
+}
+
+// ---------------------------------------------------------------- sort
+// Element = (key, source index).  32-bit keys travel as one 64-bit word.
+template <typename KeyT>
+struct Elem;
+template <>
+struct Elem<uint32_t> {
+  uint64_t kv;
+  __device__ static Elem make(uint32_t k, int32_t v) { return Elem{(uint64_t(k) << 32) | uint32_t(v)}; }
+  __device__ static Elem last() { return Elem{~uint64_t(0)}; }  // above every (key, index) pair
+  __device__ uint32_t key() const { return static_cast<uint32_t>(kv >> 32); }
+  __device__ int32_t val() const { return static_cast<int32_t>(uint32_t(kv)); }
+  __device__ bool operator<(const Elem& o) const { return kv < o.kv; }
+};
+template <>
+struct Elem<uint64_t> {
+  uint64_t k;
+  int32_t v;
+  __device__ static Elem make(uint64_t k, int32_t v) { return Elem{k, v}; }
+  __device__ static Elem last() { return Elem{~uint64_t(0), 0x7fffffff}; }
+  __device__ uint64_t key() const { return k; }
+  __device__ int32_t val() const { return v; }
+  __device__ bool operator<(const Elem& o) const { return k < o.k || (k == o.k && v < o.v); }
+};
+
+// Accessors: the tile in LDS, or the bucket's range in global memory.
+template <typename KeyT>
+struct LdsTile {
+  Elem<KeyT>* e;
+  __device__ Elem<KeyT> get(int i) const { return e[i]; }
+  __device__ void put(int i, const Elem<KeyT>& x) const { e[i] = x; }
+};
+template <typename KeyT>
+struct GlobalRange {
+  KeyT* k;
+  int32_t* v;
+  __device__ Elem<KeyT> get(int i) const { return Elem<KeyT>::make(k[i], v[i]); }
+  __device__ void put(int i, const Elem<KeyT>& x) const {
+    k[i] = x.key();
+    v[i] = x.val();
+  }
+};
+
+template <typename Acc>
+__device__ inline void bs_cmpxchg(const Acc& a, int i, int j) {
+  const auto x = a.get(i), y = a.get(j);
+  if (y < x) {
+    a.put(i, y);
+    a.put(j, x);
+  }
+}
+
+// LDS position of tile element i: one element of padding per 32, so that the strided accesses
+// of the short compare distances (a thread's 8 elements are then neighbours, and lanes are 8
+// elements apart) spread over the banks instead of hitting the same few.
+__device__ inline int bs_at(int i) { return i + (i >> 5); }
+
+// Standard bitonic network on a power-of-two tile in LDS, NB consecutive compare distances per
+// barrier: the thread's 2^NB elements are those whose indices differ in bits ltop .. ltop-NB+1.
+// The merge of blocks of 2^lk sorts ascending where bit lk of the index is clear.
+template <int NB, typename E>
+__device__ inline void bs_lds_round(E* tile, int P, int lk, int ltop) {
+  constexpr int R = 1 << NB;
+  const int lbot = ltop - NB + 1;
+  for (int t = threadIdx.x; t < (P >> NB); t += BS_THREADS) {
+    const int base = ((t >> lbot) << (ltop + 1)) | (t & ((1 << lbot) - 1));
+    const bool asc = (base & (1 << lk)) == 0;
+    E e[R];
+#pragma unroll
+    for (int q = 0; q < R; ++q) e[q] = tile[bs_at(base | (q << lbot))];
+#pragma unroll
+    for (int sb = NB - 1; sb >= 0; --sb)
+#pragma unroll
+      for (int q = 0; q < R; ++q)
+        if (!(q & (1 << sb))) {
+          const int q2 = q | (1 << sb);
+          const bool sw = asc ? (e[q2] < e[q]) : (e[q] < e[q2]);
+          const E lo = sw ? e[q2] : e[q], hi = sw ? e[q] : e[q2];
+          e[q] = lo;
+          e[q2] = hi;
+        }
+#pragma unroll
+    for (int q = 0; q < R; ++q) tile[bs_at(base | (q << lbot))] = e[q];
+  }
+  __syncthreads();
+}
+
+// Sorts tile[0, P), P = 2^lp; every thread of the workgroup calls it.
+template <typename E>
+__device__ inline void bs_lds_bitonic(E* tile, int lp) {
+  const int P = 1 << lp;
+  for (int lk = 1; lk <= lp; ++lk) {
+    int ltop = lk - 1;  // compare distances 2^(lk-1) .. 1
+    const int first = lk % 3;
+    if (first == 1) {
+      bs_lds_round<1>(tile, P, lk, ltop);
+      ltop -= 1;
+    } else if (first == 2) {
+      bs_lds_round<2>(tile, P, lk, ltop);
+      ltop -= 2;
+    }
+    for (; ltop >= 2; ltop -= 3) bs_lds_round<3>(tile, P, lk, ltop);
+  }
+}
+
+// Sorts positions [0, m) ascending; every thread of the workgroup calls it.
+template <typename Acc>
+__device__ inline void bs_bitonic(const Acc& a, int m) {
+  int lp = 0;
+  while ((1 << lp) < m) ++lp;
+  const int half = (1 << lp) >> 1;
+  for (int lk = 1; lk <= lp; ++lk) {  // merges of blocks of k = 2^lk
+    const int k = 1 << lk, lh = lk - 1;
+    for (int t = threadIdx.x; t < half; t += BS_THREADS) {  // mirrored step
+      const int blk = t >> lh, off = t & ((1 << lh) - 1);
+      const int i = (blk << lk) + off, j = (blk << lk) + k - 1 - off;
+      if (j < m) bs_cmpxchg(a, i, j);
+    }
+    __syncthreads();
+    for (int ld = lk - 2; ld >= 0; --ld) {  // half-cleaners of distance d = 2^ld
+      for (int t = threadIdx.x; t < half; t += BS_THREADS) {
+        const int i = ((t >> ld) << (ld + 1)) + (t & ((1 << ld) - 1)), j = i + (1 << ld);
+        if (j < m) bs_cmpxchg(a, i, j);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// One workgroup per bucket.  UNIQUE: out_k receives the bucket's distinct keys at the start
+// of its range and ucount[bucket] their number; otherwise out_k/out_v the sorted pairs.
+template <typename KeyT, bool UNIQUE>
+__global__ __launch_bounds__(BS_THREADS) void bs_sort_kernel(KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
+                                                             const int32_t* __restrict__ bstart, int shift,
+                                                             KeyT* __restrict__ out_k, int32_t* __restrict__ out_v,
+                                                             int32_t* __restrict__ ucount) {
+  constexpr int CAP = bs_cap<KeyT>();
+  __shared__ Elem<KeyT> tile[CAP + CAP / 32];
+  __shared__ int wave_tot[BS_THREADS / 64];
+  const int s = bstart[blockIdx.x], m = bstart[blockIdx.x + 1] - s;
+  if (m <= 0) {
+    if (UNIQUE && threadIdx.x == 0) ucount[blockIdx.x] = 0;
+    return;
+  }
+  const bool in_lds = m <= CAP;
+  if (in_lds) {
+    int lp = 0;
+    while ((1 << lp) < m) ++lp;
+    for (int i = threadIdx.x; i < (1 << lp); i += BS_THREADS)
+      tile[bs_at(i)] = i < m ? Elem<KeyT>::make(keys1[s + i], vals1[s + i]) : Elem<KeyT>::last();
+    __syncthreads();
+    bs_lds_bitonic(tile, lp);
+  } else {
+    bs_bitonic(GlobalRange<KeyT>{keys1 + s, vals1 + s}, m);
+  }
+  auto key_at = [&](int i) -> KeyT { return in_lds ? tile[bs_at(i)].key() : keys1[s + i]; };
+  if (!UNIQUE) {
+    for (int i = threadIdx.x; i < m; i += BS_THREADS) {
+      out_k[s + i] = key_at(i);
+      if (out_v) out_v[s + i] = in_lds ? tile[bs_at(i)].val() : vals1[s + i];
+    }
+  } else {
+    // heads of runs of equal keys, compacted in order (positions are visited in array order)
+    int run = 0;
+    for (int i0 = 0; i0 < m; i0 += BS_THREADS) {
+      const int i = i0 + threadIdx.x;
+      const bool head = i < m && (i == 0 || key_at(i) != key_at(i - 1));
+      const KeyT kv = i < m ? key_at(i) : KeyT(0);
+      const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+      const unsigned long long bal = __ballot(head);
+      if (lane == 0) wave_tot[wave] = __popcll(bal);
+      __syncthreads();
+      int base = run, tot = 0;
+      for (int w = 0; w < BS_THREADS / 64; ++w) {
+        if (w < wave) base += wave_tot[w];
+        tot += wave_tot[w];
+      }
+      // out_k is a different buffer from keys1, so positions still to be read are not overwritten
+      if (head) out_k[s + base + __popcll(bal & ((1ull << lane) - 1ull))] = kv;
+      run += tot;
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) ucount[blockIdx.x] = run;
+  }
+}
+
+// Compacts the buckets' unique keys: out[prefix(ucount)[b] + i] = in[bstart[b] + i]; total to *n_out.
+template <typename KeyT>
+__global__ __launch_bounds__(BS_THREADS) void bs_gather_kernel(const KeyT* __restrict__ in, const int32_t* __restrict__ bstart,
+                                                               const int32_t* __restrict__ ucount, int n_bucket,
+                                                               KeyT* __restrict__ out, int32_t* __restrict__ n_out) {
+  __shared__ int pre[BS_MAX_BUCKET];
+  __shared__ int wave_tot[BS_THREADS / 64];
+  constexpr int PER = BS_MAX_BUCKET / BS_THREADS;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  int loc[PER], sum = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int b = t * PER + j;
+    loc[j] = b < n_bucket ? ucount[b] : 0;
+    sum += loc[j];
+  }
+  int x = sum;
+  for (int d = 1; d < 64; d <<= 1) {
+    const int y = __shfl_up(x, d, 64);
+    if (lane >= d) x += y;
+  }
+  if (lane == 63) wave_tot[wave] = x;
+  __syncthreads();
+  int base = x - sum, total = 0;
+  for (int w = 0; w < BS_THREADS / 64; ++w) {
+    if (w < wave) base += wave_tot[w];
+    total += wave_tot[w];
+  }
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int b = t * PER + j;
+    if (b < n_bucket) pre[b] = base;
+    base += loc[j];
+  }
+  __syncthreads();
+  if (blockIdx.x == 0 && t == 0) *n_out = total;
+  for (int b = blockIdx.x; b < n_bucket; b += gridDim.x) {
+    const int c = ucount[b], src = bstart[b], dst = pre[b];
+    for (int i = t; i < c; i += BS_THREADS) out[dst + i] = in[src + i];
+  }
+}
+
+// ---------------------------------------------------------------- host
+BucketPlan bucket_plan(int64_t n, int used_bits) {
+  BucketPlan p{};
+  int n_wg = static_cast<int>(std::min<int64_t>(std::max<int64_t>((n + 4095) / 4096, 1), BS_MAX_WG));
+  p.per = static_cast<int>(((n + n_wg - 1) / n_wg + BS_WIDE - 1) / BS_WIDE * BS_WIDE);
+  p.n_wg = static_cast<int>(std::max<int64_t>((n + p.per - 1) / p.per, 1));
+  // About 16 keys per bin of the key space: packing descriptors round every field up to whole
+  // bits and scenes are far from cubic, so typically a quarter of the bins is populated.
+  int fb = 8;
+  while (fb < BS_MAX_BIN_BITS && (int64_t(16) << fb) < n) ++fb;
+  fb = std::max(2, std::min(fb, used_bits));
+  p.shift = used_bits - fb;
+  p.n_bin = 1 << fb;
+  p.target = BS_TARGET;
+  p.n_bucket = static_cast<int>(std::max<int64_t>((n + p.target - 1) / p.target, 1));
+  return p;
+}
+
+size_t bucket_sort_ws_bytes(int key_bits, int64_t n) {
+  const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
+  const size_t k = (nn * (key_bits / 8) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
+  return 2 * k + v + (2 * size_t(BS_MAX_WG) * BS_MAX_BIN + BS_MAX_BIN + 64 + 2 * (size_t(BS_MAX_BUCKET) + 64)) * 4;
+}
+
+namespace {
+template <typename KeyT>
+struct Ws {
+  KeyT* keys0;
+  KeyT* keys1;
+  int32_t* vals1;
+  int32_t* table;
+  int32_t* before;
+  int32_t* fstart;
+  int32_t* bstart;
+  int32_t* ucount;
+};
+template <typename KeyT>
+Ws<KeyT> carve(void* ws, int64_t n) {
+  const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
+  const size_t k = (nn * sizeof(KeyT) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
+  char* c = static_cast<char*>(ws);
+  Ws<KeyT> w;
+  w.keys0 = reinterpret_cast<KeyT*>(c);
+  w.keys1 = reinterpret_cast<KeyT*>(c + k);
+  w.vals1 = reinterpret_cast<int32_t*>(c + 2 * k);
+  w.table = reinterpret_cast<int32_t*>(c + 2 * k + v);
+  w.before = w.table + size_t(BS_MAX_WG) * BS_MAX_BIN;
+  w.fstart = w.before + size_t(BS_MAX_WG) * BS_MAX_BIN;
+  w.bstart = w.fstart + BS_MAX_BIN + 64;
+  w.ucount = w.bstart + BS_MAX_BUCKET + 64;
+  return w;
+}
+
+// count, scan, scatter: keys1/vals1 partitioned by fine bin, bstart = bucket boundaries
+template <typename KeyT, bool DEDUP, typename Src>
+void partition(const Src& src, int64_t n, const BucketPlan& p, const Ws<KeyT>& w, hipStream_t s) {
+  const size_t lds = 0;
+  hipLaunchKernelGGL((bs_count_kernel<KeyT, Src>), dim3(p.n_wg), dim3(BS_WIDE), lds, s, src, n, p.per, p.shift, p.n_bin, w.keys0,
+                     w.table);
+  const int col_wg = (p.n_bin / 4 + BS_COL_THREADS - 1) / BS_COL_THREADS;
+  hipLaunchKernelGGL(bs_colscan_kernel, dim3(col_wg), dim3(BS_COL_THREADS), 0, s, w.table, w.before, p.n_wg, p.n_bin, w.fstart);
+  hipLaunchKernelGGL((bs_scatter_kernel<KeyT, DEDUP>), dim3(p.n_wg), dim3(BS_WIDE), 0, s, w.keys0, n, p.per, p.shift, p.n_bin, w.before,
+                     w.fstart, p.target, p.n_bucket, w.keys1, w.vals1, w.bstart);
+}
+}  // namespace
+
+template <typename KeyT>
+static int pack_sort_t(const int4* coords, int64_t n, const PackParams& pp, int used_bits, int32_t* status, void* keys_out,
+                       int32_t* perm_out, void* ws, hipStream_t s) {
+  const BucketPlan p = bucket_plan(n, used_bits);
+  const Ws<KeyT> w = carve<KeyT>(ws, n);
+  partition<KeyT, false>(SrcPack<KeyT>{coords, pp, status}, n, p, w, s);
+  hipLaunchKernelGGL((bs_sort_kernel<KeyT, false>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, p.shift,
+                     static_cast<KeyT*>(keys_out), perm_out, static_cast<int32_t*>(nullptr));
+  if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "sort launch failed");
+  return SPC_OK;
+}
+
+int bucket_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int used_bits, int32_t* status,
+                     void* keys_out, int32_t* perm_out, void* ws, hipStream_t s) {
+  return key_bits == 32 ? pack_sort_t<uint32_t>(coords, n, pp, used_bits, status, keys_out, perm_out, ws, s)
+                        : pack_sort_t<uint64_t>(coords, n, pp, used_bits, status, keys_out, perm_out, ws, s);
+}
+
+template <typename KeyT>
+static int mask_unique_t(const void* keys_in, int64_t n, uint64_t mask, int used_bits, void* keys_out, int32_t* n_out, void* ws,
+                         hipStream_t s) {
+  const BucketPlan p = bucket_plan(n, used_bits);
+  const Ws<KeyT> w = carve<KeyT>(ws, n);
+  partition<KeyT, true>(SrcMask<KeyT>{static_cast<const KeyT*>(keys_in), static_cast<KeyT>(mask)}, n, p, w, s);
+  // distinct keys of every bucket land at the start of its range in keys0 (free again by now)
+  hipLaunchKernelGGL((bs_sort_kernel<KeyT, true>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, p.shift,
+                     w.keys0, static_cast<int32_t*>(nullptr), w.ucount);
+  hipLaunchKernelGGL(bs_gather_kernel<KeyT>, dim3(std::min(p.n_bucket, 256)), dim3(BS_THREADS), 0, s, w.keys0, w.bstart, w.ucount,
+                     p.n_bucket, static_cast<KeyT*>(keys_out), n_out);
+  if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "downsample launch failed");
+  return SPC_OK;
+}
+
+int bucket_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, int used_bits, void* keys_out,
+                       int32_t* n_out, void* ws, hipStream_t s) {
+  return key_bits == 32 ? mask_unique_t<uint32_t>(keys_in, n, mask, used_bits, keys_out, n_out, ws, s)
+                        : mask_unique_t<uint64_t>(keys_in, n, mask, used_bits, keys_out, n_out, ws, s);
+}
+
+}  // namespace spc

@@ -48,33 +48,14 @@ int sort_keys(int key_bits, const void* ki, void* ko, int64_t n, int end_bit, vo
 }
 
 // ---------------------------------------------------------------- kernels
-struct PackParams {
-  int sh_b, sh_x, sh_y;
-  int bits_b, bits_x, bits_y, bits_z;
-  int ox, oy, oz, pad;
-};
-
 // One thread per voxel: 16-byte coalesced load of (b,x,y,z), one key store.
-// status bit 0 is raised if a field (with its guard band on both sides) does not fit.
 template <typename KeyT>
 __global__ __launch_bounds__(256) void pack_kernel(const int4* __restrict__ coords, int64_t n, PackParams p,
                                                    KeyT* __restrict__ keys, int32_t* __restrict__ iota,
                                                    int32_t* __restrict__ status) {
   const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   if (i >= n) return;
-  const int4 c = coords[i];
-  const int64_t fx = int64_t(c.y) - p.ox, fy = int64_t(c.z) - p.oy, fz = int64_t(c.w) - p.oz;
-  const bool ok = c.x >= 0 && (int64_t(c.x) < (int64_t(1) << p.bits_b)) && fx >= 0 && fy >= 0 && fz >= 0 &&
-                  fx + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_x) && fy + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_y) &&
-                  fz + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_z);
-  KeyT key;
-  if (ok) {
-    key = (KeyT(c.x) << p.sh_b) | (KeyT(fx + p.pad) << p.sh_x) | (KeyT(fy + p.pad) << p.sh_y) | KeyT(fz + p.pad);
-  } else {
-    key = ~KeyT(0);
-    if (status) atomicOr(status, 1);
-  }
-  keys[i] = key;
+  keys[i] = pack_key<KeyT>(coords[i], p, status);
   if (iota) iota[i] = static_cast<int32_t>(i);
 }
 
@@ -170,6 +151,13 @@ __global__ __launch_bounds__(UQ_THREADS) void unique_write_kernel(const KeyT* __
 
 template <typename KeyT>
 static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, Level* lv, hipStream_t s) {
+  if (n >= BS_MIN_N && n <= BS_MAX_N) {
+    char* scratch = static_cast<char*>(pool_alloc(bucket_sort_ws_bytes(pi.key_bits, n), s));
+    if (!scratch) return SPC_ERR_NOMEM;
+    const int rc = bucket_mask_unique(pi.key_bits, src, n, level_mask(pi, m), pi.used_bits, lv->keys, lv->n_dev, scratch, s);
+    pool_free(scratch, s);  // reuse is ordered behind these kernels on this stream
+    return rc;
+  }
   const size_t ksz = sizeof(KeyT);
   const size_t tb = sort_keys_temp_bytes(pi.key_bits, n);
   const int n_blocks = static_cast<int>((n + UQ_BLOCK - 1) / UQ_BLOCK);
@@ -248,7 +236,9 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   const size_t off_iota = (nn * ksz + 255) / 256 * 256;
   const size_t off_status = off_iota + (nn * 4 + 255) / 256 * 256;
   const size_t off_temp = off_status + 256;
-  const size_t tb = std::max(sort_pairs_temp_bytes(pi.key_bits, nn), sort_keys_temp_bytes(pi.key_bits, nn));
+  const bool bucket = n >= BS_MIN_N && n <= BS_MAX_N;
+  const size_t tb = bucket ? bucket_sort_ws_bytes(pi.key_bits, nn)
+                           : std::max(sort_pairs_temp_bytes(pi.key_bits, nn), sort_keys_temp_bytes(pi.key_bits, nn));
   const size_t need = off_temp + tb + 256;
   if (!workspace) {
     *workspace_bytes = need;
@@ -264,7 +254,17 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   int32_t* status = (flags & SPC_PACK_VALIDATE) ? reinterpret_cast<int32_t*>(ws + off_status) : nullptr;
   PackParams p{pi.sh_b, pi.sh_x, pi.sh_y, pi.bits_b, pi.bits_x, pi.bits_y, pi.bits_z, d->origin[0], d->origin[1], d->origin[2], d->pad};
   if (status) hipLaunchKernelGGL(set_int_kernel, dim3(1), dim3(1), 0, s, status, 0);
-  if (n > 0) {
+  if (bucket) {
+    SPC_RETURN_IF(bucket_pack_sort(pi.key_bits, reinterpret_cast<const int4*>(coords), n, p, pi.used_bits, status, keys_out, perm_out,
+                                   ws + off_temp, s));
+    if (flags & SPC_PACK_VALIDATE) {
+      const int grid = static_cast<int>((n + 255) / 256);
+      if (pi.key_bits == 32)
+        hipLaunchKernelGGL(dup_check_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint32_t*>(keys_out), n, status);
+      else
+        hipLaunchKernelGGL(dup_check_kernel<uint64_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint64_t*>(keys_out), n, status);
+    }
+  } else if (n > 0) {
     const int grid = static_cast<int>((n + 255) / 256);
     if (pi.key_bits == 32)
       hipLaunchKernelGGL(pack_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, reinterpret_cast<const int4*>(coords), n, p,

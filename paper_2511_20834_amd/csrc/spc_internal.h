@@ -70,6 +70,47 @@ bool stream_is_capturing(hipStream_t s);
 int downsample_level(const void* src_keys, int64_t n_src, const int* n_src_dev, const PackInfo& pi, int m,
                      Level** out, hipStream_t stream);
 
+// ---------------------------------------------------------------- packing (Section 5.3)
+struct PackParams {
+  int sh_b, sh_x, sh_y;
+  int bits_b, bits_x, bits_y, bits_z;
+  int ox, oy, oz, pad;
+};
+
+#ifdef __HIPCC__
+// Key of one (b,x,y,z) row.  A field that does not fit (guard band on both sides included)
+// gives the all-ones key and raises bit 0 of *status (when status is not NULL).
+template <typename KeyT>
+__device__ inline KeyT pack_key(const int4 c, const PackParams& p, int32_t* status) {
+  const int64_t fx = int64_t(c.y) - p.ox, fy = int64_t(c.z) - p.oy, fz = int64_t(c.w) - p.oz;
+  const bool ok = c.x >= 0 && (int64_t(c.x) < (int64_t(1) << p.bits_b)) && fx >= 0 && fy >= 0 && fz >= 0 &&
+                  fx + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_x) && fy + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_y) &&
+                  fz + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_z);
+  if (ok) return (KeyT(c.x) << p.sh_b) | (KeyT(fx + p.pad) << p.sh_x) | (KeyT(fy + p.pad) << p.sh_y) | KeyT(fz + p.pad);
+  if (status) atomicOr(status, 1);
+  return ~KeyT(0);
+}
+#endif
+
+// ---------------------------------------------------------------- bucket sort (own kernels)
+constexpr int BS_MAX_WG = 32;       // workgroups of the count / scatter passes
+constexpr int BS_MAX_BIN_BITS = 12;
+constexpr int BS_MAX_BIN = 1 << BS_MAX_BIN_BITS;  // fine bins (top used key bits)
+constexpr int BS_TARGET = 512;      // keys per bucket aimed at
+constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 512 * 1024;  // sizes it is used for; rocPRIM outside
+constexpr int BS_MAX_BUCKET = static_cast<int>(BS_MAX_N / BS_TARGET);
+struct BucketPlan {
+  int n_wg, per, shift, n_bin, target, n_bucket;
+};
+BucketPlan bucket_plan(int64_t n, int used_bits);
+size_t bucket_sort_ws_bytes(int key_bits, int64_t n);
+// coords -> sorted keys (+ permutation); enqueues three kernels
+int bucket_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int used_bits, int32_t* status,
+                     void* keys_out, int32_t* perm_out, void* ws, hipStream_t s);
+// sorted distinct values of keys_in & mask, count to *n_out [device]; enqueues four kernels
+int bucket_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, int used_bits, void* keys_out,
+                       int32_t* n_out, void* ws, hipStream_t s);
+
 // ---------------------------------------------------------------- sort (rocPRIM radix sort)
 size_t sort_pairs_temp_bytes(int key_bits, int64_t n);
 int sort_pairs(int key_bits, const void* keys_in, void* keys_out, const int32_t* vals_in, int32_t* vals_out,

@@ -34,6 +34,18 @@ def _cloud(name):
         return synth.random_cloud(128 * 5 + 1, (30, 30, 30), seed=4)
     if name == "one":
         return np.array([[0, 5, 6, 7]], np.int32)
+    if name.startswith("rand_n"):  # sizes around the switch between the library sort and the bucket sort
+        n = int(name[6:])
+        c = synth.random_cloud(n, (300, 280, 40), seed=40 + n % 7, batch=2)[:n]
+        c[:, 1:] -= 100
+        return c
+    if name == "skew_60k":  # half of the voxels in 3 of 400 x-planes: buckets of very different sizes
+        a = synth.random_cloud(30000, (400, 200, 60), seed=51)
+        b = synth.random_cloud(30000, (3, 200, 60), seed=52)
+        b[:, 1] += 197
+        c = np.unique(np.concatenate([a, b]), axis=0)
+        np.random.default_rng(53).shuffle(c, axis=0)
+        return c
     if name in ("slab_3k", "slab_12k"):
         # a dense two-voxel-thick slab in a wide scene: thousands of keys share the sort's top bits
         ny = 25 if name == "slab_3k" else 100
@@ -61,7 +73,9 @@ def _check_map(c0_sorted, keys_t, desc, K, s_p, s_l, transposed, kmap):
 
 # ----------------------------------------------------------------------------- pack + sort
 @pytest.mark.parametrize("name,key_bits", [("tiny", 0), ("tiny_neg", 0), ("rand_b3", 0), ("rand_b3", 64), ("one", 0),
-                                           ("slab_3k", 0), ("slab_12k", 0), ("slab_12k", 64), ("ragged", 64)])
+                                           ("slab_3k", 0), ("slab_12k", 0), ("slab_12k", 64), ("ragged", 64),
+                                           ("rand_n4095", 0), ("rand_n4096", 0), ("rand_n4097", 64), ("rand_n70001", 0),
+                                           ("rand_n70001", 64), ("skew_60k", 0), ("skew_60k", 64)])
 def test_pack_sort_matches_oracle(name, key_bits):
     c = _cloud(name)
     desc = fit_desc(c, [(3, 1, 2)], key_bits)
@@ -82,6 +96,17 @@ def test_pack_validate_errors():
     dup = np.concatenate([c, c[7:8]])
     with pytest.raises(B.SpcError) as e:
         gpu_pack(dup, desc, B.PACK_VALIDATE)
+    assert e.value.code == B.ERR_DUP
+    # the same two errors on a cloud large enough for the bucket sort
+    big = _cloud("rand_n70001")
+    dbig = fit_desc(big, [(3, 1, 1)])
+    bad = big.copy()
+    bad[12345, 2] = -20_000
+    with pytest.raises(B.SpcError) as e:
+        gpu_pack(bad, dbig, B.PACK_VALIDATE)
+    assert e.value.code == B.ERR_RANGE
+    with pytest.raises(B.SpcError) as e:
+        gpu_pack(np.concatenate([big, big[777:778]]), dbig, B.PACK_VALIDATE)
     assert e.value.code == B.ERR_DUP
     desc.bits_x = 31
     with pytest.raises(B.SpcError) as e:
