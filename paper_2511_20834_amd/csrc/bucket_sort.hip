@@ -12,11 +12,12 @@
 //            sequence into buckets of about BS_TARGET keys: the buckets adapt to the key
 //            distribution (a LiDAR sweep is many times denser near the sensor), so the sort
 //            workgroups get equal work;
-//   sort     one workgroup per bucket: bitonic network over (key, index) in LDS, three
-//            stages per barrier (a thread holds the 8 elements that three consecutive
-//            compare distances connect).  With variant UNIQUE the bucket's distinct keys are
-//            counted and left at the start of the bucket's range (the caller compacts the
-//            ranges with `gather`).
+//   sort     one workgroup per bucket: bitonic network over the keys in LDS (min/max steps,
+//            three compare distances per pass: a thread holds the 8 keys those distances
+//            connect; distances below 512 run inside the waves without barriers), then every
+//            (key, index) pair finds its key in the sorted tile.  With variant UNIQUE the
+//            bucket's distinct keys are counted and left at the start of the bucket's range
+//            (the caller compacts the ranges with `gather`).
 //
 // x is the most significant spatial field, so a bucket is a slab of the scene.  A single bin
 // that outgrows the LDS tile (a dense slab) is sorted straight in global memory by the
@@ -33,9 +34,7 @@ namespace spc {
 
 constexpr int BS_THREADS = 256;   // sort / gather workgroups
 constexpr int BS_WIDE = 1024;     // count / scan / scatter workgroups
-// keys per LDS tile (32 KB of (key, index) elements either way)
-template <typename KeyT>
-constexpr int bs_cap() { return sizeof(KeyT) == 4 ? 4096 : 2048; }
+constexpr int BS_CAP = 4096;      // keys per LDS tile
 
 __device__ inline int bs_bin(uint64_t key, int shift, int n_bin) {
   const uint64_t b = key >> shift;
@@ -69,10 +68,21 @@ __global__ __launch_bounds__(BS_WIDE) void bs_count_kernel(Src src, int64_t n, i
   for (int b = threadIdx.x; b < n_bin; b += BS_WIDE) hist[b] = 0;
   __syncthreads();
   const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
-  for (int64_t i = lo + threadIdx.x; i < hi; i += BS_WIDE) {
-    const KeyT key = src(i);
-    keys0[i] = key;
-    if (!src.skip(i, key)) atomicAdd(&hist[bs_bin(key, shift, n_bin)], 1);
+  // four keys per thread and pass: their loads are in flight together
+  for (int64_t i0 = lo + threadIdx.x; i0 < hi; i0 += 4 * BS_WIDE) {
+    KeyT key[4];
+    bool use[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = min<int64_t>(i0 + u * BS_WIDE, hi - 1);
+      key[u] = src(i);
+      use[u] = i0 + u * BS_WIDE < hi && !src.skip(i, key[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (i0 + u * BS_WIDE < hi) keys0[i0 + u * BS_WIDE] = key[u];
+      if (use[u]) atomicAdd(&hist[bs_bin(key[u], shift, n_bin)], 1);
+    }
   }
   __syncthreads();
   for (int b = threadIdx.x; b < n_bin; b += BS_WIDE) table[int64_t(blockIdx.x) * n_bin + b] = hist[b];
@@ -159,12 +169,22 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
   if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = make_int4(st.x + bef.x, st.y + bef.y, st.z + bef.z, st.w + bef.w);
   __syncthreads();
   const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
-  for (int64_t i = lo + threadIdx.x; i < hi; i += BS_WIDE) {
-    const KeyT key = keys0[i];
-    if (DEDUP && i > 0 && keys0[i - 1] == key) continue;
-    const int p = atomicAdd(&pos[bs_bin(key, shift, n_bin)], 1);
-    keys1[p] = key;
-    vals1[p] = static_cast<int32_t>(i);
+  for (int64_t i0 = lo + threadIdx.x; i0 < hi; i0 += 4 * BS_WIDE) {
+    KeyT key[4];
+    bool use[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = min<int64_t>(i0 + u * BS_WIDE, hi - 1);
+      key[u] = keys0[i];
+      use[u] = i0 + u * BS_WIDE < hi && !(DEDUP && i > 0 && keys0[i - 1] == key[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (use[u]) {
+        const int p = atomicAdd(&pos[bs_bin(key[u], shift, n_bin)], 1);
+        keys1[p] = key[u];
+        vals1[p] = static_cast<int32_t>(i0 + u * BS_WIDE);
+      }
   }
 }
 
@@ -176,7 +196,6 @@ template <>
 struct Elem<uint32_t> {
   uint64_t kv;
   __device__ static Elem make(uint32_t k, int32_t v) { return Elem{(uint64_t(k) << 32) | uint32_t(v)}; }
-  __device__ static Elem last() { return Elem{~uint64_t(0)}; }  // above every (key, index) pair
   __device__ uint32_t key() const { return static_cast<uint32_t>(kv >> 32); }
   __device__ int32_t val() const { return static_cast<int32_t>(uint32_t(kv)); }
   __device__ bool operator<(const Elem& o) const { return kv < o.kv; }
@@ -186,19 +205,12 @@ struct Elem<uint64_t> {
   uint64_t k;
   int32_t v;
   __device__ static Elem make(uint64_t k, int32_t v) { return Elem{k, v}; }
-  __device__ static Elem last() { return Elem{~uint64_t(0), 0x7fffffff}; }
   __device__ uint64_t key() const { return k; }
   __device__ int32_t val() const { return v; }
   __device__ bool operator<(const Elem& o) const { return k < o.k || (k == o.k && v < o.v); }
 };
 
-// Accessors: the tile in LDS, or the bucket's range in global memory.
-template <typename KeyT>
-struct LdsTile {
-  Elem<KeyT>* e;
-  __device__ Elem<KeyT> get(int i) const { return e[i]; }
-  __device__ void put(int i, const Elem<KeyT>& x) const { e[i] = x; }
-};
+// Accessor of the global-memory fallback: the bucket's range of (key, index) pairs.
 template <typename KeyT>
 struct GlobalRange {
   KeyT* k;
@@ -224,51 +236,98 @@ __device__ inline void bs_cmpxchg(const Acc& a, int i, int j) {
 // elements apart) spread over the banks instead of hitting the same few.
 __device__ inline int bs_at(int i) { return i + (i >> 5); }
 
-// Standard bitonic network on a power-of-two tile in LDS, NB consecutive compare distances per
-// barrier: the thread's 2^NB elements are those whose indices differ in bits ltop .. ltop-NB+1.
-// The merge of blocks of 2^lk sorts ascending where bit lk of the index is clear.
-template <int NB, typename E>
-__device__ inline void bs_lds_round(E* tile, int P, int lk, int ltop) {
+// Standard bitonic network on a power-of-two tile of keys in LDS, NB consecutive compare distances
+// per barrier: the thread's 2^NB keys are those whose indices differ in bits ltop .. ltop-NB+1.
+// The merge of blocks of 2^lk sorts ascending where bit lk of the index is clear; a descending
+// block runs the same min/max steps on complemented keys.
+template <int NB, typename KeyT>
+__device__ inline void bs_lds_round(KeyT* tile, int P, int lk, int ltop) {
   constexpr int R = 1 << NB;
   const int lbot = ltop - NB + 1;
   for (int t = threadIdx.x; t < (P >> NB); t += BS_THREADS) {
     const int base = ((t >> lbot) << (ltop + 1)) | (t & ((1 << lbot) - 1));
-    const bool asc = (base & (1 << lk)) == 0;
-    E e[R];
+    const KeyT flip = (base & (1 << lk)) ? ~KeyT(0) : KeyT(0);
+    KeyT e[R];
 #pragma unroll
-    for (int q = 0; q < R; ++q) e[q] = tile[bs_at(base | (q << lbot))];
+    for (int q = 0; q < R; ++q) e[q] = tile[bs_at(base | (q << lbot))] ^ flip;
 #pragma unroll
     for (int sb = NB - 1; sb >= 0; --sb)
 #pragma unroll
       for (int q = 0; q < R; ++q)
         if (!(q & (1 << sb))) {
           const int q2 = q | (1 << sb);
-          const bool sw = asc ? (e[q2] < e[q]) : (e[q] < e[q2]);
-          const E lo = sw ? e[q2] : e[q], hi = sw ? e[q] : e[q2];
+          const KeyT lo = min(e[q], e[q2]), hi = max(e[q], e[q2]);
           e[q] = lo;
           e[q2] = hi;
         }
 #pragma unroll
-    for (int q = 0; q < R; ++q) tile[bs_at(base | (q << lbot))] = e[q];
+    for (int q = 0; q < R; ++q) tile[bs_at(base | (q << lbot))] = e[q] ^ flip;
   }
   __syncthreads();
 }
 
-// Sorts tile[0, P), P = 2^lp; every thread of the workgroup calls it.
-template <typename E>
-__device__ inline void bs_lds_bitonic(E* tile, int lp) {
-  const int P = 1 << lp;
-  for (int lk = 1; lk <= lp; ++lk) {
-    int ltop = lk - 1;  // compare distances 2^(lk-1) .. 1
-    const int first = lk % 3;
-    if (first == 1) {
-      bs_lds_round<1>(tile, P, lk, ltop);
-      ltop -= 1;
-    } else if (first == 2) {
-      bs_lds_round<2>(tile, P, lk, ltop);
-      ltop -= 2;
+// The same step for compare distances below 512, without a barrier: a wave owns whole chunks of
+// 512 keys (64 lanes x 8 keys), the steps of such distances never leave a chunk, and the LDS
+// executes one wave's accesses in program order.
+constexpr int BS_CHUNK_BITS = 9;
+template <int NB, typename KeyT>
+__device__ inline void bs_wave_round(KeyT* tile, int P, int lk, int ltop) {
+  constexpr int R = 1 << NB;
+  const int lbot = ltop - NB + 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int csize = min(P, 1 << BS_CHUNK_BITS);
+  for (int c0 = wave << BS_CHUNK_BITS; c0 < P; c0 += (BS_THREADS / 64) << BS_CHUNK_BITS)
+    for (int u = lane; u < (csize >> NB); u += 64) {
+      const int base = c0 | ((u >> lbot) << (ltop + 1)) | (u & ((1 << lbot) - 1));
+      const KeyT flip = (base & (1 << lk)) ? ~KeyT(0) : KeyT(0);
+      KeyT e[R];
+#pragma unroll
+      for (int q = 0; q < R; ++q) e[q] = tile[bs_at(base | (q << lbot))] ^ flip;
+#pragma unroll
+      for (int sb = NB - 1; sb >= 0; --sb)
+#pragma unroll
+        for (int q = 0; q < R; ++q)
+          if (!(q & (1 << sb))) {
+            const int q2 = q | (1 << sb);
+            const KeyT lo = min(e[q], e[q2]), hi = max(e[q], e[q2]);
+            e[q] = lo;
+            e[q2] = hi;
+          }
+#pragma unroll
+      for (int q = 0; q < R; ++q) tile[bs_at(base | (q << lbot))] = e[q] ^ flip;
     }
-    for (; ltop >= 2; ltop -= 3) bs_lds_round<3>(tile, P, lk, ltop);
+  __builtin_amdgcn_wave_barrier();
+}
+
+// compare distances 2^ltop .. 1 of merge lk, all inside the waves' chunks
+template <typename KeyT>
+__device__ inline void bs_wave_rounds(KeyT* tile, int P, int lk, int ltop) {
+  const int first = (ltop + 1) % 3;
+  if (first == 1) {
+    bs_wave_round<1>(tile, P, lk, ltop);
+    ltop -= 1;
+  } else if (first == 2) {
+    bs_wave_round<2>(tile, P, lk, ltop);
+    ltop -= 2;
+  }
+  for (; ltop >= 2; ltop -= 3) bs_wave_round<3>(tile, P, lk, ltop);
+}
+
+// Sorts tile[0, P), P = 2^lp <= 4096; every thread of the workgroup calls it (after a barrier that
+// made the tile complete; it ends with one).  Merges of blocks up to 512 run inside the waves;
+// a longer merge starts with one workgroup-wide step over its distances of 512 and more.
+template <typename KeyT>
+__device__ inline void bs_lds_bitonic(KeyT* tile, int lp) {
+  const int P = 1 << lp;
+  for (int lk = 1; lk <= min(lp, BS_CHUNK_BITS); ++lk) bs_wave_rounds(tile, P, lk, lk - 1);
+  __syncthreads();
+  for (int lk = BS_CHUNK_BITS + 1; lk <= lp; ++lk) {
+    const int nb = lk - BS_CHUNK_BITS;  // 1..3 distances reach across chunks
+    if (nb == 1) bs_lds_round<1>(tile, P, lk, lk - 1);
+    else if (nb == 2) bs_lds_round<2>(tile, P, lk, lk - 1);
+    else bs_lds_round<3>(tile, P, lk, lk - 1);
+    bs_wave_rounds(tile, P, lk, BS_CHUNK_BITS - 1);
+    __syncthreads();
   }
 }
 
@@ -298,44 +357,88 @@ __device__ inline void bs_bitonic(const Acc& a, int m) {
 
 // One workgroup per bucket.  UNIQUE: out_k receives the bucket's distinct keys at the start
 // of its range and ucount[bucket] their number; otherwise out_k/out_v the sorted pairs.
+// In LDS only the keys are sorted (min/max steps); afterwards every (key, index) pair looks its
+// key up in the sorted tile and drops its index there.  Equal keys (not a valid cloud, but not
+// rejected unless validation was asked for) share out the positions of their run through a
+// counter, so the permutation is complete whatever the input.
 template <typename KeyT, bool UNIQUE>
 __global__ __launch_bounds__(BS_THREADS) void bs_sort_kernel(KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
-                                                             const int32_t* __restrict__ bstart, int shift,
-                                                             KeyT* __restrict__ out_k, int32_t* __restrict__ out_v,
-                                                             int32_t* __restrict__ ucount) {
-  constexpr int CAP = bs_cap<KeyT>();
-  __shared__ Elem<KeyT> tile[CAP + CAP / 32];
+                                                             const int32_t* __restrict__ bstart, KeyT* __restrict__ out_k,
+                                                             int32_t* __restrict__ out_v, int32_t* __restrict__ ucount) {
+  constexpr int CAP = BS_CAP;
+  constexpr int EPT = CAP / BS_THREADS;
+  __shared__ KeyT tile[CAP + CAP / 32];
+  __shared__ int dup[UNIQUE ? 1 : CAP];  // per position: how many pairs of an equal-key run have been placed
   __shared__ int wave_tot[BS_THREADS / 64];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int s = bstart[blockIdx.x], m = bstart[blockIdx.x + 1] - s;
   if (m <= 0) {
-    if (UNIQUE && threadIdx.x == 0) ucount[blockIdx.x] = 0;
+    if (UNIQUE && t == 0) ucount[blockIdx.x] = 0;
     return;
   }
   const bool in_lds = m <= CAP;
+  const bool place = !UNIQUE && out_v != nullptr;
   if (in_lds) {
     int lp = 0;
     while ((1 << lp) < m) ++lp;
-    for (int i = threadIdx.x; i < (1 << lp); i += BS_THREADS)
-      tile[bs_at(i)] = i < m ? Elem<KeyT>::make(keys1[s + i], vals1[s + i]) : Elem<KeyT>::last();
+    const int P = 1 << lp;
+    // the thread's pairs stay in registers: all their loads are in flight together, and the
+    // placement below needs them again
+    KeyT key[EPT];
+    int32_t val[EPT];
+#pragma unroll
+    for (int r = 0; r < EPT; ++r) {
+      const int i = r * BS_THREADS + t;
+      key[r] = i < m ? keys1[s + i] : ~KeyT(0);
+      val[r] = (place && i < m) ? vals1[s + i] : 0;
+    }
+#pragma unroll
+    for (int r = 0; r < EPT; ++r) {
+      const int i = r * BS_THREADS + t;
+      if (i < P) {
+        tile[bs_at(i)] = key[r];
+        if (!UNIQUE) dup[i] = 0;
+      }
+    }
     __syncthreads();
     bs_lds_bitonic(tile, lp);
+    if (place) {
+      // lower bound of every pair's key in the sorted tile (the padding compares as the largest key);
+      // four searches per thread run interleaved, their LDS reads overlap
+#pragma unroll
+      for (int r0 = 0; r0 < EPT; r0 += 4) {
+        if (r0 * BS_THREADS < m) {  // uniform
+          int pos[4] = {0, 0, 0, 0};
+          for (int step = P >> 1; step > 0; step >>= 1) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (tile[bs_at(pos[u] + step - 1)] < key[r0 + u]) pos[u] += step;
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if ((r0 + u) * BS_THREADS + t < m) {
+              int q = pos[u];
+              if (q + 1 < m && tile[bs_at(q + 1)] == key[r0 + u]) q += atomicAdd(&dup[q], 1);
+              out_v[s + q] = val[r0 + u];
+            }
+        }
+      }
+    }
   } else {
     bs_bitonic(GlobalRange<KeyT>{keys1 + s, vals1 + s}, m);
+    if (place)
+      for (int i = t; i < m; i += BS_THREADS) out_v[s + i] = vals1[s + i];
   }
-  auto key_at = [&](int i) -> KeyT { return in_lds ? tile[bs_at(i)].key() : keys1[s + i]; };
+  auto key_at = [&](int i) -> KeyT { return in_lds ? tile[bs_at(i)] : keys1[s + i]; };
   if (!UNIQUE) {
-    for (int i = threadIdx.x; i < m; i += BS_THREADS) {
-      out_k[s + i] = key_at(i);
-      if (out_v) out_v[s + i] = in_lds ? tile[bs_at(i)].val() : vals1[s + i];
-    }
+    for (int i = t; i < m; i += BS_THREADS) out_k[s + i] = key_at(i);
   } else {
     // heads of runs of equal keys, compacted in order (positions are visited in array order)
     int run = 0;
     for (int i0 = 0; i0 < m; i0 += BS_THREADS) {
-      const int i = i0 + threadIdx.x;
+      const int i = i0 + t;
       const bool head = i < m && (i == 0 || key_at(i) != key_at(i - 1));
       const KeyT kv = i < m ? key_at(i) : KeyT(0);
-      const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
       const unsigned long long bal = __ballot(head);
       if (lane == 0) wave_tot[wave] = __popcll(bal);
       __syncthreads();
@@ -349,7 +452,7 @@ __global__ __launch_bounds__(BS_THREADS) void bs_sort_kernel(KeyT* __restrict__ 
       run += tot;
       __syncthreads();
     }
-    if (threadIdx.x == 0) ucount[blockIdx.x] = run;
+    if (t == 0) ucount[blockIdx.x] = run;
   }
 }
 
@@ -467,7 +570,7 @@ static int pack_sort_t(const int4* coords, int64_t n, const PackParams& pp, int 
   const BucketPlan p = bucket_plan(n, used_bits);
   const Ws<KeyT> w = carve<KeyT>(ws, n);
   partition<KeyT, false>(SrcPack<KeyT>{coords, pp, status}, n, p, w, s);
-  hipLaunchKernelGGL((bs_sort_kernel<KeyT, false>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, p.shift,
+  hipLaunchKernelGGL((bs_sort_kernel<KeyT, false>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart,
                      static_cast<KeyT*>(keys_out), perm_out, static_cast<int32_t*>(nullptr));
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "sort launch failed");
   return SPC_OK;
@@ -486,8 +589,8 @@ static int mask_unique_t(const void* keys_in, int64_t n, uint64_t mask, int used
   const Ws<KeyT> w = carve<KeyT>(ws, n);
   partition<KeyT, true>(SrcMask<KeyT>{static_cast<const KeyT*>(keys_in), static_cast<KeyT>(mask)}, n, p, w, s);
   // distinct keys of every bucket land at the start of its range in keys0 (free again by now)
-  hipLaunchKernelGGL((bs_sort_kernel<KeyT, true>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, p.shift,
-                     w.keys0, static_cast<int32_t*>(nullptr), w.ucount);
+  hipLaunchKernelGGL((bs_sort_kernel<KeyT, true>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, w.keys0,
+                     static_cast<int32_t*>(nullptr), w.ucount);
   hipLaunchKernelGGL(bs_gather_kernel<KeyT>, dim3(std::min(p.n_bucket, 256)), dim3(BS_THREADS), 0, s, w.keys0, w.bstart, w.ucount,
                      p.n_bucket, static_cast<KeyT*>(keys_out), n_out);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "downsample launch failed");
