@@ -87,6 +87,14 @@ def bench_network(args, torch, B, synth) -> int:
     flops = sum(2.0 * float(m.nnz().sum()) * l["cin"] * l["cout"] for m, l in zip(maps, layers))
     level_sizes = sorted({(l["in_stride"], m.n_in if not l["transposed"] else m.n_out) for m, l in zip(maps, layers)})
     net.destroy_maps()
+    tuned = None
+    if args.tune:
+        # one-time tuning of the per-layer dataflow threshold on this cloud (not part of a step)
+        B.spc_permute_rows(F_raw, perm, F)
+        t0 = time.perf_counter()
+        rows = net.tune(keys, desc, F)
+        tuned = {"seconds": time.perf_counter() - t0,
+                 "layers": {name: {"best_t": best, "us": {str(t): round(v, 1) for t, v in times.items()}} for name, best, times in rows}}
     def timed(fn, reps):
         torch.cuda.synchronize()
         a, b = ev(), ev()
@@ -134,7 +142,7 @@ def bench_network(args, torch, B, synth) -> int:
         "config": {"workload": "cfg4: lidar cloud, %d voxels, 25-layer UNet-style stack, 13 kernel maps on 4 streams, OS dataflow, "
                                "step replayed from a HIP graph" % n,
                    "n_voxels": n, "levels": level_sizes, "voxel_offsets": vo, "useful_flops": flops},
-        "parts": part,
+        "parts": part, "tuning": tuned,
         "roofline": {"kernel": "conv_os_splitk_kernel + conv_os_phase_kernel (all 25 layers)", "bound": "mfma",
                      "achieved": part["forward_useful_TFLOPs"],
                      "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": part["forward_useful_TFLOPs"] / PEAK_MFMA_F16_TFLOPS,
@@ -151,6 +159,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--dataflow", default="auto", choices=["auto", "os", "ws"])
+    ap.add_argument("--hybrid-t", type=int, default=None,
+                    help="single-layer configurations: threshold of the hybrid dual dataflow (offsets with L1 norm < t run "
+                         "output-stationary, the others weight-stationary); --config 4: ignored")
+    ap.add_argument("--tune", action="store_true", help="--config 4: tune the per-layer threshold on the cloud first and report it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
@@ -182,6 +194,8 @@ def main() -> int:
     if dataflow is None:
         dataflow = B.DATAFLOW_OS  # with per-block offset skipping OS wins on all four single-layer configurations
     layout = B.LAYOUT_OS if dataflow == B.DATAFLOW_OS else B.LAYOUT_WS
+    if args.hybrid_t is not None:
+        layout = B.LAYOUT_BOTH
 
     lo, hi = coords_np[:, 1:].min(0), coords_np[:, 1:].max(0)
     reach = ((K - 1) // 2) if K % 2 else (K - 1)
@@ -224,7 +238,7 @@ def main() -> int:
         km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout, in_perm=perm)
         if marks is not None:
             marks[2].record()
-        B.spc_conv_forward(km, F_raw, Wp if use_packed else W, dataflow, conv_flags, out=out)
+        B.spc_conv_forward(km, F_raw, Wp if use_packed else W, dataflow, conv_flags, out=out, hybrid_t=args.hybrid_t)
         if marks is not None:
             marks[3].record()
         km.destroy()
@@ -293,7 +307,8 @@ def main() -> int:
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": "cfg%d: %s cloud, %d voxels -> %d outputs, K=%d, layer stride %d, C %d->%d, %s, dataflow %s"
                    % (args.config, cfg["cloud"], n, n_out, K, s_l, cin, cout, cfg["dtype"],
-                      "OS" if dataflow == B.DATAFLOW_OS else "WS"),
+                      ("hybrid t=%d" % args.hybrid_t) if args.hybrid_t is not None else
+                      ("OS" if dataflow == B.DATAFLOW_OS else "WS")),
                    "n_voxels": n, "n_out": n_out, "K": K, "cin": cin, "cout": cout, "nnz": nnz,
                    "key_bits": desc.key_bits},
         "parts": {"phase_ms": phase_ms,

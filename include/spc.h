@@ -231,6 +231,19 @@ int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const voi
                      int32_t flags, void* stream);
 
 /*
+ * Hybrid dual dataflow (Section 5.4): weight offsets whose L1 norm, in units of the layer's input
+ * stride, is below the threshold t (the dense ones: the centre and its nearest neighbours) are
+ * computed output-stationary, the others weight-stationary, and the two partial sums are merged
+ * without an extra pass: the weight-stationary part accumulates in an fp32 buffer from which the
+ * output-stationary kernel starts.  t = 0 is the pure weight-stationary dataflow, any t above the
+ * largest norm (3 * (K-1)/2 for odd K) the pure output-stationary one.  The map must hold both
+ * layouts unless one part is empty.  Everything else as spc_conv_forward.
+ */
+int spc_conv_forward_hybrid(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
+                            int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t t, int32_t flags,
+                            void* stream);
+
+/*
  * Weights are constant during inference, so their re-layout into MFMA operand order can
  * be hoisted out of the layer call.  Writes K^3*cin*cout elements to packed_out [device]
  * (same dtype) for use with SPC_CONV_PACKED_WEIGHTS.  Returns SPC_ERR_UNSUPPORTED for the

@@ -31,7 +31,7 @@ EXPORTS = [
     "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmap_perm", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
     "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
-    "spc_conv_forward",
+    "spc_conv_forward", "spc_conv_forward_hybrid",
     "spc_conv_prepare_weights", "spc_permute_rows",
     "spc_release_cache", "spc_last_error", "spc_version",
 ]
@@ -91,6 +91,7 @@ def lib():
         L.spc_kmap_destroy.argtypes = [vp]
         L.spc_kmap_destroy.restype = None
         L.spc_conv_forward.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
+        L.spc_conv_forward_hybrid.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         L.spc_conv_prepare_weights.argtypes = [vp, i32, i32, i32, i32, vp, vp]
         L.spc_permute_rows.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp]
         L.spc_last_error.restype = ctypes.c_char_p
@@ -253,9 +254,11 @@ def spc_build_kmaps_network(v0_keys: torch.Tensor, desc: PackDesc, layers, strea
 
 
 def spc_conv_forward(kmap: KMap, feats_in: torch.Tensor, weights: torch.Tensor, dataflow: int = DATAFLOW_OS,
-                     flags: int = 0, out: torch.Tensor | None = None, n_out: int | None = None, stream=None) -> torch.Tensor:
+                     flags: int = 0, out: torch.Tensor | None = None, n_out: int | None = None, stream=None,
+                     hybrid_t: int | None = None) -> torch.Tensor:
     """feats_in [n_in, cin] (row pitch = stride(0)), weights [K^3, cin, cout] contiguous.  ``out`` may be a
-    column slice of a wider buffer (row pitch = stride(0)); it is allocated when None."""
+    column slice of a wider buffer (row pitch = stride(0)); it is allocated when None.  hybrid_t: threshold of the
+    hybrid dual dataflow (spc_conv_forward_hybrid); `dataflow` is ignored then."""
     assert feats_in.is_cuda and weights.is_cuda and weights.is_contiguous()
     assert feats_in.dim() == 2 and feats_in.stride(1) == 1 and weights.dim() == 3
     assert feats_in.dtype == weights.dtype and feats_in.dtype in _TORCH_DTYPE
@@ -264,6 +267,11 @@ def spc_conv_forward(kmap: KMap, feats_in: torch.Tensor, weights: torch.Tensor, 
     if out is None:
         out = torch.empty((n_out if n_out is not None else kmap.n_out, cout), dtype=feats_in.dtype, device=feats_in.device)
     assert out.dim() == 2 and out.stride(1) == 1 and out.shape[1] == cout and out.dtype == feats_in.dtype
+    if hybrid_t is not None:
+        _check(lib().spc_conv_forward_hybrid(kmap.handle, feats_in.data_ptr(), feats_in.stride(0), weights.data_ptr(),
+                                             out.data_ptr(), out.stride(0), cin, cout, _TORCH_DTYPE[feats_in.dtype], int(hybrid_t),
+                                             flags, _stream(stream)))
+        return out
     _check(lib().spc_conv_forward(kmap.handle, feats_in.data_ptr(), feats_in.stride(0), weights.data_ptr(), out.data_ptr(),
                                   out.stride(0), cin, cout, _TORCH_DTYPE[feats_in.dtype], dataflow, flags, _stream(stream)))
     return out

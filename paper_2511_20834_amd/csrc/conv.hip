@@ -15,6 +15,7 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -54,6 +55,14 @@ template <int N, typename Fn>
 __device__ inline void static_for(Fn&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
+
+// Subset of the K^3 weight offsets a kernel works on (bit k of word k/32): all of them for a
+// single dataflow, the dense or the sparse ones of the hybrid dual dataflow (Section 5.4).
+constexpr int KMASK_WORDS = 11;  // 7^3 = 343 bits
+struct KMask {
+  uint32_t w[KMASK_WORDS];
+  __host__ __device__ bool has(int k) const { return (w[k >> 5] >> (k & 31)) & 1u; }
+};
 
 constexpr int CONV_THREADS = 256;
 constexpr int CK = 64;  // input channels staged per step
@@ -167,7 +176,8 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
                                                                    const T* __restrict__ F, int64_t ld_in,
                                                                    const T* __restrict__ Wp, T* __restrict__ out,
                                                                    int64_t ld_out, int cin, int relu, int chunks_per_phase,
-                                                                   int n_wg_per_xcd, int nb_total) {
+                                                                   int n_wg_per_xcd, int nb_total, KMask kmask,
+                                                                   const float* __restrict__ init) {
   using V8 = typename Mfma<T>::V8;
   constexpr int CKS = 16 * NKK;
   constexpr int THREADS = 64 * WAVES;
@@ -231,7 +241,7 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
       for (int rb = 0; rb < RB; ++rb)
         if (blk0 + rb < n_blocks) m |= block_masks[(blk0 + rb) * mask_words + wd];
     }
-    smask[wd] = m;
+    smask[wd] = m & kmask.w[wd];
   }
   __builtin_amdgcn_wave_barrier();
 
@@ -393,6 +403,8 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
           const int row = 8 * (r / 4) + 4 * lh + (r % 4);
           if (row < rows) {
             float v = acc[rb][nb][r];
+            // hybrid dataflow: the weight-stationary part of the sum arrives in an fp32 buffer [n_out][cout]
+            if (init) v += init[(i0 + row) * (nb_total * 32) + (slab * NB + nb) * 32 + lr];
             if (relu) v = fmaxf(v, 0.f);
             out[(i0 + row) * ld_out + nb * 32 + lr] = from_f32<T>(v);
           }
@@ -427,7 +439,8 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
                                                                           const T* __restrict__ F, int64_t ld_in,
                                                                           const T* __restrict__ Wp, T* __restrict__ out,
                                                                           int64_t ld_out, int cin, int relu, int nb_total,
-                                                                          int vec_store) {
+                                                                          int vec_store, KMask kmask,
+                                                                          const float* __restrict__ init) {
   using V8 = typename Mfma<T>::V8;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5;
@@ -451,7 +464,7 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
       if (blk0 + rb < n_blocks) m |= block_masks[(blk0 + rb) * mask_words + wd];
-    m = __builtin_amdgcn_readfirstlane(m);
+    m = __builtin_amdgcn_readfirstlane(m & kmask.w[wd]);
     if (lane < 32 && ((m >> lane) & 1u)) {
       const int rank = cnt + __builtin_popcount(m & ((1u << lane) - 1u));
       if ((rank & (SPLITK_WAVES - 1)) == wave) kl[rank / SPLITK_WAVES] = static_cast<int16_t>(wd * 32 + lane);
@@ -566,9 +579,12 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
     const int64_t i = (blk0 + rb) * 32 + row;
     const float* p = red + ((((rb * NB + nb) * 4 + q) * 64) + h * 32 + cc) * 4 + rr;
     T o[EPT];
+    // hybrid dataflow: the weight-stationary part of the sum arrives in an fp32 buffer [n_out][cout]
+    const float* ip = (init && i < n_out) ? init + i * (nb_total * 32) + slab * (NB * 32) + c0 : nullptr;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-      const float v = p[4 * j];
+      float v = p[4 * j];
+      if (ip) v += ip[j];
       o[j] = from_f32<T>(relu ? fmaxf(v, 0.f) : v);
     }
     if (i < n_out) {
@@ -594,13 +610,14 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_ws_mfma_kernel(const int32_
                                                                     const int32_t* __restrict__ nnz, int64_t ws_stride,
                                                                     const T* __restrict__ F, int64_t ld_in,
                                                                     const T* __restrict__ Wp, float* __restrict__ accum,
-                                                                    int cin) {
+                                                                    int cin, KMask kmask) {
   using V8 = typename Mfma<T>::V8;
   constexpr int WROWS = 32 * RB, TROWS = 4 * WROWS;
   extern __shared__ __align__(16) unsigned char smem[];
   V8* sB = reinterpret_cast<V8*>(smem);
   __shared__ int s_out[TROWS];
   const int k = blockIdx.y;
+  if (!kmask.has(k)) return;  // whole workgroup
   const int cnt = nnz[k];
   const int p0 = blockIdx.x * TROWS;
   if (p0 >= cnt) return;
@@ -647,14 +664,16 @@ __global__ __launch_bounds__(256) void conv_os_simple_kernel(const int32_t* __re
                                                              const int* __restrict__ n_out_d, int K3,
                                                              const T* __restrict__ F, int64_t ld_in,
                                                              const T* __restrict__ W, T* __restrict__ out,
-                                                             int64_t ld_out, int cin, int cout, int relu) {
+                                                             int64_t ld_out, int cin, int cout, int relu, KMask kmask,
+                                                             const float* __restrict__ init) {
   const int n_out = n_out_d ? *n_out_d : n_out_h;
   const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   const int64_t i = gid / cout;
   const int co = static_cast<int>(gid - i * cout);
   if (i >= n_out) return;
-  float acc = 0.f;
+  float acc = init ? init[gid] : 0.f;
   for (int k = 0; k < K3; ++k) {
+    if (!kmask.has(k)) continue;
     const int j = M[((i >> 5) * K3 + k) * 32 + (i & 31)];
     if (j < 0) continue;
     const T* f = F + int64_t(j) * ld_in;
@@ -671,8 +690,9 @@ __global__ __launch_bounds__(256) void conv_ws_simple_kernel(const int32_t* __re
                                                              const int32_t* __restrict__ nnz, int64_t ws_stride,
                                                              const T* __restrict__ F, int64_t ld_in,
                                                              const T* __restrict__ W, float* __restrict__ accum,
-                                                             int cin, int cout) {
+                                                             int cin, int cout, KMask kmask) {
   const int k = blockIdx.y;
+  if (!kmask.has(k)) return;
   const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   const int64_t p = gid / cout;
   const int co = static_cast<int>(gid - p * cout);
@@ -720,6 +740,8 @@ struct ConvArgs {
   const int* n_out_d;
   int64_t rows_cap;  // upper bound of the output rows (exact when the host knows the count)
   int64_t rows_sel;  // best host-side estimate of the output rows: kernel selection and launch shape only
+  KMask os_mask, ws_mask;  // offsets of the output-stationary / weight-stationary part
+  bool any_os, any_ws;
   hipStream_t s;
 };
 
@@ -727,7 +749,7 @@ struct ConvArgs {
 // odd multiple of 32).  Small slabs keep the accumulators of two row blocks in registers and give
 // the coarse, wide layers of a network enough workgroups to fill the chip.
 template <typename T, int NB>
-static void launch_os_mfma(const ConvArgs& a, const T* Wp) {
+static void launch_os_mfma(const ConvArgs& a, const T* Wp, const float* init) {
   constexpr int WAVES = 8;
   constexpr int RBK = 2;  // row blocks per wave
   constexpr int DEPTH = 2;
@@ -749,7 +771,7 @@ static void launch_os_mfma(const ConvArgs& a, const T* Wp) {
     hipLaunchKernelGGL((conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>), dim3(per_xcd * 8, n_slabs), dim3(64 * WAVES), lds,
                        a.s, a.m->os_map, a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3,
                        static_cast<const T*>(a.F), a.ld_in, Wp, static_cast<T*>(a.out), a.ld_out, a.cin, a.relu, cpp, per_xcd,
-                       nb_total);
+                       nb_total, a.os_mask, init);
   };
   if (a.cin % 64 == 0) go(std::integral_constant<int, 4>{});
   else if (a.cin % 32 == 0) go(std::integral_constant<int, 2>{});
@@ -763,7 +785,7 @@ static size_t splitk_lds_bytes(int K3, int NB, int RB) {
 }
 
 template <typename T, int NB, int RB>
-static void launch_os_splitk(const ConvArgs& a, const T* Wp) {
+static void launch_os_splitk(const ConvArgs& a, const T* Wp, const float* init) {
   constexpr int D = 24 / (RB + NB);  // about 96 registers of loads in flight per lane
   const int nb_total = a.cout / 32, n_slabs = nb_total / NB;
   // an estimated output count sizes the grid of the variant that walks tiles with a grid stride
@@ -785,11 +807,11 @@ static void launch_os_splitk(const ConvArgs& a, const T* Wp) {
   if (loop)
     hipLaunchKernelGGL((conv_os_splitk_kernel<T, NB, RB, D, true>), grid, dim3(64 * SPLITK_WAVES), lds, a.s, a.m->os_map,
                        a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp,
-                       out, a.ld_out, a.cin, a.relu, nb_total, vec);
+                       out, a.ld_out, a.cin, a.relu, nb_total, vec, a.os_mask, init);
   else
     hipLaunchKernelGGL((conv_os_splitk_kernel<T, NB, RB, D, false>), grid, dim3(64 * SPLITK_WAVES), lds, a.s, a.m->os_map,
                        a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3, static_cast<const T*>(a.F), a.ld_in, Wp,
-                       out, a.ld_out, a.cin, a.relu, nb_total, vec);
+                       out, a.ld_out, a.cin, a.relu, nb_total, vec, a.os_mask, init);
 }
 
 // Row blocks per workgroup of the split-k kernel: more blocks share each weight fragment read
@@ -802,10 +824,10 @@ static int splitk_rb(const ConvArgs& a, int NB) {
 }
 
 template <typename T, int NB>
-static void launch_os_splitk_any(const ConvArgs& a, const T* Wp) {
+static void launch_os_splitk_any(const ConvArgs& a, const T* Wp, const float* init) {
   switch (splitk_rb(a, NB)) {
-    case 2: launch_os_splitk<T, NB, 2>(a, Wp); break;
-    default: launch_os_splitk<T, NB, 1>(a, Wp); break;
+    case 2: launch_os_splitk<T, NB, 2>(a, Wp, init); break;
+    default: launch_os_splitk<T, NB, 1>(a, Wp, init); break;
   }
 }
 
@@ -824,38 +846,42 @@ static void launch_ws_mfma(const ConvArgs& a, const T* Wp, float* accum) {
   const size_t lds = size_t(CK / 16) * NB * 64 * 16;
   const int gx = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
   hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, a.m->K3), dim3(CONV_THREADS), lds, a.s, a.m->ws_in, a.m->ws_out,
-                     a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin);
+                     a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin, a.ws_mask);
 }
 
 // Shapes the MFMA kernels run (16-bit types): input channels a multiple of 16 (smaller or ragged
 // counts are zero-padded by the caller below), output channels a multiple of 32 for the OS
-// dataflow and one of 32/64/128/256 for the WS dataflow.
-static bool mfma_shape(int cin, int cout, int dataflow) {
+// part and one of 32/64/128/256 for the WS part.
+static bool mfma_shape(int cin, int cout, bool any_ws) {
   if (cin % 16 != 0 || cout % 32 != 0) return false;
-  return dataflow == SPC_DATAFLOW_OS ? true : (cout == 32 || cout == 64 || cout == 128 || cout == 256);
+  return !any_ws || cout == 32 || cout == 64 || cout == 128 || cout == 256;
 }
 
+// The weight-stationary part (if any) accumulates into an fp32 buffer first; the output-stationary
+// part (if any) then starts from that buffer and writes the layer's output, otherwise a small
+// kernel rounds the buffer.
 template <typename T>
 static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
   ConvArgs a = a0;
   const int K3 = a.m->K3;
   const int64_t out_elems = a.rows_cap * a.cout;
   const bool aligned = a.ld_in % 8 == 0 && reinterpret_cast<uintptr_t>(a.F) % 16 == 0;
-  if (a.packed && !(allow_mfma && mfma_shape(a.cin, a.cout, a.dataflow)))
+  if (a.packed && !(allow_mfma && mfma_shape(a.cin, a.cout, a.any_ws)))
     return set_error(SPC_ERR_ARG, "packed weights given for a shape the MFMA kernels do not run");
   if (a.packed && !aligned) return set_error(SPC_ERR_ARG, "packed weights need 16-byte aligned feature rows");
   if (a.rows_cap <= 0) return SPC_OK;
   const int cin_pad = (a.cin + 15) / 16 * 16;
   // ragged input channel counts and unaligned rows go through a zero-padded copy of the features
   const bool repack_rows = !a.packed && (cin_pad != a.cin || !aligned);
-  const bool use_mfma = allow_mfma && mfma_shape(cin_pad, a.cout, a.dataflow);
+  const bool use_mfma = allow_mfma && mfma_shape(cin_pad, a.cout, a.any_ws);
   float* accum = nullptr;
-  if (a.dataflow == SPC_DATAFLOW_WS) {
+  if (a.any_ws) {
     accum = static_cast<float*>(pool_alloc(std::max<size_t>(size_t(out_elems) * 4 + 16, 256), a.s));
     if (!accum) return SPC_ERR_NOMEM;
     const int64_t n4 = (out_elems + 3) / 4;
     hipLaunchKernelGGL(zero_f32_kernel, dim3((n4 + 255) / 256), dim3(256), 0, a.s, reinterpret_cast<float4*>(accum), n4);
   }
+  const float* init = a.any_os ? accum : nullptr;  // what the OS part starts from
   int rc = SPC_OK;
   if constexpr (!std::is_same<T, float>::value) {
     if (use_mfma) {
@@ -891,16 +917,7 @@ static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
         Wp = Wtmp;
       }
       a.cin = cin_pad;
-      if (a.dataflow == SPC_DATAFLOW_OS) {
-        const bool splitk = a.os_variant == 2 || (a.os_variant == 0 && prefer_splitk(a));
-        if (splitk) {
-          if (a.cout % 64 == 0) launch_os_splitk_any<T, 2>(a, Wp);
-          else launch_os_splitk_any<T, 1>(a, Wp);
-        } else {
-          if (a.cout % 64 == 0) launch_os_mfma<T, 2>(a, Wp);
-          else launch_os_mfma<T, 1>(a, Wp);
-        }
-      } else {
+      if (a.any_ws) {
         switch (a.cout) {
           case 32: launch_ws_mfma<T, 1, 2>(a, Wp, accum); break;
           case 64: launch_ws_mfma<T, 2, 2>(a, Wp, accum); break;
@@ -908,23 +925,33 @@ static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
           case 256: launch_ws_mfma<T, 8, 1>(a, Wp, accum); break;
         }
       }
+      if (a.any_os) {
+        const bool splitk = a.os_variant == 2 || (a.os_variant == 0 && prefer_splitk(a));
+        if (splitk) {
+          if (a.cout % 64 == 0) launch_os_splitk_any<T, 2>(a, Wp, init);
+          else launch_os_splitk_any<T, 1>(a, Wp, init);
+        } else {
+          if (a.cout % 64 == 0) launch_os_mfma<T, 2>(a, Wp, init);
+          else launch_os_mfma<T, 1>(a, Wp, init);
+        }
+      }
       // reuse of these blocks is ordered behind this stream's work
       pool_free(Wtmp, a.s);
       pool_free(Fpad, a.s);
     }
   }
-  if (use_mfma) {
-  } else if (a.dataflow == SPC_DATAFLOW_OS) {
-    hipLaunchKernelGGL(conv_os_simple_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, a.m->os_map, a.n_out_h,
-                       a.n_out_d, K3, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), static_cast<T*>(a.out),
-                       a.ld_out, a.cin, a.cout, a.relu);
-  } else {
+  if (!use_mfma) {
     // nnz[k] <= n_out for every offset
-    hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((out_elems + 255) / 256, K3), dim3(256), 0, a.s, a.m->ws_in, a.m->ws_out,
-                       a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), accum, a.cin,
-                       a.cout);
+    if (a.any_ws)
+      hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((out_elems + 255) / 256, K3), dim3(256), 0, a.s, a.m->ws_in, a.m->ws_out,
+                         a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), accum, a.cin,
+                         a.cout, a.ws_mask);
+    if (a.any_os)
+      hipLaunchKernelGGL(conv_os_simple_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, a.m->os_map, a.n_out_h,
+                         a.n_out_d, K3, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), static_cast<T*>(a.out),
+                         a.ld_out, a.cin, a.cout, a.relu, a.os_mask, init);
   }
-  if (a.dataflow == SPC_DATAFLOW_WS)
+  if (!a.any_os)
     hipLaunchKernelGGL(finalize_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, accum, a.n_out_h, a.n_out_d, a.cout,
                        static_cast<T*>(a.out), a.ld_out, a.relu);
   pool_free(accum, a.s);
@@ -932,19 +959,30 @@ static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
   return rc;
 }
 
-}  // namespace spc
+// L1 norm of weight offset k in units of the input stride (Section 5.4: offsets below the
+// threshold are the dense ones).  Even kernel sizes have offsets {0, 1} per axis.
+static int offset_l1(int K, int k) {
+  const int iz = k % K, iy = (k / K) % K, ix = k / (K * K);
+  if (K % 2 == 0) return ix + iy + iz;
+  const int c = (K - 1) / 2;
+  return std::abs(ix - c) + std::abs(iy - c) + std::abs(iz - c);
+}
 
-extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
-                                int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t dataflow, int32_t flags,
-                                void* stream) {
-  using namespace spc;
+// Common part of the two entry points: offsets with L1 norm < t run output-stationary, the others
+// weight-stationary.
+static int conv_entry(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out, int64_t ld_out,
+                      int32_t cin, int32_t cout, int32_t dtype, int32_t t, int32_t flags, void* stream) {
   if (!m || !feats_in || !weights || !feats_out) return set_error(SPC_ERR_ARG, "NULL argument");
   if (cin < 1 || cout < 1 || ld_in < cin || ld_out < cout) return set_error(SPC_ERR_ARG, "bad channel counts or row pitches");
-  if (dataflow != SPC_DATAFLOW_OS && dataflow != SPC_DATAFLOW_WS) return set_error(SPC_ERR_ARG, "bad dataflow");
-  if (dataflow == SPC_DATAFLOW_OS && !(m->desc.layout & SPC_LAYOUT_OS)) return set_error(SPC_ERR_ARG, "map has no OS layout");
-  if (dataflow == SPC_DATAFLOW_WS && !(m->desc.layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "map has no WS layout");
   ConvArgs a{};
   a.m = m;
+  for (int k = 0; k < m->K3; ++k) {
+    const bool dense = offset_l1(m->desc.K, k) < t;
+    (dense ? a.os_mask : a.ws_mask).w[k >> 5] |= 1u << (k & 31);
+    (dense ? a.any_os : a.any_ws) = true;
+  }
+  if (a.any_os && !(m->desc.layout & SPC_LAYOUT_OS)) return set_error(SPC_ERR_ARG, "map has no OS layout");
+  if (a.any_ws && !(m->desc.layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "map has no WS layout");
   a.F = feats_in;
   a.ld_in = ld_in;
   a.W = weights;
@@ -959,7 +997,6 @@ extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in
   a.splitk_rb = (flags >> 8) & 7;  // tuning aid: SPC_CONV_OS_SPLITK | (rb << 8)
   if (a.splitk_rb != 0 && a.splitk_rb != 1 && a.splitk_rb != 2)
     return set_error(SPC_ERR_ARG, "row blocks per workgroup must be 1 or 2");
-  a.dataflow = dataflow;
   const Level* ol = m->out_level;
   a.n_out_h = static_cast<int>(ol->n_host < 0 ? 0 : ol->n_host);
   a.n_out_d = ol->n_host < 0 ? ol->n_dev : nullptr;
@@ -972,6 +1009,24 @@ extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in
     case SPC_DTYPE_F32: return conv_typed<float>(a, false);
   }
   return set_error(SPC_ERR_ARG, "bad dtype");
+}
+
+}  // namespace spc
+
+extern "C" int spc_conv_forward(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
+                                int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t dataflow, int32_t flags,
+                                void* stream) {
+  if (dataflow != SPC_DATAFLOW_OS && dataflow != SPC_DATAFLOW_WS) return spc::set_error(SPC_ERR_ARG, "bad dataflow");
+  // single dataflows are the two ends of the threshold range
+  const int32_t t = dataflow == SPC_DATAFLOW_OS ? 0x7fffffff : 0;
+  return spc::conv_entry(m, feats_in, ld_in, weights, feats_out, ld_out, cin, cout, dtype, t, flags, stream);
+}
+
+extern "C" int spc_conv_forward_hybrid(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out,
+                                       int64_t ld_out, int32_t cin, int32_t cout, int32_t dtype, int32_t t, int32_t flags,
+                                       void* stream) {
+  if (t < 0) return spc::set_error(SPC_ERR_ARG, "threshold t must be >= 0");
+  return spc::conv_entry(m, feats_in, ld_in, weights, feats_out, ld_out, cin, cout, dtype, t, flags, stream);
 }
 
 extern "C" int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32_t cin, int32_t cout, int32_t dtype,

@@ -16,15 +16,17 @@ from . import binding as B
 
 
 class SpcNetwork:
-    def __init__(self, layers, weights, dataflow=None):
+    def __init__(self, layers, weights, dataflow=None, hybrid_t=None):
         """weights: list of device tensors [K^3, cin, cout]; dataflow: None (OS everywhere), a
-        single B.DATAFLOW_* value, or one value per layer."""
+        single B.DATAFLOW_* value, or one value per layer.  hybrid_t: None, or one entry per layer,
+        each None (use `dataflow`) or the threshold of the hybrid dual dataflow for that layer."""
         self.layers = layers
         self.weights = weights
         n = len(layers)
         if dataflow is None:
             dataflow = B.DATAFLOW_OS
         self.dataflow = [dataflow] * n if isinstance(dataflow, int) else list(dataflow)
+        self.hybrid_t = [None] * n if hybrid_t is None else list(hybrid_t)
         self.maps = None
         self.size_hints = None  # per layer: n_out seen by the last learn_sizes()
         self._packed = None  # per layer: weights in the MFMA operand layout, or None
@@ -41,8 +43,8 @@ class SpcNetwork:
         """use_hints: hand the level sizes of the last learn_sizes() to the new maps, so that the feature
         kernels are chosen for those sizes without anybody waiting for the true counts."""
         req = []
-        for l, df in zip(self.layers, self.dataflow):
-            layout = B.LAYOUT_OS if df == B.DATAFLOW_OS else B.LAYOUT_WS
+        for l, df, t in zip(self.layers, self.dataflow, self.hybrid_t):
+            layout = B.LAYOUT_BOTH if t is not None else (B.LAYOUT_OS if df == B.DATAFLOW_OS else B.LAYOUT_WS)
             req.append((l["K"], l["in_stride"], l["layer_stride"], l["transposed"], layout))
         self.maps = B.spc_build_kmaps_network(v0_keys, desc, req, streams, flags)
         if use_hints and self.size_hints is not None:
@@ -65,10 +67,10 @@ class SpcNetwork:
         """Re-orders every layer's weights once into the layout the MFMA kernels read (layers whose
         shape those kernels do not take directly keep their plain weights)."""
         self._packed = []
-        for w, df in zip(self.weights, self.dataflow):
+        for w, df, t in zip(self.weights, self.dataflow, self.hybrid_t):
             cin, cout = w.shape[1], w.shape[2]
             ok = w.dtype in (torch.float16, torch.bfloat16) and cin % 16 == 0 and cout % 32 == 0
-            if df == B.DATAFLOW_WS:
+            if df == B.DATAFLOW_WS or t is not None:
                 ok = ok and cout in (32, 64, 128, 256)
             self._packed.append(B.spc_conv_prepare_weights(w) if ok else None)
 
@@ -102,9 +104,75 @@ class SpcNetwork:
             w = self.weights[j]
             if self._packed[j] is not None and x.stride(0) % 8 == 0 and x.data_ptr() % 16 == 0:
                 w, flags = self._packed[j], flags | B.CONV_PACKED_WEIGHTS
-            y = B.spc_conv_forward(m, x, w, self.dataflow[j], flags, out=out, n_out=n_out)
+            y = B.spc_conv_forward(m, x, w, self.dataflow[j], flags, out=out, n_out=n_out, hybrid_t=self.hybrid_t[j])
             T[l["save"]] = y
         return (y, T) if keep else y
+
+    def tune(self, v0_keys, desc, feats, reps=5):
+        """One-time tuning of the hybrid dual dataflow (Section 5.4): on the sample cloud given, every
+        layer's feature computation is timed for every threshold t = 0 (pure weight-stationary) ..
+        L1max + 1 (pure output-stationary), the extra kernel-map build time of the layouts a threshold
+        needs is added, and the fastest threshold is kept.  Returns one row per layer:
+        (name, best t, {t: microseconds}).  Afterwards build_maps / forward use the chosen settings."""
+        n = len(self.layers)
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+
+        def timed(fn):
+            fn()
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps * 1e3
+
+        # activations of every layer with the current settings, and maps that hold both layouts
+        self.build_maps(v0_keys, desc)
+        _, T = self.forward(feats, keep=True)
+        self.destroy_maps()
+        req = [(l["K"], l["in_stride"], l["layer_stride"], l["transposed"], B.LAYOUT_BOTH) for l in self.layers]
+        maps = B.spc_build_kmaps_network(v0_keys, desc, req)
+        if self._packed is None:
+            self.prepare_weights()
+        rows = []
+        build_cost = {}
+        for j, l in enumerate(self.layers):
+            geo = (l["K"], l["in_stride"], l["layer_stride"], l["transposed"])
+            if geo not in build_cost:  # what the weight-stationary lists add to this geometry's map build
+                in_keys = v0_keys
+                t_os = timed(lambda: B.spc_build_kmaps_network(in_keys, desc, [geo + (B.LAYOUT_OS,)])[0].destroy())
+                t_both = timed(lambda: B.spc_build_kmaps_network(in_keys, desc, [geo + (B.LAYOUT_BOTH,)])[0].destroy())
+                build_cost[geo] = max(t_both - t_os, 0.0)
+            x = T[l["src"]]
+            if l["skip"] is not None:
+                x = torch.cat([T[l["src"]], T[l["skip"]]], dim=1)
+            w = self.weights[j]
+            cout = w.shape[2]
+            wp = B.spc_conv_prepare_weights(w) if (w.dtype != torch.float32 and w.shape[1] % 16 == 0 and cout % 32 == 0) else None
+            out = torch.empty((maps[j].n_out, cout), dtype=x.dtype, device=x.device)
+            l1_max = 3 if l["K"] == 2 else 3 * (l["K"] - 1) // 2
+            times = {}
+            for t in range(0, l1_max + 2):
+                ws_part = t <= l1_max
+                use_packed = wp is not None and (not ws_part or cout in (32, 64, 128, 256))
+                flags = (B.CONV_RELU if l["relu"] else 0) | (B.CONV_PACKED_WEIGHTS if use_packed else 0)
+                ww = wp if use_packed else w
+                times[t] = timed(lambda: B.spc_conv_forward(maps[j], x, ww, flags=flags, out=out, hybrid_t=t))
+                if ws_part:
+                    times[t] += build_cost[geo]
+            best = min(times, key=times.get)
+            rows.append((l["name"], best, times))
+            if best == l1_max + 1:
+                self.dataflow[j], self.hybrid_t[j] = B.DATAFLOW_OS, None
+            elif best == 0:
+                self.dataflow[j], self.hybrid_t[j] = B.DATAFLOW_WS, None
+            else:
+                self.hybrid_t[j] = best
+        for m in maps:
+            m.destroy()
+        self._packed = None  # the packable set depends on the dataflow of each layer
+        return rows
 
     def capture_step(self, coords, feats_raw, desc, streams=None, flags=0):
         """Records one full step for clouds of coords.shape[0] voxels into a HIP graph and returns a

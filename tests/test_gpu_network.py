@@ -70,12 +70,14 @@ def test_network_maps_bit_exact_and_shared(cloud_name, mode):
     net.destroy_maps()
 
 
-@pytest.mark.parametrize("cloud_name,dataflow", [("tiny", "os"), ("lidar", "os"), ("lidar", "mixed")])
+@pytest.mark.parametrize("cloud_name,dataflow", [("tiny", "os"), ("lidar", "os"), ("lidar", "mixed"), ("lidar", "hybrid")])
 def test_network_forward_matches_oracle(cloud_name, dataflow):
     coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup(cloud_name)
-    df = B.DATAFLOW_OS if dataflow == "os" else [B.DATAFLOW_WS if l["K"] == 2 or l["in_stride"] >= 8 else B.DATAFLOW_OS
-                                                 for l in layers]
-    net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W], dataflow=df)
+    df = [B.DATAFLOW_WS if l["K"] == 2 or l["in_stride"] >= 8 else B.DATAFLOW_OS for l in layers] if dataflow == "mixed" \
+        else B.DATAFLOW_OS
+    # hybrid: a different threshold on every 3x3x3 layer (1, 2, 3 in turn), single dataflows elsewhere
+    ht = [(1 + j % 3 if l["K"] == 3 else None) for j, l in enumerate(layers)] if dataflow == "hybrid" else None
+    net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W], dataflow=df, hybrid_t=ht)
     streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
     net.build_maps(keys, desc, streams)
     y, T = net.forward(Fs, keep=True)

@@ -292,6 +292,43 @@ def test_kmap_with_sort_permutation_folded_in(K, s_l):
         B.spc_build_kmap(keys, desc, 2, 1, 2, 1, B.LAYOUT_OS, in_perm=perm)
 
 
+@pytest.mark.parametrize("K,dtype,cin,cout", [(3, torch.float16, 32, 64), (5, torch.float16, 32, 32), (3, torch.float32, 6, 10),
+                                               (2, torch.bfloat16, 16, 128), (3, torch.float16, 20, 96)])
+def test_conv_hybrid_dataflow_every_threshold(K, dtype, cin, cout):
+    """Hybrid dual dataflow: offsets with L1 norm < t output-stationary, the rest weight-stationary, for every
+    t from 0 (all WS) to one above the largest norm (all OS); every split gives Eq. (2)."""
+    c = _cloud("rand_b3")
+    s_l = 2 if K == 2 else 1
+    desc = fit_desc(c, [(K, 1, s_l)])
+    keys, perm = gpu_pack(c, desc)
+    cs, operm = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_BOTH)
+    ci, co, M = oracle_layer(cs, K, 1, s_l, 0)
+    np_dt = np.float32 if dtype == torch.float32 else np.float16
+    F = synth.features(len(ci), cin, np_dt, seed=61)
+    W = synth.weights(K ** 3, cin, cout, np_dt, seed=62)
+    Ft, F64 = to_torch(F, dtype)
+    Wt, W64 = to_torch(W, dtype)
+    ref = np.maximum(oracle.conv(M, F64, W64), 0)
+    l1_max = 3 if K == 2 else 3 * (K - 1) // 2
+    for t in range(0, l1_max + 2):
+        for variant in (0, B.CONV_OS_PHASE, B.CONV_OS_SPLITK):
+            y = B.spc_conv_forward(km, Ft, Wt, flags=B.CONV_RELU | variant, hybrid_t=t)
+            err = rel_err(y.cpu().to(torch.float64).numpy(), ref)
+            assert err <= TOL[dtype], (t, variant, err)
+    # the ends of the range are the single dataflows: same kernels, same bits for OS
+    y_os = B.spc_conv_forward(km, Ft, Wt, B.DATAFLOW_OS, B.CONV_RELU)
+    y_t = B.spc_conv_forward(km, Ft, Wt, flags=B.CONV_RELU, hybrid_t=l1_max + 1)
+    assert torch.equal(y_os, y_t)
+    # a map without the WS layout serves only the all-OS end
+    km_os = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_OS)
+    B.spc_conv_forward(km_os, Ft, Wt, hybrid_t=l1_max + 1)
+    with pytest.raises(B.SpcError):
+        B.spc_conv_forward(km_os, Ft, Wt, hybrid_t=1)
+    km_os.destroy()
+    km.destroy()
+
+
 def test_conv_unaligned_feature_rows():
     """Rows that do not start on 16-byte boundaries (odd column offset) still give the right result."""
     c = _cloud("tiny")
