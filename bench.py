@@ -162,6 +162,9 @@ def main() -> int:
     ap.add_argument("--hybrid-t", type=int, default=None,
                     help="single-layer configurations: threshold of the hybrid dual dataflow (offsets with L1 norm < t run "
                          "output-stationary, the others weight-stationary); --config 4: ignored")
+    ap.add_argument("--voxels", type=int, default=0,
+                    help="single-layer configurations: replace the configuration's cloud by a uniformly random scene of this many "
+                         "voxels in a [n, n, 200] volume at 1.25 %% density (the random-scene size sweep)")
     ap.add_argument("--tune", action="store_true", help="--config 4: tune the per-layer threshold on the cloud first and report it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -187,7 +190,7 @@ def main() -> int:
     K, s_l, cin, cout = cfg["K"], cfg["layer_stride"], cfg["cin"], cfg["cout"]
     K3 = K ** 3
     tdt = {"f32": torch.float32, "f16": torch.float16}[cfg["dtype"]]
-    coords_np = synth.cloud(cfg["cloud"])
+    coords_np = synth.scaled_random_cloud(args.voxels) if args.voxels > 0 else synth.cloud(cfg["cloud"])
     n = coords_np.shape[0]
     F_np, W_np = synth.layer_tensors(args.config, n)
     dataflow = {"os": B.DATAFLOW_OS, "ws": B.DATAFLOW_WS}.get(args.dataflow)
@@ -306,7 +309,7 @@ def main() -> int:
         "ms_per_step": ms_per_step, "ms_per_step_wall": ms_per_step_wall, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": "cfg%d: %s cloud, %d voxels -> %d outputs, K=%d, layer stride %d, C %d->%d, %s, dataflow %s"
-                   % (args.config, cfg["cloud"], n, n_out, K, s_l, cin, cout, cfg["dtype"],
+                   % (args.config, "uniform random" if args.voxels > 0 else cfg["cloud"], n, n_out, K, s_l, cin, cout, cfg["dtype"],
                       ("hybrid t=%d" % args.hybrid_t) if args.hybrid_t is not None else
                       ("OS" if dataflow == B.DATAFLOW_OS else "WS")),
                    "n_voxels": n, "n_out": n_out, "K": K, "cin": cin, "cout": cout, "nnz": nnz,

@@ -672,13 +672,24 @@ __global__ __launch_bounds__(256) void conv_os_simple_kernel(const int32_t* __re
   const int co = static_cast<int>(gid - i * cout);
   if (i >= n_out) return;
   float acc = init ? init[gid] : 0.f;
-  for (int k = 0; k < K3; ++k) {
-    if (!kmask.has(k)) continue;
-    const int j = M[((i >> 5) * K3 + k) * 32 + (i & 31)];
-    if (j < 0) continue;
-    const T* f = F + int64_t(j) * ld_in;
-    const T* w = W + int64_t(k) * cin * cout + co;
-    for (int ci = 0; ci < cin; ++ci) acc = fmaf(to_f32(f[ci]), to_f32(w[int64_t(ci) * cout]), acc);
+  // map entries are fetched eight offsets at a time, so that their loads (and then the feature
+  // rows') are in flight together instead of one dependent chain per offset
+  const int32_t* Mi = M + (i >> 5) * int64_t(K3) * 32 + (i & 31);
+  for (int k0 = 0; k0 < K3; k0 += 8) {
+    int j[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int k = k0 + u;
+      j[u] = (k < K3 && kmask.has(k)) ? Mi[k * 32] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (j[u] < 0) continue;
+      const T* f = F + int64_t(j[u]) * ld_in;
+      const T* w = W + int64_t(k0 + u) * cin * cout + co;
+#pragma unroll 8
+      for (int ci = 0; ci < cin; ++ci) acc = fmaf(to_f32(f[ci]), to_f32(w[int64_t(ci) * cout]), acc);
+    }
   }
   if (relu) acc = fmaxf(acc, 0.f);
   out[i * ld_out + co] = from_f32<T>(acc);
