@@ -162,6 +162,8 @@ def main() -> int:
     ap.add_argument("--hybrid-t", type=int, default=None,
                     help="single-layer configurations: threshold of the hybrid dual dataflow (offsets with L1 norm < t run "
                          "output-stationary, the others weight-stationary); --config 4: ignored")
+    ap.add_argument("--sym", action="store_true",
+                    help="single-layer configurations with --dataflow ws: build the symmetric half-map (submanifold layers)")
     ap.add_argument("--voxels", type=int, default=0,
                     help="single-layer configurations: replace the configuration's cloud by a uniformly random scene of this many "
                          "voxels in a [n, n, 200] volume at 1.25 %% density (the random-scene size sweep)")
@@ -199,6 +201,8 @@ def main() -> int:
     layout = B.LAYOUT_OS if dataflow == B.DATAFLOW_OS else B.LAYOUT_WS
     if args.hybrid_t is not None:
         layout = B.LAYOUT_BOTH
+    if args.sym:
+        layout |= B.LAYOUT_WS_SYM
 
     lo, hi = coords_np[:, 1:].min(0), coords_np[:, 1:].max(0)
     reach = ((K - 1) // 2) if K % 2 else (K - 1)
@@ -229,6 +233,7 @@ def main() -> int:
     if use_packed:
         B.spc_conv_prepare_weights(W, Wp)
     conv_flags = B.CONV_PACKED_WEIGHTS if use_packed else 0
+    F_sorted = torch.empty_like(F_raw) if args.sym else None
 
     def step(marks=None):
         """One layer on one cloud: pack + sort the coordinates, build the kernel map (with the sort
@@ -238,10 +243,15 @@ def main() -> int:
         B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
         if marks is not None:
             marks[1].record()
-        km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout, in_perm=perm)
+        if args.sym:  # a symmetric half-map numbers inputs and outputs alike: the feature rows are moved instead
+            B.spc_permute_rows(F_raw, perm, F_sorted)
+            km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout)
+        else:
+            km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout, in_perm=perm)
         if marks is not None:
             marks[2].record()
-        B.spc_conv_forward(km, F_raw, Wp if use_packed else W, dataflow, conv_flags, out=out, hybrid_t=args.hybrid_t)
+        B.spc_conv_forward(km, F_sorted if args.sym else F_raw, Wp if use_packed else W, dataflow, conv_flags, out=out,
+                           hybrid_t=args.hybrid_t)
         if marks is not None:
             marks[3].record()
         km.destroy()

@@ -46,6 +46,12 @@ extern "C" {
 #define SPC_LAYOUT_OS 1   /* |V_q| x K^3 matrix of input indices (Section 5.4, case I) */
 #define SPC_LAYOUT_WS 2   /* per-offset filtered (in,out) lists (Section 5.4, case II) */
 #define SPC_LAYOUT_BOTH 3
+/* Modifier of the WS layout for submanifold layers (layer_stride 1, odd K): lists are kept for the
+ * offsets k < (K^3-1)/2 only.  Offset K^3-1-k is the same list with input and output swapped
+ * (delta_n = -delta_l: M[i,l] = j  <=>  M[j,n] = i) and the centre offset pairs every voxel with
+ * itself, so the feature kernel derives both from the stored half (Section 5.4).  Without the OS
+ * layout the search itself visits only that half of the offsets. */
+#define SPC_LAYOUT_WS_SYM 4
 
 #define SPC_DATAFLOW_OS 0 /* output-stationary: no atomics, bit-reproducible */
 #define SPC_DATAFLOW_WS 1 /* weight-stationary: fp32 atomic accumulation */
@@ -140,7 +146,7 @@ int spc_build_kmap(const void* in_keys, int64_t n_in, const spc_pack_desc* d, co
  * feature matrix in its original row order, so the first layer of a network needs no
  * spc_permute_rows; its output rows are in sorted order like any other layer's.  in_perm
  * is read by the build only (a build captured into a graph reads it on every replay).
- * NULL in_perm = spc_build_kmap.  Not available for transposed layers.
+ * NULL in_perm = spc_build_kmap.  Not available for transposed layers and symmetric half-maps.
  */
 int spc_build_kmap_perm(const void* in_keys, int64_t n_in, const int32_t* in_perm, const spc_pack_desc* d,
                         const spc_layer_desc* l, spc_kmap** out, void* stream);

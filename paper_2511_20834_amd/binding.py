@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libspc.so")
 OK = 0
 DTYPE_F16, DTYPE_BF16, DTYPE_F32 = 0, 1, 2
 LAYOUT_OS, LAYOUT_WS, LAYOUT_BOTH = 1, 2, 3
+LAYOUT_WS_SYM = 4  # with LAYOUT_WS: symmetric half-map of a submanifold layer
 DATAFLOW_OS, DATAFLOW_WS = 0, 1
 PACK_VALIDATE = 1
 CONV_RELU = 1

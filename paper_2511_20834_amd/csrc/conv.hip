@@ -603,59 +603,76 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
 }
 
 // Weight-stationary: workgroup = one offset k and 4 x RB blocks of 32 (in,out) pairs;
-// partial sums are merged into an fp32 buffer with hardware float atomics.
+// partial sums are merged into an fp32 buffer with hardware float atomics.  On a symmetric
+// half-map every pair block is used twice: as stored with W_k, and with input and output
+// swapped with the weights of the opposite offset (Section 5.4).
 template <typename T, int NB, int RB>
 __global__ __launch_bounds__(CONV_THREADS) void conv_ws_mfma_kernel(const int32_t* __restrict__ ws_in,
                                                                     const int32_t* __restrict__ ws_out,
                                                                     const int32_t* __restrict__ nnz, int64_t ws_stride,
                                                                     const T* __restrict__ F, int64_t ld_in,
                                                                     const T* __restrict__ Wp, float* __restrict__ accum,
-                                                                    int cin, KMask kmask) {
+                                                                    int cin, KMask kmask, int sym, int K3, int n_out_h,
+                                                                    const int* __restrict__ n_out_d) {
   using V8 = typename Mfma<T>::V8;
   constexpr int WROWS = 32 * RB, TROWS = 4 * WROWS;
   extern __shared__ __align__(16) unsigned char smem[];
   V8* sB = reinterpret_cast<V8*>(smem);
-  __shared__ int s_out[TROWS];
+  __shared__ int s_out[TROWS], s_in[TROWS];
   const int k = blockIdx.y;
   if (!kmask.has(k)) return;  // whole workgroup
-  const int cnt = nnz[k];
+  // symmetric half-map: lists exist for k < centre; the centre offset pairs every voxel with itself
+  const int kc = (K3 - 1) / 2;
+  const bool centre = sym && k == kc;
+  const int cnt = centre ? (n_out_d ? *n_out_d : n_out_h) : nnz[k];
   const int p0 = blockIdx.x * TROWS;
   if (p0 >= cnt) return;
   const int rows = min(TROWS, cnt - p0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lh = lane >> 5;
   const int32_t* li = ws_in + int64_t(k) * ws_stride + p0;
   const int32_t* lo = ws_out + int64_t(k) * ws_stride + p0;
-  for (int r = tid; r < TROWS; r += CONV_THREADS) s_out[r] = r < rows ? lo[r] : -1;
-  floatx16 acc[RB][NB];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
-  int idx[RB];
-  bool has = false;
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int r = wave * WROWS + rb * 32 + lr;
-    idx[rb] = r < rows ? li[r] : -1;
-    has |= idx[rb] >= 0;
+  for (int r = tid; r < TROWS; r += CONV_THREADS) {
+    s_out[r] = r < rows ? (centre ? p0 + r : lo[r]) : -1;
+    s_in[r] = r < rows ? (centre ? p0 + r : li[r]) : -1;
   }
-  const bool wave_has = __ballot(has) != 0ull;
+  __syncthreads();
   const int cout = NB * 32;
-  contract_offset<T, NB, RB>(F, ld_in, Wp + int64_t(k) * cin * cout, cin, idx, wave_has, sB, acc);
-  if (!wave_has) return;  // s_out was published by the barriers inside contract_offset
+  // pass 0: F[in] W_k -> out.  pass 1 (symmetric maps, not the centre): F[out] W_{K^3-1-k} -> in
+  const int passes = (sym && !centre) ? 2 : 1;
+  for (int pass = 0; pass < passes; ++pass) {
+    const int* gat = pass == 0 ? s_in : s_out;
+    const int* sca = pass == 0 ? s_out : s_in;
+    const int kw = pass == 0 ? k : K3 - 1 - k;
+    floatx16 acc[RB][NB];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = wave * WROWS + rb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-      const int o = s_out[row];
-      if (o >= 0) {
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) unsafeAtomicAdd(accum + int64_t(o) * cout + nb * 32 + lr, acc[rb][nb][r]);
-      }
+        for (int r = 0; r < 16; ++r) acc[rb][nb][r] = 0.f;
+    int idx[RB];
+    bool has = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      idx[rb] = gat[wave * WROWS + rb * 32 + lr];
+      has |= idx[rb] >= 0;
     }
+    const bool wave_has = __ballot(has) != 0ull;
+    if (pass > 0) __syncthreads();  // everybody is done with the weights of the pass before
+    contract_offset<T, NB, RB>(F, ld_in, Wp + int64_t(kw) * cin * cout, cin, idx, wave_has, sB, acc);
+    if (!wave_has) continue;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = wave * WROWS + rb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+        const int o = sca[row];
+        if (o >= 0) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) unsafeAtomicAdd(accum + int64_t(o) * cout + nb * 32 + lr, acc[rb][nb][r]);
+        }
+      }
+  }
 }
 
 // ---------------------------------------------------------------- plain FMA kernels
@@ -701,19 +718,26 @@ __global__ __launch_bounds__(256) void conv_ws_simple_kernel(const int32_t* __re
                                                              const int32_t* __restrict__ nnz, int64_t ws_stride,
                                                              const T* __restrict__ F, int64_t ld_in,
                                                              const T* __restrict__ W, float* __restrict__ accum,
-                                                             int cin, int cout, KMask kmask) {
+                                                             int cin, int cout, KMask kmask, int sym, int K3, int n_out_h,
+                                                             const int* __restrict__ n_out_d) {
   const int k = blockIdx.y;
   if (!kmask.has(k)) return;
+  const int kc = (K3 - 1) / 2;
+  const bool centre = sym && k == kc;
   const int64_t gid = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
   const int64_t p = gid / cout;
   const int co = static_cast<int>(gid - p * cout);
-  if (p >= nnz[k]) return;
-  const int j = ws_in[int64_t(k) * ws_stride + p], o = ws_out[int64_t(k) * ws_stride + p];
-  const T* f = F + int64_t(j) * ld_in;
-  const T* w = W + int64_t(k) * cin * cout + co;
-  float acc = 0.f;
-  for (int ci = 0; ci < cin; ++ci) acc = fmaf(to_f32(f[ci]), to_f32(w[int64_t(ci) * cout]), acc);
-  unsafeAtomicAdd(accum + int64_t(o) * cout + co, acc);
+  if (p >= (centre ? (n_out_d ? *n_out_d : n_out_h) : nnz[k])) return;
+  const int j = centre ? static_cast<int>(p) : ws_in[int64_t(k) * ws_stride + p];
+  const int o = centre ? static_cast<int>(p) : ws_out[int64_t(k) * ws_stride + p];
+  const int passes = (sym && !centre) ? 2 : 1;  // second pass: the opposite offset, roles swapped
+  for (int pass = 0; pass < passes; ++pass) {
+    const T* f = F + int64_t(pass == 0 ? j : o) * ld_in;
+    const T* w = W + int64_t(pass == 0 ? k : K3 - 1 - k) * cin * cout + co;
+    float acc = 0.f;
+    for (int ci = 0; ci < cin; ++ci) acc = fmaf(to_f32(f[ci]), to_f32(w[int64_t(ci) * cout]), acc);
+    unsafeAtomicAdd(accum + int64_t(pass == 0 ? o : j) * cout + co, acc);
+  }
 }
 
 __global__ __launch_bounds__(256) void zero_f32_kernel(float4* __restrict__ p, int64_t n4) {
@@ -856,8 +880,10 @@ static void launch_ws_mfma(const ConvArgs& a, const T* Wp, float* accum) {
   constexpr int TROWS = 128 * RB;
   const size_t lds = size_t(CK / 16) * NB * 64 * 16;
   const int gx = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
-  hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, a.m->K3), dim3(CONV_THREADS), lds, a.s, a.m->ws_in, a.m->ws_out,
-                     a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin, a.ws_mask);
+  const int gy = a.m->sym ? (a.m->K3 - 1) / 2 + 1 : a.m->K3;  // a symmetric map is walked up to the centre offset
+  hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, gy), dim3(CONV_THREADS), lds, a.s, a.m->ws_in, a.m->ws_out,
+                     a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin, a.ws_mask,
+                     a.m->sym ? 1 : 0, a.m->K3, a.n_out_h, a.n_out_d);
 }
 
 // Shapes the MFMA kernels run (16-bit types): input channels a multiple of 16 (smaller or ragged
@@ -954,9 +980,9 @@ static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
   if (!use_mfma) {
     // nnz[k] <= n_out for every offset
     if (a.any_ws)
-      hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((out_elems + 255) / 256, K3), dim3(256), 0, a.s, a.m->ws_in, a.m->ws_out,
-                         a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), accum, a.cin,
-                         a.cout, a.ws_mask);
+      hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((out_elems + 255) / 256, a.m->sym ? (K3 - 1) / 2 + 1 : K3), dim3(256), 0,
+                         a.s, a.m->ws_in, a.m->ws_out, a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in,
+                         static_cast<const T*>(a.W), accum, a.cin, a.cout, a.ws_mask, a.m->sym ? 1 : 0, K3, a.n_out_h, a.n_out_d);
     if (a.any_os)
       hipLaunchKernelGGL(conv_os_simple_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, a.m->os_map, a.n_out_h,
                          a.n_out_d, K3, static_cast<const T*>(a.F), a.ld_in, static_cast<const T*>(a.W), static_cast<T*>(a.out),

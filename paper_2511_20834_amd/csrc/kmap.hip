@@ -124,7 +124,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
     int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
     uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
-    const int32_t* __restrict__ in_perm) {
+    const int32_t* __restrict__ in_perm, int k_lim) {
   constexpr int G = K * K, K3 = K * K * K;
   constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
@@ -154,6 +154,10 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   for (int v = tid; v < rows; v += SEARCH_THREADS) okeys[v] = out_keys[i0 + v];
   for (int k = tid; k < K3; k += SEARCH_THREADS) s_cnt[k] = 0;
   for (int k = tid; k < MAX_BLOCKS * MW; k += SEARCH_THREADS) s_mask[k] = 0u;
+  for (int k = tid; k < 2 * G; k += SEARCH_THREADS) s_bound[k] = 0;
+  // only offsets k < k_lim are searched (all of them, or the first half of a symmetric map):
+  // groups past the limit get empty windows, the group the limit cuts keeps its first offsets
+  const int g_lim = (k_lim + K - 1) / K;
 #pragma unroll
   for (int g = 0; g < G; ++g)  // static indices keep the kernel arguments in scalar registers
     if (tid == g) s_gd[g] = sp.X[g / K] + sp.Y[g % K] + sp.zmin;
@@ -163,7 +167,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 
   // ---- window bounds: search s = 2*g + side, dealt round-robin to the waves, S at a time
   constexpr int S = (2 * G + NW - 1) / NW < 5 ? (2 * G + NW - 1) / NW : 5;
-  for (int s0 = wave * S; s0 < 2 * G; s0 += NW * S) {
+  for (int s0 = wave * S; s0 < 2 * g_lim; s0 += NW * S) {
     KeyT q[S];
     bool up[S];
     int res[S];
@@ -175,7 +179,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       q[j] = up[j] ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
     }
     wave_bounds<KeyT, S>(in_keys, n_in, probe, q, up, res);
-    if (lane < S && s0 + lane < 2 * G) {
+    if (lane < S && s0 + lane < 2 * g_lim) {
       int r = res[0];
 #pragma unroll
       for (int j = 1; j < S; ++j) r = (lane == j) ? res[j] : r;
@@ -240,20 +244,20 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const bool act = v < rows;
   const KeyT okey = act ? okeys[v] : KeyT(0);
   const int bl = v >> 5;
-  for (int gb = part; gb < G; gb += parts * SEARCH_GB) {
+  for (int gb = part; gb < g_lim; gb += parts * SEARCH_GB) {
     int pos[SEARCH_GB], gidx[SEARCH_GB], wsz[SEARCH_GB], woff[SEARCH_GB];
     KeyT q0[SEARCH_GB];
     int maxw = 0;
 #pragma unroll
     for (int j = 0; j < SEARCH_GB; ++j) {
       const int g = gb + j * parts;
-      gidx[j] = g < G ? g : -1;
-      const int gc = g < G ? g : 0;
+      gidx[j] = g < g_lim ? g : -1;
+      const int gc = g < g_lim ? g : 0;
       woff[j] = s_woff[gc];
-      wsz[j] = (g < G && act) ? s_wsz[gc] : 0;
+      wsz[j] = (g < g_lim && act) ? s_wsz[gc] : 0;
       q0[j] = okey + s_gd[gc];
       pos[j] = 0;
-      if (g < G && woff[j] >= 0) maxw = max(maxw, s_wsz[gc]);
+      if (g < g_lim && woff[j] >= 0) maxw = max(maxw, s_wsz[gc]);
     }
     // lower bounds in LDS: pos += bit while the key before pos+bit is smaller than the query
     for (int bit = maxw > 0 ? 1 << (31 - __clz(maxw)) : 0; bit > 0; bit >>= 1) {
@@ -290,6 +294,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
       for (int t = 0; t < K; ++t) {
         const int k = g * K + t;
+        if (k >= k_lim) continue;  // uniform
         // found positions are stored as they are, or mapped to the caller's row numbering
         int32_t jv = r[j][t];
         if (in_perm && jv >= 0) jv = in_perm[jv];
@@ -314,8 +319,12 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 // total into nnz[k].
 __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile_counts, int n_tiles_cap, int tile,
                                                       int n_out_h, const int* __restrict__ n_out_d,
-                                                      int32_t* __restrict__ nnz) {
+                                                      int32_t* __restrict__ nnz, int k_lim) {
   __shared__ int wave_sum[4];
+  if (int(blockIdx.x) >= k_lim) {  // offsets without a list of their own (second half of a symmetric map)
+    if (threadIdx.x == 0) nnz[blockIdx.x] = 0;
+    return;
+  }
   const int n_out = n_out_d ? *n_out_d : n_out_h;
   const int n_tiles = (n_out + tile - 1) / tile;
   int32_t* c = tile_counts + int64_t(blockIdx.x) * n_tiles_cap;
@@ -351,14 +360,14 @@ __global__ __launch_bounds__(256) void ws_fill_kernel(const int32_t* __restrict_
                                                       const int* __restrict__ n_out_d, int K3, int tile,
                                                       const int32_t* __restrict__ tile_base, int n_tiles_cap,
                                                       int32_t* __restrict__ ws_in, int32_t* __restrict__ ws_out,
-                                                      int64_t ws_stride) {
+                                                      int64_t ws_stride, int k_lim) {
   const int n_out = n_out_d ? *n_out_d : n_out_h;
   const int i0 = blockIdx.x * tile;
   if (i0 >= n_out) return;
   const int rows = min(tile, n_out - i0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t b0 = int64_t(i0) >> 5;
-  for (int k = wave; k < K3; k += 4) {
+  for (int k = wave; k < k_lim; k += 4) {
     int base = tile_base[int64_t(k) * n_tiles_cap + blockIdx.x];
     int32_t* li = ws_in + int64_t(k) * ws_stride;
     int32_t* lo = ws_out + int64_t(k) * ws_stride;
@@ -405,7 +414,8 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
     hipLaunchKernelGGL((kmap_search_kernel<KeyT, K>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
-                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm);
+                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm,
+                       (m->sym && !(m->desc.layout & SPC_LAYOUT_OS)) ? m->k_lim : m->K3);
   return SPC_OK;
 }
 
@@ -443,7 +453,13 @@ static int check_layer(const spc_layer_desc* l) {
   if (!pow2(l->in_stride) || !pow2(l->layer_stride)) return set_error(SPC_ERR_ARG, "strides must be powers of two");
   if (l->transposed != 0 && l->transposed != 1) return set_error(SPC_ERR_ARG, "transposed must be 0 or 1");
   if (l->transposed && l->layer_stride == 1) return set_error(SPC_ERR_ARG, "a transposed layer needs layer_stride > 1");
-  if (l->layout < 1 || l->layout > 3) return set_error(SPC_ERR_ARG, "layout must be OS, WS or BOTH");
+  const int base = l->layout & SPC_LAYOUT_BOTH;
+  if (l->layout < 1 || l->layout > 7 || base == 0) return set_error(SPC_ERR_ARG, "layout must be OS, WS or BOTH (| WS_SYM)");
+  if (l->layout & SPC_LAYOUT_WS_SYM) {
+    if (!(l->layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "WS_SYM modifies the WS layout");
+    if (l->layer_stride != 1 || l->K % 2 == 0 || l->K < 3)
+      return set_error(SPC_ERR_ARG, "the symmetric half-map needs a submanifold layer with odd K >= 3");
+  }
   return SPC_OK;
 }
 
@@ -461,6 +477,8 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->pi = pi;
   m->desc = l;
   m->K3 = l.K * l.K * l.K;
+  m->sym = (l.layout & SPC_LAYOUT_WS_SYM) != 0;
+  m->k_lim = m->sym ? (m->K3 - 1) / 2 : m->K3;
   m->stream = s;
   m->captured = stream_is_capturing(s);
   m->in_level = in;
@@ -492,10 +510,10 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   if (rc == SPC_OK && (l.layout & SPC_LAYOUT_WS)) {
     const int n_out_h = static_cast<int>(out->n_host < 0 ? 0 : out->n_host);
     hipLaunchKernelGGL(ws_scan_kernel, dim3(m->K3), dim3(256), 0, s, m->tile_counts, m->n_tiles, m->tile, n_out_h,
-                       out->n_dev, m->nnz_dev);
+                       out->n_dev, m->nnz_dev, m->k_lim);
     if (m->n_tiles > 0)
       hipLaunchKernelGGL(ws_fill_kernel, dim3(m->n_tiles), dim3(256), 0, s, m->os_map, n_out_h,
-                         out->n_dev, m->K3, m->tile, m->tile_counts, m->n_tiles, m->ws_in, m->ws_out, m->out_cap);
+                         out->n_dev, m->K3, m->tile, m->tile_counts, m->n_tiles, m->ws_in, m->ws_out, m->out_cap, m->k_lim);
   }
   if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "kernel-map launch failed");
   if (rc == SPC_OK && (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||
@@ -569,6 +587,8 @@ int spc_build_kmap_perm(const void* in_keys, int64_t n_in, const int32_t* in_per
   if (l->layer_stride > 1) rc = downsample_level(in_keys, n_in, nullptr, pi, ilog2(l->in_stride * l->layer_stride), &derived, s);
   if (rc == SPC_OK) {
     if (in_perm && l->transposed) rc = set_error(SPC_ERR_ARG, "in_perm applies to the given level, which a transposed layer writes");
+    else if (in_perm && (l->layout & SPC_LAYOUT_WS_SYM))
+      rc = set_error(SPC_ERR_ARG, "a symmetric half-map swaps inputs and outputs: both must be numbered alike (no in_perm)");
     else if (l->layer_stride == 1) rc = build_on_levels(given, given, pi, *l, s, out, in_perm);
     else if (!l->transposed) rc = build_on_levels(given, derived, pi, *l, s, out, in_perm);
     else rc = build_on_levels(derived, given, pi, *l, s, out);
@@ -646,6 +666,14 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
   std::map<Key, spc_kmap*> maps;
   std::map<Key, int> want;
   for (int i = 0; i < n_layers; ++i) want[Key(layers[i].K, layers[i].in_stride, layers[i].layer_stride, layers[i].transposed)] |= layers[i].layout;
+  for (auto& kv : want) {  // a map shared by layers that disagree about the half-map keeps the full lists
+    bool all_sym = true;
+    for (int i = 0; i < n_layers; ++i)
+      if (Key(layers[i].K, layers[i].in_stride, layers[i].layer_stride, layers[i].transposed) == kv.first &&
+          (layers[i].layout & SPC_LAYOUT_WS) && !(layers[i].layout & SPC_LAYOUT_WS_SYM))
+        all_sym = false;
+    if (!all_sym) kv.second &= ~SPC_LAYOUT_WS_SYM;
+  }
   // A stream waits for each foreign event at most once (stream order covers everything it
   // enqueues later), and the other streams join streams[0] once, at the end: few, distinct
   // cross-stream edges, which is also what a graph capture of this call records.
@@ -768,23 +796,34 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
     std::vector<int32_t> cnt(K3);
     SPC_HIP_CHECK(hipMemcpy(cnt.data(), m->nnz_dev, size_t(K3) * 4, hipMemcpyDeviceToHost));
     std::vector<int32_t> a, b;
+    const int kc = (K3 - 1) / 2;
+    auto emit = [&](int k, int32_t in, int32_t out) {
+      if (nnz < cap && triples) {
+        triples[3 * nnz] = k;
+        triples[3 * nnz + 1] = in;
+        triples[3 * nnz + 2] = out;
+      }
+      ++nnz;
+    };
     for (int k = 0; k < K3; ++k) {
-      const int c = cnt[k];
-      if (c < 0 || c > n_out) return set_error(SPC_ERR_HIP, "corrupt WS count %d at offset %d", c, k);
+      // symmetric half-map: offset k > centre is the list of K^3-1-k with the roles swapped (both
+      // index sequences of a list ascend, so the order by output index is kept); the centre pairs
+      // every voxel with itself
+      if (m->sym && k == kc) {
+        for (int64_t i = 0; i < n_out; ++i) emit(k, static_cast<int32_t>(i), static_cast<int32_t>(i));
+        continue;
+      }
+      const bool mirror = m->sym && k > kc;
+      const int ks = mirror ? K3 - 1 - k : k;
+      const int c = cnt[ks];
+      if (c < 0 || c > n_out) return set_error(SPC_ERR_HIP, "corrupt WS count %d at offset %d", c, ks);
       a.resize(c);
       b.resize(c);
       if (c) {
-        SPC_HIP_CHECK(hipMemcpy(a.data(), m->ws_in + int64_t(k) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
-        SPC_HIP_CHECK(hipMemcpy(b.data(), m->ws_out + int64_t(k) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
+        SPC_HIP_CHECK(hipMemcpy(a.data(), m->ws_in + int64_t(ks) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
+        SPC_HIP_CHECK(hipMemcpy(b.data(), m->ws_out + int64_t(ks) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
       }
-      for (int e = 0; e < c; ++e) {
-        if (nnz < cap && triples) {
-          triples[3 * nnz] = k;
-          triples[3 * nnz + 1] = a[e];
-          triples[3 * nnz + 2] = b[e];
-        }
-        ++nnz;
-      }
+      for (int e = 0; e < c; ++e) emit(k, mirror ? b[e] : a[e], mirror ? a[e] : b[e]);
     }
   }
   *nnz_out = nnz;
@@ -801,6 +840,11 @@ int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host) {
       std::vector<int32_t> c(m->K3);
       SPC_HIP_CHECK(hipMemcpy(c.data(), m->nnz_dev, size_t(m->K3) * 4, hipMemcpyDeviceToHost));
       for (int k = 0; k < m->K3; ++k) cnt[k] = c[k];
+      if (m->sym) {  // the second half mirrors the first, the centre pairs every voxel with itself
+        const int kc = (m->K3 - 1) / 2;
+        cnt[kc] = m->out_level->n_fetched;
+        for (int k = kc + 1; k < m->K3; ++k) cnt[k] = cnt[m->K3 - 1 - k];
+      }
     } else {
       const int64_t n_out = m->out_level->n_fetched;
       std::vector<int32_t> M(size_t((n_out + 31) / 32) * 32 * m->K3);

@@ -127,6 +127,8 @@ struct spc_kmap {
   spc::PackInfo pi{};
   spc_layer_desc desc{};
   int K3 = 0;
+  bool sym = false;                 // WS lists hold offsets k < (K^3-1)/2 only (symmetric half-map)
+  int k_lim = 0;                    // offsets that have a WS list of their own
   spc::Level* in_level = nullptr;   // the layer's input voxels
   spc::Level* out_level = nullptr;  // the layer's output voxels
   const int32_t* in_perm = nullptr; // caller's row number of every input voxel (borrowed), or NULL

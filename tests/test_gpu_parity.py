@@ -329,6 +329,52 @@ def test_conv_hybrid_dataflow_every_threshold(K, dtype, cin, cout):
     km.destroy()
 
 
+@pytest.mark.parametrize("name,K,key_bits,with_os", [("tiny", 3, 0, False), ("tiny_neg", 5, 0, False), ("rand_b3", 3, 64, True),
+                                                     ("ragged", 7, 0, False), ("grid", 3, 0, True)])
+def test_symmetric_half_map(name, K, key_bits, with_os):
+    """WS lists for the first half of the offsets only (submanifold layer): the exported triples, the
+    per-offset counts and the features equal those of the full map."""
+    c = _cloud(name)
+    desc = fit_desc(c, [(K, 1, 1)], key_bits)
+    keys, perm = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    layout = B.LAYOUT_WS | B.LAYOUT_WS_SYM | (B.LAYOUT_OS if with_os else 0)
+    km = B.spc_build_kmap(keys, desc, K, 1, 1, 0, layout)
+    M = oracle.kernel_map(cs, cs, K, 1)
+    ref_t = oracle.triples(M)
+    assert np.array_equal(km.export_triples(B.LAYOUT_WS), ref_t)
+    if with_os:
+        assert np.array_equal(km.export_triples(B.LAYOUT_OS), ref_t)
+    assert np.array_equal(km.nnz(), np.bincount(ref_t[:, 0], minlength=K ** 3))
+    for dtype, cin, cout in ((torch.float16, 32, 64), (torch.float32, 5, 7), (torch.bfloat16, 16, 32)):
+        np_dt = np.float32 if dtype == torch.float32 else np.float16
+        Ft, F64 = to_torch(synth.features(len(cs), cin, np_dt, seed=71), dtype)
+        Wt, W64 = to_torch(synth.weights(K ** 3, cin, cout, np_dt, seed=72), dtype)
+        ref = oracle.conv(M, F64, W64)
+        y = B.spc_conv_forward(km, Ft, Wt, B.DATAFLOW_WS)
+        assert rel_err(y.cpu().to(torch.float64).numpy(), ref) <= TOL[dtype], (dtype, "ws")
+        if with_os:  # hybrid dual dataflow on top of the half lists
+            for t in (1, 2):
+                y = B.spc_conv_forward(km, Ft, Wt, hybrid_t=t)
+                assert rel_err(y.cpu().to(torch.float64).numpy(), ref) <= TOL[dtype], (dtype, t)
+    km.destroy()
+
+
+def test_symmetric_half_map_bad_arguments():
+    c = _cloud("tiny")
+    desc = fit_desc(c, [(3, 1, 2)])
+    keys, _ = gpu_pack(c, desc)
+    for K, s_l, tr, layout in ((3, 2, 0, B.LAYOUT_WS | B.LAYOUT_WS_SYM), (2, 2, 1, B.LAYOUT_WS | B.LAYOUT_WS_SYM),
+                               (3, 1, 0, B.LAYOUT_OS | B.LAYOUT_WS_SYM), (1, 1, 0, B.LAYOUT_WS | B.LAYOUT_WS_SYM)):
+        with pytest.raises(B.SpcError) as e:
+            B.spc_build_kmap(keys, desc, K, 1, s_l, tr, layout)
+        assert e.value.code == B.ERR_ARG
+    keys1, perm1 = gpu_pack(c, fit_desc(c, [(3, 1, 1)]))
+    with pytest.raises(B.SpcError) as e:  # swapped roles need one numbering of the rows
+        B.spc_build_kmap(keys1, fit_desc(c, [(3, 1, 1)]), 3, 1, 1, 0, B.LAYOUT_WS | B.LAYOUT_WS_SYM, in_perm=perm1)
+    assert e.value.code == B.ERR_ARG
+
+
 def test_conv_unaligned_feature_rows():
     """Rows that do not start on 16-byte boundaries (odd column offset) still give the right result."""
     c = _cloud("tiny")
