@@ -46,10 +46,12 @@ __device__ inline int lanemask_lt_popc(unsigned long long m) {
 // holds the answer.  The first round probes the same 64 keys for every search of every
 // workgroup, so the caller loads them once (`probe`, one per lane) and that round costs no
 // memory access; 2^18 keys then need two dependent loads per search, all S searches of a
-// wave in flight together.
+// wave in flight together.  The searches stop once every answer is known to within `slack`
+// positions and return the outer ends (slack 0: exact bounds): a window that is a few keys
+// too wide costs less than another round of dependent loads.
 template <typename KeyT, int S>
 __device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, KeyT probe, const KeyT (&q)[S],
-                                   const bool (&upper)[S], int (&res)[S]) {
+                                   const bool (&upper)[S], int (&res)[S], int slack) {
   const int lane = threadIdx.x & 63;
   int lo[S], hi[S];
   const int chunk0 = (n + 63) >> 6;
@@ -67,11 +69,13 @@ __device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, KeyT pr
       hi[s] = min(lo[s] + chunk0 - 1, n - 1);
     }
   }
-  while (true) {
+  auto widest = [&]() {
     int maxlen = 0;
 #pragma unroll
     for (int s = 0; s < S; ++s) maxlen = max(maxlen, hi[s] - lo[s]);
-    if (maxlen == 0) break;
+    return maxlen;
+  };
+  while (widest() > slack) {
     bool pred[S];
     int chunk[S];
 #pragma unroll
@@ -100,8 +104,9 @@ __device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, KeyT pr
       }
     }
   }
+  // the answer lies in [lo, hi]: the low end for a window start, the high end for a window end
 #pragma unroll
-  for (int s = 0; s < S; ++s) res[s] = lo[s];
+  for (int s = 0; s < S; ++s) res[s] = upper[s] ? hi[s] : lo[s];
 }
 
 // Per-lane lower bound in a window of wsz keys (used for windows that stay in global memory).
@@ -130,6 +135,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
   constexpr int WIN_CAP = WIN_CAP_BYTES / sizeof(KeyT);
   constexpr int NW = SEARCH_THREADS / 64;
+  constexpr int BOUND_SLACK = G <= 9 ? 32 : 8;  // extra keys per window end: 2 * G * slack must stay small next to WIN_CAP
   extern __shared__ __align__(16) unsigned char smem[];
   KeyT* okeys = reinterpret_cast<KeyT*>(smem);   // [tile]
   KeyT* win = okeys + tile;                      // [WIN_CAP]
@@ -178,7 +184,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       up[j] = (s & 1) != 0;
       q[j] = up[j] ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
     }
-    wave_bounds<KeyT, S>(in_keys, n_in, probe, q, up, res);
+    wave_bounds<KeyT, S>(in_keys, n_in, probe, q, up, res, BOUND_SLACK);
     if (lane < S && s0 + lane < 2 * g_lim) {
       int r = res[0];
 #pragma unroll
@@ -244,49 +250,80 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const bool act = v < rows;
   const KeyT okey = act ? okeys[v] : KeyT(0);
   const int bl = v >> 5;
+  int32_t* Mrow = M + (b0 + bl) * K3 * 32 + (v & 31);
   for (int gb = part; gb < g_lim; gb += parts * SEARCH_GB) {
-    int pos[SEARCH_GB], gidx[SEARCH_GB], wsz[SEARCH_GB], woff[SEARCH_GB];
+    // wb: LDS base of the group's window.  Groups past the limit, rows past the end and windows kept in
+    // global memory get an empty window at base 0, so that every LDS read below is unconditional and
+    // in range (index -1 is the last staged output key) and the reads of a round issue back to back.
+    int pos[SEARCH_GB], gidx[SEARCH_GB], wsz[SEARCH_GB], wb[SEARCH_GB], wlo[SEARCH_GB];
+    bool glob[SEARCH_GB];
     KeyT q0[SEARCH_GB];
     int maxw = 0;
+    bool any_glob = false;
 #pragma unroll
     for (int j = 0; j < SEARCH_GB; ++j) {
       const int g = gb + j * parts;
       gidx[j] = g < g_lim ? g : -1;
       const int gc = g < g_lim ? g : 0;
-      woff[j] = s_woff[gc];
-      wsz[j] = (g < g_lim && act) ? s_wsz[gc] : 0;
+      const int woff = s_woff[gc];
+      glob[j] = g < g_lim && woff < 0;
+      any_glob |= glob[j];
+      wb[j] = woff < 0 ? 0 : woff;
+      wsz[j] = (g < g_lim && act && woff >= 0) ? s_wsz[gc] : 0;
+      wlo[j] = s_wlo[gc];
       q0[j] = okey + s_gd[gc];
       pos[j] = 0;
-      if (g < g_lim && woff[j] >= 0) maxw = max(maxw, s_wsz[gc]);
+      if (g < g_lim && woff >= 0) maxw = max(maxw, s_wsz[gc]);
     }
     // lower bounds in LDS: pos += bit while the key before pos+bit is smaller than the query
     for (int bit = maxw > 0 ? 1 << (31 - __clz(maxw)) : 0; bit > 0; bit >>= 1) {
+      KeyT kv[SEARCH_GB];
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j) kv[j] = win[wb[j] + min(pos[j] + bit, wsz[j]) - 1];
 #pragma unroll
       for (int j = 0; j < SEARCH_GB; ++j) {
         const int p = pos[j] + bit;
-        if (woff[j] >= 0 && p <= wsz[j] && win[woff[j] + p - 1] < q0[j]) pos[j] = p;
+        pos[j] = (p <= wsz[j] && kv[j] < q0[j]) ? p : pos[j];
       }
     }
-    // global-memory windows (rare): plain per-lane lower bound
+    // the K keys from each lower bound on: the K z-consecutive queries of a group hit consecutive
+    // positions (keys are sorted integers whose z components are multiples of the input stride,
+    // Section 5.2), so query t is compared with the key h hits after the first
+    KeyT w[SEARCH_GB][K];
 #pragma unroll
     for (int j = 0; j < SEARCH_GB; ++j)
-      if (gidx[j] >= 0 && woff[j] < 0) pos[j] = lane_lower_bound<KeyT>(in_keys + s_wlo[gidx[j]], wsz[j], q0[j]);
-    // the K z-consecutive queries of each group, from the position of the smallest-z one: at most
-    // one comparison per query on consecutive positions (keys are sorted integers whose z
-    // components are multiples of the input stride, Section 5.2); the groups' reads interleave
+#pragma unroll
+      for (int i = 0; i < K; ++i) w[j][i] = win[wb[j] + min(pos[j] + i, wsz[j] - 1)];
+    if (any_glob) {  // windows that stayed in global memory (rare): per-lane lower bound, same K keys
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j)
+        if (glob[j]) {
+          wsz[j] = act ? s_wsz[gidx[j]] : 0;
+          pos[j] = lane_lower_bound<KeyT>(in_keys + wlo[j], wsz[j], q0[j]);
+#pragma unroll
+          for (int i = 0; i < K; ++i) w[j][i] = in_keys[wlo[j] + max(min(pos[j] + i, wsz[j] - 1), 0)];
+        }
+    }
     int32_t r[SEARCH_GB][K];
 #pragma unroll
-    for (int t = 0; t < K; ++t) {
+    for (int j = 0; j < SEARCH_GB; ++j) {
+      int h = 0;
 #pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j) {
-        const int g = gidx[j] < 0 ? 0 : gidx[j];
+      for (int t = 0; t < K; ++t) {
         const KeyT qt = q0[j] + KeyT(t) * sp.zstep;
-        bool hit = false;
-        if (pos[j] < wsz[j]) hit = (woff[j] >= 0 ? win[woff[j] + pos[j]] : in_keys[s_wlo[g] + pos[j]]) == qt;
-        r[j][sp.zrev ? K - 1 - t : t] = hit ? s_wlo[g] + pos[j] : -1;
-        pos[j] += hit ? 1 : 0;
+        KeyT cand = w[j][0];
+        for (int i = 1; i < K; ++i) cand = (i <= t && h == i) ? w[j][i] : cand;
+        const bool hit = pos[j] + h < wsz[j] && cand == qt;
+        r[j][sp.zrev ? K - 1 - t : t] = hit ? wlo[j] + pos[j] + h : -1;
+        h += hit ? 1 : 0;
       }
     }
+    // found positions are stored as they are, or mapped to the caller's row numbering
+    int32_t jv[SEARCH_GB][K];
+#pragma unroll
+    for (int j = 0; j < SEARCH_GB; ++j)
+#pragma unroll
+      for (int t = 0; t < K; ++t) jv[j][t] = (in_perm && r[j][t] >= 0) ? in_perm[r[j][t]] : r[j][t];
 #pragma unroll
     for (int j = 0; j < SEARCH_GB; ++j) {
       const int g = gidx[j];
@@ -295,15 +332,12 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       for (int t = 0; t < K; ++t) {
         const int k = g * K + t;
         if (k >= k_lim) continue;  // uniform
-        // found positions are stored as they are, or mapped to the caller's row numbering
-        int32_t jv = r[j][t];
-        if (in_perm && jv >= 0) jv = in_perm[jv];
-        if (v < rows32) M[((b0 + bl) * K3 + k) * 32 + (v & 31)] = jv;  // rows past the end hold -1
+        if (v < rows32) Mrow[k * 32] = jv[j][t];  // rows past the end hold -1
         const unsigned long long hit = __ballot(r[j][t] >= 0);
-        if (hit) {
-          if (lane == 0 && unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
-          if (lane == 32 && unsigned(hit >> 32)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
-          if (tile_counts && lane == 0) atomicAdd(&s_cnt[k], __popcll(hit));
+        if (hit && lane == 0) {  // lane 0 speaks for the wave's two 32-row blocks
+          if (unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
+          if (unsigned(hit >> 32)) atomicOr(&s_mask[(bl + 1) * MW + (k >> 5)], 1u << (k & 31));
+          if (tile_counts) atomicAdd(&s_cnt[k], __popcll(hit));
         }
       }
     }
