@@ -318,12 +318,26 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
         h += hit ? 1 : 0;
       }
     }
-    // found positions are stored as they are, or mapped to the caller's row numbering
+    // found positions are stored as they are, or mapped to the caller's row numbering.  The
+    // lookups are unconditional (misses read entry 0) and all issued before the first store: on this
+    // target loads and stores share one counter, so a load waited for between two stores would
+    // also wait for every store before it.
     int32_t jv[SEARCH_GB][K];
+    if (in_perm && n_in > 0) {
 #pragma unroll
-    for (int j = 0; j < SEARCH_GB; ++j)
+      for (int j = 0; j < SEARCH_GB; ++j)
 #pragma unroll
-      for (int t = 0; t < K; ++t) jv[j][t] = (in_perm && r[j][t] >= 0) ? in_perm[r[j][t]] : r[j][t];
+        for (int t = 0; t < K; ++t) jv[j][t] = in_perm[max(r[j][t], 0)];
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j)
+#pragma unroll
+        for (int t = 0; t < K; ++t) jv[j][t] = r[j][t] < 0 ? -1 : jv[j][t];
+    } else {
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j)
+#pragma unroll
+        for (int t = 0; t < K; ++t) jv[j][t] = r[j][t];
+    }
 #pragma unroll
     for (int j = 0; j < SEARCH_GB; ++j) {
       const int g = gidx[j];
