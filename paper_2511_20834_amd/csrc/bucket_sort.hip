@@ -42,22 +42,42 @@ __device__ inline int bs_bin(uint64_t key, int shift, int n_bin) {
 }
 
 // ---------------------------------------------------------------- key sources
+// A source splits "fetch" from "make the key": the kernels below fetch a batch of rows first and
+// only then compute, so that the batch's loads are in flight together.
 template <typename KeyT>
 struct SrcPack {
   const int4* coords;
   PackParams p;
   int32_t* status;
-  __device__ KeyT operator()(int64_t i) const { return pack_key<KeyT>(coords[i], p, status); }
-  __device__ bool skip(int64_t, KeyT) const { return false; }
+  struct Raw {
+    int4 c;
+  };
+  __device__ Raw load(int64_t i) const { return Raw{coords[i]}; }
+  __device__ static void pin(Raw& r) { SPC_PIN_LOADED(r.c.x); }
+  __device__ KeyT key(const Raw& r, bool& bad) const { return pack_key_flag<KeyT>(r.c, p, bad); }
+  __device__ bool skip(const Raw&, KeyT) const { return false; }
+  __device__ void report(bool bad) const {
+    if (bad && status) atomicOr(status, 1);
+  }
 };
 template <typename KeyT>
 struct SrcMask {
   const KeyT* keys;
   KeyT mask;
-  __device__ KeyT operator()(int64_t i) const { return keys[i] & mask; }
+  struct Raw {
+    KeyT cur, prev;
+    bool has_prev;
+  };
+  __device__ Raw load(int64_t i) const { return Raw{keys[i], keys[i > 0 ? i - 1 : 0], i > 0}; }
+  __device__ static void pin(Raw& r) {
+    SPC_PIN_LOADED(r.cur);
+    SPC_PIN_LOADED(r.prev);
+  }
+  __device__ KeyT key(const Raw& r, bool&) const { return r.cur & mask; }
   // The finer level is sorted, so runs along z collapse to runs of equal masked keys: only the
   // first key of a run takes part (the result is the set of distinct keys either way).
-  __device__ bool skip(int64_t i, KeyT key) const { return i > 0 && (keys[i - 1] & mask) == key; }
+  __device__ bool skip(const Raw& r, KeyT key) const { return r.has_prev && (r.prev & mask) == key; }
+  __device__ void report(bool) const {}
 };
 
 // ---------------------------------------------------------------- count
@@ -68,22 +88,26 @@ __global__ __launch_bounds__(BS_WIDE) void bs_count_kernel(Src src, int64_t n, i
   for (int b = threadIdx.x; b < n_bin; b += BS_WIDE) hist[b] = 0;
   __syncthreads();
   const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
-  // four keys per thread and pass: their loads are in flight together
+  bool bad = false;
+  // four rows per thread and pass, fetched before any of them is turned into a key
   for (int64_t i0 = lo + threadIdx.x; i0 < hi; i0 += 4 * BS_WIDE) {
-    KeyT key[4];
-    bool use[4];
+    typename Src::Raw raw[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) raw[u] = src.load(min<int64_t>(i0 + u * BS_WIDE, hi - 1));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) Src::pin(raw[u]);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t i = min<int64_t>(i0 + u * BS_WIDE, hi - 1);
-      key[u] = src(i);
-      use[u] = i0 + u * BS_WIDE < hi && !src.skip(i, key[u]);
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (i0 + u * BS_WIDE < hi) keys0[i0 + u * BS_WIDE] = key[u];
-      if (use[u]) atomicAdd(&hist[bs_bin(key[u], shift, n_bin)], 1);
+      bool bad_u = false;
+      const KeyT key = src.key(raw[u], bad_u);
+      if (i0 + u * BS_WIDE < hi) {
+        bad |= bad_u;
+        keys0[i0 + u * BS_WIDE] = key;
+        if (!src.skip(raw[u], key)) atomicAdd(&hist[bs_bin(key, shift, n_bin)], 1);
+      }
     }
   }
+  src.report(bad);
   __syncthreads();
   for (int b = threadIdx.x; b < n_bin; b += BS_WIDE) table[int64_t(blockIdx.x) * n_bin + b] = hist[b];
 }
@@ -170,20 +194,30 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
   __syncthreads();
   const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
   for (int64_t i0 = lo + threadIdx.x; i0 < hi; i0 += 4 * BS_WIDE) {
-    KeyT key[4];
+    // all keys of the pass are fetched, then all positions drawn, then everything stored
+    KeyT key[4], prev[4];
     bool use[4];
+    int p[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t i = min<int64_t>(i0 + u * BS_WIDE, hi - 1);
       key[u] = keys0[i];
-      use[u] = i0 + u * BS_WIDE < hi && !(DEDUP && i > 0 && keys0[i - 1] == key[u]);
+      prev[u] = DEDUP ? keys0[i > 0 ? i - 1 : 0] : KeyT(0);
     }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      SPC_PIN_LOADED(key[u]);
+      if (DEDUP) SPC_PIN_LOADED(prev[u]);
+      const int64_t i = min<int64_t>(i0 + u * BS_WIDE, hi - 1);
+      use[u] = i0 + u * BS_WIDE < hi && !(DEDUP && i > 0 && prev[u] == key[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) p[u] = use[u] ? atomicAdd(&pos[bs_bin(key[u], shift, n_bin)], 1) : 0;
 #pragma unroll
     for (int u = 0; u < 4; ++u)
       if (use[u]) {
-        const int p = atomicAdd(&pos[bs_bin(key[u], shift, n_bin)], 1);
-        keys1[p] = key[u];
-        vals1[p] = static_cast<int32_t>(i0 + u * BS_WIDE);
+        keys1[p[u]] = key[u];
+        vals1[p[u]] = static_cast<int32_t>(i0 + u * BS_WIDE);
       }
   }
 }

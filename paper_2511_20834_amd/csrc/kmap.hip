@@ -55,13 +55,12 @@ __device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, KeyT pr
   const int lane = threadIdx.x & 63;
   int lo[S], hi[S];
   const int chunk0 = (n + 63) >> 6;
-  const int n_chunks0 = chunk0 > 0 ? (n + chunk0 - 1) / chunk0 : 0;
 #pragma unroll
   for (int s = 0; s < S; ++s) {
     // lanes past the last slice hold no probe; their predicate is false
-    const bool pr = lane < n_chunks0 && (upper[s] ? (probe <= q[s]) : (probe < q[s]));
+    const bool pr = (long long)lane * chunk0 < n && (upper[s] ? (probe <= q[s]) : (probe < q[s]));
     const int c = __popcll(__ballot(pr));
-    if (n == 0 || c >= n_chunks0) {
+    if ((long long)c * chunk0 >= n) {  // every slice lies before the answer (or there are no keys)
       lo[s] = n;
       hi[s] = n;
     } else {
@@ -93,9 +92,8 @@ __device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, KeyT pr
       const int len = hi[s] - lo[s];
       if (len > 0) {
         const int c = __popcll(__ballot(pred[s]));
-        const int n_chunks = (len + chunk[s] - 1) / chunk[s];
         const int nlo = lo[s] + c * chunk[s];
-        if (c >= n_chunks) {
+        if (c * chunk[s] >= len) {  // every slice lies before the answer
           lo[s] = hi[s];
         } else {
           hi[s] = min(nlo + chunk[s] - 1, hi[s] - 1);

@@ -79,17 +79,30 @@ struct PackParams {
 
 #ifdef __HIPCC__
 // Key of one (b,x,y,z) row.  A field that does not fit (guard band on both sides included)
-// gives the all-ones key and raises bit 0 of *status (when status is not NULL).
+// gives the all-ones key and sets `bad`.
 template <typename KeyT>
-__device__ inline KeyT pack_key(const int4 c, const PackParams& p, int32_t* status) {
+__device__ inline KeyT pack_key_flag(const int4 c, const PackParams& p, bool& bad) {
   const int64_t fx = int64_t(c.y) - p.ox, fy = int64_t(c.z) - p.oy, fz = int64_t(c.w) - p.oz;
   const bool ok = c.x >= 0 && (int64_t(c.x) < (int64_t(1) << p.bits_b)) && fx >= 0 && fy >= 0 && fz >= 0 &&
                   fx + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_x) && fy + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_y) &&
                   fz + 2 * int64_t(p.pad) < (int64_t(1) << p.bits_z);
-  if (ok) return (KeyT(c.x) << p.sh_b) | (KeyT(fx + p.pad) << p.sh_x) | (KeyT(fy + p.pad) << p.sh_y) | KeyT(fz + p.pad);
-  if (status) atomicOr(status, 1);
-  return ~KeyT(0);
+  bad |= !ok;
+  return ok ? (KeyT(c.x) << p.sh_b) | (KeyT(fx + p.pad) << p.sh_x) | (KeyT(fy + p.pad) << p.sh_y) | KeyT(fz + p.pad)
+            : ~KeyT(0);
 }
+// Same, raising bit 0 of *status (when status is not NULL) for a rejected row.
+template <typename KeyT>
+__device__ inline KeyT pack_key(const int4 c, const PackParams& p, int32_t* status) {
+  bool bad = false;
+  const KeyT k = pack_key_flag<KeyT>(c, p, bad);
+  if (bad && status) atomicOr(status, 1);
+  return k;
+}
+// Pins a loaded value in a vector register at this point of the program (used after a whole
+// batch of loads has been issued): the compiler can then neither sink the loads into later
+// branches nor spread them between other memory operations.  Loads and stores share one completion counter on this target, so a load
+// that is waited for between stores also waits for every store issued before it.
+#define SPC_PIN_LOADED(x) asm volatile("" : "+v"(x))
 #endif
 
 // ---------------------------------------------------------------- bucket sort (own kernels)
