@@ -150,7 +150,7 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
                                                              int n_bin, const int32_t* __restrict__ before,
                                                              const int32_t* __restrict__ tot, int target, int n_bucket,
                                                              KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
-                                                             int32_t* __restrict__ bstart) {
+                                                             int32_t* __restrict__ bstart, int2* __restrict__ win) {
   __shared__ int pos[BS_MAX_BIN + 1];  // bin starts, then this workgroup's running position in every bin
   __shared__ int wave_tot[BS_WIDE / 64];
   static_assert(BS_MAX_BIN == 4 * BS_WIDE, "one int4 of bins per thread");
@@ -175,7 +175,28 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
     total += wave_tot[w];
   }
   const int4 st = make_int4(base, base + c.x, base + c.x + c.y, base + c.x + c.y + c.z);
-  if (blockIdx.x == 0) {
+  if (!DEDUP) {
+    // Rank windows (see bs_rank_kernel): part p = scattered positions [p * BS_PART, ...) is ranked
+    // inside the range of whole bins that covers it.  Parts are dealt round-robin to the workgroups,
+    // one per thread: two binary searches over the bin starts in LDS.
+    if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = st;
+    if (t == 0) pos[n_bin] = total;
+    __syncthreads();
+    if (blockIdx.x == 0 && t < BS_PAD_KEYS) keys1[total + t] = ~KeyT(0);  // the rank kernel reads whole steps
+    const int part = blockIdx.x + t * gridDim.x;
+    if (int64_t(part) * BS_PART < total) {
+      const int x0 = part * BS_PART, x1 = min(x0 + BS_PART, total) - 1;
+      // last bin whose start is <= x: the (non-empty) bin that holds position x
+      auto bin_of = [&](int x) {
+        int f = 0;
+        for (int step = n_bin >> 1; step > 0; step >>= 1)
+          if (pos[f + step] <= x) f += step;
+        return f;
+      };
+      win[part] = make_int2(pos[bin_of(x0)], pos[bin_of(x1) + 1]);
+    }
+    __syncthreads();
+  } else if (blockIdx.x == 0) {
     if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = st;
     if (t == 0) pos[n_bin] = total;
     __syncthreads();
@@ -389,6 +410,125 @@ __device__ inline void bs_bitonic(const Acc& a, int m) {
   }
 }
 
+// ---------------------------------------------------------------- rank (pack + sort path)
+// After the scatter the keys are ordered by bin, unordered inside a bin.  Workgroup p takes the
+// BS_PART = 64 keys at scattered positions [p * BS_PART, ...), one per lane, each of its four waves
+// a quarter of the comparisons, and ranks each of them inside the window of whole bins that covers those positions (widened to multiples of 32
+// positions): every key before the window is smaller and every key behind it larger, so
+// window start + (number of window keys that sort before mine) is the key's final position.
+// "Sorts before" is (key, scattered position) order, which makes the positions of equal keys
+// distinct without any atomics; below and above the workgroup's own 64 positions that is a plain
+// <= resp. < on the key.  Every lane of a wave compares its key with the same window key at the same
+// time, so the window is read with scalar loads (128 bytes per step, the next step's load in
+// flight while the current one is compared) and a comparison is two vector instructions with a
+// scalar operand; LDS only carries the four partial counts of a key to the wave that stores.  (Reading the window back from LDS at a wave-uniform address
+// was measured four times slower: 16-byte LDS reads of one address by all lanes are not broadcast.)
+// Work per key grows with the window, i.e. with the size of the bins involved, but a big bin is
+// shared by as many workgroups as it has parts: no workgroup sorts a dense region of the scene
+// alone, which is what bounded the compare-exchange network this replaces on the pack + sort path.
+// The scatter leaves BS_RANK_STEP all-ones keys behind the last key, so that whole steps can be
+// read at the end of the array.
+constexpr int BS_RANK_STEP = BS_PAD_KEYS;  // positions; a window is a whole number of steps
+// 128 bytes of keys at a wave-uniform address in scalar registers.  The load is issued by hand and
+// its arrival awaited by hand, one compare step later: left to the compiler, the load of a step
+// ends up right in front of its first use and every step pays the scalar-memory latency.
+typedef uint32_t bs_u32x16 __attribute__((ext_vector_type(16)));
+struct BsChunk {
+  bs_u32x16 lo, hi;
+  __device__ void issue(const void* p) {
+    asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx16 %1, %2, 0x40" : "=&s"(lo), "=&s"(hi) : "s"(p) : "memory");
+  }
+  // the counters are operands only to keep the compare step that runs under the load in front of the wait
+  __device__ void arrive(int (&c)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(lo), "+s"(hi), "+v"(c[0]), "+v"(c[1]), "+v"(c[2]), "+v"(c[3]));
+  }
+  template <typename KeyT>
+  __device__ KeyT key(int q) const {  // q-th key of the chunk, q a compile-time constant after unrolling
+    if constexpr (sizeof(KeyT) == 4) return q < 16 ? lo[q] : hi[q - 16];
+    else return q < 8 ? (uint64_t(lo[2 * q + 1]) << 32) | lo[2 * q] : (uint64_t(hi[2 * q - 15]) << 32) | hi[2 * q - 16];
+  }
+};
+
+// keys k[a, b) that sort before (key, x): MODE 0 for positions below the workgroup's own 64 (equal
+// keys count), 2 for positions above (they do not), 1 for the own positions (full comparison).
+// a and b are multiples of BS_RANK_STEP.
+template <int MODE, typename KeyT>
+__device__ inline int bs_count_before(const KeyT* __restrict__ k, int a, int b, KeyT key, int x) {
+  constexpr int C = 128 / sizeof(KeyT);  // keys per chunk
+  static_assert(BS_RANK_STEP % C == 0, "a step of positions is a whole number of chunks");
+  int c[4] = {0, 0, 0, 0};
+  if (a >= b) return 0;
+  auto compare = [&](const BsChunk& ch, int j) {
+#pragma unroll
+    for (int q = 0; q < C; ++q) {
+      const KeyT e = ch.template key<KeyT>(q);
+      bool before;
+      if (MODE == 0) before = e <= key;
+      else if (MODE == 2) before = e < key;
+      else before = e < key || (e == key && j + q < x);
+      c[q & 3] += before ? 1 : 0;
+    }
+  };
+  BsChunk A, B;
+  A.issue(k + a);
+  A.arrive(c);
+  for (int j = a; j < b; j += 2 * C) {  // the last chunk is fetched once more instead of running past b
+    B.issue(k + min(j + C, b - C));
+    compare(A, j);
+    B.arrive(c);
+    if (j + C < b) {
+      A.issue(k + min(j + 2 * C, b - C));
+      compare(B, j + C);
+      A.arrive(c);
+    }
+  }
+  return (c[0] + c[1]) + (c[2] + c[3]);
+}
+
+template <typename KeyT>
+__global__ __launch_bounds__(BS_THREADS) void bs_rank_kernel(const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
+                                                             const int2* __restrict__ win, int n, KeyT* __restrict__ out_k,
+                                                             int32_t* __restrict__ out_v) {
+  constexpr int WAVES = BS_THREADS / 64;
+  static_assert(BS_PART == 64, "one key per lane");
+  __shared__ int partial[WAVES][BS_PART];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+  const int own0 = blockIdx.x * BS_PART;
+  const int x = own0 + lane;
+  const bool act = x < n;
+  const int2 w = win[blockIdx.x];
+  const KeyT key = act ? keys1[x] : ~KeyT(0);
+  const int32_t val = (act && out_v && wave == 0) ? vals1[x] : 0;
+  const int n_pad = (n + BS_RANK_STEP - 1) & ~(BS_RANK_STEP - 1);  // positions n .. n_pad - 1 hold all-ones keys
+  const int g0 = w.x & ~(BS_RANK_STEP - 1);
+  const int g1 = min(max((w.y + BS_RANK_STEP - 1) & ~(BS_RANK_STEP - 1), own0 + BS_PART), n_pad);
+  // the window is cut into the part below the own positions, the own positions and the part above;
+  // each is shared out among the waves in contiguous quarters (rounded to whole steps)
+  const int own1 = min(own0 + BS_PART, g1);
+  auto quarter = [&](int a, int b, int& qa, int& qb) {
+    const int steps = (b - a) / BS_RANK_STEP, per = (steps + WAVES - 1) / WAVES;
+    qa = min(a + wave * per * BS_RANK_STEP, b);
+    qb = min(qa + per * BS_RANK_STEP, b);
+  };
+  int qa, qb;
+  quarter(g0, own0, qa, qb);
+  int c = bs_count_before<0>(keys1, qa, qb, key, x);
+  quarter(own0, own1, qa, qb);
+  c += bs_count_before<1>(keys1, qa, qb, key, x);
+  quarter(own1, g1, qa, qb);
+  c += bs_count_before<2>(keys1, qa, qb, key, x);
+  partial[wave][lane] = c;
+  __syncthreads();
+  if (wave == 0 && act) {
+    int r = g0;
+#pragma unroll
+    for (int v = 0; v < WAVES; ++v) r += partial[v][lane];
+    out_k[r] = key;
+    if (out_v) out_v[r] = val;
+  }
+}
+
 // One workgroup per bucket.  UNIQUE: out_k receives the bucket's distinct keys at the start
 // of its range and ucount[bucket] their number; otherwise out_k/out_v the sorted pairs.
 // In LDS only the keys are sorted (min/max steps); afterwards every (key, index) pair looks its
@@ -552,8 +692,8 @@ BucketPlan bucket_plan(int64_t n, int used_bits) {
 
 size_t bucket_sort_ws_bytes(int key_bits, int64_t n) {
   const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
-  const size_t k = (nn * (key_bits / 8) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
-  return 2 * k + v + (2 * size_t(BS_MAX_WG) * BS_MAX_BIN + BS_MAX_BIN + 64 + 2 * (size_t(BS_MAX_BUCKET) + 64)) * 4;
+  const size_t k = ((nn + BS_PAD_KEYS) * (key_bits / 8) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
+  return 2 * k + v + (2 * size_t(BS_MAX_WG) * BS_MAX_BIN + BS_MAX_BIN + 64 + 2 * (size_t(BS_MAX_BUCKET) + 64) + 2 * BS_MAX_PART) * 4;
 }
 
 namespace {
@@ -567,11 +707,12 @@ struct Ws {
   int32_t* fstart;
   int32_t* bstart;
   int32_t* ucount;
+  int2* win;
 };
 template <typename KeyT>
 Ws<KeyT> carve(void* ws, int64_t n) {
   const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
-  const size_t k = (nn * sizeof(KeyT) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
+  const size_t k = ((nn + BS_PAD_KEYS) * sizeof(KeyT) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
   char* c = static_cast<char*>(ws);
   Ws<KeyT> w;
   w.keys0 = reinterpret_cast<KeyT*>(c);
@@ -582,6 +723,7 @@ Ws<KeyT> carve(void* ws, int64_t n) {
   w.fstart = w.before + size_t(BS_MAX_WG) * BS_MAX_BIN;
   w.bstart = w.fstart + BS_MAX_BIN + 64;
   w.ucount = w.bstart + BS_MAX_BUCKET + 64;
+  w.win = reinterpret_cast<int2*>(w.ucount + BS_MAX_BUCKET + 64);  // 8-byte aligned: every part above is a multiple of 256 bytes
   return w;
 }
 
@@ -594,7 +736,7 @@ void partition(const Src& src, int64_t n, const BucketPlan& p, const Ws<KeyT>& w
   const int col_wg = (p.n_bin / 4 + BS_COL_THREADS - 1) / BS_COL_THREADS;
   hipLaunchKernelGGL(bs_colscan_kernel, dim3(col_wg), dim3(BS_COL_THREADS), 0, s, w.table, w.before, p.n_wg, p.n_bin, w.fstart);
   hipLaunchKernelGGL((bs_scatter_kernel<KeyT, DEDUP>), dim3(p.n_wg), dim3(BS_WIDE), 0, s, w.keys0, n, p.per, p.shift, p.n_bin, w.before,
-                     w.fstart, p.target, p.n_bucket, w.keys1, w.vals1, w.bstart);
+                     w.fstart, p.target, p.n_bucket, w.keys1, w.vals1, w.bstart, w.win);
 }
 }  // namespace
 
@@ -604,8 +746,9 @@ static int pack_sort_t(const int4* coords, int64_t n, const PackParams& pp, int 
   const BucketPlan p = bucket_plan(n, used_bits);
   const Ws<KeyT> w = carve<KeyT>(ws, n);
   partition<KeyT, false>(SrcPack<KeyT>{coords, pp, status}, n, p, w, s);
-  hipLaunchKernelGGL((bs_sort_kernel<KeyT, false>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart,
-                     static_cast<KeyT*>(keys_out), perm_out, static_cast<int32_t*>(nullptr));
+  const int n_part = static_cast<int>((n + BS_PART - 1) / BS_PART);
+  hipLaunchKernelGGL(bs_rank_kernel<KeyT>, dim3(n_part), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.win, static_cast<int>(n),
+                     static_cast<KeyT*>(keys_out), perm_out);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "sort launch failed");
   return SPC_OK;
 }

@@ -112,6 +112,9 @@ constexpr int BS_MAX_BIN = 1 << BS_MAX_BIN_BITS;  // fine bins (top used key bit
 constexpr int BS_TARGET = 512;      // keys per bucket aimed at
 constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 512 * 1024;  // sizes it is used for; rocPRIM outside
 constexpr int BS_MAX_BUCKET = static_cast<int>(BS_MAX_N / BS_TARGET);
+constexpr int BS_PART = 64;         // keys per rank workgroup
+constexpr int BS_MAX_PART = static_cast<int>(BS_MAX_N / BS_PART);
+constexpr int BS_PAD_KEYS = 32;     // all-ones keys kept behind the scattered keys
 struct BucketPlan {
   int n_wg, per, shift, n_bin, target, n_bucket;
 };
