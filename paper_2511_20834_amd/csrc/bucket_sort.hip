@@ -1,6 +1,6 @@
 // Sort of packed voxel keys for the cloud sizes of this workload (thousands to about half a
-// million keys): one most-significant-digit split, then every bucket is sorted inside LDS by
-// one workgroup.  Four short launches, no look-back spinning, no global atomics:
+// million keys): one most-significant-digit split into fine bins, then ranking (pack + sort) or a
+// per-bucket network sort (downsampling).  Short launches, no look-back spinning, no global atomics:
 //
 //   count    each workgroup produces its share of the keys (packing coordinates, Section 5.3,
 //            or masking the keys of a finer level, Section 5.5), histograms the top `fb` used
@@ -8,24 +8,29 @@
 //   colscan  exclusive prefixes down the table's columns: where a workgroup's keys of a bin go
 //            inside the bin, and the bin totals;
 //   scatter  each workgroup scans the bin totals (where every bin starts) and moves its keys,
-//            with their source index, to their bin's range; workgroup 0 also cuts the bin
-//            sequence into buckets of about BS_TARGET keys: the buckets adapt to the key
-//            distribution (a LiDAR sweep is many times denser near the sensor), so the sort
-//            workgroups get equal work;
-//   sort     one workgroup per bucket: bitonic network over the keys in LDS (min/max steps,
-//            three compare distances per pass: a thread holds the 8 keys those distances
-//            connect; distances below 512 run inside the waves without barriers), then every
-//            (key, index) pair finds its key in the sorted tile.  With variant UNIQUE the
-//            bucket's distinct keys are counted and left at the start of the bucket's range
-//            (the caller compacts the ranges with `gather`).
+//            with their source index, to their bin's range.  Pack + sort: the workgroups also
+//            write, for every 64 scattered positions, the window of whole bins that covers them.
+//            Downsampling: workgroup 0 cuts the bin sequence into buckets of about BS_TARGET
+//            keys (the buckets adapt to the key distribution: a LiDAR sweep is many times denser
+//            near the sensor);
+//   rank     (pack + sort) 64 keys per workgroup; a key's final position is the start of its
+//            window plus the number of window keys that sort before it, counted by comparing
+//            against every window key (see bs_rank_kernel).  Quadratic in the bin size, but
+//            spread evenly over the chip whatever the key distribution;
+//   unique   (downsampling) one workgroup per bucket: bitonic network over the keys in LDS
+//            (min/max steps, three compare distances per pass: a thread holds the 8 keys those
+//            distances connect; distances below 512 run inside the waves without barriers);
+//            the bucket's distinct keys are counted and left at the start of the bucket's range;
+//   gather   (downsampling) compacts the buckets' distinct keys.
 //
-// x is the most significant spatial field, so a bucket is a slab of the scene.  A single bin
-// that outgrows the LDS tile (a dense slab) is sorted straight in global memory by the
-// all-ascending form of the network (first step of every merge compares mirrored positions),
-// which sorts any length when the missing tail is taken as +infinity: comparators that touch
-// the tail are skipped.  Correct for any input, slow only for degenerate ones.
-// Comparing (key, source index) pairs makes the result the stable order, independent of how
-// the scatter raced.
+// x is the most significant spatial field, so a bin is a slab of the scene.  In the downsampling
+// path a single bin that outgrows the LDS tile (a dense slab) is sorted straight in global memory
+// by the all-ascending form of the network (first step of every merge compares mirrored
+// positions), which sorts any length when the missing tail is taken as +infinity: comparators
+// that touch the tail are skipped.  Correct for any input, slow only for degenerate ones.
+// The rank kernel orders (key, scattered position) pairs, so equal keys (not a valid cloud, but
+// not rejected unless validation was asked for) still get distinct positions and the permutation
+// is complete whatever the input.
 #include <algorithm>
 
 #include "spc_internal.h"
@@ -529,105 +534,66 @@ __global__ __launch_bounds__(BS_THREADS) void bs_rank_kernel(const KeyT* __restr
   }
 }
 
-// One workgroup per bucket.  UNIQUE: out_k receives the bucket's distinct keys at the start
-// of its range and ucount[bucket] their number; otherwise out_k/out_v the sorted pairs.
-// In LDS only the keys are sorted (min/max steps); afterwards every (key, index) pair looks its
-// key up in the sorted tile and drops its index there.  Equal keys (not a valid cloud, but not
-// rejected unless validation was asked for) share out the positions of their run through a
-// counter, so the permutation is complete whatever the input.
-template <typename KeyT, bool UNIQUE>
-__global__ __launch_bounds__(BS_THREADS) void bs_sort_kernel(KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
-                                                             const int32_t* __restrict__ bstart, KeyT* __restrict__ out_k,
-                                                             int32_t* __restrict__ out_v, int32_t* __restrict__ ucount) {
+// Downsampling path: one workgroup per bucket sorts the bucket's keys with the network above and
+// leaves its distinct keys at the start of the bucket's range of out_k, their number in
+// ucount[bucket].  A bucket that outgrows the LDS tile is sorted in global memory (vals1 travels
+// along as the network's second field and is otherwise unused).
+template <typename KeyT>
+__global__ __launch_bounds__(BS_THREADS) void bs_unique_kernel(KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
+                                                               const int32_t* __restrict__ bstart, KeyT* __restrict__ out_k,
+                                                               int32_t* __restrict__ ucount) {
   constexpr int CAP = BS_CAP;
   constexpr int EPT = CAP / BS_THREADS;
   __shared__ KeyT tile[CAP + CAP / 32];
-  __shared__ int dup[UNIQUE ? 1 : CAP];  // per position: how many pairs of an equal-key run have been placed
   __shared__ int wave_tot[BS_THREADS / 64];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int s = bstart[blockIdx.x], m = bstart[blockIdx.x + 1] - s;
   if (m <= 0) {
-    if (UNIQUE && t == 0) ucount[blockIdx.x] = 0;
+    if (t == 0) ucount[blockIdx.x] = 0;
     return;
   }
   const bool in_lds = m <= CAP;
-  const bool place = !UNIQUE && out_v != nullptr;
   if (in_lds) {
     int lp = 0;
     while ((1 << lp) < m) ++lp;
     const int P = 1 << lp;
-    // the thread's pairs stay in registers: all their loads are in flight together, and the
-    // placement below needs them again
-    KeyT key[EPT];
-    int32_t val[EPT];
+    KeyT key[EPT];  // all loads of the thread in flight together
 #pragma unroll
     for (int r = 0; r < EPT; ++r) {
       const int i = r * BS_THREADS + t;
       key[r] = i < m ? keys1[s + i] : ~KeyT(0);
-      val[r] = (place && i < m) ? vals1[s + i] : 0;
     }
 #pragma unroll
     for (int r = 0; r < EPT; ++r) {
       const int i = r * BS_THREADS + t;
-      if (i < P) {
-        tile[bs_at(i)] = key[r];
-        if (!UNIQUE) dup[i] = 0;
-      }
+      if (i < P) tile[bs_at(i)] = key[r];
     }
     __syncthreads();
     bs_lds_bitonic(tile, lp);
-    if (place) {
-      // lower bound of every pair's key in the sorted tile (the padding compares as the largest key);
-      // four searches per thread run interleaved, their LDS reads overlap
-#pragma unroll
-      for (int r0 = 0; r0 < EPT; r0 += 4) {
-        if (r0 * BS_THREADS < m) {  // uniform
-          int pos[4] = {0, 0, 0, 0};
-          for (int step = P >> 1; step > 0; step >>= 1) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-              if (tile[bs_at(pos[u] + step - 1)] < key[r0 + u]) pos[u] += step;
-          }
-#pragma unroll
-          for (int u = 0; u < 4; ++u)
-            if ((r0 + u) * BS_THREADS + t < m) {
-              int q = pos[u];
-              if (q + 1 < m && tile[bs_at(q + 1)] == key[r0 + u]) q += atomicAdd(&dup[q], 1);
-              out_v[s + q] = val[r0 + u];
-            }
-        }
-      }
-    }
   } else {
     bs_bitonic(GlobalRange<KeyT>{keys1 + s, vals1 + s}, m);
-    if (place)
-      for (int i = t; i < m; i += BS_THREADS) out_v[s + i] = vals1[s + i];
   }
   auto key_at = [&](int i) -> KeyT { return in_lds ? tile[bs_at(i)] : keys1[s + i]; };
-  if (!UNIQUE) {
-    for (int i = t; i < m; i += BS_THREADS) out_k[s + i] = key_at(i);
-  } else {
-    // heads of runs of equal keys, compacted in order (positions are visited in array order)
-    int run = 0;
-    for (int i0 = 0; i0 < m; i0 += BS_THREADS) {
-      const int i = i0 + t;
-      const bool head = i < m && (i == 0 || key_at(i) != key_at(i - 1));
-      const KeyT kv = i < m ? key_at(i) : KeyT(0);
-      const unsigned long long bal = __ballot(head);
-      if (lane == 0) wave_tot[wave] = __popcll(bal);
-      __syncthreads();
-      int base = run, tot = 0;
-      for (int w = 0; w < BS_THREADS / 64; ++w) {
-        if (w < wave) base += wave_tot[w];
-        tot += wave_tot[w];
-      }
-      // out_k is a different buffer from keys1, so positions still to be read are not overwritten
-      if (head) out_k[s + base + __popcll(bal & ((1ull << lane) - 1ull))] = kv;
-      run += tot;
-      __syncthreads();
+  // heads of runs of equal keys, compacted in order (positions are visited in array order)
+  int run = 0;
+  for (int i0 = 0; i0 < m; i0 += BS_THREADS) {
+    const int i = i0 + t;
+    const bool head = i < m && (i == 0 || key_at(i) != key_at(i - 1));
+    const KeyT kv = i < m ? key_at(i) : KeyT(0);
+    const unsigned long long bal = __ballot(head);
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int base = run, tot = 0;
+    for (int w = 0; w < BS_THREADS / 64; ++w) {
+      if (w < wave) base += wave_tot[w];
+      tot += wave_tot[w];
     }
-    if (t == 0) ucount[blockIdx.x] = run;
+    // out_k is a different buffer from keys1, so positions still to be read are not overwritten
+    if (head) out_k[s + base + __popcll(bal & ((1ull << lane) - 1ull))] = kv;
+    run += tot;
+    __syncthreads();
   }
+  if (t == 0) ucount[blockIdx.x] = run;
 }
 
 // Compacts the buckets' unique keys: out[prefix(ucount)[b] + i] = in[bstart[b] + i]; total to *n_out.
@@ -766,8 +732,7 @@ static int mask_unique_t(const void* keys_in, int64_t n, uint64_t mask, int used
   const Ws<KeyT> w = carve<KeyT>(ws, n);
   partition<KeyT, true>(SrcMask<KeyT>{static_cast<const KeyT*>(keys_in), static_cast<KeyT>(mask)}, n, p, w, s);
   // distinct keys of every bucket land at the start of its range in keys0 (free again by now)
-  hipLaunchKernelGGL((bs_sort_kernel<KeyT, true>), dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, w.keys0,
-                     static_cast<int32_t*>(nullptr), w.ucount);
+  hipLaunchKernelGGL(bs_unique_kernel<KeyT>, dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, w.keys0, w.ucount);
   hipLaunchKernelGGL(bs_gather_kernel<KeyT>, dim3(std::min(p.n_bucket, 256)), dim3(BS_THREADS), 0, s, w.keys0, w.bstart, w.ucount,
                      p.n_bucket, static_cast<KeyT*>(keys_out), n_out);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "downsample launch failed");

@@ -120,10 +120,10 @@ struct BucketPlan {
 };
 BucketPlan bucket_plan(int64_t n, int used_bits);
 size_t bucket_sort_ws_bytes(int key_bits, int64_t n);
-// coords -> sorted keys (+ permutation); enqueues three kernels
+// coords -> sorted keys (+ permutation); enqueues four kernels (count, colscan, scatter, rank)
 int bucket_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int used_bits, int32_t* status,
                      void* keys_out, int32_t* perm_out, void* ws, hipStream_t s);
-// sorted distinct values of keys_in & mask, count to *n_out [device]; enqueues four kernels
+// sorted distinct values of keys_in & mask, count to *n_out [device]; enqueues five kernels
 int bucket_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, int used_bits, void* keys_out,
                        int32_t* n_out, void* ws, hipStream_t s);
 
