@@ -85,6 +85,27 @@ def test_pack_sort_matches_oracle(name, key_bits):
     assert np.array_equal(perm.cpu().numpy().astype(np.int64), operm)
 
 
+@pytest.mark.parametrize("key_bits", [0, 64])
+def test_pack_sort_repeated_voxels_still_give_a_permutation(key_bits):
+    """Repeated voxels are not a valid cloud, but unless validation is asked for they are sorted like any
+    other input: the keys come out in order and the permutation is complete (runs of equal keys longer
+    than a rank workgroup's 64 positions, across several of them, and a run of three)."""
+    base = synth.random_cloud(9000, (120, 90, 40), seed=81)
+    rng = np.random.default_rng(82)
+    c = np.concatenate([base, np.repeat(base[100:101], 700, axis=0), np.repeat(base[4000:4001], 2, axis=0),
+                        base[rng.integers(0, len(base), 1500)]])
+    rng.shuffle(c, axis=0)
+    desc = fit_desc(c, [(3, 1, 1)], key_bits)
+    keys, perm = gpu_pack(c, desc)
+    k_ref, bad = oracle.pack_keys(c, desc.bits_b, desc.bits_x, desc.bits_y, desc.bits_z, list(desc.origin), desc.pad)
+    assert bad == 0
+    got = keys_to_u64(keys)
+    pm = perm.cpu().numpy().astype(np.int64)
+    assert np.array_equal(np.sort(pm), np.arange(len(c)))
+    assert np.array_equal(got, np.sort(k_ref))
+    assert np.array_equal(k_ref[pm], got)
+
+
 def test_pack_validate_errors():
     c = _cloud("tiny")
     desc = fit_desc(c, [(3, 1, 1)])
