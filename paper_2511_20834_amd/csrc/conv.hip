@@ -391,24 +391,36 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
     __syncthreads();  // next phase visible; everybody is done with the half it will overwrite next
   }
   // D layout of the 32x32 MFMA: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+  // Row offsets are compile-time multiples of the (wave-uniform) row pitch on top of one pointer per
+  // block, and full blocks skip the per-row bound check: the 64 two-byte stores of a wave then cost a
+  // handful of instructions each instead of a 64-bit index computation.
   if (active) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       const int64_t i0 = (blk0 + rb) * 32;
       const int rows = static_cast<int>(max<int64_t>(0, min<int64_t>(32, n_out - i0)));
+      if (rows == 0) continue;
+      T* prow = out + (i0 + 4 * lh) * ld_out + lr;
+      // hybrid dataflow: the weight-stationary part of the sum arrives in an fp32 buffer [n_out][cout]
+      const int64_t ld_init = int64_t(nb_total) * 32;
+      const float* irow = init + (i0 + 4 * lh) * ld_init + slab * (NB * 32) + lr;  // used only when init is given
+      auto store_all = [&](auto FULL_) {
+        constexpr bool FULL = decltype(FULL_)::value;
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = 8 * (r / 4) + 4 * lh + (r % 4);
-          if (row < rows) {
-            float v = acc[rb][nb][r];
-            // hybrid dataflow: the weight-stationary part of the sum arrives in an fp32 buffer [n_out][cout]
-            if (init) v += init[(i0 + row) * (nb_total * 32) + (slab * NB + nb) * 32 + lr];
-            if (relu) v = fmaxf(v, 0.f);
-            out[(i0 + row) * ld_out + nb * 32 + lr] = from_f32<T>(v);
+          for (int r = 0; r < 16; ++r) {
+            const int rr = 8 * (r / 4) + (r % 4);  // row = rr + 4 * lh
+            if (FULL || rr + 4 * lh < rows) {
+              float v = acc[rb][nb][r];
+              if (init) v += irow[rr * ld_init + nb * 32];
+              if (relu) v = fmaxf(v, 0.f);
+              prow[rr * ld_out + nb * 32] = from_f32<T>(v);
+            }
           }
-        }
+      };
+      if (rows == 32) store_all(std::true_type{});
+      else store_all(std::false_type{});
     }
   }
 }
