@@ -75,7 +75,8 @@ def _check_map(c0_sorted, keys_t, desc, K, s_p, s_l, transposed, kmap):
 @pytest.mark.parametrize("name,key_bits", [("tiny", 0), ("tiny_neg", 0), ("rand_b3", 0), ("rand_b3", 64), ("one", 0),
                                            ("slab_3k", 0), ("slab_12k", 0), ("slab_12k", 64), ("ragged", 64),
                                            ("rand_n4095", 0), ("rand_n4096", 0), ("rand_n4097", 64), ("rand_n70001", 0),
-                                           ("rand_n70001", 64), ("skew_60k", 0), ("skew_60k", 64)])
+                                           ("rand_n70001", 64), ("skew_60k", 0), ("skew_60k", 64),
+                                           ("rand_n600001", 0)])  # 64 count/scatter workgroups, ten thousand rank workgroups
 def test_pack_sort_matches_oracle(name, key_bits):
     c = _cloud(name)
     desc = fit_desc(c, [(3, 1, 2)], key_bits)
