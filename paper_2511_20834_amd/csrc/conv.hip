@@ -168,6 +168,12 @@ constexpr int HALF_BYTES = 72 * 1024;  // 9 offsets of 64x64 fp16: one x-slab of
 constexpr int KLIST_CAP = 352;  // >= 7^3
 __device__ __align__(16) uint32_t g_zero_row[64];  // zero-initialised, never written
 
+constexpr int PHASE_XCD_CHUNK = 16;  // tiles (of two 32-row blocks) per chunk; 4 to 64 measured alike
+__host__ __device__ inline int64_t phase_tiles_per_xcd(int64_t n_tiles) {
+  const int64_t n_chunks = (n_tiles + PHASE_XCD_CHUNK - 1) / PHASE_XCD_CHUNK;
+  return (n_chunks + 7) / 8 * PHASE_XCD_CHUNK;
+}
+
 template <typename T, int NB, int RB, int WAVES, int NKK, int D>
 __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t* __restrict__ M,
                                                                    const uint32_t* __restrict__ block_masks,
@@ -198,10 +204,15 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   const int n_wg = n_wg_per_xcd * 8;
   const int wg = (blockIdx.x & 7) * n_wg_per_xcd + (blockIdx.x >> 3);
   const int64_t n_tiles = (n_blocks + RB - 1) / RB;
-  const int64_t tiles_per_xcd = (n_tiles + 7) / 8;
+  // The tile sequence is dealt to the XCDs in chunks of PHASE_XCD_CHUNK tiles: a chunk is long enough
+  // for its gathers to stay in one XCD's L2 (neighbours in x and y are tens to hundreds of rows away
+  // in the sorted order), and short enough that every XCD gets its share of the dense and of the
+  // sparse regions of the scene (with one contiguous range per XCD, the XCD that held the region
+  // around the sensor of a LiDAR sweep finished 7 us after the first one).
+  const int64_t tiles_per_xcd = phase_tiles_per_xcd(n_tiles);
   const int xcd = wg / n_wg_per_xcd, wg_in_xcd = wg - xcd * n_wg_per_xcd;
   const int64_t t_in_xcd = int64_t(wave) * n_wg_per_xcd + wg_in_xcd;
-  const int64_t tile = xcd * tiles_per_xcd + t_in_xcd;
+  const int64_t tile = ((t_in_xcd / PHASE_XCD_CHUNK) * 8 + xcd) * PHASE_XCD_CHUNK + t_in_xcd % PHASE_XCD_CHUNK;
   const bool active = t_in_xcd < tiles_per_xcd && tile < n_tiles;
   const int64_t blk0 = tile * RB;
   const int nch = cin / CKS;
@@ -803,7 +814,7 @@ static void launch_os_mfma(const ConvArgs& a, const T* Wp, const float* init) {
   const int nb_total = a.cout / 32, n_slabs = nb_total / NB;
   const int64_t n_blocks = (a.rows_cap + 31) / 32;
   const int64_t n_tiles = (n_blocks + RBK - 1) / RBK;
-  const int64_t tiles_per_xcd = (n_tiles + 7) / 8;
+  const int64_t tiles_per_xcd = phase_tiles_per_xcd(n_tiles);
   const int per_xcd = static_cast<int>((tiles_per_xcd + WAVES - 1) / WAVES);
   const size_t lds = 2 * HALF_BYTES + size_t(WAVES) * KLIST_CAP * 2;
   auto go = [&](auto NKK_) {
