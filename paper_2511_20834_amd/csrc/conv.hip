@@ -200,9 +200,8 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   // then look exactly like a layer with that many output channels
   const int slab = blockIdx.y;
   out += slab * (NB * 32);
-  // tile = RB adjacent blocks; tile t -> (XCD range, workgroup within the XCD, wave)
-  const int n_wg = n_wg_per_xcd * 8;
-  const int wg = (blockIdx.x & 7) * n_wg_per_xcd + (blockIdx.x >> 3);
+  // tile = RB adjacent blocks; tile t -> (XCD, workgroup within the XCD, wave).  Workgroups go to the
+  // XCDs round-robin, so blockIdx.x & 7 is the XCD.
   const int64_t n_tiles = (n_blocks + RB - 1) / RB;
   // The tile sequence is dealt to the XCDs in chunks of PHASE_XCD_CHUNK tiles: a chunk is long enough
   // for its gathers to stay in one XCD's L2 (neighbours in x and y are tens to hundreds of rows away
@@ -210,13 +209,18 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   // sparse regions of the scene (with one contiguous range per XCD, the XCD that held the region
   // around the sensor of a LiDAR sweep finished 7 us after the first one).
   const int64_t tiles_per_xcd = phase_tiles_per_xcd(n_tiles);
-  const int xcd = wg / n_wg_per_xcd, wg_in_xcd = wg - xcd * n_wg_per_xcd;
-  const int64_t t_in_xcd = int64_t(wave) * n_wg_per_xcd + wg_in_xcd;
+  const int xcd = blockIdx.x & 7, wg_in_xcd = blockIdx.x >> 3;
+  // The grid was sized from the host's bound of the output count; the count itself may only be known
+  // here.  Only as many workgroups as that count fills take part (all of their waves busy) and
+  // the tiles of an XCD are dealt to them round-robin; the others leave at once.
+  const int n_wg_used = static_cast<int>((tiles_per_xcd + WAVES - 1) / WAVES);
+  if (wg_in_xcd >= n_wg_used) return;
+  const int64_t t_in_xcd = int64_t(wave) * n_wg_used + wg_in_xcd;
   const int64_t tile = ((t_in_xcd / PHASE_XCD_CHUNK) * 8 + xcd) * PHASE_XCD_CHUNK + t_in_xcd % PHASE_XCD_CHUNK;
   const bool active = t_in_xcd < tiles_per_xcd && tile < n_tiles;
   const int64_t blk0 = tile * RB;
   const int nch = cin / CKS;
-  (void)n_wg;
+  (void)n_wg_per_xcd;
 
   // phase 0 of the weights is requested first, so that its latency overlaps the set-up below
   const int n_chunks = K3 * nch;
@@ -892,13 +896,15 @@ static void launch_os_splitk_any(const ConvArgs& a, const T* Wp, const float* in
   }
 }
 
-// Measured crossover on MI355X (3x3x3 layers, 16..256 channels): below about 80k output voxels
-// the phase kernel has too few workgroups to fill the chip and the split-k kernel wins by 1.3-4x;
-// above, the redundant weight reads of the split-k kernel cost more than the phase kernel's
-// barriers.  Large kernels (5x5x5 and up) favour the split-k kernel at every size measured.
+// Measured crossover on MI355X (3x3x3 layers, 32..256 channels, 18 k / 49 k / 120 k voxels): the phase
+// kernel wins once it has about 160 workgroups (16 row blocks each, per slab of output channels) to
+// spread over the 256 CUs; with fewer, the split-k kernel's many short workgroups win by up to 5x in
+// spite of their redundant weight reads.  Large kernels (5x5x5 and up) favour the split-k kernel at
+// every size measured.
 static bool prefer_splitk(const ConvArgs& a) {
   const int64_t n_blocks = (a.rows_sel + 31) / 32;
-  return n_blocks < 2560 || a.m->K3 > 64;
+  const int n_slabs = a.cout % 64 == 0 ? a.cout / 64 : a.cout / 32;
+  return (n_blocks + 15) / 16 * n_slabs < 160 || a.m->K3 > 64;
 }
 
 template <typename T, int NB, int RB>
