@@ -157,6 +157,7 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
                                                              KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
                                                              int32_t* __restrict__ bstart, int2* __restrict__ win) {
   __shared__ int pos[BS_MAX_BIN + 1];  // bin starts, then this workgroup's running position in every bin
+  __shared__ int bin_start[DEDUP ? 1 : BS_MAX_BIN + 1];
   __shared__ int wave_tot[BS_WIDE / 64];
   static_assert(BS_MAX_BIN == 4 * BS_WIDE, "one int4 of bins per thread");
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -180,28 +181,7 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
     total += wave_tot[w];
   }
   const int4 st = make_int4(base, base + c.x, base + c.x + c.y, base + c.x + c.y + c.z);
-  if (!DEDUP) {
-    // Rank windows (see bs_rank_kernel): part p = scattered positions [p * BS_PART, ...) is ranked
-    // inside the range of whole bins that covers it.  Parts are dealt round-robin to the workgroups,
-    // one per thread: two binary searches over the bin starts in LDS.
-    if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = st;
-    if (t == 0) pos[n_bin] = total;
-    __syncthreads();
-    if (blockIdx.x == 0 && t < BS_PAD_KEYS) keys1[total + t] = ~KeyT(0);  // the rank kernel reads whole steps
-    const int part = blockIdx.x + t * gridDim.x;
-    if (int64_t(part) * BS_PART < total) {
-      const int x0 = part * BS_PART, x1 = min(x0 + BS_PART, total) - 1;
-      // last bin whose start is <= x: the (non-empty) bin that holds position x
-      auto bin_of = [&](int x) {
-        int f = 0;
-        for (int step = n_bin >> 1; step > 0; step >>= 1)
-          if (pos[f + step] <= x) f += step;
-        return f;
-      };
-      win[part] = make_int2(pos[bin_of(x0)], pos[bin_of(x1) + 1]);
-    }
-    __syncthreads();
-  } else if (blockIdx.x == 0) {
+  if (DEDUP && blockIdx.x == 0) {
     if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = st;
     if (t == 0) pos[n_bin] = total;
     __syncthreads();
@@ -217,6 +197,10 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
     __syncthreads();
   }
   if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = make_int4(st.x + bef.x, st.y + bef.y, st.z + bef.z, st.w + bef.w);
+  if (!DEDUP) {  // the bin starts themselves, for the rank windows at the end
+    if (f0 < n_bin) *reinterpret_cast<int4*>(bin_start + f0) = st;
+    if (t == 0) bin_start[n_bin] = total;
+  }
   __syncthreads();
   const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
   for (int64_t i0 = lo + threadIdx.x; i0 < hi; i0 += 4 * BS_WIDE) {
@@ -245,6 +229,25 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
         keys1[p[u]] = key[u];
         vals1[p[u]] = static_cast<int32_t>(i0 + u * BS_WIDE);
       }
+  }
+  if (!DEDUP) {
+    // Rank windows (see bs_rank_kernel): part p = scattered positions [p * BS_PART, ...) is ranked
+    // inside the range of whole bins that covers it.  Parts are dealt round-robin to the workgroups,
+    // one per thread: two binary searches over the bin starts in LDS, done last, while the scattered
+    // stores drain.
+    if (blockIdx.x == 0 && t < BS_PAD_KEYS) keys1[total + t] = ~KeyT(0);  // the rank kernel reads whole steps
+    const int part = blockIdx.x + t * gridDim.x;
+    if (int64_t(part) * BS_PART < total) {
+      const int x0 = part * BS_PART, x1 = min(x0 + BS_PART, total) - 1;
+      // last bin whose start is <= x: the (non-empty) bin that holds position x; both searches in step
+      int fa = 0, fb = 0;
+      for (int step = n_bin >> 1; step > 0; step >>= 1) {
+        const int sa = bin_start[fa + step], sb = bin_start[fb + step];
+        if (sa <= x0) fa += step;
+        if (sb <= x1) fb += step;
+      }
+      win[part] = make_int2(bin_start[fa], bin_start[fb + 1]);
+    }
   }
 }
 
