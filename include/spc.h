@@ -103,7 +103,10 @@ int spc_pack_desc_fit(const int32_t lo[3], const int32_t hi[3], int32_t n_batch,
  *               in *workspace_bytes (nothing is enqueued then).
  *   flags       SPC_PACK_VALIDATE: wait for the stream and return SPC_ERR_RANGE /
  *               SPC_ERR_DUP if a row does not fit its field or occurs twice.  Without
- *               it nothing is waited for and such input gives undefined keys.
+ *               it nothing is waited for: a row that does not fit gets the all-ones key
+ *               (sorted last), repeated rows are sorted like any others and perm_out
+ *               stays a complete permutation; kernel maps built on such keys are not
+ *               meaningful.
  */
 int spc_pack_coords(const int32_t* coords_bxyz, int64_t n, const spc_pack_desc* d, void* keys_out,
                     int32_t* perm_out, void* workspace, size_t* workspace_bytes, int32_t flags,
