@@ -1,6 +1,6 @@
-// Sort of packed voxel keys for the cloud sizes of this workload (thousands to about half a
-// million keys): one most-significant-digit split into fine bins, then ranking (pack + sort) or a
-// per-bucket network sort (downsampling).  Short launches, no look-back spinning, no global atomics:
+// Sort of packed voxel keys for the cloud sizes of this workload (thousands to about two
+// million keys): one most-significant-digit split into fine bins, then every key is ranked by
+// counting inside the window of bins around it.  Short launches, no look-back spinning:
 //
 //   count    each workgroup produces its share of the keys (packing coordinates, Section 5.3,
 //            or masking the keys of a finer level, Section 5.5), histograms the top `fb` used
@@ -8,29 +8,19 @@
 //   colscan  exclusive prefixes down the table's columns: where a workgroup's keys of a bin go
 //            inside the bin, and the bin totals;
 //   scatter  each workgroup scans the bin totals (where every bin starts) and moves its keys,
-//            with their source index, to their bin's range.  Pack + sort: the workgroups also
-//            write, for every 64 scattered positions, the window of whole bins that covers them.
-//            Downsampling: workgroup 0 cuts the bin sequence into buckets of about BS_TARGET
-//            keys (the buckets adapt to the key distribution: a LiDAR sweep is many times denser
-//            near the sensor);
-//   rank     (pack + sort) 64 keys per workgroup; a key's final position is the start of its
-//            window plus the number of window keys that sort before it, counted by comparing
-//            against every window key (see bs_rank_kernel).  Quadratic in the bin size, but
-//            spread evenly over the chip whatever the key distribution;
-//   unique   (downsampling) one workgroup per bucket: bitonic network over the keys in LDS
-//            (min/max steps, three compare distances per pass: a thread holds the 8 keys those
-//            distances connect; distances below 512 run inside the waves without barriers);
-//            the bucket's distinct keys are counted and left at the start of the bucket's range;
-//   gather   (downsampling) compacts the buckets' distinct keys.
+//            with their source index, to their bin's range; the workgroups also write, for every
+//            64 scattered positions, the window of whole bins that covers them;
+//   rank     64 keys per workgroup; a key's final position is the start of its window plus the
+//            number of window keys that sort before it, counted by comparing against every
+//            window key (see bs_rank_kernel).  Quadratic in the bin size, but spread evenly over
+//            the chip whatever the key distribution (a LiDAR sweep is many times denser near the
+//            sensor, and x, the most significant spatial field, makes a bin a slab of the scene).
 //
-// x is the most significant spatial field, so a bin is a slab of the scene.  In the downsampling
-// path a single bin that outgrows the LDS tile (a dense slab) is sorted straight in global memory
-// by the all-ascending form of the network (first step of every merge compares mirrored
-// positions), which sorts any length when the missing tail is taken as +infinity: comparators
-// that touch the tail are skipped.  Correct for any input, slow only for degenerate ones.
-// The rank kernel orders (key, scattered position) pairs, so equal keys (not a valid cloud, but
-// not rejected unless validation was asked for) still get distinct positions and the permutation
-// is complete whatever the input.
+// Pack + sort ranks (key, scattered position) pairs, so equal keys (not a valid cloud, but not
+// rejected unless validation was asked for) still get distinct positions and the permutation is
+// complete whatever the input.  Downsampling ranks the masked keys alone: equal keys fall on one
+// position, first arrivals are marked in a bitmap and counted per chunk with global atomics,
+// and a fifth kernel, compact, closes the gaps.
 #include <algorithm>
 
 #include "spc_internal.h"
@@ -39,7 +29,6 @@ namespace spc {
 
 constexpr int BS_THREADS = 256;   // sort / gather workgroups
 constexpr int BS_WIDE = 1024;     // count / scan / scatter workgroups
-constexpr int BS_CAP = 4096;      // keys per LDS tile
 
 __device__ inline int bs_bin(uint64_t key, int shift, int n_bin) {
   const uint64_t b = key >> shift;
@@ -147,17 +136,20 @@ __global__ __launch_bounds__(BS_COL_THREADS) void bs_colscan_kernel(const int32_
 
 // ---------------------------------------------------------------- scatter
 // Every workgroup scans the bin totals on its own (16 KB; cheaper than one more launch): start
-// of bin f, then the workgroup's first position in the bin.  Workgroup 0 also cuts the bin
-// sequence into buckets: bucket j starts at the first bin whose start is >= j * target
-// (bstart[n_bucket] = n).
+// of bin f, then the workgroup's first position in the bin, and moves its keys, with their source
+// index, to their bin's range.  It also prepares the rank pass: for every BS_PART scattered
+// positions the window of whole bins that covers them, BS_PAD_KEYS all-ones keys behind the last
+// key, the number of keys that take part and, for the downsampling variant (DEDUP: of a run of
+// equal adjacent keys only the first takes part), the cleared position bitmap and chunk counters.
 template <typename KeyT, bool DEDUP>
 __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restrict__ keys0, int64_t n, int per, int shift,
                                                              int n_bin, const int32_t* __restrict__ before,
-                                                             const int32_t* __restrict__ tot, int target, int n_bucket,
-                                                             KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
-                                                             int32_t* __restrict__ bstart, int2* __restrict__ win) {
-  __shared__ int pos[BS_MAX_BIN + 1];  // bin starts, then this workgroup's running position in every bin
-  __shared__ int bin_start[DEDUP ? 1 : BS_MAX_BIN + 1];
+                                                             const int32_t* __restrict__ tot, KeyT* __restrict__ keys1,
+                                                             int32_t* __restrict__ vals1, int2* __restrict__ win,
+                                                             int32_t* __restrict__ n_part_keys, uint32_t* __restrict__ bits,
+                                                             int n_words, int32_t* __restrict__ ccnt, int n_chunks) {
+  __shared__ int pos[BS_MAX_BIN + 1];        // this workgroup's running position in every bin
+  __shared__ int bin_start[BS_MAX_BIN + 1];  // where every bin starts
   __shared__ int wave_tot[BS_WIDE / 64];
   static_assert(BS_MAX_BIN == 4 * BS_WIDE, "one int4 of bins per thread");
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -166,6 +158,10 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
   if (f0 < n_bin) {
     c = *reinterpret_cast<const int4*>(tot + f0);
     bef = *reinterpret_cast<const int4*>(before + int64_t(blockIdx.x) * n_bin + f0);
+  }
+  if (DEDUP) {  // the rank pass marks positions and counts them per chunk: both start from zero
+    for (int i = blockIdx.x * BS_WIDE + t; i < n_words; i += gridDim.x * BS_WIDE) bits[i] = 0u;
+    for (int i = blockIdx.x * BS_WIDE + t; i < n_chunks; i += gridDim.x * BS_WIDE) ccnt[i] = 0;
   }
   const int sum = c.x + c.y + c.z + c.w;
   int x = sum;
@@ -181,26 +177,11 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
     total += wave_tot[w];
   }
   const int4 st = make_int4(base, base + c.x, base + c.x + c.y, base + c.x + c.y + c.z);
-  if (DEDUP && blockIdx.x == 0) {
-    if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = st;
-    if (t == 0) pos[n_bin] = total;
-    __syncthreads();
-    // bin f opens every bucket j with start(f-1) < j * target <= start(f); bucket 0 opens at bin 0
-    for (int f = t; f < n_bin; f += BS_WIDE) {
-      const int s1 = pos[f];
-      const int j0 = f == 0 ? 0 : pos[f - 1] / target + 1;
-      for (int j = j0; j <= s1 / target && j < n_bucket; ++j) bstart[j] = s1;
-    }
-    // buckets whose threshold lies beyond the last bin's start are empty
-    for (int j = pos[n_bin - 1] / target + 1 + t; j < n_bucket; j += BS_WIDE) bstart[j] = total;
-    if (t == 0) bstart[n_bucket] = total;
-    __syncthreads();
+  if (f0 < n_bin) {
+    *reinterpret_cast<int4*>(pos + f0) = make_int4(st.x + bef.x, st.y + bef.y, st.z + bef.z, st.w + bef.w);
+    *reinterpret_cast<int4*>(bin_start + f0) = st;
   }
-  if (f0 < n_bin) *reinterpret_cast<int4*>(pos + f0) = make_int4(st.x + bef.x, st.y + bef.y, st.z + bef.z, st.w + bef.w);
-  if (!DEDUP) {  // the bin starts themselves, for the rank windows at the end
-    if (f0 < n_bin) *reinterpret_cast<int4*>(bin_start + f0) = st;
-    if (t == 0) bin_start[n_bin] = total;
-  }
+  if (t == 0) bin_start[n_bin] = total;
   __syncthreads();
   const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
   for (int64_t i0 = lo + threadIdx.x; i0 < hi; i0 += 4 * BS_WIDE) {
@@ -227,194 +208,28 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
     for (int u = 0; u < 4; ++u)
       if (use[u]) {
         keys1[p[u]] = key[u];
-        vals1[p[u]] = static_cast<int32_t>(i0 + u * BS_WIDE);
+        if (!DEDUP) vals1[p[u]] = static_cast<int32_t>(i0 + u * BS_WIDE);
       }
   }
-  if (!DEDUP) {
-    // Rank windows (see bs_rank_kernel): part p = scattered positions [p * BS_PART, ...) is ranked
-    // inside the range of whole bins that covers it.  Parts are dealt round-robin to the workgroups,
-    // one per thread: two binary searches over the bin starts in LDS, done last, while the scattered
-    // stores drain.
-    if (blockIdx.x == 0 && t < BS_PAD_KEYS) keys1[total + t] = ~KeyT(0);  // the rank kernel reads whole steps
-    const int part = blockIdx.x + t * gridDim.x;
-    if (int64_t(part) * BS_PART < total) {
-      const int x0 = part * BS_PART, x1 = min(x0 + BS_PART, total) - 1;
-      // last bin whose start is <= x: the (non-empty) bin that holds position x; both searches in step
-      int fa = 0, fb = 0;
-      for (int step = n_bin >> 1; step > 0; step >>= 1) {
-        const int sa = bin_start[fa + step], sb = bin_start[fb + step];
-        if (sa <= x0) fa += step;
-        if (sb <= x1) fb += step;
-      }
-      win[part] = make_int2(bin_start[fa], bin_start[fb + 1]);
+  // Rank windows (see bs_rank_kernel): part p = scattered positions [p * BS_PART, ...) is ranked
+  // inside the range of whole bins that covers it.  Parts are dealt round-robin to the workgroups,
+  // one per thread: two binary searches over the bin starts in LDS, done last, while the scattered
+  // stores drain.
+  if (blockIdx.x == 0) {
+    if (t < BS_PAD_KEYS) keys1[total + t] = ~KeyT(0);  // the rank kernels read whole steps
+    if (t == 0 && n_part_keys) *n_part_keys = total;
+  }
+  const int part = blockIdx.x + t * gridDim.x;
+  if (int64_t(part) * BS_PART < total) {
+    const int x0 = part * BS_PART, x1 = min(x0 + BS_PART, total) - 1;
+    // last bin whose start is <= x: the (non-empty) bin that holds position x; both searches in step
+    int fa = 0, fb = 0;
+    for (int step = n_bin >> 1; step > 0; step >>= 1) {
+      const int sa = bin_start[fa + step], sb = bin_start[fb + step];
+      if (sa <= x0) fa += step;
+      if (sb <= x1) fb += step;
     }
-  }
-}
-
-// ---------------------------------------------------------------- sort
-// Element = (key, source index).  32-bit keys travel as one 64-bit word.
-template <typename KeyT>
-struct Elem;
-template <>
-struct Elem<uint32_t> {
-  uint64_t kv;
-  __device__ static Elem make(uint32_t k, int32_t v) { return Elem{(uint64_t(k) << 32) | uint32_t(v)}; }
-  __device__ uint32_t key() const { return static_cast<uint32_t>(kv >> 32); }
-  __device__ int32_t val() const { return static_cast<int32_t>(uint32_t(kv)); }
-  __device__ bool operator<(const Elem& o) const { return kv < o.kv; }
-};
-template <>
-struct Elem<uint64_t> {
-  uint64_t k;
-  int32_t v;
-  __device__ static Elem make(uint64_t k, int32_t v) { return Elem{k, v}; }
-  __device__ uint64_t key() const { return k; }
-  __device__ int32_t val() const { return v; }
-  __device__ bool operator<(const Elem& o) const { return k < o.k || (k == o.k && v < o.v); }
-};
-
-// Accessor of the global-memory fallback: the bucket's range of (key, index) pairs.
-template <typename KeyT>
-struct GlobalRange {
-  KeyT* k;
-  int32_t* v;
-  __device__ Elem<KeyT> get(int i) const { return Elem<KeyT>::make(k[i], v[i]); }
-  __device__ void put(int i, const Elem<KeyT>& x) const {
-    k[i] = x.key();
-    v[i] = x.val();
-  }
-};
-
-template <typename Acc>
-__device__ inline void bs_cmpxchg(const Acc& a, int i, int j) {
-  const auto x = a.get(i), y = a.get(j);
-  if (y < x) {
-    a.put(i, y);
-    a.put(j, x);
-  }
-}
-
-// LDS position of tile element i: one element of padding per 32, so that the strided accesses
-// of the short compare distances (a thread's 8 elements are then neighbours, and lanes are 8
-// elements apart) spread over the banks instead of hitting the same few.
-__device__ inline int bs_at(int i) { return i + (i >> 5); }
-
-// Standard bitonic network on a power-of-two tile of keys in LDS, NB consecutive compare distances
-// per barrier: the thread's 2^NB keys are those whose indices differ in bits ltop .. ltop-NB+1.
-// The merge of blocks of 2^lk sorts ascending where bit lk of the index is clear; a descending
-// block runs the same min/max steps on complemented keys.
-template <int NB, typename KeyT>
-__device__ inline void bs_lds_round(KeyT* tile, int P, int lk, int ltop) {
-  constexpr int R = 1 << NB;
-  const int lbot = ltop - NB + 1;
-  for (int t = threadIdx.x; t < (P >> NB); t += BS_THREADS) {
-    const int base = ((t >> lbot) << (ltop + 1)) | (t & ((1 << lbot) - 1));
-    const KeyT flip = (base & (1 << lk)) ? ~KeyT(0) : KeyT(0);
-    KeyT e[R];
-#pragma unroll
-    for (int q = 0; q < R; ++q) e[q] = tile[bs_at(base | (q << lbot))] ^ flip;
-#pragma unroll
-    for (int sb = NB - 1; sb >= 0; --sb)
-#pragma unroll
-      for (int q = 0; q < R; ++q)
-        if (!(q & (1 << sb))) {
-          const int q2 = q | (1 << sb);
-          const KeyT lo = min(e[q], e[q2]), hi = max(e[q], e[q2]);
-          e[q] = lo;
-          e[q2] = hi;
-        }
-#pragma unroll
-    for (int q = 0; q < R; ++q) tile[bs_at(base | (q << lbot))] = e[q] ^ flip;
-  }
-  __syncthreads();
-}
-
-// The same step for compare distances below 512, without a barrier: a wave owns whole chunks of
-// 512 keys (64 lanes x 8 keys), the steps of such distances never leave a chunk, and the LDS
-// executes one wave's accesses in program order.
-constexpr int BS_CHUNK_BITS = 9;
-template <int NB, typename KeyT>
-__device__ inline void bs_wave_round(KeyT* tile, int P, int lk, int ltop) {
-  constexpr int R = 1 << NB;
-  const int lbot = ltop - NB + 1;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int csize = min(P, 1 << BS_CHUNK_BITS);
-  for (int c0 = wave << BS_CHUNK_BITS; c0 < P; c0 += (BS_THREADS / 64) << BS_CHUNK_BITS)
-    for (int u = lane; u < (csize >> NB); u += 64) {
-      const int base = c0 | ((u >> lbot) << (ltop + 1)) | (u & ((1 << lbot) - 1));
-      const KeyT flip = (base & (1 << lk)) ? ~KeyT(0) : KeyT(0);
-      KeyT e[R];
-#pragma unroll
-      for (int q = 0; q < R; ++q) e[q] = tile[bs_at(base | (q << lbot))] ^ flip;
-#pragma unroll
-      for (int sb = NB - 1; sb >= 0; --sb)
-#pragma unroll
-        for (int q = 0; q < R; ++q)
-          if (!(q & (1 << sb))) {
-            const int q2 = q | (1 << sb);
-            const KeyT lo = min(e[q], e[q2]), hi = max(e[q], e[q2]);
-            e[q] = lo;
-            e[q2] = hi;
-          }
-#pragma unroll
-      for (int q = 0; q < R; ++q) tile[bs_at(base | (q << lbot))] = e[q] ^ flip;
-    }
-  __builtin_amdgcn_wave_barrier();
-}
-
-// compare distances 2^ltop .. 1 of merge lk, all inside the waves' chunks
-template <typename KeyT>
-__device__ inline void bs_wave_rounds(KeyT* tile, int P, int lk, int ltop) {
-  const int first = (ltop + 1) % 3;
-  if (first == 1) {
-    bs_wave_round<1>(tile, P, lk, ltop);
-    ltop -= 1;
-  } else if (first == 2) {
-    bs_wave_round<2>(tile, P, lk, ltop);
-    ltop -= 2;
-  }
-  for (; ltop >= 2; ltop -= 3) bs_wave_round<3>(tile, P, lk, ltop);
-}
-
-// Sorts tile[0, P), P = 2^lp <= 4096; every thread of the workgroup calls it (after a barrier that
-// made the tile complete; it ends with one).  Merges of blocks up to 512 run inside the waves;
-// a longer merge starts with one workgroup-wide step over its distances of 512 and more.
-template <typename KeyT>
-__device__ inline void bs_lds_bitonic(KeyT* tile, int lp) {
-  const int P = 1 << lp;
-  for (int lk = 1; lk <= min(lp, BS_CHUNK_BITS); ++lk) bs_wave_rounds(tile, P, lk, lk - 1);
-  __syncthreads();
-  for (int lk = BS_CHUNK_BITS + 1; lk <= lp; ++lk) {
-    const int nb = lk - BS_CHUNK_BITS;  // 1..3 distances reach across chunks
-    if (nb == 1) bs_lds_round<1>(tile, P, lk, lk - 1);
-    else if (nb == 2) bs_lds_round<2>(tile, P, lk, lk - 1);
-    else bs_lds_round<3>(tile, P, lk, lk - 1);
-    bs_wave_rounds(tile, P, lk, BS_CHUNK_BITS - 1);
-    __syncthreads();
-  }
-}
-
-// Sorts positions [0, m) ascending; every thread of the workgroup calls it.
-template <typename Acc>
-__device__ inline void bs_bitonic(const Acc& a, int m) {
-  int lp = 0;
-  while ((1 << lp) < m) ++lp;
-  const int half = (1 << lp) >> 1;
-  for (int lk = 1; lk <= lp; ++lk) {  // merges of blocks of k = 2^lk
-    const int k = 1 << lk, lh = lk - 1;
-    for (int t = threadIdx.x; t < half; t += BS_THREADS) {  // mirrored step
-      const int blk = t >> lh, off = t & ((1 << lh) - 1);
-      const int i = (blk << lk) + off, j = (blk << lk) + k - 1 - off;
-      if (j < m) bs_cmpxchg(a, i, j);
-    }
-    __syncthreads();
-    for (int ld = lk - 2; ld >= 0; --ld) {  // half-cleaners of distance d = 2^ld
-      for (int t = threadIdx.x; t < half; t += BS_THREADS) {
-        const int i = ((t >> ld) << (ld + 1)) + (t & ((1 << ld) - 1)), j = i + (1 << ld);
-        if (j < m) bs_cmpxchg(a, i, j);
-      }
-      __syncthreads();
-    }
+    win[part] = make_int2(bin_start[fa], bin_start[fb + 1]);
   }
 }
 
@@ -537,107 +352,114 @@ __global__ __launch_bounds__(BS_THREADS) void bs_rank_kernel(const KeyT* __restr
   }
 }
 
-// Downsampling path: one workgroup per bucket sorts the bucket's keys with the network above and
-// leaves its distinct keys at the start of the bucket's range of out_k, their number in
-// ucount[bucket].  A bucket that outgrows the LDS tile is sorted in global memory (vals1 travels
-// along as the network's second field and is otherwise unused).
+// ---------------------------------------------------------------- rank + compact (downsampling path)
+// The distinct masked keys in ascending order.  Ranking as above, on the key alone: equal keys get
+// equal positions, so position = window start + (number of window keys smaller than mine) leaves the
+// sorted sequence with gaps where a key occurs more than once (the count pass has dropped equal
+// neighbours, but the children of one coarse voxel sit in up to four separate runs of the finer
+// level).  A position is marked in a bitmap by whoever gets there first, and counted once in its
+// chunk of BS_CHUNK positions; bs_compact_kernel then closes the gaps.
+constexpr int BS_CHUNK = 1024;
 template <typename KeyT>
-__global__ __launch_bounds__(BS_THREADS) void bs_unique_kernel(KeyT* __restrict__ keys1, int32_t* __restrict__ vals1,
-                                                               const int32_t* __restrict__ bstart, KeyT* __restrict__ out_k,
-                                                               int32_t* __restrict__ ucount) {
-  constexpr int CAP = BS_CAP;
-  constexpr int EPT = CAP / BS_THREADS;
-  __shared__ KeyT tile[CAP + CAP / 32];
-  __shared__ int wave_tot[BS_THREADS / 64];
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int s = bstart[blockIdx.x], m = bstart[blockIdx.x + 1] - s;
-  if (m <= 0) {
-    if (t == 0) ucount[blockIdx.x] = 0;
-    return;
-  }
-  const bool in_lds = m <= CAP;
-  if (in_lds) {
-    int lp = 0;
-    while ((1 << lp) < m) ++lp;
-    const int P = 1 << lp;
-    KeyT key[EPT];  // all loads of the thread in flight together
+__global__ __launch_bounds__(BS_THREADS) void bs_rank_unique_kernel(const KeyT* __restrict__ keys1, const int2* __restrict__ win,
+                                                                    const int32_t* __restrict__ n_kept,
+                                                                    KeyT* __restrict__ sorted, uint32_t* __restrict__ bits,
+                                                                    int32_t* __restrict__ ccnt) {
+  constexpr int WAVES = BS_THREADS / 64;
+  __shared__ int partial[WAVES][BS_PART];
+  __shared__ uint32_t lbits[64];
+  const int n = *n_kept;  // the grid is sized for the level before the equal neighbours were dropped
+  const int own0 = blockIdx.x * BS_PART;
+  if (own0 >= n) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+  const int x = own0 + lane;
+  const bool act = x < n;
+  const int2 w = win[blockIdx.x];
+  const KeyT key = act ? keys1[x] : ~KeyT(0);
+  const int n_pad = (n + BS_RANK_STEP - 1) & ~(BS_RANK_STEP - 1);  // positions n .. n_pad - 1 hold all-ones keys
+  const int g0 = w.x & ~(BS_RANK_STEP - 1);
+  const int g1 = min((w.y + BS_RANK_STEP - 1) & ~(BS_RANK_STEP - 1), n_pad);
+  const int steps = (g1 - g0) / BS_RANK_STEP, per = (steps + WAVES - 1) / WAVES;
+  const int qa = min(g0 + wave * per * BS_RANK_STEP, g1), qb = min(qa + per * BS_RANK_STEP, g1);
+  partial[wave][lane] = bs_count_before<2>(keys1, qa, qb, key, x);
+  __syncthreads();
+  if (wave == 0) {
+    int r = g0;
 #pragma unroll
-    for (int r = 0; r < EPT; ++r) {
-      const int i = r * BS_THREADS + t;
-      key[r] = i < m ? keys1[s + i] : ~KeyT(0);
+    for (int v = 0; v < WAVES; ++v) r += partial[v][lane];
+    if (act) sorted[r] = key;  // equal keys write the same value
+    // The 64 positions lie in the window, typically within a few hundred positions of its start:
+    // their bits are collected in LDS first (64 words from the window start on), so that the global
+    // bitmap sees one atomic per word instead of one per key; what a word's atomic finds newly set
+    // is counted for the word's chunk (a chunk is 32 words), one counter update per chunk.
+    lbits[lane] = 0u;
+    __builtin_amdgcn_wave_barrier();
+    const int rel = r - g0;
+    const bool far = act && rel >= 64 * 32;
+    if (act && !far) atomicOr(&lbits[rel >> 5], 1u << (rel & 31));
+    __builtin_amdgcn_wave_barrier();
+    const int word_i = far ? r >> 5 : (g0 >> 5) + lane;
+    const uint32_t word = far ? 1u << (r & 31) : lbits[lane];
+    int fresh = 0;
+    if (word) fresh = __popc(word & ~atomicOr(&bits[word_i], word));
+    const int chunk = word_i / (BS_CHUNK / 32);
+    unsigned long long todo = __ballot(fresh > 0);
+    while (todo) {
+      const int leader = __builtin_ctzll(todo);
+      const int c = __shfl(chunk, leader, 64);
+      const bool mine = fresh > 0 && chunk == c;
+      int sum = mine ? fresh : 0;
+      for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+      if (lane == leader) atomicAdd(&ccnt[c], sum);
+      todo &= ~__ballot(mine);
     }
-#pragma unroll
-    for (int r = 0; r < EPT; ++r) {
-      const int i = r * BS_THREADS + t;
-      if (i < P) tile[bs_at(i)] = key[r];
-    }
-    __syncthreads();
-    bs_lds_bitonic(tile, lp);
-  } else {
-    bs_bitonic(GlobalRange<KeyT>{keys1 + s, vals1 + s}, m);
   }
-  auto key_at = [&](int i) -> KeyT { return in_lds ? tile[bs_at(i)] : keys1[s + i]; };
-  // heads of runs of equal keys, compacted in order (positions are visited in array order)
-  int run = 0;
-  for (int i0 = 0; i0 < m; i0 += BS_THREADS) {
-    const int i = i0 + t;
-    const bool head = i < m && (i == 0 || key_at(i) != key_at(i - 1));
-    const KeyT kv = i < m ? key_at(i) : KeyT(0);
-    const unsigned long long bal = __ballot(head);
-    if (lane == 0) wave_tot[wave] = __popcll(bal);
-    __syncthreads();
-    int base = run, tot = 0;
-    for (int w = 0; w < BS_THREADS / 64; ++w) {
-      if (w < wave) base += wave_tot[w];
-      tot += wave_tot[w];
-    }
-    // out_k is a different buffer from keys1, so positions still to be read are not overwritten
-    if (head) out_k[s + base + __popcll(bal & ((1ull << lane) - 1ull))] = kv;
-    run += tot;
-    __syncthreads();
-  }
-  if (t == 0) ucount[blockIdx.x] = run;
 }
 
-// Compacts the buckets' unique keys: out[prefix(ucount)[b] + i] = in[bstart[b] + i]; total to *n_out.
+// out = the marked positions of `sorted`, in order; their number to *n_out.  One workgroup per chunk
+// of BS_CHUNK positions: the keys before the chunk are the sum of the earlier chunks' counters.
 template <typename KeyT>
-__global__ __launch_bounds__(BS_THREADS) void bs_gather_kernel(const KeyT* __restrict__ in, const int32_t* __restrict__ bstart,
-                                                               const int32_t* __restrict__ ucount, int n_bucket,
-                                                               KeyT* __restrict__ out, int32_t* __restrict__ n_out) {
-  __shared__ int pre[BS_MAX_BUCKET];
-  __shared__ int wave_tot[BS_THREADS / 64];
-  constexpr int PER = BS_MAX_BUCKET / BS_THREADS;
+__global__ __launch_bounds__(BS_THREADS) void bs_compact_kernel(const KeyT* __restrict__ sorted, const uint32_t* __restrict__ bits,
+                                                                const int32_t* __restrict__ ccnt,
+                                                                const int32_t* __restrict__ n_kept, KeyT* __restrict__ out,
+                                                                int32_t* __restrict__ n_out) {
+  static_assert(BS_CHUNK == 4 * BS_THREADS, "four positions per thread");
+  __shared__ int red[2][BS_THREADS / 64];
+  __shared__ int wsum[BS_CHUNK / 32];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  int loc[PER], sum = 0;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    const int b = t * PER + j;
-    loc[j] = b < n_bucket ? ucount[b] : 0;
-    sum += loc[j];
+  const int n = *n_kept, n_chunks = (n + BS_CHUNK - 1) / BS_CHUNK, b = blockIdx.x;
+  int before = 0, all = 0;
+  for (int i = t; i < n_chunks; i += BS_THREADS) {
+    const int c = ccnt[i];
+    all += c;
+    before += i < b ? c : 0;
   }
-  int x = sum;
-  for (int d = 1; d < 64; d <<= 1) {
-    const int y = __shfl_up(x, d, 64);
-    if (lane >= d) x += y;
+  for (int d = 32; d > 0; d >>= 1) {
+    before += __shfl_xor(before, d, 64);
+    all += __shfl_xor(all, d, 64);
   }
-  if (lane == 63) wave_tot[wave] = x;
+  if (lane == 0) {
+    red[0][wave] = before;
+    red[1][wave] = all;
+  }
+  const int wi = t >> 3, sub = t & 7;  // eight threads per bitmap word, four positions each
+  const uint32_t word = b < n_chunks ? bits[b * (BS_CHUNK / 32) + wi] : 0u;
+  if (sub == 0) wsum[wi] = __popc(word);
   __syncthreads();
-  int base = x - sum, total = 0;
+  before = 0;
+  all = 0;
   for (int w = 0; w < BS_THREADS / 64; ++w) {
-    if (w < wave) base += wave_tot[w];
-    total += wave_tot[w];
+    before += red[0][w];
+    all += red[1][w];
   }
+  if (b == 0 && t == 0) *n_out = all;
+  int rank = before + __popc(word & ((1u << (4 * sub)) - 1u));
+  for (int w = 0; w < wi; ++w) rank += wsum[w];
 #pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    const int b = t * PER + j;
-    if (b < n_bucket) pre[b] = base;
-    base += loc[j];
-  }
-  __syncthreads();
-  if (blockIdx.x == 0 && t == 0) *n_out = total;
-  for (int b = blockIdx.x; b < n_bucket; b += gridDim.x) {
-    const int c = ucount[b], src = bstart[b], dst = pre[b];
-    for (int i = t; i < c; i += BS_THREADS) out[dst + i] = in[src + i];
+  for (int j = 0; j < 4; ++j) {
+    const int bit = 4 * sub + j;
+    if ((word >> bit) & 1u) out[rank++] = sorted[b * BS_CHUNK + wi * 32 + bit];
   }
 }
 
@@ -654,15 +476,7 @@ BucketPlan bucket_plan(int64_t n, int used_bits) {
   fb = std::max(2, std::min(fb, used_bits));
   p.shift = used_bits - fb;
   p.n_bin = 1 << fb;
-  p.target = BS_TARGET;
-  p.n_bucket = static_cast<int>(std::max<int64_t>((n + p.target - 1) / p.target, 1));
   return p;
-}
-
-size_t bucket_sort_ws_bytes(int key_bits, int64_t n) {
-  const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
-  const size_t k = ((nn + BS_PAD_KEYS) * (key_bits / 8) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
-  return 2 * k + v + (2 * size_t(BS_MAX_WG) * BS_MAX_BIN + BS_MAX_BIN + 64 + 2 * (size_t(BS_MAX_BUCKET) + 64) + 2 * BS_MAX_PART) * 4;
 }
 
 namespace {
@@ -674,10 +488,14 @@ struct Ws {
   int32_t* table;
   int32_t* before;
   int32_t* fstart;
-  int32_t* bstart;
-  int32_t* ucount;
   int2* win;
+  int32_t* n_kept;
+  int32_t* ccnt;
+  uint32_t* bits;
+  int n_words, n_chunks;
 };
+size_t words_for(int64_t n) { return static_cast<size_t>(n / 32 + 64); }    // bitmap words the downsampling path clears and reads
+size_t chunks_for(int64_t n) { return static_cast<size_t>(n / BS_CHUNK + 2); }
 template <typename KeyT>
 Ws<KeyT> carve(void* ws, int64_t n) {
   const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
@@ -690,24 +508,33 @@ Ws<KeyT> carve(void* ws, int64_t n) {
   w.table = reinterpret_cast<int32_t*>(c + 2 * k + v);
   w.before = w.table + size_t(BS_MAX_WG) * BS_MAX_BIN;
   w.fstart = w.before + size_t(BS_MAX_WG) * BS_MAX_BIN;
-  w.bstart = w.fstart + BS_MAX_BIN + 64;
-  w.ucount = w.bstart + BS_MAX_BUCKET + 64;
-  w.win = reinterpret_cast<int2*>(w.ucount + BS_MAX_BUCKET + 64);  // 8-byte aligned: every part above is a multiple of 256 bytes
+  w.win = reinterpret_cast<int2*>(w.fstart + BS_MAX_BIN + 64);  // 8-byte aligned: every part above is a multiple of 256 bytes
+  w.n_kept = reinterpret_cast<int32_t*>(w.win + (nn / BS_PART + 2));
+  w.ccnt = w.n_kept + 2;
+  w.n_chunks = static_cast<int>(chunks_for(n));
+  w.bits = reinterpret_cast<uint32_t*>(w.ccnt + w.n_chunks);
+  w.n_words = static_cast<int>(words_for(n));
   return w;
 }
 
-// count, scan, scatter: keys1/vals1 partitioned by fine bin, bstart = bucket boundaries
+// count, column scan, scatter: keys1 (vals1) partitioned by fine bin, rank windows
 template <typename KeyT, bool DEDUP, typename Src>
 void partition(const Src& src, int64_t n, const BucketPlan& p, const Ws<KeyT>& w, hipStream_t s) {
-  const size_t lds = 0;
-  hipLaunchKernelGGL((bs_count_kernel<KeyT, Src>), dim3(p.n_wg), dim3(BS_WIDE), lds, s, src, n, p.per, p.shift, p.n_bin, w.keys0,
+  hipLaunchKernelGGL((bs_count_kernel<KeyT, Src>), dim3(p.n_wg), dim3(BS_WIDE), 0, s, src, n, p.per, p.shift, p.n_bin, w.keys0,
                      w.table);
   const int col_wg = (p.n_bin / 4 + BS_COL_THREADS - 1) / BS_COL_THREADS;
   hipLaunchKernelGGL(bs_colscan_kernel, dim3(col_wg), dim3(BS_COL_THREADS), 0, s, w.table, w.before, p.n_wg, p.n_bin, w.fstart);
   hipLaunchKernelGGL((bs_scatter_kernel<KeyT, DEDUP>), dim3(p.n_wg), dim3(BS_WIDE), 0, s, w.keys0, n, p.per, p.shift, p.n_bin, w.before,
-                     w.fstart, p.target, p.n_bucket, w.keys1, w.vals1, w.bstart, w.win);
+                     w.fstart, w.keys1, w.vals1, w.win, DEDUP ? w.n_kept : static_cast<int32_t*>(nullptr), w.bits, w.n_words, w.ccnt,
+                     w.n_chunks);
 }
 }  // namespace
+
+size_t bucket_sort_ws_bytes(int key_bits, int64_t n) {
+  const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
+  const size_t k = ((nn + BS_PAD_KEYS) * (key_bits / 8) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
+  return 2 * k + v + (2 * size_t(BS_MAX_WG) * BS_MAX_BIN + BS_MAX_BIN + 64 + 2 * (nn / BS_PART + 2) + 2 + chunks_for(n) + words_for(n)) * 4;
+}
 
 template <typename KeyT>
 static int pack_sort_t(const int4* coords, int64_t n, const PackParams& pp, int used_bits, int32_t* status, void* keys_out,
@@ -734,10 +561,12 @@ static int mask_unique_t(const void* keys_in, int64_t n, uint64_t mask, int used
   const BucketPlan p = bucket_plan(n, used_bits);
   const Ws<KeyT> w = carve<KeyT>(ws, n);
   partition<KeyT, true>(SrcMask<KeyT>{static_cast<const KeyT*>(keys_in), static_cast<KeyT>(mask)}, n, p, w, s);
-  // distinct keys of every bucket land at the start of its range in keys0 (free again by now)
-  hipLaunchKernelGGL(bs_unique_kernel<KeyT>, dim3(p.n_bucket), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.bstart, w.keys0, w.ucount);
-  hipLaunchKernelGGL(bs_gather_kernel<KeyT>, dim3(std::min(p.n_bucket, 256)), dim3(BS_THREADS), 0, s, w.keys0, w.bstart, w.ucount,
-                     p.n_bucket, static_cast<KeyT*>(keys_out), n_out);
+  // the sorted keys (with gaps) go to keys0, which is free again by now
+  const int n_part = static_cast<int>((n + BS_PART - 1) / BS_PART), n_chunk = static_cast<int>((n + BS_CHUNK - 1) / BS_CHUNK);
+  hipLaunchKernelGGL(bs_rank_unique_kernel<KeyT>, dim3(n_part), dim3(BS_THREADS), 0, s, w.keys1, w.win, w.n_kept, w.keys0, w.bits,
+                     w.ccnt);
+  hipLaunchKernelGGL(bs_compact_kernel<KeyT>, dim3(n_chunk), dim3(BS_THREADS), 0, s, w.keys0, w.bits, w.ccnt, w.n_kept,
+                     static_cast<KeyT*>(keys_out), n_out);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "downsample launch failed");
   return SPC_OK;
 }

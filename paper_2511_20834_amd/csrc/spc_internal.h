@@ -109,14 +109,11 @@ __device__ inline KeyT pack_key(const int4 c, const PackParams& p, int32_t* stat
 constexpr int BS_MAX_WG = 64;       // workgroups of the count / scatter passes
 constexpr int BS_MAX_BIN_BITS = 12;
 constexpr int BS_MAX_BIN = 1 << BS_MAX_BIN_BITS;  // fine bins (top used key bits)
-constexpr int BS_TARGET = 512;      // keys per bucket aimed at
 constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 2048 * 1024;  // sizes it is used for; rocPRIM outside
-constexpr int BS_MAX_BUCKET = static_cast<int>(BS_MAX_N / BS_TARGET);
 constexpr int BS_PART = 64;         // keys per rank workgroup
-constexpr int BS_MAX_PART = static_cast<int>(BS_MAX_N / BS_PART);
 constexpr int BS_PAD_KEYS = 32;     // all-ones keys kept behind the scattered keys
 struct BucketPlan {
-  int n_wg, per, shift, n_bin, target, n_bucket;
+  int n_wg, per, shift, n_bin;
 };
 BucketPlan bucket_plan(int64_t n, int used_bits);
 size_t bucket_sort_ws_bytes(int key_bits, int64_t n);
