@@ -399,20 +399,26 @@ __global__ __launch_bounds__(BS_THREADS) void bs_rank_unique_kernel(const KeyT* 
     const bool far = act && rel >= 64 * 32;
     if (act && !far) atomicOr(&lbits[rel >> 5], 1u << (rel & 31));
     __builtin_amdgcn_wave_barrier();
-    const int word_i = far ? r >> 5 : (g0 >> 5) + lane;
-    const uint32_t word = far ? 1u << (r & 31) : lbits[lane];
-    int fresh = 0;
-    if (word) fresh = __popc(word & ~atomicOr(&bits[word_i], word));
-    const int chunk = word_i / (BS_CHUNK / 32);
-    unsigned long long todo = __ballot(fresh > 0);
-    while (todo) {
-      const int leader = __builtin_ctzll(todo);
-      const int c = __shfl(chunk, leader, 64);
-      const bool mine = fresh > 0 && chunk == c;
-      int sum = mine ? fresh : 0;
-      for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
-      if (lane == leader) atomicAdd(&ccnt[c], sum);
-      todo &= ~__ballot(mine);
+    // lane i then owns word i of the 64; a position beyond them (a very large window) goes to the
+    // global bitmap on its own, in a second round
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+      const int word_i = round == 0 ? (g0 >> 5) + lane : r >> 5;
+      const uint32_t word = round == 0 ? lbits[lane] : (far ? 1u << (r & 31) : 0u);
+      if (round == 1 && !__ballot(far)) break;  // uniform
+      int fresh = 0;
+      if (word) fresh = __popc(word & ~atomicOr(&bits[word_i], word));
+      const int chunk = word_i / (BS_CHUNK / 32);
+      unsigned long long todo = __ballot(fresh > 0);
+      while (todo) {
+        const int leader = __builtin_ctzll(todo);
+        const int c = __shfl(chunk, leader, 64);
+        const bool mine = fresh > 0 && chunk == c;
+        int sum = mine ? fresh : 0;
+        for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+        if (lane == leader) atomicAdd(&ccnt[c], sum);
+        todo &= ~__ballot(mine);
+      }
     }
   }
 }

@@ -168,6 +168,24 @@ def test_kmap_on_coarse_level():
     down.destroy()
 
 
+@pytest.mark.parametrize("name,key_bits", [("rand_n70001", 0), ("rand_n70001", 64), ("skew_60k", 0), ("slab_12k", 0),
+                                           ("slab_12k", 64), ("rand_n4097", 0), ("rand_n600001", 0)])
+def test_downsampled_levels_match_oracle(name, key_bits):
+    """Levels 2, 4 and 8 straight from V_0 (Section 5.5) on clouds large enough for the library's own
+    sort path: dense slabs (thousands of keys in one bin), skewed densities, both key widths."""
+    c = _cloud(name)
+    desc = fit_desc(c, [(2, 4, 2)], key_bits)
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    maps = B.spc_build_kmaps_network(keys, desc, [(2, s, 2, 0, B.LAYOUT_OS) for s in (1, 2, 4)])
+    for m, stride in zip(maps, (2, 4, 8)):
+        ref = oracle_keys(oracle.downsample(cs, stride), desc)
+        assert m.n_out == len(ref)
+        assert np.array_equal(m.out_keys(), ref), stride
+    for m in maps:
+        m.destroy()
+
+
 def test_kmap_empty_input():
     desc = B.spc_pack_desc_fit([0, 0, 0], [10, 10, 10], 1, 2, 1)
     keys = torch.empty(0, dtype=torch.int32, device="cuda")
