@@ -300,6 +300,10 @@ def main() -> int:
     else:
         map_bytes = n * key_b + n_out * key_b + nnz * 8 + K3 * 4
     kmap_gbs = map_bytes / (phase_ms["kmap_build"] * 1e-3) / 1e9
+    # compulsory bytes of the feature kernel: every input and output row once, the weights once, the map once
+    elt = 4 if tdt == torch.float32 else 2
+    conv_bytes = (n * cin + n_out * cout + K3 * cin * cout) * elt + (n_out * K3 * 4 if layout == B.LAYOUT_OS else nnz * 8)
+    conv_gbs = conv_bytes / (phase_ms["conv"] * 1e-3) / 1e9
     if tdt == torch.float32:
         roof = {"kernel": "conv_%s_simple_kernel" % ("os" if dataflow == B.DATAFLOW_OS else "ws"), "bound": "alu",
                 "achieved": conv_tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
@@ -330,7 +334,8 @@ def main() -> int:
         "parts": {"phase_ms": phase_ms,
                   "kmap_build_Mvoxel_offsets_per_s": voxel_offsets / (phase_ms["kmap_build"] * 1e-3) / 1e6,
                   "kmap_build_algorithmic_GBps": kmap_gbs, "kmap_build_frac_of_hbm_peak": kmap_gbs / PEAK_HBM_GBS,
-                  "conv_useful_TFLOPs": conv_tflops, "conv_frac_of_mfma_peak": conv_tflops / PEAK_MFMA_F16_TFLOPS},
+                  "conv_useful_TFLOPs": conv_tflops, "conv_frac_of_mfma_peak": conv_tflops / PEAK_MFMA_F16_TFLOPS,
+                  "conv_compulsory_GBps": conv_gbs, "conv_frac_of_hbm_peak": conv_gbs / PEAK_HBM_GBS},
         "roofline": roof,
     }
 
