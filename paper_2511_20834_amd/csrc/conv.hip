@@ -174,6 +174,17 @@ __host__ __device__ inline int64_t phase_tiles_per_xcd(int64_t n_tiles) {
   return (n_chunks + 7) / 8 * PHASE_XCD_CHUNK;
 }
 
+// Workgroups per XCD: as few as hold the XCD's tiles with every wave busy, but not fewer than the XCD has
+// CUs for this launch (32, shared by the slabs of output channels): one workgroup fills a CU's LDS, so a launch
+// with fewer workgroups than CUs leaves CUs idle while the others gather at a fixed rate per CU; better that
+// every CU runs a workgroup with some of its waves idle.
+__host__ __device__ inline int phase_wgs_per_xcd(int64_t tiles_per_xcd, int waves, int n_slabs) {
+  const int64_t full = (tiles_per_xcd + waves - 1) / waves;
+  const int64_t spread = 32 / n_slabs > 1 ? 32 / n_slabs : 1;
+  const int64_t s = spread < tiles_per_xcd ? spread : tiles_per_xcd;
+  return static_cast<int>(full > s ? full : s);
+}
+
 template <typename T, int NB, int RB, int WAVES, int NKK, int D>
 __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t* __restrict__ M,
                                                                    const uint32_t* __restrict__ block_masks,
@@ -213,7 +224,7 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
   // The grid was sized from the host's bound of the output count; the count itself may only be known
   // here.  Only as many workgroups as that count fills take part (all of their waves busy) and
   // the tiles of an XCD are dealt to them round-robin; the others leave at once.
-  const int n_wg_used = static_cast<int>((tiles_per_xcd + WAVES - 1) / WAVES);
+  const int n_wg_used = phase_wgs_per_xcd(tiles_per_xcd, WAVES, gridDim.y);
   if (wg_in_xcd >= n_wg_used) return;
   const int64_t t_in_xcd = int64_t(wave) * n_wg_used + wg_in_xcd;
   const int64_t tile = ((t_in_xcd / PHASE_XCD_CHUNK) * 8 + xcd) * PHASE_XCD_CHUNK + t_in_xcd % PHASE_XCD_CHUNK;
@@ -822,7 +833,7 @@ static void launch_os_mfma(const ConvArgs& a, const T* Wp, const float* init) {
   const int64_t n_blocks = (a.rows_cap + 31) / 32;
   const int64_t n_tiles = (n_blocks + RBK - 1) / RBK;
   const int64_t tiles_per_xcd = phase_tiles_per_xcd(n_tiles);
-  const int per_xcd = static_cast<int>((tiles_per_xcd + WAVES - 1) / WAVES);
+  const int per_xcd = phase_wgs_per_xcd(tiles_per_xcd, WAVES, n_slabs);
   const size_t lds = 2 * HALF_BYTES + size_t(WAVES) * KLIST_CAP * 2;
   auto go = [&](auto NKK_) {
     constexpr int NKK = decltype(NKK_)::value;
@@ -897,14 +908,14 @@ static void launch_os_splitk_any(const ConvArgs& a, const T* Wp, const float* in
 }
 
 // Measured crossover on MI355X (3x3x3 layers, 32..256 channels, 18 k / 49 k / 120 k voxels): the phase
-// kernel wins once it has about 160 workgroups (16 row blocks each, per slab of output channels) to
-// spread over the 256 CUs; with fewer, the split-k kernel's many short workgroups win by up to 5x in
-// spite of their redundant weight reads.  Large kernels (5x5x5 and up) favour the split-k kernel at
-// every size measured.
+// kernel wins once its tiles fill about 64 sixteen-wave workgroups (16 row blocks each, per slab of
+// output channels; they are dealt to up to 256 workgroups, see phase_wgs_per_xcd); below that the
+// split-k kernel's many short workgroups win in spite of their redundant weight reads.  Large
+// kernels (5x5x5 and up) favour the split-k kernel at every size measured.
 static bool prefer_splitk(const ConvArgs& a) {
   const int64_t n_blocks = (a.rows_sel + 31) / 32;
   const int n_slabs = a.cout % 64 == 0 ? a.cout / 64 : a.cout / 32;
-  return (n_blocks + 15) / 16 * n_slabs < 160 || a.m->K3 > 64;
+  return (n_blocks + 15) / 16 * n_slabs < 64 || a.m->K3 > 64;
 }
 
 template <typename T, int NB, int RB>
