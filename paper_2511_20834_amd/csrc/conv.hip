@@ -838,12 +838,11 @@ static void launch_os_mfma(const ConvArgs& a, const T* Wp, const float* init) {
   auto go = [&](auto NKK_) {
     constexpr int NKK = decltype(NKK_)::value;
     const int cpp = std::max(1, HALF_BYTES / (16 * NKK * NB * 32 * int(sizeof(T))));
-    static bool attr_set = false;  // one per instantiation
-    if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-      attr_set = true;
-    }
+    // once per instantiation (initialisation of a local static is thread-safe); a failure shows up as a failed launch
+    static const hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    (void)attr;
     hipLaunchKernelGGL((conv_os_phase_kernel<T, NB, RBK, WAVES, NKK, DEPTH>), dim3(per_xcd * 8, n_slabs), dim3(64 * WAVES), lds,
                        a.s, a.m->os_map, a.m->block_masks, a.m->mask_words, a.n_out_h, a.n_out_d, a.m->K3,
                        static_cast<const T*>(a.F), a.ld_in, Wp, static_cast<T*>(a.out), a.ld_out, a.cin, a.relu, cpp, per_xcd,
@@ -868,14 +867,15 @@ static void launch_os_splitk(const ConvArgs& a, const T* Wp, const float* init) 
   const bool loop = a.rows_sel != a.rows_cap;
   const int64_t n_blocks = std::max<int64_t>((a.rows_sel + 31) / 32, 1);
   const size_t lds = splitk_lds_bytes(a.m->K3, NB, RB);
-  static size_t lds_attr = 64 * 1024;  // one per instantiation
-  if (lds > lds_attr) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D, false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D, true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    lds_attr = lds;
-  }
+  // once per instantiation: both variants may use all of a CU's LDS (large kernels need more than the default 64 KB)
+  static const hipError_t attr = [] {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D, false>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    const hipError_t f = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_os_splitk_kernel<T, NB, RB, D, true>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return e != hipSuccess ? e : f;
+  }();
+  (void)attr;
   constexpr int EPT = NB * 4;
   T* out = static_cast<T*>(a.out);
   const int vec = a.ld_out % EPT == 0 && reinterpret_cast<uintptr_t>(out) % (EPT * sizeof(T)) == 0;

@@ -39,7 +39,7 @@ def _cloud(name):
         c = synth.random_cloud(n, (300, 280, 40), seed=40 + n % 7, batch=2)[:n]
         c[:, 1:] -= 100
         return c
-    if name == "skew_60k":  # half of the voxels in 3 of 400 x-planes: buckets of very different sizes
+    if name == "skew_60k":  # half of the voxels in 3 of 400 x-planes: bins of very different sizes
         a = synth.random_cloud(30000, (400, 200, 60), seed=51)
         b = synth.random_cloud(30000, (3, 200, 60), seed=52)
         b[:, 1] += 197
