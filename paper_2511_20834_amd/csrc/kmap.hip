@@ -40,71 +40,96 @@ __device__ inline int lanemask_lt_popc(unsigned long long m) {
   return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(m >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(m), 0));
 }
 
-// S simultaneous wave-wide searches over keys[0,n).  upper[s]=false: first index with
-// key >= q; true: first index with key > q.  All lanes get the results.  Each round
-// every lane probes the last key of its 1/64 slice; the ballot tells the slice that
-// holds the answer.  The first round probes the same 64 keys for every search of every
-// workgroup, so the caller loads them once (`probe`, one per lane) and that round costs no
-// memory access; 2^18 keys then need two dependent loads per search, all S searches of a
-// wave in flight together.  The searches stop once every answer is known to within `slack`
-// positions and return the outer ends (slack 0: exact bounds): a window that is a few keys
-// too wide costs less than another round of dependent loads.
-template <typename KeyT, int S>
-__device__ inline void wave_bounds(const KeyT* __restrict__ keys, int n, KeyT probe, const KeyT (&q)[S],
-                                   const bool (&upper)[S], int (&res)[S], int slack) {
-  const int lane = threadIdx.x & 63;
-  int lo[S], hi[S];
+// Window-bound searches over keys[0,n): groups of P lanes run one search each (64/P searches per wave
+// instruction), U passes of them interleaved so that the loads of all passes are in flight together.
+// upper=false: first index with key >= q; true: first index with key > q.  q and upper are the same
+// in all lanes of a group, and odd groups search upper bounds.  The first round needs no memory
+// access: every search starts from the same 64 probes (the last key of every 1/64 slice, loaded once
+// per workgroup, one per lane), and a ballot per group tells the slice that holds the answer.  From then on
+// lane p of a group probes the last key of the p-th of P sub-slices, and the group's bits of the ballot
+// give the sub-slice.  The searches stop once every answer is known to within `slack` positions and return
+// the outer ends (slack 0: exact bounds): a window that is a few keys too wide costs less than
+// another round of dependent loads.  P = 16 reads 16 cache lines per search and round where a search
+// by the whole wave read 64, for the same number of dependent rounds at these sizes (2^18 keys:
+// 4096 -> 256 -> 16); with 25 groups of offsets the wave-wide form spent most of the kernel
+// fetching probe lines.
+template <typename KeyT>
+__device__ inline KeyT lane_value(KeyT v, int src_lane) {
+  if constexpr (sizeof(KeyT) == 4) {
+    return static_cast<KeyT>(__builtin_amdgcn_readlane(static_cast<int>(v), src_lane));
+  } else {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v)), src_lane);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v >> 32)), src_lane);
+    return (static_cast<KeyT>(hi) << 32) | lo;
+  }
+}
+
+template <typename KeyT, int P, int U>
+__device__ inline void group_bounds(const KeyT* __restrict__ keys, int n, KeyT probe, const KeyT (&q)[U], int (&res)[U],
+                                    int slack) {
+  constexpr int Q = 64 / P;
+  static_assert(Q % 2 == 0, "odd groups search upper bounds");
+  const int lane = threadIdx.x & 63, grp = lane / P, p = lane % P;
+  const bool upper = (grp & 1) != 0;
   const int chunk0 = (n + 63) >> 6;
+  const bool has_probe = (long long)lane * chunk0 < n;  // lanes past the last slice hold no probe
+  int lo[U], hi[U];
 #pragma unroll
-  for (int s = 0; s < S; ++s) {
-    // lanes past the last slice hold no probe; their predicate is false
-    const bool pr = (long long)lane * chunk0 < n && (upper[s] ? (probe <= q[s]) : (probe < q[s]));
-    const int c = __popcll(__ballot(pr));
+  for (int u = 0; u < U; ++u) {
+    int c = 0;
+#pragma unroll
+    for (int g = 0; g < Q; ++g) {
+      const KeyT qg = lane_value(q[u], g * P);
+      const bool pr = has_probe && ((g & 1) ? (probe <= qg) : (probe < qg));
+      const int cg = __popcll(__ballot(pr));
+      c = grp == g ? cg : c;
+    }
     if ((long long)c * chunk0 >= n) {  // every slice lies before the answer (or there are no keys)
-      lo[s] = n;
-      hi[s] = n;
+      lo[u] = n;
+      hi[u] = n;
     } else {
-      lo[s] = c * chunk0;
-      hi[s] = min(lo[s] + chunk0 - 1, n - 1);
+      lo[u] = c * chunk0;
+      hi[u] = min(lo[u] + chunk0 - 1, n - 1);
     }
   }
-  auto widest = [&]() {
+  auto unfinished = [&]() {
     int maxlen = 0;
 #pragma unroll
-    for (int s = 0; s < S; ++s) maxlen = max(maxlen, hi[s] - lo[s]);
-    return maxlen;
+    for (int u = 0; u < U; ++u) maxlen = max(maxlen, hi[u] - lo[u]);
+    return __ballot(maxlen > slack) != 0;
   };
-  while (widest() > slack) {
-    bool pred[S];
-    int chunk[S];
+  while (unfinished()) {  // every round shortens every unfinished search
+    bool pred[U];
+    int chunk[U];
 #pragma unroll
-    for (int s = 0; s < S; ++s) {
-      const int len = hi[s] - lo[s];
-      chunk[s] = (len + 63) >> 6;
-      const long long first = (long long)lo[s] + (long long)lane * chunk[s];
-      // clamped, unconditional load: all S loads of a round are issued back to back
-      const long long idx = max(0ll, min(min(first + chunk[s] - 1, (long long)hi[s] - 1), (long long)n - 1));
+    for (int u = 0; u < U; ++u) {
+      const int len = hi[u] - lo[u];
+      chunk[u] = (len + P - 1) / P;
+      const long long first = (long long)lo[u] + (long long)p * chunk[u];
+      // clamped, unconditional load: the loads of all passes are issued back to back
+      const long long idx = max(0ll, min(min(first + chunk[u] - 1, (long long)hi[u] - 1), (long long)n - 1));
       const KeyT v = keys[idx];
-      pred[s] = len > 0 && first < hi[s] && (upper[s] ? (v <= q[s]) : (v < q[s]));
+      pred[u] = len > 0 && first < hi[u] && (upper ? (v <= q[u]) : (v < q[u]));
     }
 #pragma unroll
-    for (int s = 0; s < S; ++s) {
-      const int len = hi[s] - lo[s];
+    for (int u = 0; u < U; ++u) {
+      const int len = hi[u] - lo[u];
+      const unsigned long long bal = __ballot(pred[u]);
       if (len > 0) {
-        const int c = __popcll(__ballot(pred[s]));
-        const int nlo = lo[s] + c * chunk[s];
-        if (c * chunk[s] >= len) {  // every slice lies before the answer
-          lo[s] = hi[s];
+        const int c = __popcll((bal >> (grp * P)) & ((1ull << P) - 1));
+        const int nlo = lo[u] + c * chunk[u];
+        if (c * chunk[u] >= len) {  // every sub-slice lies before the answer
+          lo[u] = hi[u];
         } else {
-          hi[s] = min(nlo + chunk[s] - 1, hi[s] - 1);
-          lo[s] = nlo;
+          hi[u] = min(nlo + chunk[u] - 1, hi[u] - 1);
+          lo[u] = nlo;
         }
       }
     }
   }
   // the answer lies in [lo, hi]: the low end for a window start, the high end for a window end
 #pragma unroll
-  for (int s = 0; s < S; ++s) res[s] = upper[s] ? hi[s] : lo[s];
+  for (int u = 0; u < U; ++u) res[u] = upper ? hi[u] : lo[u];
 }
 
 // Per-lane lower bound in a window of wsz keys (used for windows that stay in global memory).
@@ -133,7 +158,10 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
   constexpr int WIN_CAP = WIN_CAP_BYTES / sizeof(KeyT);
   constexpr int NW = SEARCH_THREADS / 64;
-  constexpr int BOUND_SLACK = G <= 9 ? 32 : 8;  // extra keys per window end: 2 * G * slack must stay small next to WIN_CAP
+  // lanes per window-bound search: with many groups of offsets the probe lines fetched count for more than the
+  // number of dependent rounds (240 k voxels, 5x5x5: 16 lanes 98.6 us, 8 lanes 94.6, 4 lanes 92.2)
+  constexpr int BOUND_P = G <= 9 ? 16 : 4;
+  constexpr int BOUND_SLACK = G <= 9 ? 32 : 16;  // extra keys per window end: 2 * G * slack must stay small next to WIN_CAP
   extern __shared__ __align__(16) unsigned char smem[];
   KeyT* okeys = reinterpret_cast<KeyT*>(smem);   // [tile]
   KeyT* win = okeys + tile;                      // [WIN_CAP]
@@ -169,25 +197,25 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const KeyT kfirst = okeys[0], klast = okeys[rows - 1];
   const KeyT zspan = KeyT(K - 1) * sp.zstep;
 
-  // ---- window bounds: search s = 2*g + side, dealt round-robin to the waves, S at a time
-  constexpr int S = (2 * G + NW - 1) / NW < 5 ? (2 * G + NW - 1) / NW : 5;
-  for (int s0 = wave * S; s0 < 2 * g_lim; s0 += NW * S) {
-    KeyT q[S];
-    bool up[S];
-    int res[S];
+  // ---- window bounds: search s = 2*g + side; pass u of wave w runs searches (u*NW + w)*Q .. +Q-1, one per group
+  // of BOUND_P lanes (searches past the last one repeat it and are not recorded)
+  {
+    constexpr int Q = 64 / BOUND_P;
+    constexpr int U = (2 * G + NW * Q - 1) / (NW * Q);
+    const int grp = lane / BOUND_P;
+    KeyT q[U];
+    int res[U];
 #pragma unroll
-    for (int j = 0; j < S; ++j) {
-      const int s = min(s0 + j, 2 * G - 1);
-      const KeyT d = s_gd[s >> 1];
-      up[j] = (s & 1) != 0;
-      q[j] = up[j] ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
+    for (int u = 0; u < U; ++u) {
+      const int sc = min((u * NW + wave) * Q + grp, 2 * G - 1);
+      const KeyT d = s_gd[sc >> 1];
+      q[u] = (grp & 1) ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
     }
-    wave_bounds<KeyT, S>(in_keys, n_in, probe, q, up, res, BOUND_SLACK);
-    if (lane < S && s0 + lane < 2 * g_lim) {
-      int r = res[0];
+    group_bounds<KeyT, BOUND_P, U>(in_keys, n_in, probe, q, res, BOUND_SLACK);
 #pragma unroll
-      for (int j = 1; j < S; ++j) r = (lane == j) ? res[j] : r;
-      s_bound[s0 + lane] = r;
+    for (int u = 0; u < U; ++u) {
+      const int sc = (u * NW + wave) * Q + grp;
+      if (lane % BOUND_P == 0 && sc < 2 * g_lim) s_bound[sc] = res[u];
     }
   }
   __syncthreads();
