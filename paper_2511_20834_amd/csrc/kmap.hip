@@ -154,6 +154,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
     const int32_t* __restrict__ in_perm, int k_lim) {
   constexpr int G = K * K, K3 = K * K * K;
+  constexpr int G_POW2 = G <= 1 ? 1 : G <= 4 ? 4 : G <= 16 ? 16 : G <= 64 ? 64 : 128;  // power of two >= G
   constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
   constexpr int WIN_CAP = WIN_CAP_BYTES / sizeof(KeyT);
@@ -252,8 +253,15 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       const int e = e0 + i * SEARCH_THREADS + tid;
       tmp[i] = 0;
       if (e < total) {
+        // groups whose staged window ends at or before e form a prefix (windows that do not fit, marked -1,
+        // are a suffix): count them by bit steps instead of walking up to K^2 entries
         int g = 0;
-        while (g + 1 < G && s_wend[g + 1] >= 0 && e >= s_wend[g + 1]) ++g;
+#pragma unroll
+        for (int bit = G_POW2 >> 1; bit > 0; bit >>= 1) {
+          const int t = g + bit;
+          const int we = s_wend[min(t, G)];
+          g = (t < G && we >= 0 && e >= we) ? t : g;
+        }
         tmp[i] = in_keys[s_wlo[g] + (e - s_woff[g])];
       }
     }
