@@ -166,6 +166,7 @@ __device__ inline void contract_offset(const T* __restrict__ F, int64_t ld_in, c
 // which gather the same feature rows, run on the same XCD and share its L2.
 constexpr int HALF_BYTES = 72 * 1024;  // 9 offsets of 64x64 fp16: one x-slab of a 3x3x3 kernel per phase
 constexpr int KLIST_CAP = 352;  // >= 7^3
+constexpr int WS_MAX_K3 = 343;  // 7^3: the largest kernel the library takes
 __device__ __align__(16) uint32_t g_zero_row[64];  // zero-initialised, never written
 
 constexpr int PHASE_XCD_CHUNK = 16;  // tiles (of two 32-row blocks) per chunk; 4 to 64 measured alike
@@ -657,24 +658,51 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_ws_mfma_kernel(const int32_
   extern __shared__ __align__(16) unsigned char smem[];
   V8* sB = reinterpret_cast<V8*>(smem);
   __shared__ int s_out[TROWS], s_in[TROWS];
-  const int k = blockIdx.y;
-  if (!kmask.has(k)) return;  // whole workgroup
+  __shared__ int s_first[WS_MAX_K3 + 1];  // first work item of every offset; [n_k] = number of items
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lh = lane >> 5;
+  // The list lengths only exist on the device, so the grid cannot be cut to the work: a fixed number of
+  // workgroups walks the items (offset k, chunk of TROWS pairs) with a grid stride.  Every workgroup
+  // numbers the items itself: chunks per offset, scanned by wave 0.
   // symmetric half-map: lists exist for k < centre; the centre offset pairs every voxel with itself
   const int kc = (K3 - 1) / 2;
+  const int n_k = sym ? kc + 1 : K3;
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  if (wave == 0) {
+    int carry = 0;
+    for (int k0 = 0; k0 < n_k; k0 += 64) {
+      const int k = k0 + lane;
+      int c = 0;
+      if (k < n_k && kmask.has(k)) c = ((sym && k == kc ? n_out : nnz[k]) + TROWS - 1) / TROWS;
+      int x = c;
+      for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+      }
+      if (k < n_k) s_first[k] = carry + x - c;
+      carry += __shfl(x, 63, 64);
+    }
+    if (lane == 0) s_first[n_k] = carry;
+  }
+  __syncthreads();
+  const int n_items = s_first[n_k];
+  const int cout = NB * 32;
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  // last offset whose first item is <= item (offsets without items share their successor's first item)
+  int k = 0;
+  for (int bit = 256; bit > 0; bit >>= 1)
+    if (k + bit < n_k && s_first[k + bit] <= item) k += bit;
   const bool centre = sym && k == kc;
-  const int cnt = centre ? (n_out_d ? *n_out_d : n_out_h) : nnz[k];
-  const int p0 = blockIdx.x * TROWS;
-  if (p0 >= cnt) return;
+  const int cnt = centre ? n_out : nnz[k];
+  const int p0 = (item - s_first[k]) * TROWS;
   const int rows = min(TROWS, cnt - p0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lh = lane >> 5;
   const int32_t* li = ws_in + int64_t(k) * ws_stride + p0;
   const int32_t* lo = ws_out + int64_t(k) * ws_stride + p0;
+  __syncthreads();  // everybody is done with the item before (its index lists and its weights)
   for (int r = tid; r < TROWS; r += CONV_THREADS) {
     s_out[r] = r < rows ? (centre ? p0 + r : lo[r]) : -1;
     s_in[r] = r < rows ? (centre ? p0 + r : li[r]) : -1;
   }
   __syncthreads();
-  const int cout = NB * 32;
   // pass 0: F[in] W_k -> out.  pass 1 (symmetric maps, not the centre): F[out] W_{K^3-1-k} -> in
   const int passes = (sym && !centre) ? 2 : 1;
   for (int pass = 0; pass < passes; ++pass) {
@@ -711,6 +739,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_ws_mfma_kernel(const int32_
         }
       }
   }
+  }  // items
 }
 
 // ---------------------------------------------------------------- plain FMA kernels
@@ -922,9 +951,12 @@ template <typename T, int NB, int RB>
 static void launch_ws_mfma(const ConvArgs& a, const T* Wp, float* accum) {
   constexpr int TROWS = 128 * RB;
   const size_t lds = size_t(CK / 16) * NB * 64 * 16;
-  const int gx = static_cast<int>((a.rows_cap + TROWS - 1) / TROWS);
+  // at most this many items exist (every offset's list holds at most one pair per output row); the grid stops
+  // at a few workgroups per CU and strides
   const int gy = a.m->sym ? (a.m->K3 - 1) / 2 + 1 : a.m->K3;  // a symmetric map is walked up to the centre offset
-  hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx, gy), dim3(CONV_THREADS), lds, a.s, a.m->ws_in, a.m->ws_out,
+  const int64_t max_items = ((a.rows_cap + TROWS - 1) / TROWS) * gy;
+  const int gx = static_cast<int>(std::min<int64_t>(max_items, 2048));
+  hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx), dim3(CONV_THREADS), lds, a.s, a.m->ws_in, a.m->ws_out,
                      a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin, a.ws_mask,
                      a.m->sym ? 1 : 0, a.m->K3, a.n_out_h, a.n_out_d);
 }

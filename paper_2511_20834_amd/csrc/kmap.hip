@@ -442,6 +442,7 @@ __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile
 // One workgroup per tile of the search kernel.  In the blocked map a column (fixed k) of a
 // 32-row block is contiguous, so a wave filters two blocks of one offset per step with a
 // coalesced load and a ballot; list k comes out ordered by output index without atomics.
+constexpr int WS_FILL_U = 8;
 __global__ __launch_bounds__(256) void ws_fill_kernel(const int32_t* __restrict__ M, int n_out_h,
                                                       const int* __restrict__ n_out_d, int K3, int tile,
                                                       const int32_t* __restrict__ tile_base, int n_tiles_cap,
@@ -453,20 +454,38 @@ __global__ __launch_bounds__(256) void ws_fill_kernel(const int32_t* __restrict_
   const int rows = min(tile, n_out - i0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t b0 = int64_t(i0) >> 5;
-  for (int k = wave; k < k_lim; k += 4) {
-    int base = tile_base[int64_t(k) * n_tiles_cap + blockIdx.x];
-    int32_t* li = ws_in + int64_t(k) * ws_stride;
-    int32_t* lo = ws_out + int64_t(k) * ws_stride;
-    for (int v0 = 0; v0 < rows; v0 += 64) {
-      const int v = v0 + lane;
-      const int j = v < rows ? M[((b0 + (v >> 5)) * K3 + k) * 32 + (v & 31)] : -1;
-      const unsigned long long m = __ballot(j >= 0);
-      if (j >= 0) {
-        const int r = base + lanemask_lt_popc(m);
-        li[r] = j;
-        lo[r] = i0 + v;
+  // a wave takes WS_FILL_U offsets at a time: their list positions and all their map entries of the tile
+  // (at most 128 rows: two per lane) are requested together, then compacted offset by offset
+  constexpr int U = WS_FILL_U;
+  for (int k0 = wave * U; k0 < k_lim; k0 += 4 * U) {
+    int base[U], j[U][2];
+#pragma unroll
+    for (int u = 0; u < U; ++u) base[u] = tile_base[int64_t(min(k0 + u, k_lim - 1)) * n_tiles_cap + blockIdx.x];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int v = h * 64 + lane;
+        const int vc = min(v, rows - 1);
+        const int e = M[((b0 + (vc >> 5)) * K3 + min(k0 + u, k_lim - 1)) * 32 + (vc & 31)];
+        j[u][h] = v < rows ? e : -1;
       }
-      base += __popcll(m);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (k0 + u >= k_lim) break;
+      int32_t* li = ws_in + int64_t(k0 + u) * ws_stride;
+      int32_t* lo = ws_out + int64_t(k0 + u) * ws_stride;
+      int at = base[u];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const unsigned long long m = __ballot(j[u][h] >= 0);
+        if (j[u][h] >= 0) {
+          const int r = at + lanemask_lt_popc(m);
+          li[r] = j[u][h];
+          lo[r] = i0 + h * 64 + lane;
+        }
+        at += __popcll(m);
+      }
     }
   }
 }
