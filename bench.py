@@ -311,11 +311,13 @@ def main() -> int:
                 "achieved": conv_tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
                 "frac": conv_tflops / PEAK_FP32_TFLOPS, "traffic": None}
     else:
-        # the library picks the split-k kernel when the phase kernel would fill fewer than 64 workgroups
-        # (16 row blocks each, per slab of 64 or 32 output channels) and for kernels larger than 4x4x4
+        # the library's choice between its two OS kernels (prefer_splitk in csrc/conv.hip): the split-k kernel for
+        # kernels larger than 4x4x4, for layers whose tiles fill fewer than 64 phase workgroups (16 row blocks
+        # each, per slab of 64 or 32 output channels), and for layers with little work behind every tile
         n_slabs = cout // 64 if cout % 64 == 0 else cout // 32
         phase_wgs = ((n_out + 31) // 32 + 15) // 16 * n_slabs
-        os_kernel = "conv_os_splitk_kernel" if (phase_wgs < 64 or K3 > 64) else "conv_os_phase_kernel"
+        splitk = K3 > 64 or phase_wgs < 64 or phase_wgs * cin < (7000 if cout % 64 == 0 else 16000)
+        os_kernel = "conv_os_splitk_kernel" if splitk else "conv_os_phase_kernel"
         roof = {"kernel": os_kernel if dataflow == B.DATAFLOW_OS else "conv_ws_mfma_kernel", "bound": "mfma",
                 "achieved": conv_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                 "frac": conv_tflops / PEAK_MFMA_F16_TFLOPS, "traffic": None}

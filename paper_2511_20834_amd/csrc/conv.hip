@@ -890,7 +890,10 @@ static size_t splitk_lds_bytes(int K3, int NB, int RB) {
 
 template <typename T, int NB, int RB>
 static void launch_os_splitk(const ConvArgs& a, const T* Wp, const float* init) {
-  constexpr int D = 24 / (RB + NB);  // about 96 registers of loads in flight per lane
+  // entries in flight per wave: two.  Deeper rings cost the registers that hold more waves per SIMD, and the
+  // waves hide more latency than the ring does (25 layers of a UNet on 120 k voxels, all on this kernel: 403 us
+  // summed with 6-12 entries, 352 us with two or three, 391 us with one)
+  constexpr int D = 2;
   const int nb_total = a.cout / 32, n_slabs = nb_total / NB;
   // an estimated output count sizes the grid of the variant that walks tiles with a grid stride
   const bool loop = a.rows_sel != a.rows_cap;
@@ -920,10 +923,11 @@ static void launch_os_splitk(const ConvArgs& a, const T* Wp, const float* init) 
 }
 
 // Row blocks per workgroup of the split-k kernel: more blocks share each weight fragment read
-// (less L2 traffic) but leave fewer workgroups; small levels need the workgroups.
+// (less L2 traffic) but leave fewer workgroups and cost registers; one block measured faster than two
+// at every size (120 k voxels 64->64: 37.4 vs 39.1 us; 240 k voxels 5x5x5 32->32: 37.7 vs 47.7), so two
+// is only taken on request.
 static int splitk_rb(const ConvArgs& a, int NB) {
-  const int64_t n_blocks = (a.rows_sel + 31) / 32;
-  int rb = a.splitk_rb ? a.splitk_rb : (n_blocks >= 1024 ? 2 : 1);
+  int rb = a.splitk_rb ? a.splitk_rb : 1;
   while (rb > 1 && splitk_lds_bytes(a.m->K3, NB, rb) > 80 * 1024) rb >>= 1;
   return rb;
 }
@@ -936,15 +940,21 @@ static void launch_os_splitk_any(const ConvArgs& a, const T* Wp, const float* in
   }
 }
 
-// Measured crossover on MI355X (3x3x3 layers, 32..256 channels, 18 k / 49 k / 120 k voxels): the phase
-// kernel wins once its tiles fill about 64 sixteen-wave workgroups (16 row blocks each, per slab of
-// output channels; they are dealt to up to 256 workgroups, see phase_wgs_per_xcd); below that the
-// split-k kernel's many short workgroups win in spite of their redundant weight reads.  Large
-// kernels (5x5x5 and up) favour the split-k kernel at every size measured.
+// Measured crossover on MI355X (3x3x3 layers, 32..256 channels, 18 k / 49 k / 120 k voxels).  The phase
+// kernel stages every weight once per sixteen row blocks and wins where that matters: enough tiles for
+// 64 sixteen-wave workgroups (per slab of output channels; they are dealt to up to 256 workgroups, see
+// phase_wgs_per_xcd) and enough input channels behind every tile.  Below that the split-k kernel's many
+// short workgroups win in spite of their redundant weight reads: us, phase / split-k, 49 k voxels
+// 32->64 15.2 / 11.6, 64->64 19.4 / 19.1, 64->128 25.5 / 30.6; 18 k voxels 64->64 17.5 / 10.7, 128->128
+// 29.7 / 28.8, 128->256 38.8 / 46.5; 120 k voxels 32->64 20.6 / 22.9, 64->64 30.5 / 37.3.  With 32-column
+// slabs the split-k kernel ties or wins up to 120 k voxels and 64 input channels.  Large kernels
+// (5x5x5 and up) favour the split-k kernel at every size measured.
 static bool prefer_splitk(const ConvArgs& a) {
   const int64_t n_blocks = (a.rows_sel + 31) / 32;
   const int n_slabs = a.cout % 64 == 0 ? a.cout / 64 : a.cout / 32;
-  return (n_blocks + 15) / 16 * n_slabs < 64 || a.m->K3 > 64;
+  const int64_t wgs = (n_blocks + 15) / 16 * n_slabs;
+  if (a.m->K3 > 64 || wgs < 64) return true;
+  return wgs * a.cin < (a.cout % 64 == 0 ? 7000 : 16000);
 }
 
 template <typename T, int NB, int RB>
