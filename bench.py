@@ -347,7 +347,9 @@ def main() -> int:
     # captured graph of the same step; replays go round-robin over the streams, so the latency-bound sort and
     # search kernels of one scene run next to the feature kernel of another.  Reported beside the headline, which
     # stays the one-scene-at-a-time number.
-    if args.scene_streams > 1 and dataflow == B.DATAFLOW_OS and not args.sym and args.hybrid_t is None:
+    # (the step can be captured when the library's own sort runs: 4096 to 2 Mi voxels, see include/spc.h)
+    capturable = 4096 <= n <= 2048 * 1024
+    if args.scene_streams > 1 and capturable and dataflow == B.DATAFLOW_OS and not args.sym and args.hybrid_t is None:
         class Scene:
             def __init__(self):
                 self.coords, self.F = coords.clone(), F_raw.clone()

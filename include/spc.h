@@ -231,7 +231,12 @@ void spc_kmap_destroy(spc_kmap* m);
  * cache holds the scratch sizes of this call (i.e. after one call of the same shape on the same
  * stream), so a warmed-up call sequence can be captured into a HIP graph: spc_pack_coords
  * (without SPC_PACK_VALIDATE), spc_build_kmap(s_network), spc_conv_forward and
- * spc_permute_rows only enqueue kernels, event records and event waits.  Maps built under
+ * spc_permute_rows only enqueue kernels, event records and event waits — as long as every sort
+ * is the library's own, i.e. the cloud (for strided layers: the level that is downsampled) has
+ * between 4096 and 2 097 152 voxels.  Outside that range the sort is rocPRIM's, which also
+ * enqueues memsets; under stream capture spc_pack_coords and the builders then return
+ * SPC_ERR_UNSUPPORTED instead of recording them (replayed memset nodes are not reliable on the
+ * target systems, and a radix sort that starts from stale counters writes out of bounds).  Maps built under
  * capture must stay alive as long as the graph; their accessors that wait (n_out, nnz,
  * export) drain the device and read the values of the latest replay.
  */

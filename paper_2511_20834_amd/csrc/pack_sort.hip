@@ -9,6 +9,18 @@
 namespace spc {
 
 // ---------------------------------------------------------------- sort wrappers
+// The library sort used outside the size range of the library's own sort enqueues more than kernels
+// (its single-pass form clears its digit counters and look-back states with hipMemsetAsync), and such
+// nodes in a captured graph have given wrong results on replays: a stale look-back state sends keys
+// to positions outside the arrays.  Under stream capture these sizes are refused.
+static int refuse_if_capturing(hipStream_t s, int64_t n) {
+  if (!stream_is_capturing(s)) return SPC_OK;
+  return set_error(SPC_ERR_UNSUPPORTED,
+                   "%lld keys are sorted by the library sort, which cannot be recorded into a graph; "
+                   "capture is supported for %d..%d keys",
+                   static_cast<long long>(n), BS_MIN_N, BS_MAX_N);
+}
+
 template <typename KeyT>
 static int sort_pairs_t(const void* ki, void* ko, const int32_t* vi, int32_t* vo, int64_t n, int end_bit, void* temp,
                         size_t& temp_bytes, hipStream_t s) {
@@ -158,6 +170,7 @@ static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, L
     pool_free(scratch, s);  // reuse is ordered behind these kernels on this stream
     return rc;
   }
+  if (n > 0) SPC_RETURN_IF(refuse_if_capturing(s, n));
   const size_t ksz = sizeof(KeyT);
   const size_t tb = sort_keys_temp_bytes(pi.key_bits, n);
   const int n_blocks = static_cast<int>((n + UQ_BLOCK - 1) / UQ_BLOCK);
@@ -247,6 +260,7 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   if (*workspace_bytes < need) return set_error(SPC_ERR_ARG, "workspace too small: %zu < %zu", *workspace_bytes, need);
   if (!coords || !keys_out) return set_error(SPC_ERR_ARG, "NULL coords or keys_out");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!bucket && n > 0) SPC_RETURN_IF(refuse_if_capturing(s, n));
   char* ws = static_cast<char*>(workspace);
   void* keys_tmp = ws;
   int32_t* iota = reinterpret_cast<int32_t*>(ws + off_iota);

@@ -149,3 +149,36 @@ def test_network_step_graph_replays_match_eager():
         # eager work between the replays
         _ = eager((i + 1) % 3)
     cap.destroy()
+
+
+def test_capture_is_refused_where_the_sort_is_not_the_librarys_own():
+    """Below 4096 (and above 2 Mi) voxels the sort is rocPRIM's, which enqueues memsets next to its
+    kernels; recording those into a graph is refused with an error instead of being left to go wrong
+    on a replay.  Nothing runs on the GPU inside the capture; the eager call still works."""
+    c = synth.random_cloud(1500, (40, 40, 16), seed=synth.SEED_BASE + 700)
+    desc = B.spc_pack_desc_fit(c[:, 1:].min(0), c[:, 1:].max(0), 1, 2, 1)
+    coords = torch.from_numpy(c).cuda()
+    ws = torch.empty(B.spc_pack_workspace_bytes(len(c), desc), dtype=torch.uint8, device="cuda")
+    keys = torch.empty(len(c), dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device="cuda")
+    perm = torch.empty(len(c), dtype=torch.int32, device="cuda")
+    B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+    torch.cuda.synchronize()
+    ref = keys.clone()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with pytest.raises(B.SpcError) as err:
+        with torch.cuda.graph(graph, stream=stream, capture_error_mode="relaxed"):
+            B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+    assert err.value.code == B.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    # strided map from a small level: the downsampling sort is refused the same way
+    B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS).destroy()  # eager, and warms the block cache
+    torch.cuda.synchronize()
+    with pytest.raises(B.SpcError):
+        with torch.cuda.graph(torch.cuda.CUDAGraph(), stream=stream, capture_error_mode="relaxed"):
+            B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS)
+    torch.cuda.synchronize()
+    keys.zero_()
+    B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+    torch.cuda.synchronize()
+    assert torch.equal(keys, ref)
