@@ -482,8 +482,6 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
                                                                           const float* __restrict__ init) {
   using V8 = typename Mfma<T>::V8;
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n_out = n_out_d ? *n_out_d : n_out_h;
   const int64_t n_blocks = (int64_t(n_out) + 31) >> 5;
   const int slab = blockIdx.y;
@@ -491,6 +489,13 @@ __global__ __launch_bounds__(64 * SPLITK_WAVES) void conv_os_splitk_kernel(const
   // tiles of RB blocks; the trip count is uniform per workgroup, so the barriers below are
   // reached by all of its waves or by none
   for (int64_t blk0 = int64_t(blockIdx.x) * RB; blk0 < n_blocks; blk0 += LOOP ? int64_t(gridDim.x) * RB : n_blocks) {
+  // Everything that depends on the thread index is derived anew in every trip from a value the
+  // compiler cannot see through: hoisted out of the loop, the lane constants of the set-up and of the
+  // epilogue would stay in registers across the whole body (26 registers, two waves per SIMD).
+  int tid = threadIdx.x;
+  if constexpr (LOOP) asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, lr = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int idx_rows = (K3 + SPLITK_WAVES - 1) / SPLITK_WAVES + 1;  // per wave, with the all-invalid row at the end
   int32_t* sIdx = reinterpret_cast<int32_t*>(smem) + wave * idx_rows * (RB * 32);
   int16_t* kl = reinterpret_cast<int16_t*>(smem + size_t(SPLITK_WAVES) * idx_rows * (RB * 128)) + wave * SPLITK_KL_CAP;
