@@ -78,7 +78,7 @@ struct SrcMask {
 template <typename KeyT, typename Src>
 __global__ __launch_bounds__(BS_WIDE) void bs_count_kernel(Src src, int64_t n, int per, int shift, int n_bin,
                                                            KeyT* __restrict__ keys0, int32_t* __restrict__ table) {
-  __shared__ int hist[BS_MAX_BIN];
+  extern __shared__ int hist[];  // [n_bin]
   for (int b = threadIdx.x; b < n_bin; b += BS_WIDE) hist[b] = 0;
   __syncthreads();
   const int64_t lo = int64_t(blockIdx.x) * per, hi = min<int64_t>(n, lo + per);
@@ -148,38 +148,49 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
                                                              int32_t* __restrict__ vals1, int2* __restrict__ win,
                                                              int32_t* __restrict__ n_part_keys, uint32_t* __restrict__ bits,
                                                              int n_words, int32_t* __restrict__ ccnt, int n_chunks) {
-  __shared__ int pos[BS_MAX_BIN + 1];        // this workgroup's running position in every bin
-  __shared__ int bin_start[BS_MAX_BIN + 1];  // where every bin starts
+  extern __shared__ int lds_bins[];
+  int* pos = lds_bins;                    // [n_bin + 1] this workgroup's running position in every bin
+  int* bin_start = lds_bins + n_bin + 1;  // [n_bin + 1] where every bin starts
   __shared__ int wave_tot[BS_WIDE / 64];
-  static_assert(BS_MAX_BIN == 4 * BS_WIDE, "one int4 of bins per thread");
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int f0 = t * 4;
-  int4 c = make_int4(0, 0, 0, 0), bef = c;
-  if (f0 < n_bin) {
-    c = *reinterpret_cast<const int4*>(tot + f0);
-    bef = *reinterpret_cast<const int4*>(before + int64_t(blockIdx.x) * n_bin + f0);
-  }
   if (DEDUP) {  // the rank pass marks positions and counts them per chunk: both start from zero
     for (int i = blockIdx.x * BS_WIDE + t; i < n_words; i += gridDim.x * BS_WIDE) bits[i] = 0u;
     for (int i = blockIdx.x * BS_WIDE + t; i < n_chunks; i += gridDim.x * BS_WIDE) ccnt[i] = 0;
   }
-  const int sum = c.x + c.y + c.z + c.w;
-  int x = sum;
-  for (int d = 1; d < 64; d <<= 1) {
-    const int y = __shfl_up(x, d, 64);
-    if (lane >= d) x += y;
-  }
-  if (lane == 63) wave_tot[wave] = x;
-  __syncthreads();
-  int base = x - sum, total = 0;  // total: keys that take part (all of them unless DEDUP)
-  for (int w = 0; w < BS_WIDE / 64; ++w) {
-    if (w < wave) base += wave_tot[w];
-    total += wave_tot[w];
-  }
-  const int4 st = make_int4(base, base + c.x, base + c.x + c.y, base + c.x + c.y + c.z);
-  if (f0 < n_bin) {
-    *reinterpret_cast<int4*>(pos + f0) = make_int4(st.x + bef.x, st.y + bef.y, st.z + bef.z, st.w + bef.w);
-    *reinterpret_cast<int4*>(bin_start + f0) = st;
+  // exclusive scan of the bin totals, four bins per thread and round (one round up to 4096 bins)
+  int total = 0;  // keys that take part (all of them unless DEDUP)
+  for (int r0 = 0; r0 < n_bin; r0 += 4 * BS_WIDE) {
+    const int f0 = r0 + t * 4;
+    int4 c = make_int4(0, 0, 0, 0), bef = c;
+    if (f0 < n_bin) {
+      c = *reinterpret_cast<const int4*>(tot + f0);
+      bef = *reinterpret_cast<const int4*>(before + int64_t(blockIdx.x) * n_bin + f0);
+    }
+    const int sum = c.x + c.y + c.z + c.w;
+    int x = sum;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int y = __shfl_up(x, d, 64);
+      if (lane >= d) x += y;
+    }
+    if (r0 > 0) __syncthreads();  // the wave totals of the round before have been read
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    int base = total + x - sum;
+    for (int w = 0; w < BS_WIDE / 64; ++w) {
+      if (w < wave) base += wave_tot[w];
+      total += wave_tot[w];
+    }
+    if (f0 < n_bin) {
+      const int s0 = base, s1 = base + c.x, s2 = s1 + c.y, s3 = s2 + c.z;
+      pos[f0] = s0 + bef.x;
+      pos[f0 + 1] = s1 + bef.y;
+      pos[f0 + 2] = s2 + bef.z;
+      pos[f0 + 3] = s3 + bef.w;
+      bin_start[f0] = s0;
+      bin_start[f0 + 1] = s1;
+      bin_start[f0 + 2] = s2;
+      bin_start[f0 + 3] = s3;
+    }
   }
   if (t == 0) bin_start[n_bin] = total;
   __syncthreads();
@@ -475,10 +486,16 @@ BucketPlan bucket_plan(int64_t n, int used_bits) {
   int n_wg = static_cast<int>(std::min<int64_t>(std::max<int64_t>((n + 4095) / 4096, 1), BS_MAX_WG));
   p.per = static_cast<int>(((n + n_wg - 1) / n_wg + BS_WIDE - 1) / BS_WIDE * BS_WIDE);
   p.n_wg = static_cast<int>(std::max<int64_t>((n + p.per - 1) / p.per, 1));
-  // About 16 keys per bin of the key space: packing descriptors round every field up to whole
-  // bits and scenes are far from cubic, so typically a quarter of the bins is populated.
+  // About 16 keys per bin of the key space up to 4096 bins: packing descriptors round every field up
+  // to whole bits and scenes are far from cubic, so typically a quarter of the bins is populated.
+  // Beyond that, more bins only pay once the rank pass is bound by its comparisons and not by its
+  // launch: 8192 bins from 200 k keys, 16384 from 512 k (10^6 keys: rank 51 -> 32 us; 300 k keys
+  // with 16384 bins: slower by 2 us for the longer scans).
   int fb = 8;
-  while (fb < BS_MAX_BIN_BITS && (int64_t(16) << fb) < n) ++fb;
+  while (fb < 12 && (int64_t(16) << fb) < n) ++fb;
+  if (n > 200000) fb = 13;
+  if (n > 524288) fb = 14;
+  static_assert(BS_MAX_BIN_BITS >= 14, "bin table sizes");
   fb = std::max(2, std::min(fb, used_bits));
   p.shift = used_bits - fb;
   p.n_bin = 1 << fb;
@@ -512,9 +529,11 @@ Ws<KeyT> carve(void* ws, int64_t n) {
   w.keys1 = reinterpret_cast<KeyT*>(c + k);
   w.vals1 = reinterpret_cast<int32_t*>(c + 2 * k);
   w.table = reinterpret_cast<int32_t*>(c + 2 * k + v);
-  w.before = w.table + size_t(BS_MAX_WG) * BS_MAX_BIN;
-  w.fstart = w.before + size_t(BS_MAX_WG) * BS_MAX_BIN;
-  w.win = reinterpret_cast<int2*>(w.fstart + BS_MAX_BIN + 64);  // 8-byte aligned: every part above is a multiple of 256 bytes
+  const BucketPlan cap = bucket_plan(n, 64);  // as many workgroups and at least as many bins as any plan for n keys
+  const size_t tbl = (size_t(cap.n_wg) * cap.n_bin + 63) / 64 * 64;
+  w.before = w.table + tbl;
+  w.fstart = w.before + tbl;
+  w.win = reinterpret_cast<int2*>(w.fstart + cap.n_bin + 64);  // 8-byte aligned: every part above is a multiple of 256 bytes
   w.n_kept = reinterpret_cast<int32_t*>(w.win + (nn / BS_PART + 2));
   w.ccnt = w.n_kept + 2;
   w.n_chunks = static_cast<int>(chunks_for(n));
@@ -526,11 +545,16 @@ Ws<KeyT> carve(void* ws, int64_t n) {
 // count, column scan, scatter: keys1 (vals1) partitioned by fine bin, rank windows
 template <typename KeyT, bool DEDUP, typename Src>
 void partition(const Src& src, int64_t n, const BucketPlan& p, const Ws<KeyT>& w, hipStream_t s) {
-  hipLaunchKernelGGL((bs_count_kernel<KeyT, Src>), dim3(p.n_wg), dim3(BS_WIDE), 0, s, src, n, p.per, p.shift, p.n_bin, w.keys0,
-                     w.table);
+  hipLaunchKernelGGL((bs_count_kernel<KeyT, Src>), dim3(p.n_wg), dim3(BS_WIDE), size_t(p.n_bin) * 4, s, src, n, p.per, p.shift,
+                     p.n_bin, w.keys0, w.table);
   const int col_wg = (p.n_bin / 4 + BS_COL_THREADS - 1) / BS_COL_THREADS;
   hipLaunchKernelGGL(bs_colscan_kernel, dim3(col_wg), dim3(BS_COL_THREADS), 0, s, w.table, w.before, p.n_wg, p.n_bin, w.fstart);
-  hipLaunchKernelGGL((bs_scatter_kernel<KeyT, DEDUP>), dim3(p.n_wg), dim3(BS_WIDE), 0, s, w.keys0, n, p.per, p.shift, p.n_bin, w.before,
+  // (the scatter pass holds two ints per bin: beyond 8191 bins that is more than the default LDS limit)
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bs_scatter_kernel<KeyT, DEDUP>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (2 * BS_MAX_BIN + 2) * 4);
+  (void)attr;
+  hipLaunchKernelGGL((bs_scatter_kernel<KeyT, DEDUP>), dim3(p.n_wg), dim3(BS_WIDE), size_t(2 * p.n_bin + 2) * 4, s, w.keys0, n, p.per,
+                     p.shift, p.n_bin, w.before,
                      w.fstart, w.keys1, w.vals1, w.win, DEDUP ? w.n_kept : static_cast<int32_t*>(nullptr), w.bits, w.n_words, w.ccnt,
                      w.n_chunks);
 }
@@ -539,7 +563,9 @@ void partition(const Src& src, int64_t n, const BucketPlan& p, const Ws<KeyT>& w
 size_t bucket_sort_ws_bytes(int key_bits, int64_t n) {
   const size_t nn = static_cast<size_t>(std::max<int64_t>(n, 1));
   const size_t k = ((nn + BS_PAD_KEYS) * (key_bits / 8) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
-  return 2 * k + v + (2 * size_t(BS_MAX_WG) * BS_MAX_BIN + BS_MAX_BIN + 64 + 2 * (nn / BS_PART + 2) + 2 + chunks_for(n) + words_for(n)) * 4;
+  const BucketPlan cap = bucket_plan(n, 64);
+  const size_t tbl = (size_t(cap.n_wg) * cap.n_bin + 63) / 64 * 64;
+  return 2 * k + v + (2 * tbl + cap.n_bin + 64 + 2 * (nn / BS_PART + 2) + 2 + chunks_for(n) + words_for(n)) * 4;
 }
 
 template <typename KeyT>

@@ -106,8 +106,8 @@ __device__ inline KeyT pack_key(const int4 c, const PackParams& p, int32_t* stat
 #endif
 
 // ---------------------------------------------------------------- bucket sort (own kernels)
-constexpr int BS_MAX_WG = 64;       // workgroups of the count / scatter passes
-constexpr int BS_MAX_BIN_BITS = 12;
+constexpr int BS_MAX_WG = 128;      // workgroups of the count / scatter passes
+constexpr int BS_MAX_BIN_BITS = 14;
 constexpr int BS_MAX_BIN = 1 << BS_MAX_BIN_BITS;  // fine bins (top used key bits)
 constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 2048 * 1024;  // sizes it is used for; rocPRIM outside
 constexpr int BS_PART = 64;         // keys per rank workgroup
