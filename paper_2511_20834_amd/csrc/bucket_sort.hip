@@ -262,6 +262,9 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
 // alone, which is what bounded the compare-exchange network this replaces on the pack + sort path.
 // The scatter leaves BS_RANK_STEP all-ones keys behind the last key, so that whole steps can be
 // read at the end of the array.
+#ifndef BS_RANK_SOLO_N
+#define BS_RANK_SOLO_N 400000
+#endif
 constexpr int BS_RANK_STEP = BS_PAD_KEYS;  // positions; a window is a whole number of steps
 // 128 bytes of keys at a wave-uniform address in scalar registers.  The load is issued by hand and
 // its arrival awaited by hand, one compare step later: left to the compiler, the load of a step
@@ -319,11 +322,10 @@ __device__ inline int bs_count_before(const KeyT* __restrict__ k, int a, int b, 
   return (c[0] + c[1]) + (c[2] + c[3]);
 }
 
-template <typename KeyT>
-__global__ __launch_bounds__(BS_THREADS) void bs_rank_kernel(const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
+template <typename KeyT, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void bs_rank_kernel(const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
                                                              const int2* __restrict__ win, int n, KeyT* __restrict__ out_k,
                                                              int32_t* __restrict__ out_v) {
-  constexpr int WAVES = BS_THREADS / 64;
   static_assert(BS_PART == 64, "one key per lane");
   __shared__ int partial[WAVES][BS_PART];
   const int lane = threadIdx.x & 63;
@@ -352,12 +354,15 @@ __global__ __launch_bounds__(BS_THREADS) void bs_rank_kernel(const KeyT* __restr
   c += bs_count_before<1>(keys1, qa, qb, key, x);
   quarter(own1, g1, qa, qb);
   c += bs_count_before<2>(keys1, qa, qb, key, x);
-  partial[wave][lane] = c;
-  __syncthreads();
-  if (wave == 0 && act) {
-    int r = g0;
+  int r = g0 + c;
+  if constexpr (WAVES > 1) {
+    partial[wave][lane] = c;
+    __syncthreads();
+    r = g0;
 #pragma unroll
     for (int v = 0; v < WAVES; ++v) r += partial[v][lane];
+  }
+  if (wave == 0 && act) {
     out_k[r] = key;
     if (out_v) out_v[r] = val;
   }
@@ -575,8 +580,17 @@ static int pack_sort_t(const int4* coords, int64_t n, const PackParams& pp, int 
   const Ws<KeyT> w = carve<KeyT>(ws, n);
   partition<KeyT, false>(SrcPack<KeyT>{coords, pp, status}, n, p, w, s);
   const int n_part = static_cast<int>((n + BS_PART - 1) / BS_PART);
-  hipLaunchKernelGGL(bs_rank_kernel<KeyT>, dim3(n_part), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.win, static_cast<int>(n),
-                     static_cast<KeyT*>(keys_out), perm_out);
+  // Four waves share a part's window while the launch is latency-bound (its time is that of the part with
+  // the largest window); from BS_RANK_SOLO_N keys on (25 parts per CU) the pass is bound by how many parts
+  // a CU has in flight, and one wave per part (no LDS, no barrier, four times the parts per CU) is
+  // faster: 10^6 keys 32 -> 26 us, 2 * 10^6 keys 145 -> 129 us for the whole sort; at 240 k keys of
+  // dense indoor scenes it was slower (37 -> 47 us).
+  if (n >= BS_RANK_SOLO_N)
+    hipLaunchKernelGGL((bs_rank_kernel<KeyT, 1>), dim3(n_part), dim3(64), 0, s, w.keys1, w.vals1, w.win, static_cast<int>(n),
+                       static_cast<KeyT*>(keys_out), perm_out);
+  else
+    hipLaunchKernelGGL((bs_rank_kernel<KeyT, BS_THREADS / 64>), dim3(n_part), dim3(BS_THREADS), 0, s, w.keys1, w.vals1, w.win,
+                       static_cast<int>(n), static_cast<KeyT*>(keys_out), perm_out);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "sort launch failed");
   return SPC_OK;
 }
