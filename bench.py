@@ -337,7 +337,7 @@ def main() -> int:
         # each, per slab of 64 or 32 output channels), and for layers with little work behind every tile
         n_slabs = cout // 64 if cout % 64 == 0 else cout // 32
         phase_wgs = ((n_out + 31) // 32 + 15) // 16 * n_slabs
-        splitk = K3 > 64 or phase_wgs < 64 or phase_wgs * cin < (7000 if cout % 64 == 0 else 16000)
+        splitk = K3 > 64 or phase_wgs < 64 or cout % 64 != 0 or phase_wgs * cin < 7000
         os_kernel = "conv_os_splitk_kernel" if splitk else "conv_os_phase_kernel"
         roof = {"kernel": os_kernel if dataflow == B.DATAFLOW_OS else "conv_ws_mfma_kernel", "bound": "mfma",
                 "achieved": conv_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",

@@ -952,14 +952,15 @@ static void launch_os_splitk_any(const ConvArgs& a, const T* Wp, const float* in
 // short workgroups win in spite of their redundant weight reads: us, phase / split-k, 49 k voxels
 // 32->64 15.2 / 11.6, 64->64 19.4 / 19.1, 64->128 25.5 / 30.6; 18 k voxels 64->64 17.5 / 10.7, 128->128
 // 29.7 / 28.8, 128->256 38.8 / 46.5; 120 k voxels 32->64 20.6 / 22.9, 64->64 30.5 / 37.3.  With 32-column
-// slabs the split-k kernel ties or wins up to 120 k voxels and 64 input channels.  Large kernels
-// (5x5x5 and up) favour the split-k kernel at every size measured.
+// slabs the split-k kernel wins or ties at every size measured (32->32: 120 k voxels 18.8 / 15.6, 10^6
+// voxels 118 / 80, 3 * 10^6 voxels 359 / 269; 64->32 at 120 k voxels 27.6 / 27.4).  Large kernels (5x5x5
+// and up) favour the split-k kernel at every size measured.
 static bool prefer_splitk(const ConvArgs& a) {
   const int64_t n_blocks = (a.rows_sel + 31) / 32;
   const int n_slabs = a.cout % 64 == 0 ? a.cout / 64 : a.cout / 32;
   const int64_t wgs = (n_blocks + 15) / 16 * n_slabs;
-  if (a.m->K3 > 64 || wgs < 64) return true;
-  return wgs * a.cin < (a.cout % 64 == 0 ? 7000 : 16000);
+  if (a.m->K3 > 64 || wgs < 64 || a.cout % 64 != 0) return true;
+  return wgs * a.cin < 7000;
 }
 
 template <typename T, int NB, int RB>
