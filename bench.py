@@ -44,7 +44,7 @@ def _recorded_traffic(cfg: int, kernel: str):
 
 def bench_network(args, torch, B, synth) -> int:
     """Configuration 4: the 25-layer UNet-style stack.  A step = pack+sort, feature-row permutation,
-    network-wide kernel-map build on two HIP streams, and the 25 feature computations."""
+    network-wide kernel-map build on HIP streams, and the 25 feature computations."""
     from paper_2511_20834_amd.network import SpcNetwork
     dev = torch.device("cuda:0")
     coords_np = synth.cloud("lidar")
@@ -60,9 +60,9 @@ def bench_network(args, torch, B, synth) -> int:
     keys = torch.empty(n, dtype=torch.int32, device=dev)
     perm = torch.empty(n, dtype=torch.int32, device=dev)
     F = torch.empty_like(F_raw)
-    # two streams for the map builds: more were measured slower on this stack (graph replay 0.544 ms with two,
-    # 0.566 with four, 0.572 with eight, 0.60 with one)
-    streams = [torch.cuda.current_stream(), torch.cuda.Stream()]
+    # the timed graph uses the pipelined builder (levels on one stream, searches on another, layers wait for their
+    # own map: 0.485 ms per step); the join-all builder took 0.544 ms on two streams, 0.566 on four, 0.60 on one
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream()]
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def step(flags=0, marks=None, forward=True, keep=False):
@@ -122,7 +122,7 @@ def bench_network(args, torch, B, synth) -> int:
 
     # ---- the same step recorded once into a HIP graph and replayed (the timed configuration)
     caps = {}
-    for name, flags in (("streams", 0), ("sequential", B.NET_SEQUENTIAL)):
+    for name, flags in (("streams", B.NET_PIPELINED), ("sequential", B.NET_SEQUENTIAL)):
         caps[name] = net.capture_step(coords, F_raw, desc, streams[1:], flags)
         for _ in range(args.warmup):
             caps[name].replay()
@@ -167,7 +167,7 @@ def bench_network(args, torch, B, synth) -> int:
         "value": vo / (ms_per_step * 1e-3) / 1e6, "unit": "Mvoxel-offsets/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "cfg4: lidar cloud, %d voxels, 25-layer UNet-style stack, 13 kernel maps on 2 streams, OS dataflow, "
+        "config": {"workload": "cfg4: lidar cloud, %d voxels, 25-layer UNet-style stack, 13 kernel maps built pipelined on 2 streams, OS dataflow, "
                                "step replayed from a HIP graph" % n,
                    "n_voxels": n, "levels": level_sizes, "voxel_offsets": vo, "useful_flops": flops},
         "parts": part, "tuning": tuned,

@@ -64,6 +64,7 @@ extern "C" {
 #define SPC_CONV_SPLITK_RB(rb) ((rb) << 8) /* with SPC_CONV_OS_SPLITK: 32-row blocks per workgroup (1, 2; 0 = by size) */
 #define SPC_NET_SEQUENTIAL 1 /* spc_build_kmaps_network: one stream, level by level (for comparison) */
 #define SPC_NET_PHASE_BARRIER 2 /* spc_build_kmaps_network: all levels join streams[0] before any map search starts */
+#define SPC_NET_PIPELINED 4 /* spc_build_kmaps_network: maps on streams[1] (levels on streams[2]) in the order the layers need them; streams[0] is not held up */
 
 /*
  * Packing descriptor (Section 5.3).  A key holds, from the most significant bit
@@ -163,6 +164,13 @@ int spc_build_kmap_perm(const void* in_keys, int64_t n_in, const int32_t* in_per
  * spc_kmap_destroy once per returned handle).  streams [host]: n_streams hipStream_t;
  * on return streams[0] has been made to wait for all the work, nothing else is waited
  * for.  out [host]: n_layers handles.
+ * SPC_NET_PIPELINED (needs n_streams >= 2): all maps are built on streams[1], in the order in which
+ * the layers first need them, the levels on streams[2] if there is one (else on streams[1], each
+ * right before the first map that reads it), and streams[0] is not made to wait: every
+ * spc_conv_forward waits for its own map on its own stream, so the first layers of a network run
+ * while the maps of the later ones are still being built.  Under stream capture every returned
+ * map must then be used by a spc_conv_forward on the capturing stream before the capture ends
+ * (that is what joins streams[1] back).
  */
 int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc* d,
                             const spc_layer_desc* layers, int32_t n_layers, spc_kmap** out,

@@ -26,6 +26,7 @@ CONV_OS_PHASE = 4
 CONV_OS_SPLITK = 8
 NET_SEQUENTIAL = 1
 NET_PHASE_BARRIER = 2
+NET_PIPELINED = 4
 ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -4, -5, -6
 
 EXPORTS = [

@@ -1131,6 +1131,12 @@ static int conv_entry(spc_kmap* m, const void* feats_in, int64_t ld_in, const vo
   a.rows_cap = ol->n_host < 0 ? m->out_cap : ol->n_host;
   a.rows_sel = (ol->n_host < 0 && m->n_out_hint >= 0) ? std::min(m->n_out_hint, a.rows_cap) : a.rows_cap;
   a.s = static_cast<hipStream_t>(stream);
+  // a map of a pipelined network build: nobody has joined its build stream, this stream waits for the map itself
+  // (once per consumer stream: stream order covers the later layers that share the map)
+  if (m->wait_on_use && m->ready && m->stream != a.s && m->last_waiter != a.s) {
+    SPC_HIP_CHECK(hipStreamWaitEvent(a.s, m->ready, 0));
+    m->last_waiter = a.s;
+  }
   switch (dtype) {
     case SPC_DTYPE_F16: return conv_typed<_Float16>(a, true);
     case SPC_DTYPE_BF16: return conv_typed<__bf16>(a, true);

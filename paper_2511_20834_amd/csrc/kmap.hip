@@ -666,6 +666,87 @@ static int wait_map(const spc_kmap* m) {
   return SPC_OK;
 }
 
+// Layout every distinct map of a network is built with: the union of what its layers ask for; a map
+// shared by layers that disagree about the half-map keeps the full lists.
+using NetKey = std::tuple<int, int, int, int>;
+static NetKey net_key(const spc_layer_desc& l) { return NetKey(l.K, l.in_stride, l.layer_stride, l.transposed); }
+static std::map<NetKey, int> net_layouts(const spc_layer_desc* layers, int n_layers) {
+  std::map<NetKey, int> want;
+  for (int i = 0; i < n_layers; ++i) want[net_key(layers[i])] |= layers[i].layout;
+  for (auto& kv : want) {
+    bool all_sym = true;
+    for (int i = 0; i < n_layers; ++i)
+      if (net_key(layers[i]) == kv.first && (layers[i].layout & SPC_LAYOUT_WS) && !(layers[i].layout & SPC_LAYOUT_WS_SYM))
+        all_sym = false;
+    if (!all_sym) kv.second &= ~SPC_LAYOUT_WS_SYM;
+  }
+  return want;
+}
+
+// SPC_NET_PIPELINED: one build stream, work in the order of first use (a level right before the first
+// map that reads it), no join: the maps are marked so that their consumers wait for them.
+static int build_network_pipelined(const void* v0_keys, int64_t n0, const PackInfo& pi, const spc_layer_desc* layers,
+                                   int n_layers, spc_kmap** out, hipStream_t sb, hipStream_t sl, hipEvent_t fork) {
+  // sl: the stream of the coordinate levels (sb itself, or a stream of its own: every level comes straight from
+  // V_0, so the levels then run ahead of the searches, which wait for the level they read)
+  std::map<int, Level*> levels;
+  levels[1] = borrowed_level(v0_keys, n0, 1);
+  const std::map<NetKey, int> want = net_layouts(layers, n_layers);
+  std::map<NetKey, spc_kmap*> maps;
+  std::set<Level*> awaited;
+  spc_kmap* first = nullptr;
+  int rc = SPC_OK;
+  if (sl != sb)  // all levels up front, in the order of first use
+    for (int i = 0; i < n_layers && rc == SPC_OK; ++i) {
+      const int need[2] = {layers[i].in_stride, layers[i].in_stride * layers[i].layer_stride};
+      for (int j = 0; j < 2 && rc == SPC_OK; ++j) {
+        if (levels.count(need[j])) continue;
+        Level* lv = nullptr;
+        rc = downsample_level(v0_keys, n0, nullptr, pi, ilog2(need[j]), &lv, sl);
+        if (rc == SPC_OK) levels[need[j]] = lv;
+      }
+    }
+  for (int i = 0; i < n_layers && rc == SPC_OK; ++i) {
+    const NetKey key = net_key(layers[i]);
+    if (maps.count(key)) continue;
+    spc_layer_desc l = layers[i];
+    l.layout = want.at(key);
+    const int need[2] = {l.in_stride, l.in_stride * l.layer_stride};
+    for (int j = 0; j < 2 && rc == SPC_OK; ++j) {
+      if (!levels.count(need[j])) {  // one build stream: the level right before the first map that reads it
+        Level* lv = nullptr;
+        rc = downsample_level(v0_keys, n0, nullptr, pi, ilog2(need[j]), &lv, sb);
+        if (rc == SPC_OK) levels[need[j]] = lv;
+      } else if (sl != sb && levels[need[j]]->ready && awaited.insert(levels[need[j]]).second) {
+        if (hipStreamWaitEvent(sb, levels[need[j]]->ready, 0) != hipSuccess) rc = set_error(SPC_ERR_HIP, "hipStreamWaitEvent failed");
+      }
+    }
+    if (rc != SPC_OK) break;
+    Level* fine = levels[l.in_stride];
+    Level* coarse = levels[l.in_stride * l.layer_stride];
+    spc_kmap* m = nullptr;
+    rc = build_on_levels(l.transposed ? coarse : fine, l.transposed ? fine : coarse, pi, l, sb, &m);
+    if (rc == SPC_OK) {
+      m->wait_on_use = true;
+      maps[key] = m;
+      if (!first) first = m;
+    }
+  }
+  // the fork event lives as long as the maps (a capture of this call refers to it)
+  if (rc == SPC_OK && first) first->aux_events.push_back(fork);
+  else (void)hipEventDestroy(fork);
+  if (rc == SPC_OK)
+    for (int i = 0; i < n_layers; ++i) {
+      spc_kmap* m = maps[net_key(layers[i])];
+      m->refs++;
+      out[i] = m;
+    }
+  for (auto& kv : maps)  // drop the builder's own reference
+    if (kv.second->refs.fetch_sub(1) == 1) kmap_free(kv.second);
+  for (auto& kv : levels) level_unref(kv.second);
+  return rc;
+}
+
 }  // namespace spc
 
 using namespace spc;
@@ -717,11 +798,13 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
 
   // fork: every other stream waits for what streams[0] has enqueued so far (the pack/sort)
   hipEvent_t fork = nullptr;
+  const bool pipelined = (flags & SPC_NET_PIPELINED) && ns >= 2;
   if (ns > 1) {
     SPC_HIP_CHECK(hipEventCreateWithFlags(&fork, hipEventDisableTiming));
     SPC_HIP_CHECK(hipEventRecord(fork, st[0]));
-    for (int i = 1; i < ns; ++i) SPC_HIP_CHECK(hipStreamWaitEvent(st[i], fork, 0));
+    for (int i = 1; i < (pipelined ? std::min(ns, 3) : ns); ++i) SPC_HIP_CHECK(hipStreamWaitEvent(st[i], fork, 0));
   }
+  if (pipelined) return build_network_pipelined(v0_keys, n0, pi, layers, n_layers, out, st[1], ns >= 3 ? st[2] : st[1], fork);
 
   // ---- phase 1: all coordinate levels, each straight from V_0 (closed form, Section 5.5)
   std::map<int, Level*> levels;          // stride -> level
@@ -767,18 +850,9 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
   }
 
   // ---- phase 2: one search per distinct (K, in_stride, layer_stride, transposed)
-  using Key = std::tuple<int, int, int, int>;
+  using Key = NetKey;
   std::map<Key, spc_kmap*> maps;
-  std::map<Key, int> want;
-  for (int i = 0; i < n_layers; ++i) want[Key(layers[i].K, layers[i].in_stride, layers[i].layer_stride, layers[i].transposed)] |= layers[i].layout;
-  for (auto& kv : want) {  // a map shared by layers that disagree about the half-map keeps the full lists
-    bool all_sym = true;
-    for (int i = 0; i < n_layers; ++i)
-      if (Key(layers[i].K, layers[i].in_stride, layers[i].layer_stride, layers[i].transposed) == kv.first &&
-          (layers[i].layout & SPC_LAYOUT_WS) && !(layers[i].layout & SPC_LAYOUT_WS_SYM))
-        all_sym = false;
-    if (!all_sym) kv.second &= ~SPC_LAYOUT_WS_SYM;
-  }
+  std::map<Key, int> want = net_layouts(layers, n_layers);
   // A stream waits for each foreign event at most once (stream order covers everything it
   // enqueues later), and the other streams join streams[0] once, at the end: few, distinct
   // cross-stream edges, which is also what a graph capture of this call records.

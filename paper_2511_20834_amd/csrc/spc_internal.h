@@ -159,6 +159,8 @@ struct spc_kmap {
   int tile = 0, n_tiles = 0;
   std::vector<int64_t> nnz_host;    // filled lazily
   hipEvent_t ready = nullptr;       // recorded after the last build kernel
+  bool wait_on_use = false;         // nobody has joined the build stream: consumers on other streams wait for `ready`
+  hipStream_t last_waiter = nullptr;  // the consumer stream that has waited for `ready` most recently
   std::vector<hipEvent_t> aux_events;  // fork/join events of the network build that made this map
   hipStream_t stream = nullptr;     // stream the map was built on
   int device = 0;

@@ -28,13 +28,14 @@ def _setup(cloud_name):
     return coords, cs, operm, layers, W, desc, keys, F0, Fs
 
 
-@pytest.mark.parametrize("cloud_name,mode", [("tiny", "streams"), ("lidar", "streams"), ("lidar", "sequential")])
+@pytest.mark.parametrize("cloud_name,mode", [("tiny", "streams"), ("lidar", "streams"), ("lidar", "sequential"),
+                                             ("lidar", "pipelined")])
 def test_network_maps_bit_exact_and_shared(cloud_name, mode):
     coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup(cloud_name)
     net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W],
                      dataflow=[B.DATAFLOW_OS if j % 2 == 0 else B.DATAFLOW_WS for j in range(len(layers))])
     streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
-    maps = net.build_maps(keys, desc, streams, B.NET_SEQUENTIAL if mode == "sequential" else 0)
+    maps = net.build_maps(keys, desc, streams, {"sequential": B.NET_SEQUENTIAL, "pipelined": B.NET_PIPELINED}.get(mode, 0))
     torch.cuda.synchronize()
     handles = {}
     for j, (l, m) in enumerate(zip(layers, maps)):
@@ -70,16 +71,18 @@ def test_network_maps_bit_exact_and_shared(cloud_name, mode):
     net.destroy_maps()
 
 
-@pytest.mark.parametrize("cloud_name,dataflow", [("tiny", "os"), ("lidar", "os"), ("lidar", "mixed"), ("lidar", "hybrid")])
+@pytest.mark.parametrize("cloud_name,dataflow", [("tiny", "os"), ("lidar", "os"), ("lidar", "mixed"), ("lidar", "hybrid"),
+                                                 ("lidar", "os_pipelined")])
 def test_network_forward_matches_oracle(cloud_name, dataflow):
     coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup(cloud_name)
+    net_flags = B.NET_PIPELINED if dataflow.endswith("_pipelined") else 0  # maps on one side stream, layers wait for their own
     df = [B.DATAFLOW_WS if l["K"] == 2 or l["in_stride"] >= 8 else B.DATAFLOW_OS for l in layers] if dataflow == "mixed" \
         else B.DATAFLOW_OS
     # hybrid: a different threshold on every 3x3x3 layer (1, 2, 3 in turn), single dataflows elsewhere
     ht = [(1 + j % 3 if l["K"] == 3 else None) for j, l in enumerate(layers)] if dataflow == "hybrid" else None
     net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W], dataflow=df, hybrid_t=ht)
     streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
-    net.build_maps(keys, desc, streams)
+    net.build_maps(keys, desc, streams, net_flags)
     y, T = net.forward(Fs, keep=True)
     torch.cuda.synchronize()
     # (a) layer by layer: the oracle is fed the GPU's own (fp16) inputs, which isolates each layer's error
@@ -100,7 +103,8 @@ def test_network_forward_matches_oracle(cloud_name, dataflow):
     net.destroy_maps()
 
 
-def test_network_step_graph_replays_match_eager():
+@pytest.mark.parametrize("net_flags", [0, B.NET_PIPELINED])
+def test_network_step_graph_replays_match_eager(net_flags):
     """The whole step captured into a HIP graph: every replay is compared with the eager result of the
     same input, with eager work and synchronisation between the replays, for the cloud the graph was
     recorded on and for two other clouds of the same size (other level sizes) written into its input
@@ -129,7 +133,7 @@ def test_network_step_graph_replays_match_eager():
     coords_buf = torch.from_numpy(clouds[0]).cuda()
     feats_buf = torch.from_numpy(feats[0]).cuda()
     net = SpcNetwork(layers, W)
-    cap = net.capture_step(coords_buf, feats_buf, desc, side)
+    cap = net.capture_step(coords_buf, feats_buf, desc, side, net_flags)
     for rep, i in enumerate([0, 0, 1, 2, 0]):
         coords_buf.copy_(torch.from_numpy(clouds[i]).cuda())
         feats_buf.copy_(torch.from_numpy(feats[i]).cuda())
