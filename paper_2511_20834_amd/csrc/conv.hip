@@ -458,7 +458,7 @@ __global__ __launch_bounds__(64 * WAVES) void conv_os_phase_kernel(const int32_t
 // to the workgroup's four waves (a split of the reduction over k, Eq. (2)).  Nothing is staged
 // through LDS and no barrier sits inside the loop: a wave reads the B fragments of its offsets
 // straight from the prepacked weights (1 KB coalesced per fragment, L2-resident) next to the
-// gathered A rows, D (offset, 16-channel slab) entries ahead of the MFMA that consumes them.
+// gathered A rows, D = 2 (offset, 16-channel slab) entries ahead of the MFMA that consumes them.
 // The four partial accumulators meet in LDS and are summed in wave order, so results stay
 // bit-reproducible; the sum leaves LDS transposed, each thread storing consecutive channels of
 // one row.  Compared with the phase kernel this trades redundant weight reads (every block

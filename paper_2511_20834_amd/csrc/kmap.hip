@@ -10,7 +10,8 @@
 // What is different (CDNA4): a workgroup owns a contiguous tile of sorted output
 // voxels.  Because adding a constant keeps the order, all queries of a tile and group
 // fall into one contiguous window of the input array.  The 2 K^2 window bounds are found
-// by wave-wide 64-ary searches (three dependent loads for 2^18 keys instead of 18), the
+// by groups of lanes, 16-ary (4-ary for K >= 5) after a shared 64-ary first round (two or three
+// dependent loads for 2^18 keys instead of 18), the
 // windows are copied into LDS with coalesced loads, and every lane then searches in LDS.
 // Windows that do not fit the LDS budget are searched in global memory, restricted to
 // the window, with the same code.
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const int rows = min(tile, n_out - i0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // first-round probes of the wave-wide searches (the same 64 keys for everybody: L2-resident)
+  // first-round probes of the window-bound searches (the same 64 keys for everybody: L2-resident)
   const int chunk0 = (n_in + 63) >> 6;
   KeyT probe = 0;
   if (n_in > 0 && (long long)lane * chunk0 < n_in) probe = in_keys[min((long long)(lane + 1) * chunk0 - 1, (long long)n_in - 1)];
