@@ -196,6 +196,8 @@ def main() -> int:
                     help="single-layer configurations: replace the configuration's cloud by a uniformly random scene of this many "
                          "voxels in a [n, n, 200] volume at 1.25 %% density (the random-scene size sweep)")
     ap.add_argument("--tune", action="store_true", help="--config 4: tune the per-layer threshold on the cloud first and report it")
+    ap.add_argument("--key-bits", type=int, default=0, choices=[0, 64],
+                    help="configs 0-3: 64 forces 64-bit packed keys (default: 32 bits when the scene fits)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scene-streams", type=int, default=3,
                     help="configs 0-3: also time independent scenes in flight on this many streams (0 or 1: skip)")
@@ -236,7 +238,7 @@ def main() -> int:
 
     lo, hi = coords_np[:, 1:].min(0), coords_np[:, 1:].max(0)
     reach = ((K - 1) // 2) if K % 2 else (K - 1)
-    desc = B.spc_pack_desc_fit(lo, hi, int(coords_np[:, 0].max()) + 1, s_l, reach)
+    desc = B.spc_pack_desc_fit(lo, hi, int(coords_np[:, 0].max()) + 1, s_l, reach, args.key_bits)
 
     dev = torch.device("cuda:0")
     coords = torch.from_numpy(coords_np).to(dev)

@@ -146,8 +146,9 @@ __device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
   return lo;
 }
 
-// Groups whose LDS searches one lane keeps in flight together.  K <= 3: five (one lane's share of the nine groups
-// in one go, 60 registers).  Larger kernels: three; five cost the registers that hold eight waves per SIMD
+// Groups whose LDS searches one lane keeps in flight together.  K <= 3 with 32-bit keys: five (one lane's share of
+// the nine groups in one go, 60 registers; with 64-bit keys that takes 82 registers, so three there as well: 10^6
+// voxels 95 -> 89 us).  Larger kernels: three; five cost the registers that hold eight waves per SIMD
 // (240 k voxels, 5x5x5: map build 90 us with five or seven, 75 us with two, three or four).
 constexpr int SEARCH_GB_SMALL = 5, SEARCH_GB_LARGE = 3;
 
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
     const int32_t* __restrict__ in_perm, int k_lim) {
   constexpr int G = K * K, K3 = K * K * K;
-  constexpr int SEARCH_GB = K <= 3 ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
+  constexpr int SEARCH_GB = (K <= 3 && sizeof(KeyT) == 4) ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
   constexpr int G_POW2 = G <= 1 ? 1 : G <= 4 ? 4 : G <= 16 ? 16 : G <= 64 ? 64 : 128;  // power of two >= G
   constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
