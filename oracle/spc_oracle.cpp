@@ -225,8 +225,10 @@ void orc_conv(const int32_t* M, int64_t n_out, int32_t K3, const double* F, cons
 // Packed key of a voxel (Section 5.3): fields from the top: batch, x, y, z.
 // Reading for what the paper leaves open: each spatial value is stored as
 // v - origin[a] + pad (a bias that keeps neighbour queries inside their field),
-// the batch index sits above x.  Returns the number of rows with a field out of
-// range (their key is set to all ones).
+// the batch index sits above x.  A row is in range when 0 <= v - origin[a] and
+// v - origin[a] + 2*pad < 2^bits on every axis (guard band on both sides) and the
+// batch index fits its field.  Returns the number of rows out of range (their key
+// is set to all ones).
 int64_t orc_pack_keys(const int32_t* coords, int64_t n, int32_t bits_b, int32_t bits_x, int32_t bits_y,
                       int32_t bits_z, const int32_t* origin, int32_t pad, uint64_t* keys) {
   const int bits[4] = {bits_b, bits_x, bits_y, bits_z};
@@ -236,8 +238,15 @@ int64_t orc_pack_keys(const int32_t* coords, int64_t n, int32_t bits_b, int32_t 
     bool ok = true;
     for (int a = 0; a < 4; ++a) {
       int64_t v = coords[4 * i + a];
-      if (a > 0) v = v - origin[a - 1] + pad;
-      if (v < 0 || v >= (int64_t(1) << bits[a])) ok = false;
+      if (a > 0) {
+        // the guard band must fit on both sides of the value: then v + delta stays inside
+        // the field for every offset component |delta| <= pad (packed additivity, Section 5.3)
+        const int64_t f = v - origin[a - 1];
+        if (f < 0 || f + 2 * int64_t(pad) >= (int64_t(1) << bits[a])) ok = false;
+        v = f + pad;
+      } else if (v < 0 || v >= (int64_t(1) << bits[a])) {
+        ok = false;
+      }
       key = (key << bits[a]) | (static_cast<uint64_t>(v) & ((uint64_t(1) << bits[a]) - 1));
     }
     if (!ok) {

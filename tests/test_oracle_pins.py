@@ -287,7 +287,168 @@ def test_pack_order_and_additivity(orc):
     assert np.array_equal(np.stack([b, x, y, z], 1), c)
     for d in orc.offsets(5, 2):
         pd = int(d[0]) * (1 << 13) + int(d[1]) * (1 << 6) + int(d[2])  # signed packed offset
+        # the sum is the key of the shifted voxel: its fields decode to q + delta (the shifted voxel itself
+        # may lie in the guard band, where the packer accepts no input rows)
+        kd = k + pd
+        dec = np.stack([kd >> 20, ((kd >> 13) & 127) - pad + origin[0], ((kd >> 6) & 127) - pad + origin[1],
+                        (kd & 63) - pad + origin[2]], 1)
         shifted = c.copy()
         shifted[:, 1:] += d
-        k2, bad = orc.pack_keys(shifted, *bits, origin, pad)
-        assert bad == 0 and np.array_equal(k2.astype(np.int64), k + pd)
+        assert np.array_equal(dec, shifted)
+
+
+def test_pack_guard_band_rule(orc):
+    """Section 5.3 (reading of the silent point): a field stores v - origin + pad and a row is accepted
+    only if the guard band fits on both sides, 0 <= v - origin and v - origin + 2 pad < 2^bits, which is
+    exactly the condition under which adding any packed offset with |component| <= pad stays inside the
+    field.  Hand-worked edge rows: 7-bit fields, pad 4, origin -20: v - origin in [0, 119] is accepted."""
+    bits, origin, pad = (0, 7, 7, 7), [-20, -20, -20], 4
+    edge = _bxyz([[-20, -20, -20], [99, 99, 99], [-20, 99, -20]])
+    keys, bad = orc.pack_keys(edge, *bits, origin, pad)
+    assert bad == 0
+    assert keys.tolist() == [(4 << 14) | (4 << 7) | 4, (123 << 14) | (123 << 7) | 123, (4 << 14) | (123 << 7) | 4]
+    # one step into either guard band is rejected although the biased value would still fit the field
+    for row in ([-21, 0, 0], [0, 100, 0], [0, 0, -21], [100, 0, 0], [0, 0, 103]):
+        k, bad = orc.pack_keys(_bxyz([row]), *bits, origin, pad)
+        assert bad == 1 and k[0] == np.uint64(0xFFFFFFFFFFFFFFFF), row
+    # accepted extremes plus any offset of reach <= pad decode to the shifted voxel (no borrow, no carry)
+    k = keys.astype(np.int64)
+    for d in ([-4, -4, -4], [4, 4, 4], [-4, 4, 0]):
+        kd = k + d[0] * (1 << 14) + d[1] * (1 << 7) + d[2]
+        dec = np.stack([(kd >> 14) & 127, (kd >> 7) & 127, kd & 127], 1) - pad + np.array(origin)
+        assert np.array_equal(dec, edge[:, 1:] + np.array(d))
+
+
+# ----------------------------------------------------------------------------- transposed maps
+def _axis_offsets(K, s):
+    return [(i - (K - 1) // 2) * s for i in range(K)] if K % 2 else [i * s for i in range(K)]
+
+
+@pytest.mark.parametrize("K,s_fine", [(2, 1), (3, 1), (3, 2), (2, 2), (5, 1)])
+def test_kernel_map_transposed_brute_force(orc, K, s_fine):
+    """Reading for transposed layers: pair (coarse j, fine i, k) iff fine_i = coarse_j + delta_k with
+    delta_k from Delta(K, s_fine); checked against an O(N^2) scan with written-out offsets, and
+    against the strided layer's triples with the roles swapped."""
+    c = synth.random_cloud(160, (9, 8, 7), seed=31 + K, batch=2)
+    c[:, 1:] -= 3
+    c, _ = orc.sort_coords(c)
+    fine = orc.downsample(c, s_fine) if s_fine > 1 else c
+    coarse = orc.downsample(fine, 2 * s_fine)
+    Mt = orc.kernel_map_transposed(coarse, fine, K, s_fine)
+    ax = _axis_offsets(K, s_fine)
+    off = [(a, b, d) for a in ax for b in ax for d in ax]
+    ref = np.full((len(fine), K ** 3), -1, np.int32)
+    for i, f in enumerate(fine):
+        for k, d in enumerate(off):
+            src = f - np.array([0, d[0], d[1], d[2]])
+            hit = np.nonzero((coarse == src).all(1))[0]
+            if hit.size:
+                assert hit.size == 1
+                ref[i, k] = hit[0]
+    assert np.array_equal(Mt, ref)
+    M = orc.kernel_map(fine, coarse, K, s_fine)  # the strided twin
+    t, tt = orc.triples(M), orc.triples(Mt)
+    assert np.array_equal(np.array(sorted(map(tuple, tt[:, [0, 2, 1]].tolist()))).reshape(-1, 3), t)
+
+
+@pytest.mark.parametrize("s_fine", [1, 2])
+def test_transposed_conv_k3_equals_dense_conv_transpose(orc, s_fine):
+    """K=3 transposed layer at layer stride 2 = dense conv_transpose3d(kernel 3, stride 2, padding 1)
+    sampled at the active fine voxels (the strided twin is conv3d(kernel 3, stride 2, padding 1))."""
+    c, _ = orc.sort_coords(synth.tiny_cloud())
+    c = c[(c[:, 1] < 40) & (c[:, 2] < 40)]
+    fine = orc.downsample(c, s_fine) if s_fine > 1 else c
+    coarse = orc.downsample(fine, 2 * s_fine)
+    Mt = orc.kernel_map_transposed(coarse, fine, 3, s_fine)
+    rng = np.random.default_rng(14)
+    Fc = rng.normal(size=(len(coarse), 3))
+    W = rng.normal(size=(27, 3, 5))
+    got = orc.conv(Mt, Fc, W)
+    cc = coarse.copy()
+    cc[:, 1:] //= 2 * s_fine
+    dims = (40 // (2 * s_fine), 40 // (2 * s_fine), 64 // (2 * s_fine))
+    dense = _dense_from_sparse(cc, Fc, np.zeros(3, np.int64), dims)
+    wt = torch.from_numpy(W.reshape(3, 3, 3, 3, 5)).permute(3, 4, 0, 1, 2).contiguous()  # [Cin, Cout, kx, ky, kz]
+    res = torch.nn.functional.conv_transpose3d(dense, wt, stride=2, padding=1, output_padding=1)[0]
+    fi = fine[:, 1:] // s_fine
+    ref = res[:, fi[:, 0], fi[:, 1], fi[:, 2]].T.numpy()
+    assert np.allclose(got, ref, rtol=1e-11, atol=1e-11)
+
+
+# ----------------------------------------------------------------------------- layer stack
+def _chain_layers():
+    """Two-level UNet-style chain with unequal widths everywhere, so that a swapped concat order, a
+    transposed layer reading the wrong level or a misplaced ReLU / rounding changes the result."""
+    L = [
+        dict(name="stem", K=3, in_stride=1, layer_stride=1, transposed=0, cin=3, cout=4, src="input", skip=None, save="enc0"),
+        dict(name="down1", K=2, in_stride=1, layer_stride=2, transposed=0, cin=4, cout=6, src="enc0", skip=None, save="d1"),
+        dict(name="enc1", K=3, in_stride=2, layer_stride=1, transposed=0, cin=6, cout=7, src="d1", skip=None, save="enc1"),
+        dict(name="down2", K=2, in_stride=2, layer_stride=2, transposed=0, cin=7, cout=8, src="enc1", skip=None, save="d2"),
+        dict(name="enc2", K=3, in_stride=4, layer_stride=1, transposed=0, cin=8, cout=8, src="d2", skip=None, save="enc2"),
+        dict(name="up2", K=2, in_stride=2, layer_stride=2, transposed=1, cin=8, cout=5, src="enc2", skip=None, save="u2"),
+        dict(name="dec2", K=3, in_stride=2, layer_stride=1, transposed=0, cin=12, cout=6, src="u2", skip="enc1", save="dec2"),
+        dict(name="up1", K=2, in_stride=1, layer_stride=2, transposed=1, cin=6, cout=5, src="dec2", skip=None, save="u1"),
+        dict(name="dec1", K=3, in_stride=1, layer_stride=1, transposed=0, cin=9, cout=3, src="u1", skip="enc0", save="dec1"),
+    ]
+    for j, l in enumerate(L):
+        l["relu"] = j != len(L) - 1
+    return L
+
+
+def test_network_forward_equals_dense_chain(orc):
+    """The layer stack (ReLU after every layer but the last, activations rounded to fp16 with round to
+    nearest even between layers, skip concatenation [up | skip], transposed layers writing the finer
+    level) against the same chain of dense fp64 convolutions from PyTorch's CPU library on the
+    zero-filled grid, masked to the active voxels of every level."""
+    lo = np.array([-8, -8, -8])
+    c, _ = orc.sort_coords(synth.tiny_cloud())
+    c = c[(c[:, 1] < 24) & (c[:, 2] < 24) & (c[:, 3] < 32)]
+    c[:, 1:] += lo  # negative coordinates: floor, not truncation, in the level derivation
+    c, _ = orc.sort_coords(c)
+    dims = np.array([24, 24, 32])
+    layers = _chain_layers()
+    rng = np.random.default_rng(21)
+    F0 = rng.normal(size=(len(c), 3)).astype(np.float16).astype(np.float64)
+    Ws = [rng.normal(size=(l["K"] ** 3, l["cin"], l["cout"])) * np.sqrt(2.0 / (l["K"] ** 3 * l["cin"])) for l in layers]
+    Ws = [w.astype(np.float16).astype(np.float64) for w in Ws]
+    T, maps = orc.network_forward(c, F0, layers, Ws)
+
+    # dense side: level s lives on the grid dims / s; mask[s] marks its active voxels
+    level = {1: c}
+    for s in (2, 4):
+        lv = c.copy()
+        lv[:, 1:] = np.floor(c[:, 1:].astype(np.float64) / s).astype(np.int32) * s
+        level[s] = np.unique(lv, axis=0)
+
+    def cells(s):
+        return ((level[s][:, 1:] - lo) // s).T
+
+    mask = {}
+    for s in (1, 2, 4):
+        m = torch.zeros((1, 1) + tuple(dims // s), dtype=torch.float64)
+        ix = cells(s)
+        m[0, 0, ix[0], ix[1], ix[2]] = 1.0
+        mask[s] = m
+    D = {"input": _dense_from_sparse(c, F0, lo, dims)}
+    conv3d, convT = torch.nn.functional.conv3d, torch.nn.functional.conv_transpose3d
+    for l, W in zip(layers, Ws):
+        K, s = l["K"], l["in_stride"]
+        x = D[l["src"]] if l["skip"] is None else torch.cat([D[l["src"]], D[l["skip"]]], dim=1)
+        w5 = torch.from_numpy(W.reshape(K, K, K, l["cin"], l["cout"]))
+        if l["layer_stride"] == 1:
+            y, so = conv3d(x, w5.permute(4, 3, 0, 1, 2).contiguous(), padding=1), s
+        elif not l["transposed"]:
+            y, so = conv3d(x, w5.permute(4, 3, 0, 1, 2).contiguous(), stride=2), 2 * s
+        else:
+            y, so = convT(x, w5.permute(3, 4, 0, 1, 2).contiguous(), stride=2), s
+        y = y * mask[so]
+        if l["relu"]:
+            y = torch.relu(y)
+        D[l["save"]] = y.to(torch.float16).to(torch.float64)
+        ix = cells(so)
+        ref = D[l["save"]][0][:, ix[0], ix[1], ix[2]].T.numpy()
+        got = T[l["save"]]
+        assert got.shape == ref.shape, l["name"]
+        assert np.allclose(got, ref, rtol=1e-9, atol=1e-9), l["name"]
+    # the stack's result is not trivially zero anywhere along the way
+    assert all(np.abs(T[l["save"]]).max() > 1e-3 for l in layers)
