@@ -75,7 +75,11 @@ extern "C" {
  * packed(q)+packed(delta)=packed(q+delta) holds only then).  For downsampling by
  * masking to agree with floor() on the raw coordinates, origin[a] - pad must be a
  * multiple of the largest output stride used.  key_bits is 32 or 64 and
- * bits_b+bits_x+bits_y+bits_z must not exceed it.
+ * bits_b+bits_x+bits_y+bits_z must not exceed it.  The builders check both rules
+ * against every layer they are given and return SPC_ERR_ARG when pad is smaller
+ * than the layer's largest offset component ((K-1)/2 * in_stride for odd K,
+ * (K-1) * in_stride for even K) or when origin[a] - pad is not a multiple of
+ * in_stride * layer_stride: maps built on such keys would hold false matches.
  */
 typedef struct spc_pack_desc {
   int32_t key_bits;

@@ -570,6 +570,23 @@ static int check_layer(const spc_layer_desc* l) {
   return SPC_OK;
 }
 
+// The packing descriptor must suit the layer (Section 5.3): packed(q) + packed(delta) = packed(q + delta)
+// holds only while no field borrows or carries, i.e. while the guard band covers the layer's largest
+// offset component; and masking the low bits of a field equals floor() on the raw coordinate only if
+// the field's bias, origin - pad, is a multiple of the layer's output stride.
+static int check_desc_layer(const spc_pack_desc* d, const spc_layer_desc* l) {
+  const int64_t reach = int64_t(l->K % 2 ? (l->K - 1) / 2 : l->K - 1) * l->in_stride;
+  if (d->pad < reach)
+    return set_error(SPC_ERR_ARG, "guard band pad = %d is smaller than the layer's reach %lld (K = %d, in_stride = %d)", d->pad,
+                     static_cast<long long>(reach), l->K, l->in_stride);
+  const int64_t so = int64_t(l->in_stride) * l->layer_stride;
+  for (int a = 0; a < 3; ++a)
+    if ((int64_t(d->origin[a]) - d->pad) % so != 0)
+      return set_error(SPC_ERR_ARG, "origin[%d] - pad = %lld is not a multiple of the layer's output stride %lld", a,
+                       static_cast<long long>(int64_t(d->origin[a]) - d->pad), static_cast<long long>(so));
+  return SPC_OK;
+}
+
 static int ilog2(int v) {
   int b = 0;
   while ((1 << b) < v) ++b;
@@ -765,6 +782,7 @@ int spc_build_kmap_perm(const void* in_keys, int64_t n_in, const int32_t* in_per
   PackInfo pi;
   SPC_RETURN_IF(check_desc(d, &pi));
   SPC_RETURN_IF(check_layer(l));
+  SPC_RETURN_IF(check_desc_layer(d, l));
   if (!out) return set_error(SPC_ERR_ARG, "out is NULL");
   if (n_in < 0 || n_in > 0x7fffffff || (!in_keys && n_in > 0)) return set_error(SPC_ERR_ARG, "bad in_keys / n_in");
   if (int64_t(n_in) * l->K * l->K * l->K > (int64_t(1) << 40)) return set_error(SPC_ERR_ARG, "map too large");
@@ -793,7 +811,10 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
   if (!layers || !out || n_layers < 1) return set_error(SPC_ERR_ARG, "layers/out NULL or n_layers < 1");
   if (!streams || n_streams < 1) return set_error(SPC_ERR_ARG, "at least one stream is required");
   if (n0 < 0 || n0 > 0x7fffffff || (!v0_keys && n0 > 0)) return set_error(SPC_ERR_ARG, "bad v0_keys / n0");
-  for (int i = 0; i < n_layers; ++i) SPC_RETURN_IF(check_layer(&layers[i]));
+  for (int i = 0; i < n_layers; ++i) {
+    SPC_RETURN_IF(check_layer(&layers[i]));
+    SPC_RETURN_IF(check_desc_layer(d, &layers[i]));
+  }
   const int ns = (flags & SPC_NET_SEQUENTIAL) ? 1 : n_streams;
   std::vector<hipStream_t> st(ns);
   for (int i = 0; i < ns; ++i) st[i] = static_cast<hipStream_t>(streams[i]);

@@ -62,3 +62,30 @@ def test_workspace_query_needs_no_gpu():
     d = B.spc_pack_desc_fit([0, 0, 0], [100, 100, 100])
     assert B.spc_pack_workspace_bytes(1000, d) >= 1000 * 8
     assert B.spc_version().startswith("spc-gfx950")
+
+
+def test_builders_reject_descriptors_that_do_not_suit_the_layer():
+    """Section 5.3: packed additivity needs a guard band of at least the layer's reach, and masking
+    equals floor() only if origin - pad is a multiple of the output stride.  Both are checked on the
+    host before anything touches the GPU (so this runs without one)."""
+    L = B.lib()
+    h = ctypes.c_void_p()
+
+    def build(desc, K, s_p, s_l, transposed=0):
+        l = B.LayerDesc(K, s_p, s_l, transposed, B.LAYOUT_OS)
+        return L.spc_build_kmap(None, 0, ctypes.byref(desc), ctypes.byref(l), ctypes.byref(h), None)
+
+    d = B.spc_pack_desc_fit([0, 0, 0], [100, 100, 100], 1, 2, 1)  # pad 2, origin 0
+    assert d.pad == 2
+    assert build(d, 5, 2, 1) == B.ERR_ARG and b"reach" in L.spc_last_error()      # reach 4 > pad 2
+    assert build(d, 2, 4, 2) == B.ERR_ARG and b"reach" in L.spc_last_error()      # even K: (K-1) * in_stride = 4
+    assert build(d, 3, 4, 1) == B.ERR_ARG                                         # reach 4
+    assert build(d, 3, 1, 4) == B.ERR_ARG and b"multiple" in L.spc_last_error()   # origin - pad = -2, stride 4
+    d2 = B.spc_pack_desc_fit([0, 0, 0], [100, 100, 100], 1, 4, 4)
+    d2.origin[1] += 1
+    assert build(d2, 3, 1, 2) == B.ERR_ARG and b"origin[1]" in L.spc_last_error()
+    # the network builder applies the same rule to every layer
+    layers = (B.LayerDesc * 2)(B.LayerDesc(3, 1, 1, 0, 1), B.LayerDesc(3, 4, 1, 0, 1))
+    out = (ctypes.c_void_p * 2)()
+    streams = (ctypes.c_void_p * 1)(None)
+    assert L.spc_build_kmaps_network(None, 0, ctypes.byref(d), layers, 2, out, streams, 1, 0) == B.ERR_ARG
