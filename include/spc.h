@@ -200,6 +200,11 @@ const int32_t* spc_kmap_os_map(const spc_kmap* m);
  * arrays, ordered by ascending output index; *nnz_dev [device] int32[K^3].  NULL if not built. */
 int spc_kmap_ws_lists(const spc_kmap* m, const int32_t** in_idx, const int32_t** out_idx,
                       const int32_t** nnz_dev, int64_t* ws_stride);
+/* How the search of Section 5.2 was laid out for this map: *tile_rows = consecutive sorted output voxels
+ * one workgroup owns, *window_keys = input keys of their neighbour windows it can stage in LDS (the
+ * groups of offsets whose windows no longer fit are searched in global memory).  Host values, no wait.
+ * Either pointer may be NULL. */
+int spc_kmap_search_info(const spc_kmap* m, int32_t* tile_rows, int32_t* window_keys);
 /* nnz_host [host] int64[K^3]: valid entries per offset.  Waits for the build. */
 int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host);
 /*
@@ -220,6 +225,15 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
  * result.
  */
 int spc_kmap_set_size_hint(spc_kmap* m, int64_t n_out_hint);
+/*
+ * Releases a handle (maps shared by several layers of a network are reference counted).  Does not
+ * wait: the map's arrays go back to the block cache of the stream the map was built on, and that
+ * stream is first made to wait (an event, no host wait) for every stream that has run
+ * spc_conv_forward on the map, so a build that follows immediately cannot overwrite arrays a
+ * feature kernel is still reading.  Those streams must still exist when the map is destroyed.
+ * Kernels of the caller's own that read the accessor pointers (os_map, ws lists, keys) on other
+ * streams are not known to the library: order them before the destroy yourself.
+ */
 void spc_kmap_destroy(spc_kmap* m);
 
 /*

@@ -32,7 +32,7 @@ ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -
 EXPORTS = [
     "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmap_perm", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
-    "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
+    "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_search_info", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
     "spc_conv_forward", "spc_conv_forward_hybrid",
     "spc_conv_prepare_weights", "spc_permute_rows",
     "spc_release_cache", "spc_last_error", "spc_version",
@@ -88,6 +88,7 @@ def lib():
         L.spc_kmap_copy_out_keys.argtypes = [vp, vp, i64]
         L.spc_kmap_ws_lists.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.spc_kmap_nnz.argtypes = [vp, ctypes.POINTER(i64)]
+        L.spc_kmap_search_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.spc_kmap_export_triples.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i64)]
         L.spc_kmap_set_size_hint.argtypes = [vp, i64]
         L.spc_kmap_destroy.argtypes = [vp]
@@ -223,6 +224,13 @@ class KMap:
         a = np.empty(n, dtype=np.uint32 if self.desc.key_bits == 32 else np.uint64)
         _check(lib().spc_kmap_copy_out_keys(self.handle, a.ctypes.data_as(ctypes.c_void_p), n))
         return a.astype(np.uint64)
+
+
+def spc_kmap_search_info(kmap: KMap):
+    """(rows per search tile, input keys the tile's windows may occupy in LDS)."""
+    t, w = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().spc_kmap_search_info(kmap.handle, ctypes.byref(t), ctypes.byref(w)))
+    return int(t.value), int(w.value)
 
 
 def spc_build_kmap(in_keys: torch.Tensor, desc: PackDesc, K: int, in_stride: int = 1, layer_stride: int = 1,

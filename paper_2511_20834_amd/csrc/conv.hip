@@ -1137,6 +1137,10 @@ static int conv_entry(spc_kmap* m, const void* feats_in, int64_t ld_in, const vo
     SPC_HIP_CHECK(hipStreamWaitEvent(a.s, m->ready, 0));
     m->last_waiter = a.s;
   }
+  // remembered for spc_kmap_destroy: the build stream's cache must not hand the map's arrays out again
+  // before this stream's kernels have read them
+  if (a.s != m->stream && std::find(m->consumers.begin(), m->consumers.end(), a.s) == m->consumers.end())
+    m->consumers.push_back(a.s);
   switch (dtype) {
     case SPC_DTYPE_F16: return conv_typed<_Float16>(a, true);
     case SPC_DTYPE_BF16: return conv_typed<__bf16>(a, true);

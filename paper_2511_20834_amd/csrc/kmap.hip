@@ -539,6 +539,9 @@ static int launch_search_k(spc_kmap* m, hipStream_t s) {
 }
 
 static void kmap_free(spc_kmap* m) {
+  // The arrays return to the build stream's cache, where the next build may take them at once: that
+  // stream first waits for the feature kernels other streams have enqueued on this map.
+  for (hipStream_t c : m->consumers) order_stream_after(m->stream, c);
   pool_free(m->os_map, m->stream);
   pool_free(m->block_masks, m->stream);
   pool_free(m->ws_in, m->stream);
@@ -607,8 +610,10 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->captured = stream_is_capturing(s);
   m->in_level = in;
   in->refs++;
+  in->add_reader(s);
   m->out_level = out;
   out->refs++;
+  out->add_reader(s);
   (void)hipGetDevice(&m->device);
   m->out_cap = out->n_host >= 0 ? out->n_host : out->cap;
   m->tile = tile_for(l.K);
@@ -1029,6 +1034,13 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
     }
   }
   *nnz_out = nnz;
+  return SPC_OK;
+}
+
+int spc_kmap_search_info(const spc_kmap* m, int32_t* tile_rows, int32_t* window_keys) {
+  if (!m) return set_error(SPC_ERR_ARG, "map is NULL");
+  if (tile_rows) *tile_rows = m->tile;
+  if (window_keys) *window_keys = WIN_CAP_BYTES / (m->pi.key_bits / 8);
   return SPC_OK;
 }
 

@@ -87,6 +87,21 @@ void pool_free(void* p, hipStream_t stream) {
   P.live.erase(it);
 }
 
+void order_stream_after(hipStream_t waiter, hipStream_t producer) {
+  if (waiter == producer) return;
+  hipEvent_t e = nullptr;
+  if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipStreamSynchronize(producer);  // no event to be had: wait on the host instead
+    return;
+  }
+  if (hipEventRecord(e, producer) != hipSuccess || hipStreamWaitEvent(waiter, e, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipStreamSynchronize(producer);
+  }
+  (void)hipEventDestroy(e);  // released once the record has completed
+}
+
 int pool_release_all() {
   Pool& P = pool();
   std::vector<void*> blocks;
@@ -152,6 +167,10 @@ bool stream_is_capturing(hipStream_t s) {
 void level_unref(Level* l) {
   if (!l) return;
   if (l->refs.fetch_sub(1) == 1) {
+    // the blocks go back to the producing stream's cache: that stream must not reuse them before the
+    // searches that read the keys on other streams have finished
+    if (l->owns_keys || l->n_dev)
+      for (hipStream_t r : l->readers) order_stream_after(l->stream, r);
     if (l->owns_keys) pool_free(l->keys, l->stream);
     pool_free(l->n_dev, l->stream);
     if (l->ready) (void)hipEventDestroy(l->ready);

@@ -35,6 +35,10 @@ int set_error(int code, const char* fmt, ...);
 void* pool_alloc(size_t bytes, hipStream_t stream);  // nullptr on failure (error set)
 void pool_free(void* p, hipStream_t stream);
 int pool_release_all();
+// Makes everything enqueued on `waiter` from now on run after what `producer` holds at this moment
+// (an event recorded on `producer`; nothing happens when the two are the same stream).  Used before a
+// block goes back to the cache of a stream other than the one whose kernels last read it.
+void order_stream_after(hipStream_t waiter, hipStream_t producer);
 
 // ---------------------------------------------------------------- packing
 struct PackInfo {
@@ -62,6 +66,13 @@ struct Level {
   int stride = 1;
   hipEvent_t ready = nullptr;  // recorded after the level's last kernel
   hipStream_t stream = nullptr;  // stream the level was produced on
+  std::vector<hipStream_t> readers;  // other streams whose kernels read the keys (map searches)
+  void add_reader(hipStream_t s) {
+    if (s == stream) return;
+    for (hipStream_t r : readers)
+      if (r == s) return;
+    readers.push_back(s);
+  }
 };
 void level_unref(Level* l);
 bool stream_is_capturing(hipStream_t s);
@@ -161,6 +172,7 @@ struct spc_kmap {
   hipEvent_t ready = nullptr;       // recorded after the last build kernel
   bool wait_on_use = false;         // nobody has joined the build stream: consumers on other streams wait for `ready`
   hipStream_t last_waiter = nullptr;  // the consumer stream that has waited for `ready` most recently
+  std::vector<hipStream_t> consumers;  // streams other than `stream` whose feature kernels have read the map
   std::vector<hipEvent_t> aux_events;  // fork/join events of the network build that made this map
   hipStream_t stream = nullptr;     // stream the map was built on
   int device = 0;

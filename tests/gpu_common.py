@@ -60,6 +60,24 @@ def rel_err(got, ref):
     return float(np.abs(got - ref).max() / max(den, 1e-30)) if ref.size else 0.0
 
 
+def assert_close(got, ref, tol, what=None):
+    """Both forms of the tolerance: max|y - yhat| / max|yhat| <= tol, and element by element
+    |y - yhat| <= tol * (|yhat| + rms(yhat)), so that small-magnitude outputs cannot be
+    arbitrarily wrong under a global bound set by the largest one."""
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    assert np.all(np.isfinite(got)), what
+    err = rel_err(got, ref)
+    assert err <= tol, (what, err)
+    rms = np.sqrt((ref ** 2).mean())
+    excess = np.abs(got - ref) - tol * (np.abs(ref) + rms)
+    assert excess.max() <= 0, (what, "element-wise bound exceeded by", float(excess.max()), "at", int(excess.argmax()))
+    return err
+
+
 def to_torch(a, dtype):
     """numpy (fp16/fp32 values) -> device tensor of the given torch dtype; also returns the
     exact fp64 values the device tensor holds (what the oracle must be fed)."""

@@ -8,7 +8,7 @@ import oracle
 from paper_2511_20834_amd import binding as B
 from paper_2511_20834_amd import synth
 
-from gpu_common import oracle_keys, rel_err
+from gpu_common import assert_close, oracle_keys
 
 pytestmark = pytest.mark.gpu
 
@@ -41,11 +41,7 @@ def test_config_full_size(cfg):
     packed = B.spc_conv_prepare_weights(Wt) if c["dtype"] != "f32" else None
     for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
         y = B.spc_conv_forward(km, Fs, Wt, df).cpu().double().numpy()
-        err = rel_err(y, ref)
-        assert err <= tol, (cfg, df, err)
-        # element-wise form: |y - yhat| <= tol * (|yhat| + rms(yhat)) everywhere
-        rms = np.sqrt((ref ** 2).mean())
-        assert np.all(np.abs(y - ref) <= tol * (np.abs(ref) + rms))
+        assert_close(y, ref, tol, (cfg, df))  # global and element-wise form of the tolerance
         if packed is not None:
             y2 = B.spc_conv_forward(km, Fs, packed, df, B.CONV_PACKED_WEIGHTS).cpu().double().numpy()
             if df == B.DATAFLOW_OS:
@@ -53,8 +49,7 @@ def test_config_full_size(cfg):
                 # both OS kernels at full size, whichever one the size-based choice picked above
                 for variant in (B.CONV_OS_PHASE, B.CONV_OS_SPLITK):
                     y3 = B.spc_conv_forward(km, Fs, packed, df, B.CONV_PACKED_WEIGHTS | variant).cpu().double().numpy()
-                    assert rel_err(y3, ref) <= tol, (cfg, variant)
-                    assert np.all(np.abs(y3 - ref) <= tol * (np.abs(ref) + rms))
+                    assert_close(y3, ref, tol, (cfg, variant))
             else:
-                assert rel_err(y2, ref) <= tol
+                assert_close(y2, ref, tol, (cfg, df, "packed"))
     km.destroy()

@@ -9,7 +9,7 @@ from paper_2511_20834_amd import binding as B
 from paper_2511_20834_amd import synth
 from paper_2511_20834_amd.network import SpcNetwork
 
-from gpu_common import oracle_keys, rel_err
+from gpu_common import assert_close, oracle_keys, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -94,12 +94,10 @@ def test_network_forward_matches_oracle(cloud_name, dataflow):
         gpu_in.append(x)
     Tl, _ = oracle.network_forward(cs, F0[operm], layers, W, inputs_override=gpu_in)
     for j, l in enumerate(layers):
-        err = rel_err(T[l["save"]].cpu().double().numpy(), Tl[l["save"]])
-        assert err <= 1e-2, (l["name"], err)
+        assert_close(T[l["save"]].cpu().double().numpy(), Tl[l["save"]], 1e-2, l["name"])
     # (b) end to end against the oracle's own chain
     To, _ = oracle.network_forward(cs, F0[operm], layers, W)
-    err = rel_err(y.cpu().double().numpy(), To[layers[-1]["save"]])
-    assert err <= 1e-2, err
+    assert_close(y.cpu().double().numpy(), To[layers[-1]["save"]], 1e-2, "end to end")
     net.destroy_maps()
 
 
@@ -186,3 +184,29 @@ def test_capture_is_refused_where_the_sort_is_not_the_librarys_own():
     B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
     torch.cuda.synchronize()
     assert torch.equal(keys, ref)
+
+
+def test_tuner_then_forward_matches_oracle():
+    """One-time tuning of the hybrid dual dataflow (Section 5.4): every layer's threshold is chosen by
+    timing on a sample cloud; whatever it picks, the stack must still give Eq. (2)."""
+    coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup("tiny")
+    net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W])
+    rows = net.tune(keys, desc, Fs, reps=2)
+    assert len(rows) == len(layers)
+    for (name, best, times), l in zip(rows, layers):
+        l1_max = 3 if l["K"] == 2 else 3 * (l["K"] - 1) // 2
+        assert name == l["name"] and 0 <= best <= l1_max + 1
+        assert sorted(times) == list(range(l1_max + 2)) and all(t > 0 for t in times.values())
+        assert times[best] == min(times.values())
+    # force a mixed outcome as well, so that every kind of per-layer setting is exercised after tuning
+    for trial in ("tuned", "forced"):
+        if trial == "forced":
+            net.dataflow = [B.DATAFLOW_WS if j % 3 == 0 else B.DATAFLOW_OS for j in range(len(layers))]
+            net.hybrid_t = [(1 + j % 2) if j % 3 == 1 else None for j in range(len(layers))]
+            net._packed = None
+        net.build_maps(keys, desc)
+        y = net.forward(Fs)
+        torch.cuda.synchronize()
+        To, _ = oracle.network_forward(cs, F0[operm], layers, W)
+        assert_close(y.cpu().double().numpy(), To[layers[-1]["save"]], 1e-2, trial)
+        net.destroy_maps()

@@ -10,7 +10,7 @@ import oracle
 from paper_2511_20834_amd import binding as B
 from paper_2511_20834_amd import synth
 
-from gpu_common import (fit_desc, gpu_pack, keys_to_u64, oracle_keys, oracle_layer, rel_err, to_torch)
+from gpu_common import (assert_close, fit_desc, gpu_pack, keys_to_u64, oracle_keys, oracle_layer, rel_err, to_torch)
 
 pytestmark = pytest.mark.gpu
 
@@ -236,9 +236,7 @@ def _run_conv(c, K, s_l, transposed, cin, cout, dtype, seed=0, relu=False):
         y = B.spc_conv_forward(km, Ft, Wt, df, (B.CONV_RELU if relu else 0) | variant)
         torch.cuda.synchronize()
         o = y.cpu().to(torch.float64).numpy()
-        assert o.shape == ref.shape
-        err = rel_err(o, ref)
-        assert err <= TOL[dtype], (df, variant, err)
+        assert_close(o, ref, TOL[dtype], (df, variant))
         outs[df] = o
         outs[(df, variant)] = o
     km.destroy()
@@ -309,7 +307,7 @@ def test_conv_strided_rows_concat_buffer():
     for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
         B.spc_conv_forward(km, fin, W, df, out=wide_out[:, 64:128])
         ref = oracle.conv(M, fin.cpu().double().numpy(), W.cpu().double().numpy())
-        assert rel_err(wide_out[:, 64:128].cpu().double().numpy(), ref) <= 1e-2
+        assert_close(wide_out[:, 64:128].cpu().double().numpy(), ref, 1e-2, df)
         assert bool((wide_out[:, :64] == 7).all()) and bool((wide_out[:, 128:] == 7).all())
     km.destroy()
 
@@ -335,7 +333,7 @@ def test_kmap_with_sort_permutation_folded_in(K, s_l):
     ref = oracle.conv(M, F[operm].astype(np.float64), W.astype(np.float64))
     for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
         y = B.spc_conv_forward(km, torch.from_numpy(F).cuda(), torch.from_numpy(W).cuda(), df)
-        assert rel_err(y.cpu().double().numpy(), ref) <= 1e-2, df
+        assert_close(y.cpu().double().numpy(), ref, 1e-2, df)
     km.destroy()
     with pytest.raises(B.SpcError):
         B.spc_build_kmap(keys, desc, 2, 1, 2, 1, B.LAYOUT_OS, in_perm=perm)
@@ -363,8 +361,7 @@ def test_conv_hybrid_dataflow_every_threshold(K, dtype, cin, cout):
     for t in range(0, l1_max + 2):
         for variant in (0, B.CONV_OS_PHASE, B.CONV_OS_SPLITK):
             y = B.spc_conv_forward(km, Ft, Wt, flags=B.CONV_RELU | variant, hybrid_t=t)
-            err = rel_err(y.cpu().to(torch.float64).numpy(), ref)
-            assert err <= TOL[dtype], (t, variant, err)
+            assert_close(y.cpu().to(torch.float64).numpy(), ref, TOL[dtype], (t, variant))
     # the ends of the range are the single dataflows: same kernels, same bits for OS
     y_os = B.spc_conv_forward(km, Ft, Wt, B.DATAFLOW_OS, B.CONV_RELU)
     y_t = B.spc_conv_forward(km, Ft, Wt, flags=B.CONV_RELU, hybrid_t=l1_max + 1)
@@ -401,11 +398,11 @@ def test_symmetric_half_map(name, K, key_bits, with_os):
         Wt, W64 = to_torch(synth.weights(K ** 3, cin, cout, np_dt, seed=72), dtype)
         ref = oracle.conv(M, F64, W64)
         y = B.spc_conv_forward(km, Ft, Wt, B.DATAFLOW_WS)
-        assert rel_err(y.cpu().to(torch.float64).numpy(), ref) <= TOL[dtype], (dtype, "ws")
+        assert_close(y.cpu().to(torch.float64).numpy(), ref, TOL[dtype], (dtype, "ws"))
         if with_os:  # hybrid dual dataflow on top of the half lists
             for t in (1, 2):
                 y = B.spc_conv_forward(km, Ft, Wt, hybrid_t=t)
-                assert rel_err(y.cpu().to(torch.float64).numpy(), ref) <= TOL[dtype], (dtype, t)
+                assert_close(y.cpu().to(torch.float64).numpy(), ref, TOL[dtype], (dtype, t))
     km.destroy()
 
 
@@ -438,7 +435,7 @@ def test_conv_unaligned_feature_rows():
     ref = oracle.conv(M, fin.cpu().double().numpy(), W.cpu().double().numpy())
     for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
         y = B.spc_conv_forward(km, fin, W, df)
-        assert rel_err(y.cpu().double().numpy(), ref) <= 1e-2
+        assert_close(y.cpu().double().numpy(), ref, 1e-2, df)
     km.destroy()
 
 
@@ -453,3 +450,125 @@ def test_conv_bad_arguments():
         B.spc_conv_forward(km, F, W, B.DATAFLOW_WS)
     assert e.value.code == B.ERR_ARG
     km.destroy()
+
+
+# ----------------------------------------------------------------------------- large and random scenes
+def _search_geometry(km):
+    tile, cap = B.spc_kmap_search_info(km)
+    assert tile in (64, 128) and cap >= 1024
+    return tile, cap
+
+
+def _exact_window_sizes(in_keys, out_keys, desc, K, s_p, tile):
+    """Per tile of `tile` consecutive outputs and per (dx, dy) group: the number of input keys between the
+    first output's smallest-z query and the last output's largest-z query (what the search kernel has to
+    look through for that tile and group; its own windows are at least this wide)."""
+    ax = [(i - (K - 1) // 2) * s_p for i in range(K)] if K % 2 else [i * s_p for i in range(K)]
+    sh_y, sh_x = desc.bits_z, desc.bits_z + desc.bits_y
+    ik = in_keys.astype(np.int64)
+    ok = out_keys.astype(np.int64)
+    first, last = ok[0::tile], ok[np.minimum(np.arange(tile - 1, len(ok) + tile - 1, tile), len(ok) - 1)]
+    sizes = []
+    for dx in ax:
+        for dy in ax:
+            d = dx * (1 << sh_x) + dy * (1 << sh_y)
+            lo = np.searchsorted(ik, first + d + ax[0], "left")
+            hi = np.searchsorted(ik, last + d + ax[-1], "right")
+            sizes.append(np.maximum(hi - lo, 0))
+    return np.stack(sizes, 1)  # [tiles, K^2]
+
+
+@pytest.mark.parametrize("K,s_l,key_bits", [(3, 2, 0), (7, 1, 64), (5, 2, 64)])
+def test_kmap_windows_beyond_the_lds_budget(K, s_l, key_bits):
+    """Dense grids whose per-tile search windows do not fit the kernel's LDS budget: the groups past the
+    budget are searched in global memory.  That the case is reached is shown on the host from the window
+    sizes (exact ones, which the kernel's can only exceed) and the kernel's reported tile and budget."""
+    c = synth.full_grid(22, batch=2)
+    desc = fit_desc(c, [(K, 1, s_l)], key_bits)
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_BOTH)
+    ci, co, M = _check_map(cs, keys, desc, K, 1, s_l, 0, km)
+    tile, cap = _search_geometry(km)
+    w = _exact_window_sizes(oracle_keys(ci, desc), oracle_keys(co, desc), desc, K, 1, tile)
+    over = (np.cumsum(w, axis=1) > cap).any(axis=1)
+    assert over.mean() > 0.5, "most tiles must overflow the LDS window budget for this test to mean anything"
+    km.destroy()
+
+
+@pytest.mark.parametrize("n,key_bits", [(1_000_000, 0), (2_200_000, 0), (2_200_000, 64)])
+def test_large_random_scene(n, key_bits):
+    """Uniform random voxels at 1.25 % density (the ablation set-up of Section 6.6; no neighbouring
+    structure): pack + sort, kernel map and features against the oracle at 10^6 voxels and above 2^21
+    keys, both key widths."""
+    c = synth.scaled_random_cloud(n)
+    desc = fit_desc(c, [(3, 1, 1)], key_bits)
+    assert desc.key_bits == (64 if key_bits == 64 else 32)
+    keys, perm = gpu_pack(c, desc)
+    cs, operm = oracle.sort_coords(c)
+    assert np.array_equal(perm.cpu().numpy(), operm)
+    assert np.array_equal(keys_to_u64(keys), oracle_keys(cs, desc))
+    km = B.spc_build_kmap(keys, desc, 3, 1, 1, 0, B.LAYOUT_BOTH)
+    M = oracle.kernel_map(cs, cs, 3, 1)
+    ref_t = oracle.triples(M)
+    assert np.array_equal(km.export_triples(B.LAYOUT_OS), ref_t)
+    assert np.array_equal(km.export_triples(B.LAYOUT_WS), ref_t)
+    F = synth.features(n, 32, np.float16, seed=91)
+    W = synth.weights(27, 32, 32, np.float16, seed=92)
+    Fs = B.spc_permute_rows(torch.from_numpy(F).cuda(), perm)
+    ref = oracle.conv(M, F[operm].astype(np.float64), W.astype(np.float64))
+    Wt = torch.from_numpy(W).cuda()
+    for df, variant in ((B.DATAFLOW_OS, 0), (B.DATAFLOW_OS, B.CONV_OS_PHASE), (B.DATAFLOW_WS, 0)):
+        y = B.spc_conv_forward(km, Fs, Wt, df, variant)
+        assert_close(y.cpu().double().numpy(), ref, 1e-2, (n, df, variant))
+    km.destroy()
+    B.spc_release_cache()
+
+
+def test_large_random_scene_levels():
+    """Levels 2 and 4 straight from V_0 above 2^21 keys."""
+    n = 2_200_000
+    c = synth.scaled_random_cloud(n)
+    desc = fit_desc(c, [(2, 2, 2)])
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    maps = B.spc_build_kmaps_network(keys, desc, [(2, s, 2, 0, B.LAYOUT_OS) for s in (1, 2)])
+    for m, stride in zip(maps, (2, 4)):
+        ref = oracle_keys(oracle.downsample(cs, stride), desc)
+        assert m.n_out == len(ref)
+        assert np.array_equal(m.out_keys(), ref), stride
+    for m in maps:
+        m.destroy()
+    B.spc_release_cache()
+
+
+def test_destroy_and_rebuild_while_another_stream_still_reads_the_map():
+    """spc_kmap_destroy hands the map's arrays back to the build stream's block cache without waiting.  A
+    feature layer enqueued on another stream must still see its map when the next build on the build
+    stream takes those blocks again at once."""
+    c1, c2 = synth.cloud("lidar"), synth.random_cloud(120_000, (1024, 1024, 80), seed=77)
+    lo = np.minimum(c1[:, 1:].min(0), c2[:, 1:].min(0))
+    hi = np.maximum(c1[:, 1:].max(0), c2[:, 1:].max(0))
+    desc = B.spc_pack_desc_fit(lo, hi, 1, 1, 1)
+    k1, p1 = gpu_pack(c1, desc)
+    k2, _ = gpu_pack(c2, desc)
+    F = torch.from_numpy(synth.features(len(c1), 64, np.float16, seed=3)).cuda()
+    Fs = B.spc_permute_rows(F, p1)
+    W = B.spc_conv_prepare_weights(torch.from_numpy(synth.weights(27, 64, 64, np.float16, seed=4)).cuda())
+    km = B.spc_build_kmap(k1, desc, 3, 1, 1, 0, B.LAYOUT_OS)
+    ref = B.spc_conv_forward(km, Fs, W, B.DATAFLOW_OS, B.CONV_PACKED_WEIGHTS).clone()
+    torch.cuda.synchronize()
+    km.destroy()
+    build_stream, other = torch.cuda.current_stream(), torch.cuda.Stream()
+    for rep in range(5):
+        km = B.spc_build_kmap(k1, desc, 3, 1, 1, 0, B.LAYOUT_OS, stream=build_stream)
+        other.wait_stream(build_stream)
+        out = torch.empty_like(ref)
+        with torch.cuda.stream(other):
+            for _ in range(4):  # keeps `other` busy well past the destroy below
+                B.spc_conv_forward(km, Fs, W, B.DATAFLOW_OS, B.CONV_PACKED_WEIGHTS, out=out, stream=other)
+        km.destroy()  # no wait
+        km2 = B.spc_build_kmap(k2, desc, 3, 1, 1, 0, B.LAYOUT_OS, stream=build_stream)  # same sizes: same blocks
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), rep
+        km2.destroy()
