@@ -205,7 +205,7 @@ def test_kmap_bad_arguments():
         assert e.value.code == code
     # descriptors that do not suit the layer (Section 5.3): guard band below the reach; field bias
     # that is not a multiple of the output stride
-    for args in ((5, 1, 1, 0, 3), (2, 4, 2, 0, 3), (3, 1, 4, 0, 3)):
+    for args in ((7, 1, 1, 0, 3), (2, 4, 2, 0, 3), (3, 1, 4, 0, 3)):
         with pytest.raises(B.SpcError) as e:
             B.spc_build_kmap(keys, desc, *args)
         assert e.value.code == B.ERR_ARG
