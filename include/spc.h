@@ -118,6 +118,20 @@ int spc_pack_coords(const int32_t* coords_bxyz, int64_t n, const spc_pack_desc* 
                     void* stream);
 
 /*
+ * spc_pack_coords for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, flags and
+ * results as spc_pack_coords; the sort's scratch lives in a buffer that is part of the library image
+ * (13 MiB per GPU, held until the process ends), so the call neither allocates nor frees anything.
+ * Takes 4096 <= n <= SPC_NOALLOC_MAX_N voxels (the sizes the library's own sort kernels cover within
+ * that buffer); other sizes return SPC_ERR_UNSUPPORTED and enqueue nothing.  All calls on one GPU share
+ * the buffer: calls whose work may overlap on that GPU (different streams without an ordering between
+ * them, different host threads) race; order them, or use spc_pack_coords with workspaces of their own.
+ */
+#define SPC_NOALLOC_MAX_N 262144
+int spc_pack_coords_noalloc(const int32_t* coords_bxyz, int64_t n, const spc_pack_desc* d, void* keys_out,
+                            int32_t* perm_out, int32_t flags, void* stream);
+
+/*
  * One layer's voxel-indexing request.
  *   K            kernel size per axis (1, 2, 3, 5 or 7).
  *   in_stride    s_p: stride of the layer's input coordinates (power of two).

@@ -30,7 +30,7 @@ NET_PIPELINED = 4
 ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "spc_pack_desc_fit", "spc_pack_coords", "spc_build_kmap", "spc_build_kmap_perm", "spc_build_kmaps_network", "spc_kmap_n_in",
+    "spc_pack_desc_fit", "spc_pack_coords", "spc_pack_coords_noalloc", "spc_build_kmap", "spc_build_kmap_perm", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
     "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_search_info", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
     "spc_conv_forward", "spc_conv_forward_hybrid",
@@ -74,6 +74,7 @@ def lib():
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         L.spc_pack_desc_fit.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32), i32, i32, i32, i32, ctypes.POINTER(PackDesc)]
         L.spc_pack_coords.argtypes = [vp, i64, ctypes.POINTER(PackDesc), vp, vp, vp, ctypes.POINTER(ctypes.c_size_t), i32, vp]
+        L.spc_pack_coords_noalloc.argtypes = [vp, i64, ctypes.POINTER(PackDesc), vp, vp, i32, vp]
         L.spc_build_kmap.argtypes = [vp, i64, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), ctypes.POINTER(vp), vp]
         L.spc_build_kmap_perm.argtypes = [vp, i64, vp, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), ctypes.POINTER(vp), vp]
         L.spc_build_kmaps_network.argtypes = [vp, i64, ctypes.POINTER(PackDesc), ctypes.POINTER(LayerDesc), i32,
@@ -160,6 +161,20 @@ def spc_pack_coords(coords: torch.Tensor, desc: PackDesc, want_perm: bool = True
                                  _dev_ptr(perm) if want_perm else None, _dev_ptr(workspace), ctypes.byref(size), flags,
                                  _stream(stream)))
     return keys, perm
+
+
+NOALLOC_MAX_N = 262144
+
+
+def spc_pack_coords_noalloc(coords: torch.Tensor, desc: PackDesc, keys_out: torch.Tensor, perm_out: torch.Tensor | None,
+                            flags: int = 0, stream=None) -> None:
+    """spc_pack_coords on the library's static scratch buffer: the caller passes inputs and outputs only."""
+    assert coords.dtype == torch.int32 and coords.dim() == 2 and coords.shape[1] == 4
+    n = coords.shape[0]
+    assert keys_out.dtype == (torch.int32 if desc.key_bits == 32 else torch.int64) and keys_out.numel() == n
+    assert perm_out is None or (perm_out.dtype == torch.int32 and perm_out.numel() == n)
+    _check(lib().spc_pack_coords_noalloc(_dev_ptr(coords), n, ctypes.byref(desc), _dev_ptr(keys_out),
+                                         _dev_ptr(perm_out) if perm_out is not None else None, flags, _stream(stream)))
 
 
 class KMap:

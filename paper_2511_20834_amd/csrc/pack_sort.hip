@@ -237,6 +237,59 @@ int downsample_level(const void* src_keys, int64_t n_src, const int* /*n_src_dev
 }  // namespace spc
 
 // ---------------------------------------------------------------- C ABI
+// Device memory of spc_pack_coords_noalloc: the sort's scratch (partitioned keys and indices, bin
+// tables, rank windows, status word) for up to SPC_NOALLOC_MAX_N voxels with 64-bit keys.  Part of the
+// code object: every GPU the library runs on holds its own copy until the process ends.  Host code never
+// passes the array's name to a kernel: it is a host-side stand-in; the device address comes from
+// hipGetSymbolAddress, once per device.
+constexpr size_t NOALLOC_SCRATCH_BYTES = size_t(13) << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+namespace spc {
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+int noalloc_scratch(void** out) {
+  int dev = 0;
+  SPC_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return set_error(SPC_ERR_UNSUPPORTED, "device index %d beyond %d", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return set_error(SPC_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SPC_OK;
+}
+}  // namespace
+}  // namespace spc
+
+extern "C" int spc_pack_coords_noalloc(const int32_t* coords, int64_t n, const spc_pack_desc* d, void* keys_out,
+                                       int32_t* perm_out, int32_t flags, void* stream) {
+  using namespace spc;
+  PackInfo pi;
+  SPC_RETURN_IF(check_desc(d, &pi));
+  if (n < BS_MIN_N || n > SPC_NOALLOC_MAX_N)
+    return set_error(SPC_ERR_UNSUPPORTED, "spc_pack_coords_noalloc takes %lld..%lld voxels, got %lld",
+                     static_cast<long long>(BS_MIN_N), static_cast<long long>(SPC_NOALLOC_MAX_N), static_cast<long long>(n));
+  size_t need = 0;
+  SPC_RETURN_IF(spc_pack_coords(nullptr, n, d, nullptr, nullptr, nullptr, &need, flags, nullptr));
+  if (need > NOALLOC_SCRATCH_BYTES)
+    return set_error(SPC_ERR_UNSUPPORTED, "%lld voxels need %zu bytes of scratch, the static buffer holds %zu",
+                     static_cast<long long>(n), need, NOALLOC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  SPC_RETURN_IF(noalloc_scratch(&ws));
+  size_t have = NOALLOC_SCRATCH_BYTES;
+  // every part of the scratch that is read is written first by the kernels of the same call (the
+  // status word by a one-thread kernel), so nothing of the previous call's contents matters
+  return spc_pack_coords(coords, n, d, keys_out, perm_out, ws, &have, flags, stream);
+}
+
 extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_desc* d, void* keys_out, int32_t* perm_out,
                                void* workspace, size_t* workspace_bytes, int32_t flags, void* stream) {
   using namespace spc;
