@@ -24,8 +24,9 @@
 
 namespace spc {
 
-constexpr int SEARCH_THREADS = 256;
+constexpr int SEARCH_THREADS = 256;       // 128 and 512 measured slower at every level size (10^5 .. 3 * 10^6 voxels)
 constexpr int WIN_CAP_BYTES = 20 * 1024;  // LDS budget for staged windows per workgroup (several workgroups share a CU)
+constexpr int N_PROBES = 256;             // first-round probes of the window-bound searches (a power of 4 and of 16)
 constexpr int MAX_K = 7;
 
 template <typename KeyT>
@@ -44,9 +45,9 @@ __device__ inline int lanemask_lt_popc(unsigned long long m) {
 // Window-bound searches over keys[0,n): groups of P lanes run one search each (64/P searches per wave
 // instruction), U passes of them interleaved so that the loads of all passes are in flight together.
 // upper=false: first index with key >= q; true: first index with key > q.  q and upper are the same
-// in all lanes of a group, and odd groups search upper bounds.  The first round needs no memory
-// access: every search starts from the same 64 probes (the last key of every 1/64 slice, loaded once
-// per workgroup, one per lane), and a ballot per group tells the slice that holds the answer.  From then on
+// in all lanes of a group, and odd groups search upper bounds.  The first rounds need no memory
+// access: every search starts from the same N_PROBES probes (the last key of every 1/N_PROBES slice, loaded
+// once per workgroup into LDS), searched P-ary by the group's lanes with a ballot per round.  From then on
 // lane p of a group probes the last key of the p-th of P sub-slices, and the group's bits of the ballot
 // give the sub-slice.  The searches stop once every answer is known to within `slack` positions and return
 // the outer ends (slack 0: exact bounds): a window that is a few keys too wide costs less than
@@ -66,25 +67,30 @@ __device__ inline KeyT lane_value(KeyT v, int src_lane) {
 }
 
 template <typename KeyT, int P, int U>
-__device__ inline void group_bounds(const KeyT* __restrict__ keys, int n, KeyT probe, const KeyT (&q)[U], int (&res)[U],
+__device__ inline void group_bounds(const KeyT* __restrict__ keys, int n, const KeyT* s_probe, const KeyT (&q)[U], int (&res)[U],
                                     int slack) {
   constexpr int Q = 64 / P;
   static_assert(Q % 2 == 0, "odd groups search upper bounds");
   const int lane = threadIdx.x & 63, grp = lane / P, p = lane % P;
   const bool upper = (grp & 1) != 0;
-  const int chunk0 = (n + 63) >> 6;
-  const bool has_probe = (long long)lane * chunk0 < n;  // lanes past the last slice hold no probe
+  const int chunk0 = (n + N_PROBES - 1) / N_PROBES;
   int lo[U], hi[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    int c = 0;
+    // number of probes before the answer, P-ary in LDS (probe j is the last key of slice j; slices past the
+    // end of the array hold no probe and count as "not before")
+    int base = 0;
+    bool all = false;
 #pragma unroll
-    for (int g = 0; g < Q; ++g) {
-      const KeyT qg = lane_value(q[u], g * P);
-      const bool pr = has_probe && ((g & 1) ? (probe <= qg) : (probe < qg));
-      const int cg = __popcll(__ballot(pr));
-      c = grp == g ? cg : c;
+    for (int sub = N_PROBES / P; sub >= 1; sub /= P) {
+      const int j = base + (p + 1) * sub - 1;
+      const KeyT pv = s_probe[j];
+      const bool pr = (long long)j * chunk0 < n && (upper ? (pv <= q[u]) : (pv < q[u]));
+      const int c = __popcll((__ballot(pr) >> (grp * P)) & ((1ull << P) - 1));
+      if (sub == N_PROBES / P && c == P) all = true;  // only the first round can find every probe before the answer
+      base += (c == P ? P - 1 : c) * sub;  // (when all are before, the value of base no longer matters)
     }
+    const int c = all ? N_PROBES : base;
     if ((long long)c * chunk0 >= n) {  // every slice lies before the answer (or there are no keys)
       lo[u] = n;
       hi[u] = n;
@@ -172,6 +178,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   extern __shared__ __align__(16) unsigned char smem[];
   KeyT* okeys = reinterpret_cast<KeyT*>(smem);   // [tile]
   KeyT* win = okeys + tile;                      // [WIN_CAP]
+  __shared__ KeyT s_probe[N_PROBES];
   __shared__ int s_wlo[G], s_wsz[G], s_woff[G], s_wend[G + 1];
   __shared__ int s_bound[2 * G];
   __shared__ int s_cnt[K3];
@@ -185,10 +192,12 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const int rows = min(tile, n_out - i0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // first-round probes of the window-bound searches (the same 64 keys for everybody: L2-resident)
-  const int chunk0 = (n_in + 63) >> 6;
-  KeyT probe = 0;
-  if (n_in > 0 && (long long)lane * chunk0 < n_in) probe = in_keys[min((long long)(lane + 1) * chunk0 - 1, (long long)n_in - 1)];
+  // first-round probes of the window-bound searches (the same N_PROBES keys for everybody: L2-resident)
+  {
+    const int chunk0 = (n_in + N_PROBES - 1) / N_PROBES;
+    for (int j = tid; j < N_PROBES; j += SEARCH_THREADS)
+      s_probe[j] = (n_in > 0 && (long long)j * chunk0 < n_in) ? in_keys[min((long long)(j + 1) * chunk0 - 1, (long long)n_in - 1)] : KeyT(0);
+  }
 
   for (int v = tid; v < rows; v += SEARCH_THREADS) okeys[v] = out_keys[i0 + v];
   for (int k = tid; k < K3; k += SEARCH_THREADS) s_cnt[k] = 0;
@@ -218,7 +227,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       const KeyT d = s_gd[sc >> 1];
       q[u] = (grp & 1) ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
     }
-    group_bounds<KeyT, BOUND_P, U>(in_keys, n_in, probe, q, res, BOUND_SLACK);
+    group_bounds<KeyT, BOUND_P, U>(in_keys, n_in, s_probe, q, res, BOUND_SLACK);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int sc = (u * NW + wave) * Q + grp;
