@@ -28,6 +28,7 @@ constexpr int SEARCH_THREADS = 256;       // 128 and 512 measured slower at ever
 constexpr int WIN_CAP_BYTES = 20 * 1024;  // LDS budget for staged windows per workgroup (several workgroups share a CU)
 constexpr int N_PROBES = 256;             // first-round probes of the window-bound searches (a power of 4 and of 16)
 constexpr int MAX_K = 7;
+constexpr int WS_MAX_K3_SEARCH = MAX_K * MAX_K * MAX_K;
 
 template <typename KeyT>
 struct SearchParams {
@@ -158,12 +159,18 @@ __device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
 // (240 k voxels, 5x5x5: map build 90 us with five or seven, 75 us with two, three or four).
 constexpr int SEARCH_GB_SMALL = 5, SEARCH_GB_LARGE = 3;
 
-template <typename KeyT, int K>
+// PAIRS = false: the blocked |V_q| x K^3 matrix M, the per-block offset masks and (when tile_counts is given)
+// the per-tile hit counts are written.  PAIRS = true (weight-stationary layout alone): no matrix exists anywhere;
+// a tile keeps, per (group, row), the position of its lower bound and the hit bits of the group's K queries in
+// LDS (5 bytes where the matrix has 4 K), and once all groups are searched it writes its hits as compacted
+// (in, out) pairs, offset-major and row-ascending, into its own slab of `tile_pairs` (slab = tile * K^3 pairs, of
+// which only the first sum-of-hits are touched); tile_counts gets the hits per (offset, tile).
+template <typename KeyT, int K, bool PAIRS>
 __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
     int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
     uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
-    const int32_t* __restrict__ in_perm, int k_lim) {
+    const int32_t* __restrict__ in_perm, int k_lim, int2* __restrict__ tile_pairs) {
   constexpr int G = K * K, K3 = K * K * K;
   constexpr int SEARCH_GB = (K <= 3 && sizeof(KeyT) == 4) ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
   constexpr int G_POW2 = G <= 1 ? 1 : G <= 4 ? 4 : G <= 16 ? 16 : G <= 64 ? 64 : 128;  // power of two >= G
@@ -178,6 +185,9 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   extern __shared__ __align__(16) unsigned char smem[];
   KeyT* okeys = reinterpret_cast<KeyT*>(smem);   // [tile]
   KeyT* win = okeys + tile;                      // [WIN_CAP]
+  int32_t* s_pos = reinterpret_cast<int32_t*>(win + WIN_CAP);         // PAIRS: [G][tile] input position of the group's lower bound
+  uint8_t* s_hit = reinterpret_cast<uint8_t*>(s_pos + G * tile);      // PAIRS: [G][tile] bit t: the group's t-th query (ascending z) hit
+  __shared__ int s_off[PAIRS ? K3 + 1 : 1];                           // PAIRS: where every offset's pairs start in the tile's slab
   __shared__ KeyT s_probe[N_PROBES];
   __shared__ int s_wlo[G], s_wsz[G], s_woff[G], s_wend[G + 1];
   __shared__ int s_bound[2 * G];
@@ -354,9 +364,11 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
         }
     }
     int32_t r[SEARCH_GB][K];
+    unsigned hm[SEARCH_GB];  // bit t: query t (ascending z) hit
 #pragma unroll
     for (int j = 0; j < SEARCH_GB; ++j) {
       int h = 0;
+      hm[j] = 0u;
 #pragma unroll
       for (int t = 0; t < K; ++t) {
         const KeyT qt = q0[j] + KeyT(t) * sp.zstep;
@@ -364,8 +376,27 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
         for (int i = 1; i < K; ++i) cand = (i <= t && h == i) ? w[j][i] : cand;
         const bool hit = pos[j] + h < wsz[j] && cand == qt;
         r[j][sp.zrev ? K - 1 - t : t] = hit ? wlo[j] + pos[j] + h : -1;
+        hm[j] |= hit ? 1u << t : 0u;
         h += hit ? 1 : 0;
       }
+    }
+    if constexpr (PAIRS) {
+      // the tile's records stay in LDS; hits are counted per offset (a wave speaks for its 64 rows)
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j) {
+        const int g = gidx[j];
+        if (g < 0) continue;  // uniform in the wave
+        s_pos[g * tile + v] = wlo[j] + pos[j];
+        s_hit[g * tile + v] = static_cast<uint8_t>(hm[j]);
+#pragma unroll
+        for (int t = 0; t < K; ++t) {
+          const int k = g * K + t;
+          if (k >= k_lim) continue;  // uniform
+          const unsigned long long hit = __ballot(r[j][t] >= 0);
+          if (hit && lane == 0) atomicAdd(&s_cnt[k], __popcll(hit));
+        }
+      }
+      continue;
     }
     // found positions are stored as they are, or mapped to the caller's row numbering.  The
     // lookups are unconditional (misses read entry 0) and all issued before the first store: on this
@@ -406,14 +437,107 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     }
   }
   __syncthreads();
+  if constexpr (PAIRS) {
+    // where every offset's pairs start in the slab: exclusive prefix of the counts, by wave 0
+    if (wave == 0) {
+      int carry = 0;
+      for (int k0 = 0; k0 < K3; k0 += 64) {
+        const int k = k0 + lane;
+        const int c = k < K3 ? s_cnt[k] : 0;
+        int x = c;
+        for (int d = 1; d < 64; d <<= 1) {
+          const int y = __shfl_up(x, d, 64);
+          if (lane >= d) x += y;
+        }
+        if (k < K3) s_off[k] = carry + x - c;
+        carry += __shfl(x, 63, 64);
+      }
+      if (lane == 0) s_off[K3] = carry;
+    }
+    for (int k = tid; k < K3; k += SEARCH_THREADS) tile_counts[int64_t(k) * n_tiles_cap + blockIdx.x] = s_cnt[k];
+    __syncthreads();
+    // compaction: a wave takes an offset at a time and walks the tile's rows in steps of 64; the hit's input
+    // position is the group's lower bound plus the number of the group's earlier queries that hit
+    int2* slab = tile_pairs + int64_t(blockIdx.x) * tile * K3;
+    for (int k = wave; k < k_lim; k += NW) {
+      if (s_cnt[k] == 0) continue;  // uniform
+      const int g = k / K, tk = k - g * K, tq = sp.zrev ? K - 1 - tk : tk;
+      int at = s_off[k];
+      for (int v0 = 0; v0 < rows; v0 += 64) {
+        const int vv = v0 + lane;
+        const unsigned msk = vv < tile ? s_hit[g * tile + vv] : 0u;
+        const bool hit = vv < rows && ((msk >> tq) & 1u);
+        const unsigned long long bal = __ballot(hit);
+        if (hit) {
+          const int jpos = s_pos[g * tile + vv] + __popc(msk & ((1u << tq) - 1u));
+          slab[at + lanemask_lt_popc(bal)] = make_int2(in_perm ? in_perm[jpos] : jpos, i0 + vv);
+        }
+        at += __popcll(bal);
+      }
+    }
+    return;
+  }
   const int n_bl = rows32 >> 5;
   for (int e = tid; e < n_bl * MW; e += SEARCH_THREADS) block_masks[b0 * MW + e] = s_mask[e];
   if (tile_counts)
     for (int k = tid; k < K3; k += SEARCH_THREADS) tile_counts[int64_t(k) * n_tiles_cap + blockIdx.x] = s_cnt[k];
 }
 
-// One workgroup per offset k: exclusive scan of that offset's per-tile counts in place,
-// total into nnz[k].
+// Weight-stationary lists from the tiles' slabs of compacted pairs (the search kernel in its PAIRS form): one
+// workgroup per tile copies its hits, offset by offset, to where the scan of the per-tile counts puts them.  List k
+// comes out ordered by output index, without atomics and without a |V_q| x K^3 matrix having existed.
+__global__ __launch_bounds__(256) void ws_fill_pairs_kernel(const int2* __restrict__ tile_pairs, int n_out_h,
+                                                            const int* __restrict__ n_out_d, int K3, int tile,
+                                                            const int32_t* __restrict__ tile_base, int n_tiles_cap,
+                                                            const int32_t* __restrict__ nnz, int32_t* __restrict__ ws_in,
+                                                            int32_t* __restrict__ ws_out, int64_t ws_stride, int k_lim) {
+  __shared__ int s_off[WS_MAX_K3_SEARCH + 1], s_dst[WS_MAX_K3_SEARCH];
+  const int n_out = n_out_d ? *n_out_d : n_out_h;
+  const int i0 = blockIdx.x * tile;
+  if (i0 >= n_out) return;
+  const int n_tiles = (n_out + tile - 1) / tile;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // counts of this tile (difference of consecutive scanned bases) and their exclusive prefix
+  if (wave == 0) {
+    int carry = 0;
+    for (int k0 = 0; k0 < K3; k0 += 64) {
+      const int k = k0 + lane;
+      int c = 0;
+      if (k < k_lim) {
+        const int32_t* col = tile_base + int64_t(k) * n_tiles_cap;
+        const int b = col[blockIdx.x];
+        c = (int(blockIdx.x) + 1 < n_tiles ? col[blockIdx.x + 1] : nnz[k]) - b;
+        s_dst[k] = b;
+      }
+      int x = c;
+      for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+      }
+      if (k < K3) s_off[k] = carry + x - c;
+      carry += __shfl(x, 63, 64);
+    }
+    if (lane == 0) s_off[K3] = carry;
+  }
+  __syncthreads();
+  const int total = s_off[K3];
+  const int2* slab = tile_pairs + int64_t(blockIdx.x) * tile * K3;
+  for (int e = tid; e < total; e += 256) {
+    int k = 0;  // last offset whose pairs start at or before e (offsets without pairs share their successor's start)
+    for (int bit = 256; bit > 0; bit >>= 1)
+      if (k + bit < K3 && s_off[k + bit] <= e) k += bit;
+    const int2 pr = slab[e];
+    const int64_t dst = int64_t(k) * ws_stride + s_dst[k] + (e - s_off[k]);
+    ws_in[dst] = pr.x;
+    ws_out[dst] = pr.y;
+  }
+}
+
+// One workgroup per offset k: exclusive scan of that offset's per-tile counts in place, total into nnz[k].
+// A thread owns a run of consecutive tiles; the runs are fetched in batches of WS_SCAN_U loads per thread that are
+// all in flight together (a loop of load, scan, store rounds over 256 tiles at a time took 7.6 us for 3750 tiles:
+// fifteen dependent round trips).
+constexpr int WS_SCAN_U = 8;
 __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile_counts, int n_tiles_cap, int tile,
                                                       int n_out_h, const int* __restrict__ n_out_d,
                                                       int32_t* __restrict__ nnz, int k_lim) {
@@ -427,14 +551,20 @@ __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile
   int32_t* c = tile_counts + int64_t(blockIdx.x) * n_tiles_cap;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int carry = 0;
-  for (int b0 = 0; b0 < n_tiles; b0 += 256) {
-    const int i = b0 + threadIdx.x;
-    const int v = i < n_tiles ? c[i] : 0;
-    int x = v;
+  for (int b0 = 0; b0 < n_tiles; b0 += 256 * WS_SCAN_U) {
+    const int first = b0 + threadIdx.x * WS_SCAN_U;  // this thread's run: tiles first .. first + WS_SCAN_U - 1
+    int v[WS_SCAN_U];
+#pragma unroll
+    for (int u = 0; u < WS_SCAN_U; ++u) v[u] = first + u < n_tiles ? c[first + u] : 0;
+    int sum = 0;
+#pragma unroll
+    for (int u = 0; u < WS_SCAN_U; ++u) sum += v[u];
+    int x = sum;
     for (int d = 1; d < 64; d <<= 1) {
       const int y = __shfl_up(x, d, 64);
       if (lane >= d) x += y;
     }
+    if (b0 > 0) __syncthreads();  // the wave sums of the round before have been read
     if (lane == 63) wave_sum[wave] = x;
     __syncthreads();
     int base = 0, tot = 0;
@@ -443,8 +573,12 @@ __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile
       if (w < wave) base += s;
       tot += s;
     }
-    __syncthreads();
-    if (i < n_tiles) c[i] = carry + base + x - v;
+    int run = carry + base + x - sum;
+#pragma unroll
+    for (int u = 0; u < WS_SCAN_U; ++u) {
+      if (first + u < n_tiles) c[first + u] = run;
+      run += v[u];
+    }
     carry += tot;
   }
   if (threadIdx.x == 0) nnz[blockIdx.x] = carry;
@@ -525,13 +659,23 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
   sp.zrev = (K > 1 && z_a > z_b) ? 1 : 0;
   const Level* in = m->in_level;
   const Level* out = m->out_level;
-  const size_t lds = size_t(m->tile) * sizeof(KeyT) + WIN_CAP_BYTES;
-  if (m->n_tiles > 0)
-    hipLaunchKernelGGL((kmap_search_kernel<KeyT, K>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
+  const bool pairs = !(m->desc.layout & SPC_LAYOUT_OS);
+  const size_t lds = size_t(m->tile) * sizeof(KeyT) + WIN_CAP_BYTES + (pairs ? size_t(K) * K * m->tile * 5 : 0);
+  auto go = [&](auto PAIRS_) {
+    constexpr bool PAIRS = decltype(PAIRS_)::value;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&kmap_search_kernel<KeyT, K, PAIRS>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    (void)attr;
+    hipLaunchKernelGGL((kmap_search_kernel<KeyT, K, PAIRS>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
                        sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm,
-                       (m->sym && !(m->desc.layout & SPC_LAYOUT_OS)) ? m->k_lim : m->K3);
+                       (m->sym && pairs) ? m->k_lim : m->K3, m->tile_pairs);
+  };
+  if (m->n_tiles > 0) {
+    if (pairs) go(std::true_type{});
+    else go(std::false_type{});
+  }
   return SPC_OK;
 }
 
@@ -557,6 +701,7 @@ static void kmap_free(spc_kmap* m) {
   pool_free(m->ws_out, m->stream);
   pool_free(m->nnz_dev, m->stream);
   pool_free(m->tile_counts, m->stream);
+  pool_free(m->tile_pairs, m->stream);
   level_unref(m->in_level);
   level_unref(m->out_level);
   if (m->ready) (void)hipEventDestroy(m->ready);
@@ -630,15 +775,21 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->n_blocks_cap = (m->out_cap + 31) / 32;
   m->mask_words = (m->K3 + 31) / 32;
   const size_t cells = std::max<size_t>(size_t(m->n_blocks_cap) * 32 * m->K3, 64);
-  m->os_map = static_cast<int32_t*>(pool_alloc(cells * 4, s));
-  m->block_masks = static_cast<uint32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * m->mask_words * 4, 256), s));
+  const bool with_os = (l.layout & SPC_LAYOUT_OS) != 0;
+  // the |V_q| x K^3 matrix and its block masks exist only when the output-stationary layout is asked for
+  if (with_os) {
+    m->os_map = static_cast<int32_t*>(pool_alloc(cells * 4, s));
+    m->block_masks = static_cast<uint32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * m->mask_words * 4, 256), s));
+  }
   m->nnz_dev = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->K3) * 4, 256), s));
-  bool ok = m->os_map && m->nnz_dev && m->block_masks;
+  bool ok = m->nnz_dev && (!with_os || (m->os_map && m->block_masks));
   if (ok && (l.layout & SPC_LAYOUT_WS)) {
     m->ws_in = static_cast<int32_t*>(pool_alloc(cells * 4, s));
     m->ws_out = static_cast<int32_t*>(pool_alloc(cells * 4, s));
     m->tile_counts = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->K3 * 4, 256), s));
-    ok = m->ws_in && m->ws_out && m->tile_counts;
+    // slabs of compacted pairs, one per search tile (bounded by tile * K^3 pairs each; a tile writes its hits only)
+    if (!with_os) m->tile_pairs = static_cast<int2*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->tile * m->K3 * 8, 256), s));
+    ok = m->ws_in && m->ws_out && m->tile_counts && (with_os || m->tile_pairs);
   }
   if (!ok) {
     kmap_free(m);
@@ -649,9 +800,15 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
     const int n_out_h = static_cast<int>(out->n_host < 0 ? 0 : out->n_host);
     hipLaunchKernelGGL(ws_scan_kernel, dim3(m->K3), dim3(256), 0, s, m->tile_counts, m->n_tiles, m->tile, n_out_h,
                        out->n_dev, m->nnz_dev, m->k_lim);
-    if (m->n_tiles > 0)
+    if (m->n_tiles > 0 && with_os)
       hipLaunchKernelGGL(ws_fill_kernel, dim3(m->n_tiles), dim3(256), 0, s, m->os_map, n_out_h,
                          out->n_dev, m->K3, m->tile, m->tile_counts, m->n_tiles, m->ws_in, m->ws_out, m->out_cap, m->k_lim);
+    else if (m->n_tiles > 0)
+      hipLaunchKernelGGL(ws_fill_pairs_kernel, dim3(m->n_tiles), dim3(256), 0, s, m->tile_pairs, n_out_h, out->n_dev, m->K3,
+                         m->tile, m->tile_counts, m->n_tiles, m->nnz_dev, m->ws_in, m->ws_out, m->out_cap, m->k_lim);
+    // the slabs are dead once the lists are filled: back to the cache (reuse is ordered behind this stream's work)
+    pool_free(m->tile_pairs, s);
+    m->tile_pairs = nullptr;
   }
   if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "kernel-map launch failed");
   if (rc == SPC_OK && (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||

@@ -166,7 +166,8 @@ struct spc_kmap {
   int32_t* ws_in = nullptr;         // [K3][out_cap]
   int32_t* ws_out = nullptr;        // [K3][out_cap]
   int32_t* nnz_dev = nullptr;       // [K3]
-  int32_t* tile_counts = nullptr;   // [n_tiles][K3] scratch of the two-pass compaction
+  int32_t* tile_counts = nullptr;   // [K3][n_tiles] scratch of the two-pass compaction
+  int2* tile_pairs = nullptr;       // WS-only builds: per search tile a slab of compacted (in, out) pairs (scratch)
   int tile = 0, n_tiles = 0;
   std::vector<int64_t> nnz_host;    // filled lazily
   hipEvent_t ready = nullptr;       // recorded after the last build kernel

@@ -572,3 +572,37 @@ def test_destroy_and_rebuild_while_another_stream_still_reads_the_map():
         torch.cuda.synchronize()
         assert torch.equal(out, ref), rep
         km2.destroy()
+
+
+@pytest.mark.parametrize("name,K,s_l,transposed,key_bits,with_perm", [
+    ("tiny", 3, 1, 0, 0, False), ("tiny_neg", 5, 1, 0, 0, True), ("tiny", 7, 1, 0, 64, False), ("tiny", 1, 1, 0, 0, False),
+    ("tiny_neg", 3, 2, 0, 0, True), ("tiny_neg", 2, 2, 0, 0, False), ("tiny_neg", 2, 2, 1, 0, False), ("tiny", 3, 2, 1, 64, False),
+    ("rand_b3", 3, 1, 0, 0, True), ("rand_b3", 5, 1, 0, 64, False), ("grid", 3, 1, 0, 0, False), ("ragged", 5, 1, 0, 0, False),
+    ("one", 3, 1, 0, 0, False), ("rand_n70001", 3, 1, 0, 0, True), ("skew_60k", 5, 1, 0, 0, False),
+])
+def test_kmap_ws_layout_alone(name, K, s_l, transposed, key_bits, with_perm):
+    """The weight-stationary layout built on its own (no |V_q| x K^3 matrix is ever written): lists, counts
+    and features equal the oracle's, with and without the sort permutation folded in."""
+    c = _cloud(name)
+    desc = fit_desc(c, [(K, 1, s_l)], key_bits)
+    keys, perm = gpu_pack(c, desc)
+    cs, operm = oracle.sort_coords(c)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, transposed, B.LAYOUT_WS, in_perm=perm if with_perm else None)
+    ci, co, M = oracle_layer(cs, K, 1, s_l, transposed)
+    ref_t = oracle.triples(M)
+    assert km.n_out == len(co)
+    got = km.export_triples(B.LAYOUT_WS)
+    if with_perm:
+        ref_t[:, 1] = operm[ref_t[:, 1]]  # sorted position -> original row
+    assert np.array_equal(got, ref_t[np.lexsort((ref_t[:, 2], ref_t[:, 0]))])
+    assert np.array_equal(km.nnz(), np.bincount(ref_t[:, 0], minlength=K ** 3))
+    with pytest.raises(B.SpcError):
+        km.export_triples(B.LAYOUT_OS)
+    F = synth.features(len(c) if with_perm else len(ci), 32, np.float16, seed=41)
+    W = synth.weights(K ** 3, 32, 64, np.float16, seed=42)
+    ref = oracle.conv(M, (F[operm] if with_perm else F).astype(np.float64), W.astype(np.float64))
+    y = B.spc_conv_forward(km, torch.from_numpy(F).cuda(), torch.from_numpy(W).cuda(), B.DATAFLOW_WS)
+    assert_close(y.cpu().double().numpy(), ref, 1e-2, name)
+    with pytest.raises(B.SpcError):
+        B.spc_conv_forward(km, torch.from_numpy(F).cuda(), torch.from_numpy(W).cuda(), B.DATAFLOW_OS)
+    km.destroy()
