@@ -52,6 +52,12 @@ extern "C" {
  * itself, so the feature kernel derives both from the stored half (Section 5.4).  Without the OS
  * layout the search itself visits only that half of the offsets. */
 #define SPC_LAYOUT_WS_SYM 4
+/* Modifier of SPC_LAYOUT_BOTH for the hybrid dual dataflow with threshold t (Section 5.4, 1 <= t <= 255): the
+ * offsets whose L1 norm (in units of the input stride) is below t, the dense ones, are written into the OS
+ * matrix only, the others into the WS lists only, so the map build moves |V_q| x K_dense matrix entries plus the
+ * sparse offsets' pairs instead of both full layouts.  Such a map serves spc_conv_forward_hybrid with that same
+ * t (other requests return SPC_ERR_ARG); accessors report each offset from the layout that holds it. */
+#define SPC_LAYOUT_HYBRID_T(t) ((t) << 8)
 
 #define SPC_DATAFLOW_OS 0 /* output-stationary: no atomics, bit-reproducible */
 #define SPC_DATAFLOW_WS 1 /* weight-stationary: fp32 atomic accumulation */
@@ -142,7 +148,9 @@ int spc_pack_coords_noalloc(const int32_t* coords_bxyz, int64_t n, const spc_pac
  *                out_i = in_j + delta_k with delta_k from Delta(K, in_stride) — the
  *                pairs of the strided layer with roles swapped.  (The paper does not
  *                define transposed layers; this is the usual generalised-SpC reading.)
- *   layout       SPC_LAYOUT_OS, _WS or _BOTH: which representation(s) to build.
+ *   layout       SPC_LAYOUT_OS, _WS or _BOTH: which representation(s) to build (| SPC_LAYOUT_WS_SYM,
+ *                | SPC_LAYOUT_HYBRID_T(t)).  The WS lists are compacted tile by tile inside the search
+ *                and never pass through a |V_q| x K^3 matrix; without SPC_LAYOUT_OS no matrix exists.
  */
 typedef struct spc_layer_desc {
   int32_t K, in_stride, layer_stride, transposed, layout;

@@ -18,6 +18,14 @@ OK = 0
 DTYPE_F16, DTYPE_BF16, DTYPE_F32 = 0, 1, 2
 LAYOUT_OS, LAYOUT_WS, LAYOUT_BOTH = 1, 2, 3
 LAYOUT_WS_SYM = 4  # with LAYOUT_WS: symmetric half-map of a submanifold layer
+
+
+def LAYOUT_HYBRID_T(t: int) -> int:
+    """with LAYOUT_BOTH: build for the hybrid dual dataflow with threshold t (dense offsets in the OS matrix only,
+    sparse ones in the WS lists only)."""
+    return int(t) << 8
+
+
 DATAFLOW_OS, DATAFLOW_WS = 0, 1
 PACK_VALIDATE = 1
 CONV_RELU = 1

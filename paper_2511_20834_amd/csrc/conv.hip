@@ -56,14 +56,6 @@ __device__ inline void static_for(Fn&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
-// Subset of the K^3 weight offsets a kernel works on (bit k of word k/32): all of them for a
-// single dataflow, the dense or the sparse ones of the hybrid dual dataflow (Section 5.4).
-constexpr int KMASK_WORDS = 11;  // 7^3 = 343 bits
-struct KMask {
-  uint32_t w[KMASK_WORDS];
-  __host__ __device__ bool has(int k) const { return (w[k >> 5] >> (k & 31)) & 1u; }
-};
-
 constexpr int CONV_THREADS = 256;
 constexpr int CK = 64;  // input channels staged per step
 
@@ -1087,15 +1079,6 @@ static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
   return rc;
 }
 
-// L1 norm of weight offset k in units of the input stride (Section 5.4: offsets below the
-// threshold are the dense ones).  Even kernel sizes have offsets {0, 1} per axis.
-static int offset_l1(int K, int k) {
-  const int iz = k % K, iy = (k / K) % K, ix = k / (K * K);
-  if (K % 2 == 0) return ix + iy + iz;
-  const int c = (K - 1) / 2;
-  return std::abs(ix - c) + std::abs(iy - c) + std::abs(iz - c);
-}
-
 // Common part of the two entry points: offsets with L1 norm < t run output-stationary, the others
 // weight-stationary.
 static int conv_entry(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights, void* feats_out, int64_t ld_out,
@@ -1111,6 +1094,15 @@ static int conv_entry(spc_kmap* m, const void* feats_in, int64_t ld_in, const vo
   }
   if (a.any_os && !(m->desc.layout & SPC_LAYOUT_OS)) return set_error(SPC_ERR_ARG, "map has no OS layout");
   if (a.any_ws && !(m->desc.layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "map has no WS layout");
+  // a map built for one threshold of the hybrid dual dataflow holds every offset in one layout only
+  for (int k = 0; k < m->K3 && m->hybrid_t; ++k) {
+    const bool dense = a.os_mask.has(k);
+    const int ks = (m->sym && k > (m->K3 - 1) / 2) ? m->K3 - 1 - k : k;  // a symmetric map derives the second half
+    const bool have = dense ? m->os_k.has(k) : (m->ws_k.has(ks) || (m->sym && k == (m->K3 - 1) / 2));
+    if (!have)
+      return set_error(SPC_ERR_ARG, "map was built for the hybrid threshold %d: offset %d is not in the %s layout", m->hybrid_t, k,
+                       dense ? "OS" : "WS");
+  }
   a.F = feats_in;
   a.ld_in = ld_in;
   a.W = weights;

@@ -159,18 +159,22 @@ __device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
 // (240 k voxels, 5x5x5: map build 90 us with five or seven, 75 us with two, three or four).
 constexpr int SEARCH_GB_SMALL = 5, SEARCH_GB_LARGE = 3;
 
-// PAIRS = false: the blocked |V_q| x K^3 matrix M, the per-block offset masks and (when tile_counts is given)
-// the per-tile hit counts are written.  PAIRS = true (weight-stationary layout alone): no matrix exists anywhere;
-// a tile keeps, per (group, row), the position of its lower bound and the hit bits of the group's K queries in
-// LDS (5 bytes where the matrix has 4 K), and once all groups are searched it writes its hits as compacted
-// (in, out) pairs, offset-major and row-ascending, into its own slab of `tile_pairs` (slab = tile * K^3 pairs, of
-// which only the first sum-of-hits are touched); tile_counts gets the hits per (offset, tile).
+// Two outputs, each for its own subset of the K^3 offsets (Section 5.4: all offsets in one of them for a single
+// dataflow; the dense offsets in the matrix and the sparse ones in the lists for the hybrid dual dataflow):
+//   os_k: columns of the blocked |V_q| x K^3 matrix M and bits of the per-block offset masks (M = NULL: none);
+//   ws_k: (PAIRS = true) weight-stationary lists.  They never pass through a matrix: a tile keeps, per (group,
+//         row), the position of its lower bound and the hit bits of the group's K queries in LDS (5 bytes where
+//         the matrix has 4 K), and once all groups are searched it writes the hits of the ws_k offsets as
+//         compacted (in, out) pairs, offset-major and row-ascending, into its own slab of `tile_pairs` (slab =
+//         tile * K^3 pairs, of which only the first sum-of-hits are touched); tile_counts gets the hits per
+//         (offset, tile).
+// Groups none of whose offsets is wanted are not searched (the second half of a symmetric map, for example).
 template <typename KeyT, int K, bool PAIRS>
 __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
     int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
     uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
-    const int32_t* __restrict__ in_perm, int k_lim, int2* __restrict__ tile_pairs) {
+    const int32_t* __restrict__ in_perm, KMask os_k, KMask ws_k, int2* __restrict__ tile_pairs) {
   constexpr int G = K * K, K3 = K * K * K;
   constexpr int SEARCH_GB = (K <= 3 && sizeof(KeyT) == 4) ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
   constexpr int G_POW2 = G <= 1 ? 1 : G <= 4 ? 4 : G <= 16 ? 16 : G <= 64 ? 64 : 128;  // power of two >= G
@@ -194,6 +198,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   __shared__ int s_cnt[K3];
   __shared__ unsigned s_mask[MAX_BLOCKS * MW];
   __shared__ KeyT s_gd[G];  // packed (dx,dy,zmin) offset of every group
+  __shared__ uint32_t s_osk[KMASK_WORDS], s_wsk[KMASK_WORDS];  // the offset subsets, readable at run-time indices
+  __shared__ int s_need[G];                                    // group g has an offset in either subset
 
   const int n_in = n_in_d ? *n_in_d : n_in_h;
   const int n_out = n_out_d ? *n_out_d : n_out_h;
@@ -213,12 +219,24 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   for (int k = tid; k < K3; k += SEARCH_THREADS) s_cnt[k] = 0;
   for (int k = tid; k < MAX_BLOCKS * MW; k += SEARCH_THREADS) s_mask[k] = 0u;
   for (int k = tid; k < 2 * G; k += SEARCH_THREADS) s_bound[k] = 0;
-  // only offsets k < k_lim are searched (all of them, or the first half of a symmetric map):
-  // groups past the limit get empty windows, the group the limit cuts keeps its first offsets
-  const int g_lim = (k_lim + K - 1) / K;
+#pragma unroll
+  for (int wd = 0; wd < KMASK_WORDS; ++wd)
+    if (tid == wd) {
+      s_osk[wd] = M ? os_k.w[wd] : 0u;
+      s_wsk[wd] = PAIRS ? ws_k.w[wd] : 0u;
+    }
 #pragma unroll
   for (int g = 0; g < G; ++g)  // static indices keep the kernel arguments in scalar registers
     if (tid == g) s_gd[g] = sp.X[g / K] + sp.Y[g % K] + sp.zmin;
+  __syncthreads();
+  auto os_has = [&](int k) { return (s_osk[k >> 5] >> (k & 31)) & 1u; };
+  auto ws_has = [&](int k) { return (s_wsk[k >> 5] >> (k & 31)) & 1u; };
+  // only groups with a wanted offset are searched: the others get empty windows
+  if (tid < G) {
+    int need = 0;
+    for (int t = 0; t < K; ++t) need |= os_has(tid * K + t) | ws_has(tid * K + t);
+    s_need[tid] = need;
+  }
   __syncthreads();
   const KeyT kfirst = okeys[0], klast = okeys[rows - 1];
   const KeyT zspan = KeyT(K - 1) * sp.zstep;
@@ -241,7 +259,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int sc = (u * NW + wave) * Q + grp;
-      if (lane % BOUND_P == 0 && sc < 2 * g_lim) s_bound[sc] = res[u];
+      if (lane % BOUND_P == 0 && sc < 2 * G && s_need[sc >> 1]) s_bound[sc] = res[u];
     }
   }
   __syncthreads();
@@ -310,7 +328,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const KeyT okey = act ? okeys[v] : KeyT(0);
   const int bl = v >> 5;
   int32_t* Mrow = M + (b0 + bl) * K3 * 32 + (v & 31);
-  for (int gb = part; gb < g_lim; gb += parts * SEARCH_GB) {
+  for (int gb = part; gb < G; gb += parts * SEARCH_GB) {
     // wb: LDS base of the group's window.  Groups past the limit, rows past the end and windows kept in
     // global memory get an empty window at base 0, so that every LDS read below is unconditional and
     // in range (index -1 is the last staged output key) and the reads of a round issue back to back.
@@ -322,17 +340,18 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
     for (int j = 0; j < SEARCH_GB; ++j) {
       const int g = gb + j * parts;
-      gidx[j] = g < g_lim ? g : -1;
-      const int gc = g < g_lim ? g : 0;
+      const bool wanted = g < G && s_need[min(g, G - 1)];
+      gidx[j] = wanted ? g : -1;
+      const int gc = wanted ? g : 0;
       const int woff = s_woff[gc];
-      glob[j] = g < g_lim && woff < 0;
+      glob[j] = wanted && woff < 0;
       any_glob |= glob[j];
       wb[j] = woff < 0 ? 0 : woff;
-      wsz[j] = (g < g_lim && act && woff >= 0) ? s_wsz[gc] : 0;
+      wsz[j] = (wanted && act && woff >= 0) ? s_wsz[gc] : 0;
       wlo[j] = s_wlo[gc];
       q0[j] = okey + s_gd[gc];
       pos[j] = 0;
-      if (g < g_lim && woff >= 0) maxw = max(maxw, s_wsz[gc]);
+      if (wanted && woff >= 0) maxw = max(maxw, s_wsz[gc]);
     }
     // lower bounds in LDS: pos += bit while the key before pos+bit is smaller than the query
     for (int bit = maxw > 0 ? 1 << (31 - __clz(maxw)) : 0; bit > 0; bit >>= 1) {
@@ -391,13 +410,13 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
         for (int t = 0; t < K; ++t) {
           const int k = g * K + t;
-          if (k >= k_lim) continue;  // uniform
+          if (!ws_has(k)) continue;  // uniform
           const unsigned long long hit = __ballot(r[j][t] >= 0);
           if (hit && lane == 0) atomicAdd(&s_cnt[k], __popcll(hit));
         }
       }
-      continue;
     }
+    if (!M) continue;  // no offset goes to the matrix (uniform over the launch)
     // found positions are stored as they are, or mapped to the caller's row numbering.  The
     // lookups are unconditional (misses read entry 0) and all issued before the first store: on this
     // target loads and stores share one counter, so a load waited for between two stores would
@@ -425,13 +444,12 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
       for (int t = 0; t < K; ++t) {
         const int k = g * K + t;
-        if (k >= k_lim) continue;  // uniform
+        if (!os_has(k)) continue;  // uniform
         if (v < rows32) Mrow[k * 32] = jv[j][t];  // rows past the end hold -1
         const unsigned long long hit = __ballot(r[j][t] >= 0);
         if (hit && lane == 0) {  // lane 0 speaks for the wave's two 32-row blocks
           if (unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
           if (unsigned(hit >> 32)) atomicOr(&s_mask[(bl + 1) * MW + (k >> 5)], 1u << (k & 31));
-          if (tile_counts) atomicAdd(&s_cnt[k], __popcll(hit));
         }
       }
     }
@@ -459,8 +477,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     // compaction: a wave takes an offset at a time and walks the tile's rows in steps of 64; the hit's input
     // position is the group's lower bound plus the number of the group's earlier queries that hit
     int2* slab = tile_pairs + int64_t(blockIdx.x) * tile * K3;
-    for (int k = wave; k < k_lim; k += NW) {
-      if (s_cnt[k] == 0) continue;  // uniform
+    for (int k = wave; k < K3; k += NW) {
+      if (s_cnt[k] == 0) continue;  // uniform (offsets outside ws_k are never counted)
       const int g = k / K, tk = k - g * K, tq = sp.zrev ? K - 1 - tk : tk;
       int at = s_off[k];
       for (int v0 = 0; v0 < rows; v0 += 64) {
@@ -475,12 +493,11 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
         at += __popcll(bal);
       }
     }
-    return;
   }
-  const int n_bl = rows32 >> 5;
-  for (int e = tid; e < n_bl * MW; e += SEARCH_THREADS) block_masks[b0 * MW + e] = s_mask[e];
-  if (tile_counts)
-    for (int k = tid; k < K3; k += SEARCH_THREADS) tile_counts[int64_t(k) * n_tiles_cap + blockIdx.x] = s_cnt[k];
+  if (M) {
+    const int n_bl = rows32 >> 5;
+    for (int e = tid; e < n_bl * MW; e += SEARCH_THREADS) block_masks[b0 * MW + e] = s_mask[e];
+  }
 }
 
 // Weight-stationary lists from the tiles' slabs of compacted pairs (the search kernel in its PAIRS form): one
@@ -584,57 +601,6 @@ __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile
   if (threadIdx.x == 0) nnz[blockIdx.x] = carry;
 }
 
-// One workgroup per tile of the search kernel.  In the blocked map a column (fixed k) of a
-// 32-row block is contiguous, so a wave filters two blocks of one offset per step with a
-// coalesced load and a ballot; list k comes out ordered by output index without atomics.
-constexpr int WS_FILL_U = 8;
-__global__ __launch_bounds__(256) void ws_fill_kernel(const int32_t* __restrict__ M, int n_out_h,
-                                                      const int* __restrict__ n_out_d, int K3, int tile,
-                                                      const int32_t* __restrict__ tile_base, int n_tiles_cap,
-                                                      int32_t* __restrict__ ws_in, int32_t* __restrict__ ws_out,
-                                                      int64_t ws_stride, int k_lim) {
-  const int n_out = n_out_d ? *n_out_d : n_out_h;
-  const int i0 = blockIdx.x * tile;
-  if (i0 >= n_out) return;
-  const int rows = min(tile, n_out - i0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t b0 = int64_t(i0) >> 5;
-  // a wave takes WS_FILL_U offsets at a time: their list positions and all their map entries of the tile
-  // (at most 128 rows: two per lane) are requested together, then compacted offset by offset
-  constexpr int U = WS_FILL_U;
-  for (int k0 = wave * U; k0 < k_lim; k0 += 4 * U) {
-    int base[U], j[U][2];
-#pragma unroll
-    for (int u = 0; u < U; ++u) base[u] = tile_base[int64_t(min(k0 + u, k_lim - 1)) * n_tiles_cap + blockIdx.x];
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int v = h * 64 + lane;
-        const int vc = min(v, rows - 1);
-        const int e = M[((b0 + (vc >> 5)) * K3 + min(k0 + u, k_lim - 1)) * 32 + (vc & 31)];
-        j[u][h] = v < rows ? e : -1;
-      }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (k0 + u >= k_lim) break;
-      int32_t* li = ws_in + int64_t(k0 + u) * ws_stride;
-      int32_t* lo = ws_out + int64_t(k0 + u) * ws_stride;
-      int at = base[u];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const unsigned long long m = __ballot(j[u][h] >= 0);
-        if (j[u][h] >= 0) {
-          const int r = at + lanemask_lt_popc(m);
-          li[r] = j[u][h];
-          lo[r] = i0 + h * 64 + lane;
-        }
-        at += __popcll(m);
-      }
-    }
-  }
-}
-
 __global__ void copy_int_kernel(const int* src, int* dst) { *dst = *src; }
 
 // ---------------------------------------------------------------- host side
@@ -659,7 +625,7 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
   sp.zrev = (K > 1 && z_a > z_b) ? 1 : 0;
   const Level* in = m->in_level;
   const Level* out = m->out_level;
-  const bool pairs = !(m->desc.layout & SPC_LAYOUT_OS);
+  const bool pairs = (m->desc.layout & SPC_LAYOUT_WS) != 0;
   const size_t lds = size_t(m->tile) * sizeof(KeyT) + WIN_CAP_BYTES + (pairs ? size_t(K) * K * m->tile * 5 : 0);
   auto go = [&](auto PAIRS_) {
     constexpr bool PAIRS = decltype(PAIRS_)::value;
@@ -669,8 +635,8 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
     hipLaunchKernelGGL((kmap_search_kernel<KeyT, K, PAIRS>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
-                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm,
-                       (m->sym && pairs) ? m->k_lim : m->K3, m->tile_pairs);
+                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm, m->os_k, m->ws_k,
+                       m->tile_pairs);
   };
   if (m->n_tiles > 0) {
     if (pairs) go(std::true_type{});
@@ -718,7 +684,10 @@ static int check_layer(const spc_layer_desc* l) {
   if (l->transposed != 0 && l->transposed != 1) return set_error(SPC_ERR_ARG, "transposed must be 0 or 1");
   if (l->transposed && l->layer_stride == 1) return set_error(SPC_ERR_ARG, "a transposed layer needs layer_stride > 1");
   const int base = l->layout & SPC_LAYOUT_BOTH;
-  if (l->layout < 1 || l->layout > 7 || base == 0) return set_error(SPC_ERR_ARG, "layout must be OS, WS or BOTH (| WS_SYM)");
+  const int thr = (l->layout >> 8) & 0xff;
+  if (l->layout < 1 || (l->layout & ~0xff07) || base == 0)
+    return set_error(SPC_ERR_ARG, "layout must be OS, WS or BOTH (| WS_SYM) (| HYBRID_T(t))");
+  if (thr && base != SPC_LAYOUT_BOTH) return set_error(SPC_ERR_ARG, "a hybrid threshold needs both layouts");
   if (l->layout & SPC_LAYOUT_WS_SYM) {
     if (!(l->layout & SPC_LAYOUT_WS)) return set_error(SPC_ERR_ARG, "WS_SYM modifies the WS layout");
     if (l->layer_stride != 1 || l->K % 2 == 0 || l->K < 3)
@@ -760,6 +729,16 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   m->K3 = l.K * l.K * l.K;
   m->sym = (l.layout & SPC_LAYOUT_WS_SYM) != 0;
   m->k_lim = m->sym ? (m->K3 - 1) / 2 : m->K3;
+  // Offsets of the matrix and of the lists.  With a threshold (hybrid dual dataflow, Section 5.4) the offsets
+  // whose L1 norm is below it go to the matrix only and the others to the lists only; a symmetric map keeps
+  // lists for the first half of its offsets.
+  m->hybrid_t = (l.layout >> 8) & 0xff;
+  for (int k = 0; k < m->K3; ++k) {
+    const bool dense = m->hybrid_t == 0 || offset_l1(l.K, k) < m->hybrid_t;
+    const bool sparse = m->hybrid_t == 0 || !dense;
+    if ((l.layout & SPC_LAYOUT_OS) && dense) m->os_k.w[k >> 5] |= 1u << (k & 31);
+    if ((l.layout & SPC_LAYOUT_WS) && sparse && k < m->k_lim) m->ws_k.w[k >> 5] |= 1u << (k & 31);
+  }
   m->stream = s;
   m->captured = stream_is_capturing(s);
   m->in_level = in;
@@ -788,8 +767,8 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
     m->ws_out = static_cast<int32_t*>(pool_alloc(cells * 4, s));
     m->tile_counts = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->K3 * 4, 256), s));
     // slabs of compacted pairs, one per search tile (bounded by tile * K^3 pairs each; a tile writes its hits only)
-    if (!with_os) m->tile_pairs = static_cast<int2*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->tile * m->K3 * 8, 256), s));
-    ok = m->ws_in && m->ws_out && m->tile_counts && (with_os || m->tile_pairs);
+    m->tile_pairs = static_cast<int2*>(pool_alloc(std::max<size_t>(size_t(m->n_tiles) * m->tile * m->K3 * 8, 256), s));
+    ok = m->ws_in && m->ws_out && m->tile_counts && m->tile_pairs;
   }
   if (!ok) {
     kmap_free(m);
@@ -800,10 +779,7 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
     const int n_out_h = static_cast<int>(out->n_host < 0 ? 0 : out->n_host);
     hipLaunchKernelGGL(ws_scan_kernel, dim3(m->K3), dim3(256), 0, s, m->tile_counts, m->n_tiles, m->tile, n_out_h,
                        out->n_dev, m->nnz_dev, m->k_lim);
-    if (m->n_tiles > 0 && with_os)
-      hipLaunchKernelGGL(ws_fill_kernel, dim3(m->n_tiles), dim3(256), 0, s, m->os_map, n_out_h,
-                         out->n_dev, m->K3, m->tile, m->tile_counts, m->n_tiles, m->ws_in, m->ws_out, m->out_cap, m->k_lim);
-    else if (m->n_tiles > 0)
+    if (m->n_tiles > 0)
       hipLaunchKernelGGL(ws_fill_pairs_kernel, dim3(m->n_tiles), dim3(256), 0, s, m->tile_pairs, n_out_h, out->n_dev, m->K3,
                          m->tile, m->tile_counts, m->n_tiles, m->nnz_dev, m->ws_in, m->ws_out, m->out_cap, m->k_lim);
     // the slabs are dead once the lists are filled: back to the cache (reuse is ordered behind this stream's work)
@@ -862,7 +838,17 @@ using NetKey = std::tuple<int, int, int, int>;
 static NetKey net_key(const spc_layer_desc& l) { return NetKey(l.K, l.in_stride, l.layer_stride, l.transposed); }
 static std::map<NetKey, int> net_layouts(const spc_layer_desc* layers, int n_layers) {
   std::map<NetKey, int> want;
-  for (int i = 0; i < n_layers; ++i) want[net_key(layers[i])] |= layers[i].layout;
+  for (int i = 0; i < n_layers; ++i) want[net_key(layers[i])] |= layers[i].layout & 0xff;
+  // a hybrid threshold survives only if every layer that shares the map asks for that same threshold
+  for (auto& kv : want) {
+    int thr = -1;
+    for (int i = 0; i < n_layers; ++i)
+      if (net_key(layers[i]) == kv.first) {
+        const int t = (layers[i].layout >> 8) & 0xff;
+        thr = thr < 0 ? t : (thr == t ? t : 0);
+      }
+    if (thr > 0) kv.second |= thr << 8;
+  }
   for (auto& kv : want) {
     bool all_sym = true;
     for (int i = 0; i < n_layers; ++i)
@@ -1155,7 +1141,7 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
     std::vector<int32_t> M(size_t((n_out + 31) / 32) * 32 * K3);
     if (!M.empty()) SPC_HIP_CHECK(hipMemcpy(M.data(), m->os_map, M.size() * 4, hipMemcpyDeviceToHost));
     for (int k = 0; k < K3; ++k)
-      for (int64_t i = 0; i < n_out; ++i) {
+      for (int64_t i = 0; i < n_out && m->os_k.has(k); ++i) {  // (a hybrid map holds the dense offsets only)
         const int32_t j = M[((i >> 5) * K3 + k) * 32 + (i & 31)];
         if (j < 0) continue;
         if (nnz < cap && triples) {
@@ -1179,6 +1165,7 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
       ++nnz;
     };
     for (int k = 0; k < K3; ++k) {
+      if (m->hybrid_t && m->os_k.has(k)) continue;  // a hybrid map keeps lists for the sparse offsets only
       // symmetric half-map: offset k > centre is the list of K^3-1-k with the roles swapped (both
       // index sequences of a list ascend, so the order by output index is kept); the centre pairs
       // every voxel with itself
@@ -1216,7 +1203,14 @@ int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host) {
     SPC_RETURN_IF(wait_map(m));
     SPC_RETURN_IF(fetch_level_n(m->out_level));
     std::vector<int64_t> cnt(m->K3, 0);
-    if (m->desc.layout & SPC_LAYOUT_WS) {
+    if (m->hybrid_t) {  // dense offsets are counted in the matrix below, the others come from the lists' lengths
+      std::vector<int32_t> c(m->K3);
+      SPC_HIP_CHECK(hipMemcpy(c.data(), m->nnz_dev, size_t(m->K3) * 4, hipMemcpyDeviceToHost));
+      const int kc = (m->K3 - 1) / 2;
+      for (int k = 0; k < m->K3; ++k)
+        if (!m->os_k.has(k)) cnt[k] = (m->sym && k == kc) ? m->out_level->n_fetched : c[(m->sym && k > kc) ? m->K3 - 1 - k : k];
+    }
+    if ((m->desc.layout & SPC_LAYOUT_WS) && !m->hybrid_t) {
       std::vector<int32_t> c(m->K3);
       SPC_HIP_CHECK(hipMemcpy(c.data(), m->nnz_dev, size_t(m->K3) * 4, hipMemcpyDeviceToHost));
       for (int k = 0; k < m->K3; ++k) cnt[k] = c[k];
@@ -1230,7 +1224,8 @@ int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host) {
       std::vector<int32_t> M(size_t((n_out + 31) / 32) * 32 * m->K3);
       if (!M.empty()) SPC_HIP_CHECK(hipMemcpy(M.data(), m->os_map, M.size() * 4, hipMemcpyDeviceToHost));
       for (int64_t i = 0; i < n_out; ++i)
-        for (int k = 0; k < m->K3; ++k) cnt[k] += M[((i >> 5) * m->K3 + k) * 32 + (i & 31)] >= 0;
+        for (int k = 0; k < m->K3; ++k)
+          if (m->os_k.has(k)) cnt[k] += M[((i >> 5) * m->K3 + k) * 32 + (i & 31)] >= 0;
     }
     m->nnz_host = cnt;
   }

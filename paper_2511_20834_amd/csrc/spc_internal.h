@@ -51,6 +51,26 @@ int check_desc(const spc_pack_desc* d, PackInfo* pi);
 // Mask that clears the low m bits of every spatial field (Section 5.3).
 uint64_t level_mask(const PackInfo& pi, int m);
 
+// ---------------------------------------------------------------- offset subsets
+// Subset of the K^3 weight offsets (bit k of word k/32): all of them for a single dataflow, the dense or the
+// sparse ones of the hybrid dual dataflow (Section 5.4).
+constexpr int KMASK_WORDS = 11;  // 7^3 = 343 bits
+struct KMask {
+  uint32_t w[KMASK_WORDS];
+#ifdef __HIPCC__
+  __host__ __device__
+#endif
+  bool has(int k) const { return (w[k >> 5] >> (k & 31)) & 1u; }
+};
+// L1 norm of weight offset k in units of the input stride (Section 5.4: offsets below the threshold are the
+// dense ones).  Even kernel sizes have offsets {0, 1} per axis.
+inline int offset_l1(int K, int k) {
+  const int iz = k % K, iy = (k / K) % K, ix = k / (K * K);
+  if (K % 2 == 0) return ix + iy + iz;
+  const int c = (K - 1) / 2;
+  return (ix > c ? ix - c : c - ix) + (iy > c ? iy - c : c - iy) + (iz > c ? iz - c : c - iz);
+}
+
 // ---------------------------------------------------------------- coordinate levels
 // One sorted packed-key array (a stride level).  n is known on the host for the
 // caller's own array; for derived levels it lives on the device until the host asks.
@@ -153,6 +173,8 @@ struct spc_kmap {
   int K3 = 0;
   bool sym = false;                 // WS lists hold offsets k < (K^3-1)/2 only (symmetric half-map)
   int k_lim = 0;                    // offsets that have a WS list of their own
+  int hybrid_t = 0;                 // > 0: built for the hybrid dual dataflow with this threshold
+  spc::KMask os_k{}, ws_k{};        // offsets whose matrix column / whose list the build wrote
   spc::Level* in_level = nullptr;   // the layer's input voxels
   spc::Level* out_level = nullptr;  // the layer's output voxels
   const int32_t* in_perm = nullptr; // caller's row number of every input voxel (borrowed), or NULL

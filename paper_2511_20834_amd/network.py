@@ -44,7 +44,8 @@ class SpcNetwork:
         kernels are chosen for those sizes without anybody waiting for the true counts."""
         req = []
         for l, df, t in zip(self.layers, self.dataflow, self.hybrid_t):
-            layout = B.LAYOUT_BOTH if t is not None else (B.LAYOUT_OS if df == B.DATAFLOW_OS else B.LAYOUT_WS)
+            # a hybrid layer asks for exactly the split it will use: dense offsets in the matrix, sparse ones in lists
+            layout = (B.LAYOUT_BOTH | B.LAYOUT_HYBRID_T(t)) if t is not None else (B.LAYOUT_OS if df == B.DATAFLOW_OS else B.LAYOUT_WS)
             req.append((l["K"], l["in_stride"], l["layer_stride"], l["transposed"], layout))
         self.maps = B.spc_build_kmaps_network(v0_keys, desc, req, streams, flags)
         if use_hints and self.size_hints is not None:

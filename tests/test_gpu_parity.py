@@ -606,3 +606,50 @@ def test_kmap_ws_layout_alone(name, K, s_l, transposed, key_bits, with_perm):
     with pytest.raises(B.SpcError):
         B.spc_conv_forward(km, torch.from_numpy(F).cuda(), torch.from_numpy(W).cuda(), B.DATAFLOW_OS)
     km.destroy()
+
+
+def _l1(K, k):
+    iz, iy, ix = k % K, (k // K) % K, k // (K * K)
+    if K % 2 == 0:
+        return ix + iy + iz
+    c = (K - 1) // 2
+    return abs(ix - c) + abs(iy - c) + abs(iz - c)
+
+
+@pytest.mark.parametrize("name,K,s_l,sym", [("rand_b3", 3, 1, False), ("tiny_neg", 5, 1, False), ("tiny", 3, 1, True),
+                                            ("tiny_neg", 2, 2, False), ("rand_n70001", 3, 1, False), ("tiny", 5, 1, True)])
+def test_hybrid_layout_holds_each_offset_once(name, K, s_l, sym):
+    """Map built for one threshold t of the hybrid dual dataflow (Section 5.4): the OS matrix holds the offsets
+    with L1 norm < t only, the WS lists the others only; together they are the oracle's map, and the hybrid
+    feature computation with that t gives Eq. (2)."""
+    c = _cloud(name)
+    desc = fit_desc(c, [(K, 1, s_l)])
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    ci, co, M = oracle_layer(cs, K, 1, s_l, 0)
+    ref_t = oracle.triples(M)
+    l1 = np.array([_l1(K, k) for k in range(K ** 3)])
+    F, W = synth.features(len(ci), 32, np.float16, seed=81), synth.weights(K ** 3, 32, 64, np.float16, seed=82)
+    Ft, Wt = torch.from_numpy(F).cuda(), torch.from_numpy(W).cuda()
+    ref = oracle.conv(M, F.astype(np.float64), W.astype(np.float64))
+    l1_max = int(l1.max())
+    for t in range(1, l1_max + 1):
+        layout = B.LAYOUT_BOTH | B.LAYOUT_HYBRID_T(t) | (B.LAYOUT_WS_SYM if sym else 0)
+        km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout)
+        dense = l1[ref_t[:, 0]] < t
+        assert np.array_equal(km.export_triples(B.LAYOUT_OS), ref_t[dense]), t
+        assert np.array_equal(km.export_triples(B.LAYOUT_WS), ref_t[~dense]), t
+        assert np.array_equal(km.nnz(), np.bincount(ref_t[:, 0], minlength=K ** 3)), t
+        y = B.spc_conv_forward(km, Ft, Wt, hybrid_t=t)
+        assert_close(y.cpu().double().numpy(), ref, 1e-2, (name, t))
+        for bad_t in (t + 1, t - 1):  # another split needs offsets this map does not hold in that layout
+            if sym and bad_t == 0:
+                continue  # (a symmetric map serves the centre offset in either dataflow: it pairs every voxel with itself)
+            with pytest.raises(B.SpcError) as e:
+                B.spc_conv_forward(km, Ft, Wt, hybrid_t=bad_t)
+            assert e.value.code == B.ERR_ARG
+        with pytest.raises(B.SpcError):
+            B.spc_conv_forward(km, Ft, Wt, B.DATAFLOW_OS)
+        km.destroy()
+    with pytest.raises(B.SpcError):  # a threshold needs both layouts
+        B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_OS | B.LAYOUT_HYBRID_T(1))
