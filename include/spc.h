@@ -227,6 +227,11 @@ int spc_kmap_ws_lists(const spc_kmap* m, const int32_t** in_idx, const int32_t**
  * groups of offsets whose windows no longer fit are searched in global memory).  Host values, no wait.
  * Either pointer may be NULL. */
 int spc_kmap_search_info(const spc_kmap* m, int32_t* tile_rows, int32_t* window_keys);
+/* Number of kernel-map searches this process has enqueued so far (host counter, no wait).  A network build
+ * searches once per distinct map, and not at all for a transposed map whose strided twin (same K, strides; K equal
+ * to the layer stride, as the 2x2x2 stride-2 layers of a UNet) is part of the same build: that map is derived from
+ * the twin's pairs (Section 5.5, maps shared between layers). */
+int64_t spc_search_count(void);
 /* nnz_host [host] int64[K^3]: valid entries per offset.  Waits for the build. */
 int spc_kmap_nnz(spc_kmap* m, int64_t* nnz_host);
 /*

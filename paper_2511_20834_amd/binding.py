@@ -40,7 +40,7 @@ ERR_ARG, ERR_RANGE, ERR_DUP, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = -1, -2, -3, -
 EXPORTS = [
     "spc_pack_desc_fit", "spc_pack_coords", "spc_pack_coords_noalloc", "spc_build_kmap", "spc_build_kmap_perm", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
-    "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_search_info", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
+    "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_search_info", "spc_search_count", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
     "spc_conv_forward", "spc_conv_forward_hybrid",
     "spc_conv_prepare_weights", "spc_permute_rows",
     "spc_release_cache", "spc_last_error", "spc_version",
@@ -98,6 +98,7 @@ def lib():
         L.spc_kmap_ws_lists.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64)]
         L.spc_kmap_nnz.argtypes = [vp, ctypes.POINTER(i64)]
         L.spc_kmap_search_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.spc_search_count.restype = i64
         L.spc_kmap_export_triples.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i64)]
         L.spc_kmap_set_size_hint.argtypes = [vp, i64]
         L.spc_kmap_destroy.argtypes = [vp]
@@ -247,6 +248,11 @@ class KMap:
         a = np.empty(n, dtype=np.uint32 if self.desc.key_bits == 32 else np.uint64)
         _check(lib().spc_kmap_copy_out_keys(self.handle, a.ctypes.data_as(ctypes.c_void_p), n))
         return a.astype(np.uint64)
+
+
+def spc_search_count() -> int:
+    """Kernel-map searches enqueued by this process so far."""
+    return int(lib().spc_search_count())
 
 
 def spc_kmap_search_info(kmap: KMap):

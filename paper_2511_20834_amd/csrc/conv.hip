@@ -965,7 +965,7 @@ static void launch_ws_mfma(const ConvArgs& a, const T* Wp, float* accum) {
   const int64_t max_items = ((a.rows_cap + TROWS - 1) / TROWS) * gy;
   const int gx = static_cast<int>(std::min<int64_t>(max_items, 2048));
   hipLaunchKernelGGL((conv_ws_mfma_kernel<T, NB, RB>), dim3(gx), dim3(CONV_THREADS), lds, a.s, a.m->ws_in, a.m->ws_out,
-                     a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin, a.ws_mask,
+                     a.m->nnz_dev, a.m->ws_stride, static_cast<const T*>(a.F), a.ld_in, Wp, accum, a.cin, a.ws_mask,
                      a.m->sym ? 1 : 0, a.m->K3, a.n_out_h, a.n_out_d);
 }
 
@@ -1064,7 +1064,7 @@ static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
     // nnz[k] <= n_out for every offset
     if (a.any_ws)
       hipLaunchKernelGGL(conv_ws_simple_kernel<T>, dim3((out_elems + 255) / 256, a.m->sym ? (K3 - 1) / 2 + 1 : K3), dim3(256), 0,
-                         a.s, a.m->ws_in, a.m->ws_out, a.m->nnz_dev, a.m->out_cap, static_cast<const T*>(a.F), a.ld_in,
+                         a.s, a.m->ws_in, a.m->ws_out, a.m->nnz_dev, a.m->ws_stride, static_cast<const T*>(a.F), a.ld_in,
                          static_cast<const T*>(a.W), accum, a.cin, a.cout, a.ws_mask, a.m->sym ? 1 : 0, K3, a.n_out_h, a.n_out_d);
     if (a.any_os)
       hipLaunchKernelGGL(conv_os_simple_kernel<T>, dim3((out_elems + 255) / 256), dim3(256), 0, a.s, a.m->os_map, a.n_out_h,

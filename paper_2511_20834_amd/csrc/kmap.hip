@@ -174,7 +174,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
     int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
     uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
-    const int32_t* __restrict__ in_perm, KMask os_k, KMask ws_k, int2* __restrict__ tile_pairs) {
+    const int32_t* __restrict__ in_perm, KMask os_k, KMask ws_k, int2* __restrict__ tile_pairs,
+    int32_t* __restrict__ inv_parent) {
   constexpr int G = K * K, K3 = K * K * K;
   constexpr int SEARCH_GB = (K <= 3 && sizeof(KeyT) == 4) ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
   constexpr int G_POW2 = G <= 1 ? 1 : G <= 4 ? 4 : G <= 16 ? 16 : G <= 64 ? 64 : 128;  // power of two >= G
@@ -399,6 +400,15 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
         h += hit ? 1 : 0;
       }
     }
+    // inverse of a strided map whose offsets partition the inputs (K = layer stride): every input voxel is hit by
+    // exactly one (output, offset), which is all its transposed twin needs
+    if (inv_parent) {
+#pragma unroll
+      for (int j = 0; j < SEARCH_GB; ++j)
+#pragma unroll
+        for (int t = 0; t < K; ++t)
+          if (gidx[j] >= 0 && r[j][t] >= 0) inv_parent[r[j][t]] = (i0 + v) * K3 + gidx[j] * K + t;
+    }
     if constexpr (PAIRS) {
       // the tile's records stay in LDS; hits are counted per offset (a wave speaks for its 64 rows)
 #pragma unroll
@@ -601,12 +611,38 @@ __global__ __launch_bounds__(256) void ws_scan_kernel(int32_t* __restrict__ tile
   if (threadIdx.x == 0) nnz[blockIdx.x] = carry;
 }
 
+// Output-stationary layout of a transposed layer from the inverse its strided twin's search left behind (pairs
+// of a transposed layer are the twin's pairs with the roles swapped, Section 5.5: maps shared between layers).
+// Where the twin's offsets partition its inputs (K = layer stride, e.g. 2x2x2 at stride 2), every output voxel p of
+// the transposed layer has exactly one pair, (input parent[p] / K^3, offset parent[p] % K^3): a thread per voxel
+// writes its row of the blocked matrix (full lines per offset) and the block masks fall out of ballots.
+__global__ __launch_bounds__(256) void transposed_from_parent_kernel(const int32_t* __restrict__ parent, int n_h,
+                                                                     const int* __restrict__ n_d, int K3,
+                                                                     int32_t* __restrict__ Mt, uint32_t* __restrict__ block_masks) {
+  const int n = n_d ? *n_d : n_h;
+  const int64_t p = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  const int64_t blk = p >> 5;
+  if (blk * 32 >= n) return;  // whole 32-row blocks leave together (the ballots below stay among one wave's lanes)
+  const int pr = p < n ? parent[p] : -1;
+  const int q = pr < 0 ? -1 : pr / K3, kp = pr < 0 ? -1 : pr - q * K3;
+  const int half = (threadIdx.x >> 5) & 1;
+  uint32_t mask = 0;  // K3 <= 32 here
+  for (int k = 0; k < K3; ++k) {
+    Mt[(blk * K3 + k) * 32 + (p & 31)] = k == kp ? q : -1;
+    const unsigned long long b = __ballot(k == kp);
+    if ((half ? unsigned(b >> 32) : unsigned(b)) != 0u) mask |= 1u << k;
+  }
+  if ((p & 31) == 0) block_masks[blk] = mask;
+}
+
 __global__ void copy_int_kernel(const int* src, int* dst) { *dst = *src; }
 
 // ---------------------------------------------------------------- host side
 static int axis_offset(int K, int s, int i) { return (K % 2 == 1) ? (i - (K - 1) / 2) * s : i * s; }
 
 static int tile_for(int K) { return K <= 3 ? 128 : 64; }
+
+static std::atomic<int64_t> g_search_launches{0};  // searches enqueued by this process (see spc_search_count)
 
 template <typename KeyT, int K>
 static int launch_search(spc_kmap* m, hipStream_t s) {
@@ -636,12 +672,13 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
                        sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm, m->os_k, m->ws_k,
-                       m->tile_pairs);
+                       m->tile_pairs, m->inv_parent);
   };
   if (m->n_tiles > 0) {
     if (pairs) go(std::true_type{});
     else go(std::false_type{});
   }
+  g_search_launches.fetch_add(1, std::memory_order_relaxed);
   return SPC_OK;
 }
 
@@ -658,6 +695,18 @@ static int launch_search_k(spc_kmap* m, hipStream_t s) {
 }
 
 static void kmap_free(spc_kmap* m) {
+  if (m->twin) {  // a transposed map derived from its strided twin: the lists (if any) are the twin's
+    if (m->ws_in) {
+      m->ws_in = m->ws_out = nullptr;
+      m->nnz_dev = nullptr;
+    }
+    // whoever read this map may have read the twin's arrays: the twin's release waits for them as well
+    for (hipStream_t c : m->consumers) m->twin->consumers.push_back(c);
+    m->twin->consumers.push_back(m->stream);
+    spc_kmap* t = m->twin;
+    m->twin = nullptr;
+    if (t->refs.fetch_sub(1) == 1) kmap_free(t);
+  }
   // The arrays return to the build stream's cache, where the next build may take them at once: that
   // stream first waits for the feature kernels other streams have enqueued on this map.
   for (hipStream_t c : m->consumers) order_stream_after(m->stream, c);
@@ -668,6 +717,7 @@ static void kmap_free(spc_kmap* m) {
   pool_free(m->nnz_dev, m->stream);
   pool_free(m->tile_counts, m->stream);
   pool_free(m->tile_pairs, m->stream);
+  pool_free(m->inv_parent, m->stream);
   level_unref(m->in_level);
   level_unref(m->out_level);
   if (m->ready) (void)hipEventDestroy(m->ready);
@@ -721,7 +771,7 @@ static int ilog2(int v) {
 
 // Builds the map object for given input/output levels (references are taken).
 static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_layer_desc& l, hipStream_t s, spc_kmap** res,
-                           const int32_t* in_perm = nullptr) {
+                           const int32_t* in_perm = nullptr, bool want_inverse = false) {
   spc_kmap* m = new spc_kmap;
   m->in_perm = in_perm;
   m->pi = pi;
@@ -761,7 +811,10 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
     m->block_masks = static_cast<uint32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * m->mask_words * 4, 256), s));
   }
   m->nnz_dev = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->K3) * 4, 256), s));
-  bool ok = m->nnz_dev && (!with_os || (m->os_map && m->block_masks));
+  m->ws_stride = m->out_cap;
+  if (want_inverse && !in_perm)
+    m->inv_parent = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(in->n_host >= 0 ? in->n_host : in->cap) * 4, 256), s));
+  bool ok = m->nnz_dev && (!with_os || (m->os_map && m->block_masks)) && (m->inv_parent || !(want_inverse && !in_perm));
   if (ok && (l.layout & SPC_LAYOUT_WS)) {
     m->ws_in = static_cast<int32_t*>(pool_alloc(cells * 4, s));
     m->ws_out = static_cast<int32_t*>(pool_alloc(cells * 4, s));
@@ -785,6 +838,76 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
     // the slabs are dead once the lists are filled: back to the cache (reuse is ordered behind this stream's work)
     pool_free(m->tile_pairs, s);
     m->tile_pairs = nullptr;
+  }
+  if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "kernel-map launch failed");
+  if (rc == SPC_OK && (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||
+                       hipEventRecord(m->ready, s) != hipSuccess))
+    rc = set_error(SPC_ERR_HIP, "event record failed");
+  if (rc != SPC_OK) {
+    kmap_free(m);
+    return rc;
+  }
+  *res = m;
+  return SPC_OK;
+}
+
+// A strided layer whose offsets partition its inputs (K = layer stride, even K: offsets {0..K-1} * in_stride) can
+// hand its pairs to the transposed layer of the same geometry instead of a second search.
+static bool twin_can_share(const spc_layer_desc& strided, const spc_layer_desc& transposed) {
+  return !strided.transposed && transposed.transposed && strided.K == transposed.K && strided.in_stride == transposed.in_stride &&
+         strided.layer_stride == transposed.layer_stride && strided.K == strided.layer_stride && strided.K % 2 == 0 &&
+         strided.K * strided.K * strided.K <= 32;
+}
+
+// The transposed map from its strided twin (see transposed_from_parent_kernel): the matrix from the twin's inverse,
+// the lists by taking the twin's with inputs and outputs swapped (for a fixed offset both index sequences ascend
+// together, so the order by output index is kept).  Returns SPC_ERR_UNSUPPORTED when the twin lacks what is needed.
+static int build_transposed_from_twin(spc_kmap* twin, Level* coarse, Level* fine, const PackInfo& pi, const spc_layer_desc& l,
+                                      hipStream_t s, spc_kmap** res) {
+  const bool with_os = (l.layout & SPC_LAYOUT_OS) != 0, with_ws = (l.layout & SPC_LAYOUT_WS) != 0;
+  if (!twin_can_share(twin->desc, l) || (l.layout & ~SPC_LAYOUT_BOTH) || (with_os && !twin->inv_parent) ||
+      (with_ws && (!(twin->desc.layout & SPC_LAYOUT_WS) || twin->hybrid_t || twin->sym)))
+    return SPC_ERR_UNSUPPORTED;
+  spc_kmap* m = new spc_kmap;
+  m->pi = pi;
+  m->desc = l;
+  m->K3 = l.K * l.K * l.K;
+  m->k_lim = m->K3;
+  for (int k = 0; k < m->K3; ++k) {
+    if (with_os) m->os_k.w[k >> 5] |= 1u << (k & 31);
+    if (with_ws) m->ws_k.w[k >> 5] |= 1u << (k & 31);
+  }
+  m->stream = s;
+  m->captured = stream_is_capturing(s);
+  m->in_level = coarse;
+  coarse->refs++;
+  m->out_level = fine;
+  fine->refs++;
+  (void)hipGetDevice(&m->device);
+  m->out_cap = fine->n_host >= 0 ? fine->n_host : fine->cap;
+  m->tile = tile_for(l.K);
+  m->n_tiles = static_cast<int>((m->out_cap + m->tile - 1) / m->tile);
+  m->n_blocks_cap = (m->out_cap + 31) / 32;
+  m->mask_words = 1;
+  m->twin = twin;
+  twin->refs++;
+  int rc = SPC_OK;
+  if (s != twin->stream && twin->ready && hipStreamWaitEvent(s, twin->ready, 0) != hipSuccess)
+    rc = set_error(SPC_ERR_HIP, "hipStreamWaitEvent failed");
+  if (rc == SPC_OK && with_os) {
+    m->os_map = static_cast<int32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * 32 * m->K3 * 4, 256), s));
+    m->block_masks = static_cast<uint32_t*>(pool_alloc(std::max<size_t>(size_t(m->n_blocks_cap) * 4, 256), s));
+    if (!m->os_map || !m->block_masks) rc = SPC_ERR_NOMEM;
+    else if (m->out_cap > 0)
+      hipLaunchKernelGGL(transposed_from_parent_kernel, dim3(static_cast<unsigned>((m->out_cap + 255) / 256)), dim3(256), 0, s,
+                         twin->inv_parent, static_cast<int>(fine->n_host < 0 ? 0 : fine->n_host), fine->n_host < 0 ? fine->n_dev : nullptr,
+                         m->K3, m->os_map, m->block_masks);
+  }
+  if (rc == SPC_OK && with_ws) {
+    m->ws_in = twin->ws_out;
+    m->ws_out = twin->ws_in;
+    m->nnz_dev = twin->nnz_dev;
+    m->ws_stride = twin->ws_stride;
   }
   if (rc == SPC_OK && hipGetLastError() != hipSuccess) rc = set_error(SPC_ERR_HIP, "kernel-map launch failed");
   if (rc == SPC_OK && (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||
@@ -859,6 +982,27 @@ static std::map<NetKey, int> net_layouts(const spc_layer_desc* layers, int n_lay
   return want;
 }
 
+// One map of a network build.  A transposed layer whose strided twin has been built on the same stream (no
+// cross-stream edge is added) takes the twin's pairs; a strided layer with such a transposed twin among the
+// wanted maps leaves its inverse behind for it.  Everything else is searched.
+static int build_network_map(const NetKey& key, const spc_layer_desc& l, const std::map<NetKey, int>& want,
+                             const std::map<NetKey, spc_kmap*>& maps, Level* fine, Level* coarse, const PackInfo& pi, hipStream_t s,
+                             spc_kmap** m) {
+  const NetKey other(std::get<0>(key), std::get<1>(key), std::get<2>(key), l.transposed ? 0 : 1);
+  if (l.transposed) {
+    auto it = maps.find(other);
+    if (it != maps.end() && it->second->stream == s) {
+      const int rc = build_transposed_from_twin(it->second, coarse, fine, pi, l, s, m);
+      if (rc != SPC_ERR_UNSUPPORTED) return rc;
+    }
+    return build_on_levels(coarse, fine, pi, l, s, m);
+  }
+  spc_layer_desc t = l;
+  t.transposed = 1;
+  const bool inverse = want.count(other) != 0 && twin_can_share(l, t);
+  return build_on_levels(fine, coarse, pi, l, s, m, nullptr, inverse);
+}
+
 // SPC_NET_PIPELINED: one build stream, work in the order of first use (a level right before the first
 // map that reads it), no join: the maps are marked so that their consumers wait for them.
 static int build_network_pipelined(const void* v0_keys, int64_t n0, const PackInfo& pi, const spc_layer_desc* layers,
@@ -901,7 +1045,7 @@ static int build_network_pipelined(const void* v0_keys, int64_t n0, const PackIn
     Level* fine = levels[l.in_stride];
     Level* coarse = levels[l.in_stride * l.layer_stride];
     spc_kmap* m = nullptr;
-    rc = build_on_levels(l.transposed ? coarse : fine, l.transposed ? fine : coarse, pi, l, sb, &m);
+    rc = build_network_map(key, l, want, maps, fine, coarse, pi, sb, &m);
     if (rc == SPC_OK) {
       m->wait_on_use = true;
       maps[key] = m;
@@ -1037,6 +1181,7 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
   // enqueues later), and the other streams join streams[0] once, at the end: few, distinct
   // cross-stream edges, which is also what a graph capture of this call records.
   std::vector<std::set<hipEvent_t>> waited(ns);
+  std::map<Key, int> map_stream;
   next = 0;
   for (auto& kv : want) {
     if (rc != SPC_OK) break;
@@ -1045,14 +1190,18 @@ int spc_build_kmaps_network(const void* v0_keys, int64_t n0, const spc_pack_desc
     Level* coarse = levels[l.in_stride * l.layer_stride];
     Level* in = l.transposed ? coarse : fine;
     Level* outl = l.transposed ? fine : coarse;
-    const int si = (next++) % ns;
+    // a transposed map goes to the stream of its strided twin (built just before it: the keys are ordered that way),
+    // so that it can take the twin's pairs without a cross-stream wait
+    const Key twin_key(std::get<0>(kv.first), std::get<1>(kv.first), std::get<2>(kv.first), 0);
+    const int si = (l.transposed && map_stream.count(twin_key)) ? map_stream[twin_key] : (next++) % ns;
+    map_stream[kv.first] = si;
     for (Level* dep : {in, outl})  // the map's stream waits for the levels it reads
       if (!barrier && dep->ready && level_stream[dep->stride] != si && waited[si].insert(dep->ready).second) {
         hipError_t e = hipStreamWaitEvent(st[si], dep->ready, 0);
         if (e != hipSuccess) rc = set_error(SPC_ERR_HIP, "hipStreamWaitEvent: %s", hipGetErrorString(e));
       }
     spc_kmap* m = nullptr;
-    if (rc == SPC_OK) rc = build_on_levels(in, outl, pi, l, st[si], &m);
+    if (rc == SPC_OK) rc = build_network_map(kv.first, l, want, maps, fine, coarse, pi, st[si], &m);
     if (rc == SPC_OK) maps[kv.first] = m;
   }
   // join: streams[0] continues only after everything the other streams were given
@@ -1123,7 +1272,7 @@ int spc_kmap_ws_lists(const spc_kmap* m, const int32_t** in_idx, const int32_t**
   if (in_idx) *in_idx = m->ws_in;
   if (out_idx) *out_idx = m->ws_out;
   if (nnz_dev) *nnz_dev = m->nnz_dev;
-  if (ws_stride) *ws_stride = m->out_cap;
+  if (ws_stride) *ws_stride = m->ws_stride;
   return SPC_OK;
 }
 
@@ -1176,12 +1325,12 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
       const bool mirror = m->sym && k > kc;
       const int ks = mirror ? K3 - 1 - k : k;
       const int c = cnt[ks];
-      if (c < 0 || c > n_out) return set_error(SPC_ERR_HIP, "corrupt WS count %d at offset %d", c, ks);
+      if (c < 0 || c > m->ws_stride) return set_error(SPC_ERR_HIP, "corrupt WS count %d at offset %d", c, ks);
       a.resize(c);
       b.resize(c);
       if (c) {
-        SPC_HIP_CHECK(hipMemcpy(a.data(), m->ws_in + int64_t(ks) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
-        SPC_HIP_CHECK(hipMemcpy(b.data(), m->ws_out + int64_t(ks) * m->out_cap, size_t(c) * 4, hipMemcpyDeviceToHost));
+        SPC_HIP_CHECK(hipMemcpy(a.data(), m->ws_in + int64_t(ks) * m->ws_stride, size_t(c) * 4, hipMemcpyDeviceToHost));
+        SPC_HIP_CHECK(hipMemcpy(b.data(), m->ws_out + int64_t(ks) * m->ws_stride, size_t(c) * 4, hipMemcpyDeviceToHost));
       }
       for (int e = 0; e < c; ++e) emit(k, mirror ? b[e] : a[e], mirror ? a[e] : b[e]);
     }
@@ -1189,6 +1338,8 @@ int spc_kmap_export_triples(spc_kmap* m, int32_t which, int32_t* triples, int64_
   *nnz_out = nnz;
   return SPC_OK;
 }
+
+int64_t spc_search_count(void) { return g_search_launches.load(std::memory_order_relaxed); }
 
 int spc_kmap_search_info(const spc_kmap* m, int32_t* tile_rows, int32_t* window_keys) {
   if (!m) return set_error(SPC_ERR_ARG, "map is NULL");

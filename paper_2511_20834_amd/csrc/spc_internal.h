@@ -189,7 +189,10 @@ struct spc_kmap {
   int32_t* ws_out = nullptr;        // [K3][out_cap]
   int32_t* nnz_dev = nullptr;       // [K3]
   int32_t* tile_counts = nullptr;   // [K3][n_tiles] scratch of the two-pass compaction
-  int2* tile_pairs = nullptr;       // WS-only builds: per search tile a slab of compacted (in, out) pairs (scratch)
+  int2* tile_pairs = nullptr;       // per search tile a slab of compacted (in, out) pairs (scratch of the list build)
+  int64_t ws_stride = 0;            // entries between consecutive lists in ws_in / ws_out
+  int32_t* inv_parent = nullptr;    // strided maps, on request: for every INPUT voxel p its pair (out q, offset k) as q*K^3+k
+  spc_kmap* twin = nullptr;         // transposed map derived from its strided twin (a reference is held): WS lists alias the twin's
   int tile = 0, n_tiles = 0;
   std::vector<int64_t> nnz_host;    // filled lazily
   hipEvent_t ready = nullptr;       // recorded after the last build kernel

@@ -35,7 +35,16 @@ def test_network_maps_bit_exact_and_shared(cloud_name, mode):
     net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W],
                      dataflow=[B.DATAFLOW_OS if j % 2 == 0 else B.DATAFLOW_WS for j in range(len(layers))])
     streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(3)]
+    searches = B.spc_search_count()
     maps = net.build_maps(keys, desc, streams, {"sequential": B.NET_SEQUENTIAL, "pipelined": B.NET_PIPELINED}.get(mode, 0))
+    # 13 distinct maps; a transposed 2x2x2 map is derived from its strided twin's pairs instead of being searched
+    # (its lists are the twin's, so the twin must have lists if the transposed layer wants them)
+    ws_of = {}
+    for l, df in zip(layers, net.dataflow):
+        key = (l["K"], l["in_stride"], l["layer_stride"], l["transposed"])
+        ws_of[key] = ws_of.get(key, False) or df == B.DATAFLOW_WS
+    derived = sum(1 for key, ws in ws_of.items() if key[3] == 1 and (not ws or ws_of[key[:3] + (0,)]))
+    assert B.spc_search_count() - searches == 13 - derived
     torch.cuda.synchronize()
     handles = {}
     for j, (l, m) in enumerate(zip(layers, maps)):
@@ -184,6 +193,18 @@ def test_capture_is_refused_where_the_sort_is_not_the_librarys_own():
     B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
     torch.cuda.synchronize()
     assert torch.equal(keys, ref)
+
+
+def test_network_build_searches_nine_maps():
+    """Configuration 4 in its default (all output-stationary) setting: 25 layers, 13 distinct maps, 9 searches."""
+    coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup("lidar")
+    for flags in (0, B.NET_PIPELINED, B.NET_SEQUENTIAL):
+        net = SpcNetwork(layers, [torch.from_numpy(w).cuda() for w in W])
+        before = B.spc_search_count()
+        net.build_maps(keys, desc, [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(2)], flags)
+        assert B.spc_search_count() - before == 9
+        torch.cuda.synchronize()
+        net.destroy_maps()
 
 
 def test_tuner_then_forward_matches_oracle():
