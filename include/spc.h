@@ -128,7 +128,7 @@ int spc_pack_coords(const int32_t* coords_bxyz, int64_t n, const spc_pack_desc* 
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, flags and
  * results as spc_pack_coords; the sort's scratch lives in a buffer that is part of the library image
  * (13 MiB per GPU, held until the process ends), so the call neither allocates nor frees anything.
- * Takes 4096 <= n <= SPC_NOALLOC_MAX_N voxels (the sizes the library's own sort kernels cover within
+ * Takes 1 <= n <= SPC_NOALLOC_MAX_N voxels (the sizes the library's own sort kernels cover within
  * that buffer); other sizes return SPC_ERR_UNSUPPORTED and enqueue nothing.  All calls on one GPU share
  * the buffer: calls whose work may overlap on that GPU (different streams without an ordering between
  * them, different host threads) race; order them, or use spc_pack_coords with workspaces of their own.
@@ -286,7 +286,7 @@ void spc_kmap_destroy(spc_kmap* m);
  * (without SPC_PACK_VALIDATE), spc_build_kmap(s_network), spc_conv_forward and
  * spc_permute_rows only enqueue kernels, event records and event waits — as long as every sort
  * is the library's own, i.e. the cloud (for strided layers: the level that is downsampled) has
- * between 4096 and 2 097 152 voxels.  Outside that range the sort is rocPRIM's, which also
+ * at most 2 097 152 voxels.  Above that the sort is rocPRIM's, which also
  * enqueues memsets; under stream capture spc_pack_coords and the builders then return
  * SPC_ERR_UNSUPPORTED instead of recording them (replayed memset nodes are not reliable on the
  * target systems, and a radix sort that starts from stale counters writes out of bounds).  Maps built under

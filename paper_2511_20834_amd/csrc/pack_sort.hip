@@ -17,8 +17,8 @@ static int refuse_if_capturing(hipStream_t s, int64_t n) {
   if (!stream_is_capturing(s)) return SPC_OK;
   return set_error(SPC_ERR_UNSUPPORTED,
                    "%lld keys are sorted by the library sort, which cannot be recorded into a graph; "
-                   "capture is supported for %d..%d keys",
-                   static_cast<long long>(n), BS_MIN_N, BS_MAX_N);
+                   "capture is supported up to %lld keys",
+                   static_cast<long long>(n), static_cast<long long>(BS_MAX_N));
 }
 
 template <typename KeyT>
@@ -170,6 +170,7 @@ static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, L
     pool_free(scratch, s);  // reuse is ordered behind these kernels on this stream
     return rc;
   }
+  if (n > 0 && n < BS_MIN_N) return small_mask_unique(pi.key_bits, src, n, level_mask(pi, m), lv->keys, lv->n_dev, s);
   if (n > 0) SPC_RETURN_IF(refuse_if_capturing(s, n));
   const size_t ksz = sizeof(KeyT);
   const size_t tb = sort_keys_temp_bytes(pi.key_bits, n);
@@ -274,9 +275,9 @@ extern "C" int spc_pack_coords_noalloc(const int32_t* coords, int64_t n, const s
   using namespace spc;
   PackInfo pi;
   SPC_RETURN_IF(check_desc(d, &pi));
-  if (n < BS_MIN_N || n > SPC_NOALLOC_MAX_N)
-    return set_error(SPC_ERR_UNSUPPORTED, "spc_pack_coords_noalloc takes %lld..%lld voxels, got %lld",
-                     static_cast<long long>(BS_MIN_N), static_cast<long long>(SPC_NOALLOC_MAX_N), static_cast<long long>(n));
+  if (n < 1 || n > SPC_NOALLOC_MAX_N)
+    return set_error(SPC_ERR_UNSUPPORTED, "spc_pack_coords_noalloc takes 1..%lld voxels, got %lld",
+                     static_cast<long long>(SPC_NOALLOC_MAX_N), static_cast<long long>(n));
   size_t need = 0;
   SPC_RETURN_IF(spc_pack_coords(nullptr, n, d, nullptr, nullptr, nullptr, &need, flags, nullptr));
   if (need > NOALLOC_SCRATCH_BYTES)
@@ -313,7 +314,8 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   if (*workspace_bytes < need) return set_error(SPC_ERR_ARG, "workspace too small: %zu < %zu", *workspace_bytes, need);
   if (!coords || !keys_out) return set_error(SPC_ERR_ARG, "NULL coords or keys_out");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!bucket && n > 0) SPC_RETURN_IF(refuse_if_capturing(s, n));
+  const bool small = n > 0 && n < BS_MIN_N;
+  if (!bucket && !small && n > 0) SPC_RETURN_IF(refuse_if_capturing(s, n));
   char* ws = static_cast<char*>(workspace);
   void* keys_tmp = ws;
   int32_t* iota = reinterpret_cast<int32_t*>(ws + off_iota);
@@ -324,6 +326,15 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   if (bucket) {
     SPC_RETURN_IF(bucket_pack_sort(pi.key_bits, reinterpret_cast<const int4*>(coords), n, p, pi.used_bits, status, keys_out, perm_out,
                                    ws + off_temp, s));
+    if (flags & SPC_PACK_VALIDATE) {
+      const int grid = static_cast<int>((n + 255) / 256);
+      if (pi.key_bits == 32)
+        hipLaunchKernelGGL(dup_check_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint32_t*>(keys_out), n, status);
+      else
+        hipLaunchKernelGGL(dup_check_kernel<uint64_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint64_t*>(keys_out), n, status);
+    }
+  } else if (small) {
+    SPC_RETURN_IF(small_pack_sort(pi.key_bits, reinterpret_cast<const int4*>(coords), n, p, status, keys_out, perm_out, s));
     if (flags & SPC_PACK_VALIDATE) {
       const int grid = static_cast<int>((n + 255) / 256);
       if (pi.key_bits == 32)

@@ -140,7 +140,7 @@ __device__ inline KeyT pack_key(const int4 c, const PackParams& p, int32_t* stat
 constexpr int BS_MAX_WG = 128;      // workgroups of the count / scatter passes
 constexpr int BS_MAX_BIN_BITS = 14;
 constexpr int BS_MAX_BIN = 1 << BS_MAX_BIN_BITS;  // fine bins (top used key bits)
-constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 2048 * 1024;  // sizes it is used for; rocPRIM outside
+constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 2048 * 1024;  // sizes of the partitioning sort; below: one workgroup in LDS; above: rocPRIM
 constexpr int BS_PART = 64;         // keys per rank workgroup
 constexpr int BS_PAD_KEYS = 32;     // all-ones keys kept behind the scattered keys
 struct BucketPlan {
@@ -154,6 +154,11 @@ int bucket_pack_sort(int key_bits, const int4* coords, int64_t n, const PackPara
 // sorted distinct values of keys_in & mask, count to *n_out [device]; enqueues five kernels
 int bucket_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, int used_bits, void* keys_out,
                        int32_t* n_out, void* ws, hipStream_t s);
+
+// fewer than BS_MIN_N keys: one workgroup sorts them in LDS, one launch (n_out [device] receives the distinct count)
+int small_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int32_t* status, void* keys_out,
+                    int32_t* perm_out, hipStream_t s);
+int small_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, void* keys_out, int32_t* n_out, hipStream_t s);
 
 // ---------------------------------------------------------------- sort (rocPRIM radix sort)
 size_t sort_pairs_temp_bytes(int key_bits, int64_t n);

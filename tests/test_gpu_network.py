@@ -162,37 +162,47 @@ def test_network_step_graph_replays_match_eager(net_flags):
     cap.destroy()
 
 
-def test_capture_is_refused_where_the_sort_is_not_the_librarys_own():
-    """Below 4096 (and above 2 Mi) voxels the sort is rocPRIM's, which enqueues memsets next to its
-    kernels; recording those into a graph is refused with an error instead of being left to go wrong
-    on a replay.  Nothing runs on the GPU inside the capture; the eager call still works."""
-    c = synth.random_cloud(1500, (40, 40, 16), seed=synth.SEED_BASE + 700)
-    desc = B.spc_pack_desc_fit(c[:, 1:].min(0), c[:, 1:].max(0), 1, 2, 1)
-    coords = torch.from_numpy(c).cuda()
-    ws = torch.empty(B.spc_pack_workspace_bytes(len(c), desc), dtype=torch.uint8, device="cuda")
-    keys = torch.empty(len(c), dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device="cuda")
-    perm = torch.empty(len(c), dtype=torch.int32, device="cuda")
-    B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
-    torch.cuda.synchronize()
-    ref = keys.clone()
+def test_capture_of_a_small_cloud_replays():
+    """Below 4096 voxels the sort (and every downsampled level's) is a single-workgroup kernel: pack + sort and a
+    strided map of a 1500-voxel cloud are recorded into a graph and replayed, with eager work in between, and every
+    replay equals the eager result."""
+    clouds = [synth.random_cloud(1500, (40, 40, 16), seed=synth.SEED_BASE + 700 + i) for i in range(2)]
+    lo = np.min([c[:, 1:].min(0) for c in clouds], axis=0)
+    hi = np.max([c[:, 1:].max(0) for c in clouds], axis=0)
+    desc = B.spc_pack_desc_fit(lo, hi, 1, 2, 1)
+    n = 1500
+    coords = torch.from_numpy(clouds[0]).cuda()
+    ws = torch.empty(B.spc_pack_workspace_bytes(n, desc), dtype=torch.uint8, device="cuda")
+    keys = torch.empty(n, dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device="cuda")
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+
+    def eager(c):
+        k, p = B.spc_pack_coords(torch.from_numpy(c).cuda(), desc, True)
+        km = B.spc_build_kmap(k, desc, 2, 1, 2, 0, B.LAYOUT_OS)
+        t, ok = km.export_triples(B.LAYOUT_OS), km.out_keys()
+        km.destroy()
+        return k.clone(), p.clone(), t, ok
+
+    refs = [eager(c) for c in clouds]
     stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):  # warm the block cache on the capturing stream
+        B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+        B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS).destroy()
+    torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
-    with pytest.raises(B.SpcError) as err:
-        with torch.cuda.graph(graph, stream=stream, capture_error_mode="relaxed"):
-            B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
-    assert err.value.code == B.ERR_UNSUPPORTED
-    torch.cuda.synchronize()
-    # strided map from a small level: the downsampling sort is refused the same way
-    B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS).destroy()  # eager, and warms the block cache
-    torch.cuda.synchronize()
-    with pytest.raises(B.SpcError):
-        with torch.cuda.graph(torch.cuda.CUDAGraph(), stream=stream, capture_error_mode="relaxed"):
-            B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS)
-    torch.cuda.synchronize()
-    keys.zero_()
-    B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
-    torch.cuda.synchronize()
-    assert torch.equal(keys, ref)
+    with torch.cuda.graph(graph, stream=stream, capture_error_mode="relaxed"):
+        B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+        km = B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS)
+    for rep, i in enumerate([0, 1, 1, 0]):
+        coords.copy_(torch.from_numpy(clouds[i]).cuda())
+        keys.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(keys, refs[i][0]) and torch.equal(perm, refs[i][1]), rep
+        assert np.array_equal(km.export_triples(B.LAYOUT_OS), refs[i][2]) and np.array_equal(km.out_keys(), refs[i][3]), rep
+        eager(clouds[1 - i])  # eager work between the replays
+    km.destroy()
 
 
 def test_network_build_searches_nine_maps():

@@ -44,12 +44,15 @@ def test_noalloc_pack_matches_pack_coords_twice_in_a_row(key_bits):
 
 def test_noalloc_pack_size_limits():
     desc = B.spc_pack_desc_fit([0, 0, 0], [2000, 2000, 200], 1, 1, 1)
-    for n in (100, B.NOALLOC_MAX_N + 1):
+    for n in (0, B.NOALLOC_MAX_N + 1):
         coords = torch.zeros((n, 4), dtype=torch.int32, device="cuda")
         keys = torch.empty(n, dtype=torch.int32, device="cuda")
         with pytest.raises(B.SpcError) as e:
             B.spc_pack_coords_noalloc(coords, desc, keys, None)
         assert e.value.code == B.ERR_UNSUPPORTED
+    # small clouds go through the one-workgroup sort, on no scratch at all
+    c = synth.random_cloud(777, (50, 40, 30), seed=10)
+    _both(c, B.spc_pack_desc_fit(c[:, 1:].min(0), c[:, 1:].max(0), 1, 1, 1))
     # the largest size it takes
     c = synth.random_cloud(B.NOALLOC_MAX_N, (2000, 2000, 200), seed=9)
     d64 = B.spc_pack_desc_fit(c[:, 1:].min(0), c[:, 1:].max(0), 1, 16, 16, 64)
