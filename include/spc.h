@@ -329,6 +329,17 @@ int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32_t cin, int
 int spc_permute_rows(const void* src, int64_t src_pitch, const int32_t* perm, int64_t n, int64_t row_bytes,
                      void* dst, int64_t dst_pitch, void* stream);
 
+/*
+ * Measurement aids (Section 6 reports rates; these give the machine's own denominators next to the data-sheet
+ * ones).  spc_probe_copy: a plain copy kernel, dst[0..bytes) = src[0..bytes) ([device], bytes a multiple of 16):
+ * its rate is what a streaming kernel can reach on this GPU, and its known size calibrates the profiler's byte
+ * counters.  spc_probe_mfma: every wave of the chip issues `iters` x 4 independent 32x32x16 fp16 MFMAs from
+ * registers; *flops [host] receives the floating-point operations of the launch, sink [device] one float.
+ * Both only enqueue; time them with events on `stream`.
+ */
+int spc_probe_copy(const void* src, void* dst, int64_t bytes, void* stream);
+int spc_probe_mfma(int32_t iters, float* sink, double* flops, void* stream);
+
 /* Releases the library's cached device blocks (maps still alive keep theirs). Waits for the device. */
 int spc_release_cache(void);
 

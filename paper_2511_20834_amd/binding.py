@@ -43,6 +43,7 @@ EXPORTS = [
     "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_search_info", "spc_search_count", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
     "spc_conv_forward", "spc_conv_forward_hybrid",
     "spc_conv_prepare_weights", "spc_permute_rows",
+    "spc_probe_copy", "spc_probe_mfma",
     "spc_release_cache", "spc_last_error", "spc_version",
 ]
 
@@ -107,6 +108,8 @@ def lib():
         L.spc_conv_forward_hybrid.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         L.spc_conv_prepare_weights.argtypes = [vp, i32, i32, i32, i32, vp, vp]
         L.spc_permute_rows.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp]
+        L.spc_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.spc_probe_mfma.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.spc_last_error.restype = ctypes.c_char_p
         L.spc_version.restype = ctypes.c_char_p
         _lib = L
@@ -335,6 +338,22 @@ def spc_permute_rows(src: torch.Tensor, perm: torch.Tensor, out: torch.Tensor | 
     _check(lib().spc_permute_rows(src.data_ptr(), src.stride(0) * es, perm.data_ptr(), perm.shape[0], src.shape[1] * es,
                                   out.data_ptr(), out.stride(0) * es, _stream(stream)))
     return out
+
+
+def spc_probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:
+    """dst = src by the library's plain copy kernel; returns the bytes moved one way."""
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(lib().spc_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)))
+    return nbytes
+
+
+def spc_probe_mfma(iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueues the register-resident MFMA loop; returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().spc_probe_mfma(int(iters), sink.data_ptr(), ctypes.byref(flops), _stream(stream)))
+    return float(flops.value)
 
 
 def spc_release_cache() -> None:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspc.so")
-SOURCES = ["runtime.hip", "pack_sort.hip", "bucket_sort.hip", "kmap.hip", "conv.hip"]
+SOURCES = ["runtime.hip", "pack_sort.hip", "bucket_sort.hip", "kmap.hip", "conv.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

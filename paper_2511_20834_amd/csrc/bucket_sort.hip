@@ -486,75 +486,92 @@ __global__ __launch_bounds__(BS_THREADS) void bs_compact_kernel(const KeyT* __re
 }
 
 // ---------------------------------------------------------------- small levels: one workgroup, one launch
-// Fewer than BS_MIN_N keys (the tiny cloud of a unit test, the coarsest levels of a network): the keys are
-// produced (packed or masked) straight into LDS, sorted there as (key, source index) pairs by a bitonic network
-// (fixed cost whatever the key distribution; the index breaks ties, so equal keys of an invalid cloud still get
-// distinct places) and written out; the downsampling form drops the index and keeps the first key of every run of
-// equal keys (a scan over the head flags).  One launch of a few microseconds where the partitioning path has four
-// (five) and a library sort more, and nothing but kernels is enqueued, so it can be recorded into a graph.
+// Fewer than BS_MIN_N keys (the tiny cloud of a unit test, the coarsest levels of a network): the partitioning
+// scheme of the large path inside one workgroup and LDS.  The keys are produced (packed or masked) straight into
+// LDS and counted into 256 bins of their top used bits; a scan gives the bin starts; the keys move, with their source
+// index, to their bin's range; and every key's final place is its bin's start plus the number of (key, index)
+// pairs of the bin that sort before it (the index breaks ties, so equal keys of an invalid cloud still get distinct
+// places).  The downsampling form writes the sorted keys back to LDS and keeps the first key of every run of equal
+// keys (a scan over the head flags).  One launch of a few microseconds where the large path has four (five) and a
+// library sort more; nothing but kernels is enqueued, so it can be recorded into a graph.  Work is quadratic in the
+// bin sizes: a cloud whose keys all share their top 8 bits costs n^2 = 16 M comparisons at most.
 constexpr int BS_SMALL_THREADS = 1024;
+constexpr int BS_SMALL_BINS = 256;
+constexpr int BS_SMALL_MAX = 4096;  // >= BS_MIN_N - 1
 template <typename KeyT, typename Src, bool DEDUP>
-__global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src, int n, KeyT* __restrict__ out_k,
+__global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src, int n, int shift, KeyT* __restrict__ out_k,
                                                                         int32_t* __restrict__ out_v, int32_t* __restrict__ n_out) {
-  extern __shared__ __align__(16) unsigned char small_smem[];
+  __shared__ KeyT sk0[BS_SMALL_MAX], sk1[BS_SMALL_MAX];
+  __shared__ int16_t sv1[BS_SMALL_MAX];
+  __shared__ int s_start[BS_SMALL_BINS + 1], s_cur[BS_SMALL_BINS];
   __shared__ int wave_tot[BS_SMALL_THREADS / 64];
-  int np = 64;
-  while (np < n) np <<= 1;  // network size: the next power of two (n <= 4096)
-  KeyT* sk = reinterpret_cast<KeyT*>(small_smem);
-  int32_t* sv = reinterpret_cast<int32_t*>(sk + np);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < BS_SMALL_BINS) s_cur[tid] = 0;
+  __syncthreads();
   bool bad = false;
-  for (int i = tid; i < np; i += BS_SMALL_THREADS) {
-    KeyT key = ~KeyT(0);
-    if (i < n) {
-      bool bad_i = false;
-      key = src.key(src.load(i), bad_i);
-      bad |= bad_i;
-    }
-    sk[i] = key;
-    if (!DEDUP) sv[i] = i;  // padding entries sort behind every real one (largest key, largest index)
+  for (int i = tid; i < n; i += BS_SMALL_THREADS) {
+    bool bad_i = false;
+    const KeyT key = src.key(src.load(i), bad_i);
+    bad |= bad_i;
+    sk0[i] = key;
+    atomicAdd(&s_cur[bs_bin(key, shift, BS_SMALL_BINS)], 1);
   }
   src.report(bad);
   __syncthreads();
-  for (int k = 2; k <= np; k <<= 1)
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int t = tid; t < (np >> 1); t += BS_SMALL_THREADS) {
-        const int i = 2 * t - (t & (j - 1)), p = i + j;
-        const bool up = (i & k) == 0;
-        const KeyT a = sk[i], b = sk[p];
-        bool gt;
-        int va = 0, vb = 0;
-        if (DEDUP) {
-          gt = a > b;
-        } else {
-          va = sv[i];
-          vb = sv[p];
-          gt = a > b || (a == b && va > vb);
-        }
-        if (gt == up) {
-          sk[i] = b;
-          sk[p] = a;
-          if (!DEDUP) {
-            sv[i] = vb;
-            sv[p] = va;
-          }
-        }
-      }
-      __syncthreads();
+  if (wave == 0) {  // exclusive scan of the 256 bin counts, four per lane
+    int c[4], sum = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      c[u] = s_cur[lane * 4 + u];
+      sum += c[u];
     }
-  if (!DEDUP) {
-    for (int i = tid; i < n; i += BS_SMALL_THREADS) {
-      out_k[i] = sk[i];
-      if (out_v) out_v[i] = sv[i];
+    int x = sum;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int y = __shfl_up(x, d, 64);
+      if (lane >= d) x += y;
     }
-    return;
+    int run = x - sum;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      s_start[lane * 4 + u] = run;
+      s_cur[lane * 4 + u] = run;
+      run += c[u];
+    }
+    if (lane == 63) s_start[BS_SMALL_BINS] = run;
   }
+  __syncthreads();
+  for (int i = tid; i < n; i += BS_SMALL_THREADS) {
+    const KeyT key = sk0[i];
+    const int p = atomicAdd(&s_cur[bs_bin(key, shift, BS_SMALL_BINS)], 1);
+    sk1[p] = key;
+    sv1[p] = static_cast<int16_t>(i);
+  }
+  __syncthreads();
+  for (int x = tid; x < n; x += BS_SMALL_THREADS) {
+    const KeyT key = sk1[x];
+    const int vi = sv1[x];
+    const int b = bs_bin(key, shift, BS_SMALL_BINS);
+    const int a = s_start[b], e = s_start[b + 1];
+    int r = a;
+    for (int y = a; y < e; ++y) {
+      const KeyT ky = sk1[y];
+      r += (ky < key || (ky == key && sv1[y] < vi)) ? 1 : 0;
+    }
+    if (DEDUP) {
+      sk0[r] = key;  // sorted sequence, kept in LDS for the pass below
+    } else {
+      out_k[r] = key;
+      if (out_v) out_v[r] = vi;
+    }
+  }
+  if (!DEDUP) return;
+  __syncthreads();
   // distinct keys: thread t owns the run of positions [t * per, (t + 1) * per)
-  const int per = (np + BS_SMALL_THREADS - 1) / BS_SMALL_THREADS;
+  const int per = (n + BS_SMALL_THREADS - 1) / BS_SMALL_THREADS;
   int cnt = 0;
   for (int u = 0; u < per; ++u) {
     const int i = tid * per + u;
-    cnt += (i < n && (i == 0 || sk[i] != sk[i - 1])) ? 1 : 0;
+    cnt += (i < n && (i == 0 || sk0[i] != sk0[i - 1])) ? 1 : 0;
   }
   int x = cnt;
   for (int d = 1; d < 64; d <<= 1) {
@@ -570,35 +587,37 @@ __global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src
   }
   for (int u = 0; u < per; ++u) {
     const int i = tid * per + u;
-    if (i < n && (i == 0 || sk[i] != sk[i - 1])) out_k[base++] = sk[i];
+    if (i < n && (i == 0 || sk0[i] != sk0[i - 1])) out_k[base++] = sk0[i];
   }
   if (tid == 0) *n_out = total;
 }
 
 template <typename KeyT, typename Src, bool DEDUP>
-static void launch_small_sort(const Src& src, int64_t n, void* out_k, int32_t* out_v, int32_t* n_out, hipStream_t s) {
-  int np = 64;
-  while (np < n) np <<= 1;
-  const size_t lds = size_t(np) * (sizeof(KeyT) + (DEDUP ? 0 : 4));
-  hipLaunchKernelGGL((bs_small_sort_kernel<KeyT, Src, DEDUP>), dim3(1), dim3(BS_SMALL_THREADS), lds, s, src, static_cast<int>(n),
+static void launch_small_sort(const Src& src, int64_t n, int used_bits, void* out_k, int32_t* out_v, int32_t* n_out, hipStream_t s) {
+  static_assert(BS_SMALL_MAX >= BS_MIN_N - 1, "the small path covers every size below the partitioning sort's");
+  const int shift = std::max(0, used_bits - 8);  // bins = the top 8 used key bits
+  hipLaunchKernelGGL((bs_small_sort_kernel<KeyT, Src, DEDUP>), dim3(1), dim3(BS_SMALL_THREADS), 0, s, src, static_cast<int>(n), shift,
                      static_cast<KeyT*>(out_k), out_v, n_out);
 }
 
-int small_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int32_t* status, void* keys_out,
+int small_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int used_bits, int32_t* status, void* keys_out,
                     int32_t* perm_out, hipStream_t s) {
-  if (key_bits == 32) launch_small_sort<uint32_t, SrcPack<uint32_t>, false>(SrcPack<uint32_t>{coords, pp, status}, n, keys_out, perm_out, nullptr, s);
-  else launch_small_sort<uint64_t, SrcPack<uint64_t>, false>(SrcPack<uint64_t>{coords, pp, status}, n, keys_out, perm_out, nullptr, s);
+  if (key_bits == 32)
+    launch_small_sort<uint32_t, SrcPack<uint32_t>, false>(SrcPack<uint32_t>{coords, pp, status}, n, used_bits, keys_out, perm_out, nullptr, s);
+  else
+    launch_small_sort<uint64_t, SrcPack<uint64_t>, false>(SrcPack<uint64_t>{coords, pp, status}, n, used_bits, keys_out, perm_out, nullptr, s);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "sort launch failed");
   return SPC_OK;
 }
 
-int small_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, void* keys_out, int32_t* n_out, hipStream_t s) {
+int small_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, int used_bits, void* keys_out, int32_t* n_out,
+                      hipStream_t s) {
   if (key_bits == 32)
     launch_small_sort<uint32_t, SrcMask<uint32_t>, true>(SrcMask<uint32_t>{static_cast<const uint32_t*>(keys_in), static_cast<uint32_t>(mask)}, n,
-                                                         keys_out, nullptr, n_out, s);
+                                                         used_bits, keys_out, nullptr, n_out, s);
   else
-    launch_small_sort<uint64_t, SrcMask<uint64_t>, true>(SrcMask<uint64_t>{static_cast<const uint64_t*>(keys_in), mask}, n, keys_out, nullptr,
-                                                         n_out, s);
+    launch_small_sort<uint64_t, SrcMask<uint64_t>, true>(SrcMask<uint64_t>{static_cast<const uint64_t*>(keys_in), mask}, n, used_bits,
+                                                         keys_out, nullptr, n_out, s);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "downsample launch failed");
   return SPC_OK;
 }

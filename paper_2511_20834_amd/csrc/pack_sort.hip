@@ -170,7 +170,7 @@ static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, L
     pool_free(scratch, s);  // reuse is ordered behind these kernels on this stream
     return rc;
   }
-  if (n > 0 && n < BS_MIN_N) return small_mask_unique(pi.key_bits, src, n, level_mask(pi, m), lv->keys, lv->n_dev, s);
+  if (n > 0 && n < BS_MIN_N) return small_mask_unique(pi.key_bits, src, n, level_mask(pi, m), pi.used_bits, lv->keys, lv->n_dev, s);
   if (n > 0) SPC_RETURN_IF(refuse_if_capturing(s, n));
   const size_t ksz = sizeof(KeyT);
   const size_t tb = sort_keys_temp_bytes(pi.key_bits, n);
@@ -334,7 +334,7 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
         hipLaunchKernelGGL(dup_check_kernel<uint64_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint64_t*>(keys_out), n, status);
     }
   } else if (small) {
-    SPC_RETURN_IF(small_pack_sort(pi.key_bits, reinterpret_cast<const int4*>(coords), n, p, status, keys_out, perm_out, s));
+    SPC_RETURN_IF(small_pack_sort(pi.key_bits, reinterpret_cast<const int4*>(coords), n, p, pi.used_bits, status, keys_out, perm_out, s));
     if (flags & SPC_PACK_VALIDATE) {
       const int grid = static_cast<int>((n + 255) / 256);
       if (pi.key_bits == 32)

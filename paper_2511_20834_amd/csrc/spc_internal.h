@@ -156,9 +156,10 @@ int bucket_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t ma
                        int32_t* n_out, void* ws, hipStream_t s);
 
 // fewer than BS_MIN_N keys: one workgroup sorts them in LDS, one launch (n_out [device] receives the distinct count)
-int small_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int32_t* status, void* keys_out,
+int small_pack_sort(int key_bits, const int4* coords, int64_t n, const PackParams& pp, int used_bits, int32_t* status, void* keys_out,
                     int32_t* perm_out, hipStream_t s);
-int small_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, void* keys_out, int32_t* n_out, hipStream_t s);
+int small_mask_unique(int key_bits, const void* keys_in, int64_t n, uint64_t mask, int used_bits, void* keys_out, int32_t* n_out,
+                      hipStream_t s);
 
 // ---------------------------------------------------------------- sort (rocPRIM radix sort)
 size_t sort_pairs_temp_bytes(int key_bits, int64_t n);
