@@ -157,7 +157,15 @@ __device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
 // the nine groups in one go, 60 registers; with 64-bit keys that takes 82 registers, so three there as well: 10^6
 // voxels 95 -> 89 us).  Larger kernels: three; five cost the registers that hold eight waves per SIMD
 // (240 k voxels, 5x5x5: map build 90 us with five or seven, 75 us with two, three or four).
-constexpr int SEARCH_GB_SMALL = 5, SEARCH_GB_LARGE = 3;
+constexpr int SEARCH_GB_SMALL = 5, SEARCH_GB_LARGE = 4;
+// Whether some part p < parts has `rem` groups left after whole batches of gb (its groups are p, p + parts, ... < G).
+__host__ __device__ constexpr bool remainder_occurs(int G, int parts, int gb, int rem) {
+  for (int p = 0; p < parts && p < G; ++p)
+    if (((G - p + parts - 1) / parts) % gb == rem) return true;
+  return false;
+}
+// Output voxels per search workgroup (a multiple of the wave size that divides SEARCH_THREADS).
+__host__ __device__ constexpr int search_tile(int K) { return K <= 3 ? 128 : 64; }
 
 // Two outputs, each for its own subset of the K^3 offsets (Section 5.4: all offsets in one of them for a single
 // dataflow; the dense offsets in the matrix and the sparse ones in the lists for the hybrid dual dataflow):
@@ -172,12 +180,13 @@ constexpr int SEARCH_GB_SMALL = 5, SEARCH_GB_LARGE = 3;
 template <typename KeyT, int K, bool PAIRS>
 __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
-    int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int tile, int32_t* __restrict__ M,
+    int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int32_t* __restrict__ M,
     uint32_t* __restrict__ block_masks, int32_t* __restrict__ tile_counts, int n_tiles_cap,
     const int32_t* __restrict__ in_perm, KMask os_k, KMask ws_k, int2* __restrict__ tile_pairs,
     int32_t* __restrict__ inv_parent) {
   constexpr int G = K * K, K3 = K * K * K;
-  constexpr int SEARCH_GB = (K <= 3 && sizeof(KeyT) == 4) ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
+  constexpr int tile = search_tile(K);
+  constexpr int SEARCH_GB = K <= 3 ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
   constexpr int G_POW2 = G <= 1 ? 1 : G <= 4 ? 4 : G <= 16 ? 16 : G <= 64 ? 64 : 128;  // power of two >= G
   constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
@@ -189,8 +198,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   constexpr int BOUND_SLACK = G <= 9 ? 32 : 16;  // extra keys per window end: 2 * G * slack must stay small next to WIN_CAP
   extern __shared__ __align__(16) unsigned char smem[];
   KeyT* okeys = reinterpret_cast<KeyT*>(smem);   // [tile]
-  KeyT* win = okeys + tile;                      // [WIN_CAP]
-  int32_t* s_pos = reinterpret_cast<int32_t*>(win + WIN_CAP);         // PAIRS: [G][tile] input position of the group's lower bound
+  KeyT* win = okeys + tile;                      // [WIN_CAP + MAX_K]: staged windows, and room for reads behind the last one
+  int32_t* s_pos = reinterpret_cast<int32_t*>(win + WIN_CAP + MAX_K);       // PAIRS: [G][tile] input position of the group's lower bound
   uint8_t* s_hit = reinterpret_cast<uint8_t*>(s_pos + G * tile);      // PAIRS: [G][tile] bit t: the group's t-th query (ascending z) hit
   __shared__ int s_off[PAIRS ? K3 + 1 : 1];                           // PAIRS: where every offset's pairs start in the tile's slab
   __shared__ KeyT s_probe[N_PROBES];
@@ -286,183 +295,242 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   }
   __syncthreads();
 
-  // ---- staging, flattened over all windows that fit: element e of the concatenation belongs to
-  // the group g with wend[g] <= e < wend[g+1]; loads are issued four at a time per thread
-  int total = 0;
-  for (int g = 0; g < G; ++g) total = max(total, s_wend[g + 1]);
-  for (int e0 = 0; e0 < total; e0 += 4 * SEARCH_THREADS) {
-    KeyT tmp[4];
+  // ---- staging, window after window.  A team of lanes copies a window, lane e its keys e, e + team size, ...:
+  // the whole workgroup for the long windows of 128-row tiles, a wave for the short ones of 64-row tiles (with
+  // 25 or 49 groups a workgroup-wide copy would leave three lanes in four idle), the waves then taking different
+  // groups.  Window positions and sizes are read into scalar registers, so a copy costs a compare and two
+  // address additions per lane, and the loads of all of a team's windows are in flight together.
+  {
+    constexpr int TEAM = tile >= 128 ? SEARCH_THREADS : 64;  // lanes per window
+    constexpr int N_TEAMS = SEARCH_THREADS / TEAM;
+    constexpr int STAGE_U = (G + N_TEAMS - 1) / N_TEAMS;       // windows per team
+    const int team = __builtin_amdgcn_readfirstlane(tid / TEAM), lt = tid % TEAM;
+    KeyT tmp[STAGE_U];
+    int woff[STAGE_U], wsz[STAGE_U], wlo[STAGE_U];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int e = e0 + i * SEARCH_THREADS + tid;
+    for (int i = 0; i < STAGE_U; ++i) {
+      const int g = team + i * N_TEAMS, gc = min(g, G - 1);
+      woff[i] = __builtin_amdgcn_readfirstlane(s_woff[gc]);
+      wsz[i] = g < G && woff[i] >= 0 ? __builtin_amdgcn_readfirstlane(s_wsz[gc]) : 0;
+      wlo[i] = __builtin_amdgcn_readfirstlane(s_wlo[gc]);
       tmp[i] = 0;
-      if (e < total) {
-        // groups whose staged window ends at or before e form a prefix (windows that do not fit, marked -1,
-        // are a suffix): count them by bit steps instead of walking up to K^2 entries
-        int g = 0;
-#pragma unroll
-        for (int bit = G_POW2 >> 1; bit > 0; bit >>= 1) {
-          const int t = g + bit;
-          const int we = s_wend[min(t, G)];
-          g = (t < G && we >= 0 && e >= we) ? t : g;
-        }
-        tmp[i] = in_keys[s_wlo[g] + (e - s_woff[g])];
-      }
+      if (lt < wsz[i]) tmp[i] = (in_keys + wlo[i])[lt];
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int e = e0 + i * SEARCH_THREADS + tid;
-      if (e < total) win[e] = tmp[i];
-    }
+    for (int i = 0; i < STAGE_U; ++i)
+      if (lt < wsz[i]) (win + woff[i])[lt] = tmp[i];
+#pragma unroll
+    for (int i = 0; i < STAGE_U; ++i)
+      for (int e = lt + TEAM; e < wsz[i]; e += TEAM) (win + woff[i])[e] = (in_keys + wlo[i])[e];
   }
   __syncthreads();
 
-  // ---- per-lane searches.  A wave holds 64 consecutive output voxels; a lane runs the lower
-  // bounds of up to SEARCH_GB groups interleaved (independent LDS chains hide each other's
-  // latency) with the branch-free bit-stepping form, whose trip count depends only on the window
-  // sizes.  Every store into the blocked map M[block][k][32] is two full 128-byte segments.
+  // ---- per-lane searches.  A wave holds 64 consecutive output voxels and takes NJ groups of offsets at a time,
+  // their searches interleaved (independent LDS chains hide each other's latency).  The phase is bound by the
+  // number of vector instructions, so everything that is the same for the 64 lanes lives in scalar registers:
+  // a group's window (LDS position, size, position in the input array) and the remaining length n of its search.
+  // A search keeps the LDS byte address `ab` of the key before its lower bound's current base; a round probes the
+  // key half = ceil(n/2) further on and moves the base behind it when that key is smaller than the query, which
+  // leaves floor(n/2) keys: one addition, one compare and one select per round, no bounds to check (a probe never
+  // leaves the window; finished searches probe the key at `ab` again, which changes nothing).
   const int64_t b0 = int64_t(i0) >> 5;
   const int rows32 = (rows + 31) & ~31;
-  const int parts = SEARCH_THREADS / tile;         // threads per output voxel
-  const int v = tid % tile, part = tid / tile;     // part is uniform in a wave (tile is a multiple of 64)
+  constexpr int parts = SEARCH_THREADS / tile;     // threads per output voxel
+  const int v = tid % tile;
+  const int part = __builtin_amdgcn_readfirstlane(tid / tile);  // uniform in a wave (tile is a multiple of 64)
   const bool act = v < rows;
-  const KeyT okey = act ? okeys[v] : KeyT(0);
-  const int bl = v >> 5;
-  int32_t* Mrow = M + (b0 + bl) * K3 * 32 + (v & 31);
-  for (int gb = part; gb < G; gb += parts * SEARCH_GB) {
-    // wb: LDS base of the group's window.  Groups past the limit, rows past the end and windows kept in
-    // global memory get an empty window at base 0, so that every LDS read below is unconditional and
-    // in range (index -1 is the last staged output key) and the reads of a round issue back to back.
-    int pos[SEARCH_GB], gidx[SEARCH_GB], wsz[SEARCH_GB], wb[SEARCH_GB], wlo[SEARCH_GB];
-    bool glob[SEARCH_GB];
-    KeyT q0[SEARCH_GB];
-    int maxw = 0;
+  const bool stored = v < rows32;                  // rows past the end of the last block hold -1
+  const KeyT okey = okeys[min(v, rows - 1)];       // lanes past the end repeat the last row; their results are dropped
+  const int v0 = __builtin_amdgcn_readfirstlane(v & ~63);
+  const int bl0 = v0 >> 5;                         // the wave's two 32-row blocks: bl0, bl0 + 1
+  int32_t* Mw = M + (b0 + bl0) * int64_t(K3) * 32;  // uniform; lane l writes at l%32 of block bl0 + l/32
+  const unsigned lane_off = unsigned(lane >> 5) * unsigned(K3 * 32) + unsigned(lane & 31);
+  // (pointers typed as LDS addresses: 32 bits wide, and every access through them is an LDS instruction)
+  using LdsBytes = const __attribute__((address_space(3))) unsigned char*;
+  using LdsKey = const __attribute__((address_space(3))) KeyT*;
+  const LdsBytes lbase = (LdsBytes)smem;
+  constexpr unsigned KB = sizeof(KeyT);
+  unsigned hbits[MW];  // offsets this lane's row has hit, among those of the matrix (the block masks are their OR over 32 lanes)
+#pragma unroll
+  for (int w = 0; w < MW; ++w) hbits[w] = 0u;
+  // subset tests on the kernel arguments: the word is picked with scalar selects (static indices keep the masks in
+  // scalar registers), so a test costs no LDS access
+  auto subset_word = [&](const KMask& m, int wd) {
+    unsigned x = m.w[0];
+#pragma unroll
+    for (int i = 1; i < MW; ++i) x = wd == i ? m.w[i] : x;
+    return x;
+  };
+  // the K bits of group g (offsets g*K .. g*K + K - 1) in a subset
+  auto subset_field = [&](const KMask& m, int g) {
+    const int wd = (g * K) >> 5, sh = (g * K) & 31;
+    const unsigned long long two = (static_cast<unsigned long long>(wd + 1 < MW ? subset_word(m, wd + 1) : 0u) << 32) | subset_word(m, wd);
+    return static_cast<unsigned>(two >> sh) & ((1u << K) - 1u);
+  };
+  // row numbers are fetched through a buffer descriptor of in_perm's n_in entries: the hardware returns 0 for
+  // positions past the end (candidates behind the last key of the array), so no lane needs a bounds check
+  const __amdgpu_buffer_rsrc_t perm_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(in_perm), 0, in_perm ? n_in * 4 : 0, 0x00020000);
+  auto search_groups = [&](auto NJ_, int gb) {
+    constexpr int NJ = decltype(NJ_)::value;
+    int g[NJ], wsz[NJ], wlo[NJ], n[NJ];
+    bool glob[NJ];
+    LdsBytes ab0[NJ], ab[NJ];
+    KeyT q0[NJ];
+    int nmax = 0;
     bool any_glob = false;
 #pragma unroll
-    for (int j = 0; j < SEARCH_GB; ++j) {
-      const int g = gb + j * parts;
-      const bool wanted = g < G && s_need[min(g, G - 1)];
-      gidx[j] = wanted ? g : -1;
-      const int gc = wanted ? g : 0;
-      const int woff = s_woff[gc];
-      glob[j] = wanted && woff < 0;
+    for (int j = 0; j < NJ; ++j) {
+      g[j] = gb + j * parts;  // < G (the caller counts the groups)
+      const bool need = __builtin_amdgcn_readfirstlane(s_need[g[j]]) != 0;
+      const int woff = __builtin_amdgcn_readfirstlane(s_woff[g[j]]);
+      wsz[j] = need ? __builtin_amdgcn_readfirstlane(s_wsz[g[j]]) : 0;
+      wlo[j] = __builtin_amdgcn_readfirstlane(s_wlo[g[j]]);
+      glob[j] = need && woff < 0 && wsz[j] > 0;  // window kept in global memory
       any_glob |= glob[j];
-      wb[j] = woff < 0 ? 0 : woff;
-      wsz[j] = (wanted && act && woff >= 0) ? s_wsz[gc] : 0;
-      wlo[j] = s_wlo[gc];
-      q0[j] = okey + s_gd[gc];
-      pos[j] = 0;
-      if (wanted && woff >= 0) maxw = max(maxw, s_wsz[gc]);
+      n[j] = woff >= 0 ? wsz[j] : 0;
+      if (woff < 0 && !glob[j]) wsz[j] = 0;
+      // LDS address of the key before the window: the output keys lie before the windows, so this is a valid
+      // address for the first window too
+      ab0[j] = lbase + (unsigned(tile) + unsigned(max(woff, 0))) * KB - KB;
+      ab[j] = ab0[j];
+      q0[j] = okey + s_gd[g[j]];
+      nmax = max(nmax, n[j]);
     }
-    // lower bounds in LDS: pos += bit while the key before pos+bit is smaller than the query
-    for (int bit = maxw > 0 ? 1 << (31 - __clz(maxw)) : 0; bit > 0; bit >>= 1) {
-      KeyT kv[SEARCH_GB];
+    for (int rounds = nmax > 0 ? 32 - __builtin_clz(nmax) : 0; rounds > 0; --rounds) {
+      LdsBytes cand[NJ];
+      KeyT kv[NJ];
 #pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j) kv[j] = win[wb[j] + min(pos[j] + bit, wsz[j]) - 1];
-#pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j) {
-        const int p = pos[j] + bit;
-        pos[j] = (p <= wsz[j] && kv[j] < q0[j]) ? p : pos[j];
+      for (int j = 0; j < NJ; ++j) {
+        const int rest = n[j] >> 1, half = n[j] - rest;  // half = ceil(n / 2)
+        n[j] = rest;
+        cand[j] = ab[j] + unsigned(half) * KB;
+        kv[j] = *(LdsKey)cand[j];
       }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) ab[j] = kv[j] < q0[j] ? cand[j] : ab[j];
     }
     // the K keys from each lower bound on: the K z-consecutive queries of a group hit consecutive
     // positions (keys are sorted integers whose z components are multiples of the input stride,
-    // Section 5.2), so query t is compared with the key h hits after the first
-    KeyT w[SEARCH_GB][K];
+    // Section 5.2).  Reads may run up to K - 1 keys past the window, into the next window or the padding
+    // behind the last one; `rem` below says how many of them belong to the window.
+    KeyT w[NJ][K];
+    int pos[NJ];
 #pragma unroll
-    for (int j = 0; j < SEARCH_GB; ++j)
+    for (int j = 0; j < NJ; ++j) {
 #pragma unroll
-      for (int i = 0; i < K; ++i) w[j][i] = win[wb[j] + min(pos[j] + i, wsz[j] - 1)];
+      for (int i = 0; i < K; ++i) w[j][i] = *(LdsKey)(ab[j] + (i + 1) * KB);
+      pos[j] = static_cast<int>((ab[j] - ab0[j]) / KB);
+    }
     if (any_glob) {  // windows that stayed in global memory (rare): per-lane lower bound, same K keys
 #pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j)
+      for (int j = 0; j < NJ; ++j)
         if (glob[j]) {
-          wsz[j] = act ? s_wsz[gidx[j]] : 0;
           pos[j] = lane_lower_bound<KeyT>(in_keys + wlo[j], wsz[j], q0[j]);
 #pragma unroll
-          for (int i = 0; i < K; ++i) w[j][i] = in_keys[wlo[j] + max(min(pos[j] + i, wsz[j] - 1), 0)];
+          for (int i = 0; i < K; ++i) w[j][i] = in_keys[wlo[j] + min(pos[j] + i, wsz[j] - 1)];
         }
     }
-    int32_t r[SEARCH_GB][K];
-    unsigned hm[SEARCH_GB];  // bit t: query t (ascending z) hit
+    // what the map stores for position rpos + i: the position, or the caller's row number of that voxel.  The
+    // row numbers of all NJ groups are requested before the first of them is used.
+    int rpos[NJ];
+    int32_t val[NJ][K];
+    bool valid[NJ][K];
 #pragma unroll
-    for (int j = 0; j < SEARCH_GB; ++j) {
-      int h = 0;
-      hm[j] = 0u;
+    for (int j = 0; j < NJ; ++j) {
+      const int rem = wsz[j] - pos[j];  // window keys from the lower bound on
+      rpos[j] = wlo[j] + pos[j];        // the lower bound's position in the input array
 #pragma unroll
-      for (int t = 0; t < K; ++t) {
-        const KeyT qt = q0[j] + KeyT(t) * sp.zstep;
-        KeyT cand = w[j][0];
-        for (int i = 1; i < K; ++i) cand = (i <= t && h == i) ? w[j][i] : cand;
-        const bool hit = pos[j] + h < wsz[j] && cand == qt;
-        r[j][sp.zrev ? K - 1 - t : t] = hit ? wlo[j] + pos[j] + h : -1;
-        hm[j] |= hit ? 1u << t : 0u;
-        h += hit ? 1 : 0;
+      for (int i = 0; i < K; ++i) {
+        valid[j][i] = act && i < rem;
+        val[j][i] = rpos[j] + i;
+      }
+      if (in_perm) {
+#pragma unroll
+        for (int i = 0; i < K; ++i) val[j][i] = __builtin_amdgcn_raw_buffer_load_b32(perm_rsrc, rpos[j] * 4 + i * 4, 0, 0);
       }
     }
-    // inverse of a strided map whose offsets partition the inputs (K = layer stride): every input voxel is hit by
-    // exactly one (output, offset), which is all its transposed twin needs
-    if (inv_parent) {
 #pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j)
+    for (int j = 0; j < NJ; ++j) {
+      // query t (ascending z) sits i <= t positions behind the lower bound, i = number of earlier queries that hit
+      KeyT d[K];
+#pragma unroll
+      for (int i = 0; i < K; ++i) d[i] = w[j][i] - q0[j];
+      int32_t r[K];
+      bool hit[K];
+      unsigned hm = 0u;  // bit t: query t hit
+#pragma unroll
+      for (int t = 0; t < K; ++t) {
+        r[t] = -1;
+        hit[t] = false;
+        const KeyT dt = KeyT(t) * sp.zstep;
+#pragma unroll
+        for (int i = 0; i <= t; ++i) {
+          const bool m = valid[j][i] && d[i] == dt;
+          r[t] = m ? val[j][i] : r[t];
+          hit[t] = hit[t] || m;
+        }
+        if constexpr (PAIRS) hm |= hit[t] ? 1u << t : 0u;
+      }
+      const int gj = g[j];
+      // column of query t: offsets of a group ascend with z, queries too unless the z offsets descend with iz
+      auto col = [&](int t) { return sp.zrev ? K - 1 - t : t; };
+      // inverse of a strided map whose offsets partition the inputs (K = layer stride): every input voxel is hit by
+      // exactly one (output, offset), which is all its transposed twin needs (such maps are built without a
+      // row permutation, so r holds positions)
+      if (inv_parent) {
 #pragma unroll
         for (int t = 0; t < K; ++t)
-          if (gidx[j] >= 0 && r[j][t] >= 0) inv_parent[r[j][t]] = (i0 + v) * K3 + gidx[j] * K + t;
-    }
-    if constexpr (PAIRS) {
-      // the tile's records stay in LDS; hits are counted per offset (a wave speaks for its 64 rows)
-#pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j) {
-        const int g = gidx[j];
-        if (g < 0) continue;  // uniform in the wave
-        s_pos[g * tile + v] = wlo[j] + pos[j];
-        s_hit[g * tile + v] = static_cast<uint8_t>(hm[j]);
+          if (hit[t]) inv_parent[r[t]] = (i0 + v) * K3 + gj * K + col(t);
+      }
+      if constexpr (PAIRS) {
+        // the tile's records stay in LDS; hits are counted per offset (a wave speaks for its 64 rows)
+        const unsigned wsf = subset_field(ws_k, gj);
+        s_pos[gj * tile + v] = rpos[j];
+        s_hit[gj * tile + v] = static_cast<uint8_t>(hm);
 #pragma unroll
         for (int t = 0; t < K; ++t) {
-          const int k = g * K + t;
-          if (!ws_has(k)) continue;  // uniform
-          const unsigned long long hit = __ballot(r[j][t] >= 0);
-          if (hit && lane == 0) atomicAdd(&s_cnt[k], __popcll(hit));
+          if (!((wsf >> col(t)) & 1u)) continue;
+          const unsigned long long bal = __ballot(hit[t]);
+          if (bal && lane == 0) atomicAdd(&s_cnt[gj * K + col(t)], __popcll(bal));
         }
       }
-    }
-    if (!M) continue;  // no offset goes to the matrix (uniform over the launch)
-    // found positions are stored as they are, or mapped to the caller's row numbering.  The
-    // lookups are unconditional (misses read entry 0) and all issued before the first store: on this
-    // target loads and stores share one counter, so a load waited for between two stores would
-    // also wait for every store before it.
-    int32_t jv[SEARCH_GB][K];
-    if (in_perm && n_in > 0) {
+      if (!M) continue;  // no offset goes to the matrix (uniform over the launch)
+      const unsigned osf = subset_field(os_k, gj);
+      // Every store into the blocked map M[block][k][32] is two full 128-byte segments.
+      if (stored) {
 #pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j)
-#pragma unroll
-        for (int t = 0; t < K; ++t) jv[j][t] = in_perm[max(r[j][t], 0)];
-#pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j)
-#pragma unroll
-        for (int t = 0; t < K; ++t) jv[j][t] = r[j][t] < 0 ? -1 : jv[j][t];
-    } else {
-#pragma unroll
-      for (int j = 0; j < SEARCH_GB; ++j)
-#pragma unroll
-        for (int t = 0; t < K; ++t) jv[j][t] = r[j][t];
-    }
-#pragma unroll
-    for (int j = 0; j < SEARCH_GB; ++j) {
-      const int g = gidx[j];
-      if (g < 0) continue;  // uniform in the wave
-#pragma unroll
-      for (int t = 0; t < K; ++t) {
-        const int k = g * K + t;
-        if (!os_has(k)) continue;  // uniform
-        if (v < rows32) Mrow[k * 32] = jv[j][t];  // rows past the end hold -1
-        const unsigned long long hit = __ballot(r[j][t] >= 0);
-        if (hit && lane == 0) {  // lane 0 speaks for the wave's two 32-row blocks
-          if (unsigned(hit)) atomicOr(&s_mask[bl * MW + (k >> 5)], 1u << (k & 31));
-          if (unsigned(hit >> 32)) atomicOr(&s_mask[(bl + 1) * MW + (k >> 5)], 1u << (k & 31));
-        }
+        for (int t = 0; t < K; ++t)
+          if ((osf >> col(t)) & 1u) (Mw + (gj * K + col(t)) * 32)[lane_off] = r[t];
       }
+      // the row's hits among the matrix offsets, as bits gj*K .. gj*K + K - 1 of the lane's mask words
+      unsigned hc = 0u;
+#pragma unroll
+      for (int t = 0; t < K; ++t) hc |= hit[t] ? 1u << col(t) : 0u;
+      const int wd = (gj * K) >> 5, sh = (gj * K) & 31;
+      const unsigned long long f = static_cast<unsigned long long>(hc & osf) << sh;
+#pragma unroll
+      for (int w = 0; w < MW; ++w) hbits[w] |= (wd == w ? static_cast<unsigned>(f) : 0u) | (wd + 1 == w ? static_cast<unsigned>(f >> 32) : 0u);
     }
+  };
+  // the wave's groups: part, part + parts, ...; SEARCH_GB at a time, then the remainder
+  {
+    const int mine = part < G ? (G - part + parts - 1) / parts : 0;
+    int done = 0;
+    for (; done + SEARCH_GB <= mine; done += SEARCH_GB) search_groups(std::integral_constant<int, SEARCH_GB>{}, part + done * parts);
+    const int left = mine - done;
+    const int gb = part + done * parts;
+    // (only the remainders that some part of this kernel size can have are compiled)
+    if constexpr (remainder_occurs(G, parts, SEARCH_GB, 1)) if (left == 1) search_groups(std::integral_constant<int, 1>{}, gb);
+    if constexpr (remainder_occurs(G, parts, SEARCH_GB, 2)) if (left == 2) search_groups(std::integral_constant<int, 2>{}, gb);
+    if constexpr (remainder_occurs(G, parts, SEARCH_GB, 3)) if (left == 3) search_groups(std::integral_constant<int, 3>{}, gb);
+    if constexpr (remainder_occurs(G, parts, SEARCH_GB, 4)) if (left == 4) search_groups(std::integral_constant<int, 4>{}, gb);
+    static_assert(SEARCH_GB <= 5, "remainders above four groups are not dispatched");
+  }
+  if (M) {
+#pragma unroll
+    for (int w = 0; w < MW; ++w)
+      if (hbits[w]) atomicOr(&s_mask[(bl0 + (lane >> 5)) * MW + w], hbits[w]);
   }
   __syncthreads();
   if constexpr (PAIRS) {
@@ -640,7 +708,7 @@ __global__ void copy_int_kernel(const int* src, int* dst) { *dst = *src; }
 // ---------------------------------------------------------------- host side
 static int axis_offset(int K, int s, int i) { return (K % 2 == 1) ? (i - (K - 1) / 2) * s : i * s; }
 
-static int tile_for(int K) { return K <= 3 ? 128 : 64; }
+static int tile_for(int K) { return search_tile(K); }
 
 static std::atomic<int64_t> g_search_launches{0};  // searches enqueued by this process (see spc_search_count)
 
@@ -662,7 +730,7 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
   const Level* in = m->in_level;
   const Level* out = m->out_level;
   const bool pairs = (m->desc.layout & SPC_LAYOUT_WS) != 0;
-  const size_t lds = size_t(m->tile) * sizeof(KeyT) + WIN_CAP_BYTES + (pairs ? size_t(K) * K * m->tile * 5 : 0);
+  const size_t lds = size_t(m->tile) * sizeof(KeyT) + WIN_CAP_BYTES + MAX_K * sizeof(KeyT) + (pairs ? size_t(K) * K * m->tile * 5 : 0);
   auto go = [&](auto PAIRS_) {
     constexpr bool PAIRS = decltype(PAIRS_)::value;
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&kmap_search_kernel<KeyT, K, PAIRS>),
@@ -671,7 +739,7 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
     hipLaunchKernelGGL((kmap_search_kernel<KeyT, K, PAIRS>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
-                       sp, m->tile, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm, m->os_k, m->ws_k,
+                       sp, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm, m->os_k, m->ws_k,
                        m->tile_pairs, m->inv_parent);
   };
   if (m->n_tiles > 0) {
