@@ -32,11 +32,12 @@ constexpr int WS_MAX_K3_SEARCH = MAX_K * MAX_K * MAX_K;
 
 template <typename KeyT>
 struct SearchParams {
-  KeyT X[MAX_K];  // packed x offsets per ix (wrapping arithmetic)
-  KeyT Y[MAX_K];  // packed y offsets per iy
+  KeyT X0, dX;    // packed x offset of ix = 0 and its step per ix (wrapping arithmetic: the offsets of an axis are
+  KeyT Y0, dY;    // an arithmetic sequence); the same for y
   KeyT zmin;      // packed smallest z offset
   KeyT zstep;     // distance between consecutive z offsets (= input stride)
   int zrev;       // 1: z offsets descend with iz (transposed maps)
+  unsigned long long need;  // bit g: group g = ix * K + iy has an offset in one of the two subsets
 };
 
 __device__ inline int lanemask_lt_popc(unsigned long long m) {
@@ -187,7 +188,6 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   constexpr int G = K * K, K3 = K * K * K;
   constexpr int tile = search_tile(K);
   constexpr int SEARCH_GB = K <= 3 ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
-  constexpr int G_POW2 = G <= 1 ? 1 : G <= 4 ? 4 : G <= 16 ? 16 : G <= 64 ? 64 : 128;  // power of two >= G
   constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
   constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
   constexpr int WIN_CAP = WIN_CAP_BYTES / sizeof(KeyT);
@@ -203,13 +203,11 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   uint8_t* s_hit = reinterpret_cast<uint8_t*>(s_pos + G * tile);      // PAIRS: [G][tile] bit t: the group's t-th query (ascending z) hit
   __shared__ int s_off[PAIRS ? K3 + 1 : 1];                           // PAIRS: where every offset's pairs start in the tile's slab
   __shared__ KeyT s_probe[N_PROBES];
-  __shared__ int s_wlo[G], s_wsz[G], s_woff[G], s_wend[G + 1];
+  __shared__ int4 s_grp[G];  // window of group g: x = first input position, y = keys, z = place in `win` (-1: not staged)
   __shared__ int s_bound[2 * G];
   __shared__ int s_cnt[K3];
   __shared__ unsigned s_mask[MAX_BLOCKS * MW];
   __shared__ KeyT s_gd[G];  // packed (dx,dy,zmin) offset of every group
-  __shared__ uint32_t s_osk[KMASK_WORDS], s_wsk[KMASK_WORDS];  // the offset subsets, readable at run-time indices
-  __shared__ int s_need[G];                                    // group g has an offset in either subset
 
   const int n_in = n_in_d ? *n_in_d : n_in_h;
   const int n_out = n_out_d ? *n_out_d : n_out_h;
@@ -229,24 +227,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   for (int k = tid; k < K3; k += SEARCH_THREADS) s_cnt[k] = 0;
   for (int k = tid; k < MAX_BLOCKS * MW; k += SEARCH_THREADS) s_mask[k] = 0u;
   for (int k = tid; k < 2 * G; k += SEARCH_THREADS) s_bound[k] = 0;
-#pragma unroll
-  for (int wd = 0; wd < KMASK_WORDS; ++wd)
-    if (tid == wd) {
-      s_osk[wd] = M ? os_k.w[wd] : 0u;
-      s_wsk[wd] = PAIRS ? ws_k.w[wd] : 0u;
-    }
-#pragma unroll
-  for (int g = 0; g < G; ++g)  // static indices keep the kernel arguments in scalar registers
-    if (tid == g) s_gd[g] = sp.X[g / K] + sp.Y[g % K] + sp.zmin;
-  __syncthreads();
-  auto os_has = [&](int k) { return (s_osk[k >> 5] >> (k & 31)) & 1u; };
-  auto ws_has = [&](int k) { return (s_wsk[k >> 5] >> (k & 31)) & 1u; };
-  // only groups with a wanted offset are searched: the others get empty windows
-  if (tid < G) {
-    int need = 0;
-    for (int t = 0; t < K; ++t) need |= os_has(tid * K + t) | ws_has(tid * K + t);
-    s_need[tid] = need;
-  }
+  if (tid < G) s_gd[tid] = sp.X0 + KeyT(tid / K) * sp.dX + sp.Y0 + KeyT(tid % K) * sp.dY + sp.zmin;
   __syncthreads();
   const KeyT kfirst = okeys[0], klast = okeys[rows - 1];
   const KeyT zspan = KeyT(K - 1) * sp.zstep;
@@ -269,7 +250,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int sc = (u * NW + wave) * Q + grp;
-      if (lane % BOUND_P == 0 && sc < 2 * G && s_need[sc >> 1]) s_bound[sc] = res[u];
+      // only groups with a wanted offset are searched: the others keep empty windows
+      if (lane % BOUND_P == 0 && sc < 2 * G && ((sp.need >> (sc >> 1)) & 1ull)) s_bound[sc] = res[u];
     }
   }
   __syncthreads();
@@ -284,14 +266,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       const int y = __shfl_up(incl, d, 64);
       if (lane >= d) incl += y;
     }
-    if (lane < G) {
-      const bool fits = incl <= WIN_CAP;
-      s_wlo[lane] = lo;
-      s_wsz[lane] = sz;
-      s_woff[lane] = fits ? incl - sz : -1;
-      s_wend[lane + 1] = fits ? incl : -1;
-    }
-    if (lane == 0) s_wend[0] = 0;
+    if (lane < G) s_grp[lane] = make_int4(lo, sz, incl <= WIN_CAP ? incl - sz : -1, 0);
   }
   __syncthreads();
 
@@ -307,21 +282,26 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const int team = __builtin_amdgcn_readfirstlane(tid / TEAM), lt = tid % TEAM;
     KeyT tmp[STAGE_U];
     int woff[STAGE_U], wsz[STAGE_U], wlo[STAGE_U];
+    int longest = 0;
 #pragma unroll
     for (int i = 0; i < STAGE_U; ++i) {
-      const int g = team + i * N_TEAMS, gc = min(g, G - 1);
-      woff[i] = __builtin_amdgcn_readfirstlane(s_woff[gc]);
-      wsz[i] = g < G && woff[i] >= 0 ? __builtin_amdgcn_readfirstlane(s_wsz[gc]) : 0;
-      wlo[i] = __builtin_amdgcn_readfirstlane(s_wlo[gc]);
+      const int g = team + i * N_TEAMS;
+      const int4 gw = s_grp[min(g, G - 1)];
+      wlo[i] = __builtin_amdgcn_readfirstlane(gw.x);
+      woff[i] = __builtin_amdgcn_readfirstlane(gw.z);
+      wsz[i] = g < G && woff[i] >= 0 ? __builtin_amdgcn_readfirstlane(gw.y) : 0;
+      longest = max(longest, wsz[i]);
       tmp[i] = 0;
       if (lt < wsz[i]) tmp[i] = (in_keys + wlo[i])[lt];
     }
 #pragma unroll
     for (int i = 0; i < STAGE_U; ++i)
       if (lt < wsz[i]) (win + woff[i])[lt] = tmp[i];
+    if (longest > TEAM) {  // rare
 #pragma unroll
-    for (int i = 0; i < STAGE_U; ++i)
-      for (int e = lt + TEAM; e < wsz[i]; e += TEAM) (win + woff[i])[e] = (in_keys + wlo[i])[e];
+      for (int i = 0; i < STAGE_U; ++i)
+        for (int e = lt + TEAM; e < wsz[i]; e += TEAM) (win + woff[i])[e] = (in_keys + wlo[i])[e];
+    }
   }
   __syncthreads();
 
@@ -382,14 +362,13 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       g[j] = gb + j * parts;  // < G (the caller counts the groups)
-      const bool need = __builtin_amdgcn_readfirstlane(s_need[g[j]]) != 0;
-      const int woff = __builtin_amdgcn_readfirstlane(s_woff[g[j]]);
-      wsz[j] = need ? __builtin_amdgcn_readfirstlane(s_wsz[g[j]]) : 0;
-      wlo[j] = __builtin_amdgcn_readfirstlane(s_wlo[g[j]]);
-      glob[j] = need && woff < 0 && wsz[j] > 0;  // window kept in global memory
+      const int4 gw = s_grp[g[j]];  // (groups without a wanted offset have empty windows)
+      wlo[j] = __builtin_amdgcn_readfirstlane(gw.x);
+      wsz[j] = __builtin_amdgcn_readfirstlane(gw.y);
+      const int woff = __builtin_amdgcn_readfirstlane(gw.z);
+      glob[j] = woff < 0 && wsz[j] > 0;  // window kept in global memory
       any_glob |= glob[j];
       n[j] = woff >= 0 ? wsz[j] : 0;
-      if (woff < 0 && !glob[j]) wsz[j] = 0;
       // LDS address of the key before the window: the output keys lie before the windows, so this is a valid
       // address for the first window too
       ab0[j] = lbase + (unsigned(tile) + unsigned(max(woff, 0))) * KB - KB;
@@ -499,9 +478,14 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       const unsigned osf = subset_field(os_k, gj);
       // Every store into the blocked map M[block][k][32] is two full 128-byte segments.
       if (stored) {
+        if (osf == (1u << K) - 1u) {  // all of the group's offsets (the usual case)
 #pragma unroll
-        for (int t = 0; t < K; ++t)
-          if ((osf >> col(t)) & 1u) (Mw + (gj * K + col(t)) * 32)[lane_off] = r[t];
+          for (int t = 0; t < K; ++t) (Mw + (gj * K + col(t)) * 32)[lane_off] = r[t];
+        } else {
+#pragma unroll
+          for (int t = 0; t < K; ++t)
+            if ((osf >> col(t)) & 1u) (Mw + (gj * K + col(t)) * 32)[lane_off] = r[t];
+        }
       }
       // the row's hits among the matrix offsets, as bits gj*K .. gj*K + K - 1 of the lane's mask words
       unsigned hc = 0u;
@@ -718,15 +702,20 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
   const int sp_stride = m->desc.in_stride;
   const int sign = m->desc.transposed ? -1 : 1;
   SearchParams<KeyT> sp{};
-  for (int i = 0; i < K; ++i) {
-    const int64_t o = int64_t(sign) * axis_offset(K, sp_stride, i);
-    sp.X[i] = static_cast<KeyT>(static_cast<uint64_t>(o) << pi.sh_x);
-    sp.Y[i] = static_cast<KeyT>(static_cast<uint64_t>(o) << pi.sh_y);
-  }
+  auto packed = [&](int i, int shift) {  // offset of index i along an axis, shifted into its field (wrapping)
+    return static_cast<KeyT>(static_cast<uint64_t>(int64_t(sign) * axis_offset(K, sp_stride, i)) << shift);
+  };
+  sp.X0 = packed(0, pi.sh_x);
+  sp.dX = K > 1 ? static_cast<KeyT>(packed(1, pi.sh_x) - sp.X0) : KeyT(0);
+  sp.Y0 = packed(0, pi.sh_y);
+  sp.dY = K > 1 ? static_cast<KeyT>(packed(1, pi.sh_y) - sp.Y0) : KeyT(0);
   const int64_t z_a = int64_t(sign) * axis_offset(K, sp_stride, 0), z_b = int64_t(sign) * axis_offset(K, sp_stride, K - 1);
   sp.zmin = static_cast<KeyT>(static_cast<uint64_t>(std::min(z_a, z_b)));
   sp.zstep = static_cast<KeyT>(sp_stride);
   sp.zrev = (K > 1 && z_a > z_b) ? 1 : 0;
+  for (int g = 0; g < K * K; ++g)
+    for (int t = 0; t < K; ++t)
+      if ((m->os_map && m->os_k.has(g * K + t)) || m->ws_k.has(g * K + t)) sp.need |= 1ull << g;
   const Level* in = m->in_level;
   const Level* out = m->out_level;
   const bool pairs = (m->desc.layout & SPC_LAYOUT_WS) != 0;
