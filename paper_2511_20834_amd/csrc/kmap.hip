@@ -238,21 +238,27 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     constexpr int Q = 64 / BOUND_P;
     constexpr int U = (2 * G + NW * Q - 1) / (NW * Q);
     const int grp = lane / BOUND_P;
-    KeyT q[U];
-    int res[U];
+    auto run_bounds = [&](auto U_) {
+      constexpr int UU = decltype(U_)::value;
+      KeyT q[UU];
+      int res[UU];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int sc = min((u * NW + wave) * Q + grp, 2 * G - 1);
-      const KeyT d = s_gd[sc >> 1];
-      q[u] = (grp & 1) ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
-    }
-    group_bounds<KeyT, BOUND_P, U>(in_keys, n_in, s_probe, q, res, BOUND_SLACK);
+      for (int u = 0; u < UU; ++u) {
+        const int sc = min((u * NW + wave) * Q + grp, 2 * G - 1);
+        const KeyT d = s_gd[sc >> 1];
+        q[u] = (grp & 1) ? KeyT(klast + d + zspan) : KeyT(kfirst + d);
+      }
+      group_bounds<KeyT, BOUND_P, UU>(in_keys, n_in, s_probe, q, res, BOUND_SLACK);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int sc = (u * NW + wave) * Q + grp;
-      // only groups with a wanted offset are searched: the others keep empty windows
-      if (lane % BOUND_P == 0 && sc < 2 * G && ((sp.need >> (sc >> 1)) & 1ull)) s_bound[sc] = res[u];
-    }
+      for (int u = 0; u < UU; ++u) {
+        const int sc = (u * NW + wave) * Q + grp;
+        // only groups with a wanted offset are searched: the others keep empty windows
+        if (lane % BOUND_P == 0 && sc < 2 * G && ((sp.need >> (sc >> 1)) & 1ull)) s_bound[sc] = res[u];
+      }
+    };
+    // the last pass is short of searches: only the waves that have one there run it
+    if (U == 1 || ((U - 1) * NW + wave) * Q < 2 * G) run_bounds(std::integral_constant<int, U>{});
+    else run_bounds(std::integral_constant<int, (U > 1 ? U - 1 : 1)>{});
   }
   __syncthreads();
 
@@ -277,6 +283,8 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   // address additions per lane, and the loads of all of a team's windows are in flight together.
   {
     constexpr int TEAM = tile >= 128 ? SEARCH_THREADS : 64;  // lanes per window
+    const __amdgpu_buffer_rsrc_t keys_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<KeyT*>(in_keys), 0, sizeof(KeyT) == 4 ? n_in * 4 : 0, 0x00020000);
     constexpr int N_TEAMS = SEARCH_THREADS / TEAM;
     constexpr int STAGE_U = (G + N_TEAMS - 1) / N_TEAMS;       // windows per team
     const int team = __builtin_amdgcn_readfirstlane(tid / TEAM), lt = tid % TEAM;
@@ -291,8 +299,14 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       woff[i] = __builtin_amdgcn_readfirstlane(gw.z);
       wsz[i] = g < G && woff[i] >= 0 ? __builtin_amdgcn_readfirstlane(gw.y) : 0;
       longest = max(longest, wsz[i]);
-      tmp[i] = 0;
-      if (lt < wsz[i]) tmp[i] = (in_keys + wlo[i])[lt];
+      // (through a descriptor of the n_in keys: lanes past the window read a neighbouring key or, past the
+      // array, zero; nothing of that is stored)
+      if constexpr (sizeof(KeyT) == 4) {
+        tmp[i] = __builtin_amdgcn_raw_buffer_load_b32(keys_rsrc, lt * 4, wlo[i] * 4, 0);
+      } else {
+        tmp[i] = 0;
+        if (lt < wsz[i]) tmp[i] = (in_keys + wlo[i])[lt];
+      }
     }
 #pragma unroll
     for (int i = 0; i < STAGE_U; ++i)
@@ -324,7 +338,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   const int v0 = __builtin_amdgcn_readfirstlane(v & ~63);
   const int bl0 = v0 >> 5;                         // the wave's two 32-row blocks: bl0, bl0 + 1
   int32_t* Mw = M + (b0 + bl0) * int64_t(K3) * 32;  // uniform; lane l writes at l%32 of block bl0 + l/32
-  const unsigned lane_off = unsigned(lane >> 5) * unsigned(K3 * 32) + unsigned(lane & 31);
+  const unsigned lane_off = (unsigned(lane >> 5) * unsigned(K3 * 32) + unsigned(lane & 31)) * 4u;  // bytes
   // (pointers typed as LDS addresses: 32 bits wide, and every access through them is an LDS instruction)
   using LdsBytes = const __attribute__((address_space(3))) unsigned char*;
   using LdsKey = const __attribute__((address_space(3))) KeyT*;
@@ -351,6 +365,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
   // positions past the end (candidates behind the last key of the array), so no lane needs a bounds check
   const __amdgpu_buffer_rsrc_t perm_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(in_perm), 0, in_perm ? n_in * 4 : 0, 0x00020000);
+  const int col0 = sp.zrev ? K - 1 : 0, cstep = sp.zrev ? -1 : 1;  // column of a group's query t: col0 + t * cstep
   auto search_groups = [&](auto NJ_, int gb) {
     constexpr int NJ = decltype(NJ_)::value;
     int g[NJ], wsz[NJ], wlo[NJ], n[NJ];
@@ -453,7 +468,7 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       }
       const int gj = g[j];
       // column of query t: offsets of a group ascend with z, queries too unless the z offsets descend with iz
-      auto col = [&](int t) { return sp.zrev ? K - 1 - t : t; };
+      auto col = [&](int t) { return col0 + t * cstep; };
       // inverse of a strided map whose offsets partition the inputs (K = layer stride): every input voxel is hit by
       // exactly one (output, offset), which is all its transposed twin needs (such maps are built without a
       // row permutation, so r holds positions)
@@ -478,13 +493,14 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
       const unsigned osf = subset_field(os_k, gj);
       // Every store into the blocked map M[block][k][32] is two full 128-byte segments.
       if (stored) {
+        char* Mb = reinterpret_cast<char*>(Mw);  // + a 32-bit offset: column k starts k * 128 bytes into the block
         if (osf == (1u << K) - 1u) {  // all of the group's offsets (the usual case)
 #pragma unroll
-          for (int t = 0; t < K; ++t) (Mw + (gj * K + col(t)) * 32)[lane_off] = r[t];
+          for (int t = 0; t < K; ++t) *reinterpret_cast<int32_t*>(Mb + (lane_off + unsigned(gj * K + col(t)) * 128u)) = r[t];
         } else {
 #pragma unroll
           for (int t = 0; t < K; ++t)
-            if ((osf >> col(t)) & 1u) (Mw + (gj * K + col(t)) * 32)[lane_off] = r[t];
+            if ((osf >> col(t)) & 1u) *reinterpret_cast<int32_t*>(Mb + (lane_off + unsigned(gj * K + col(t)) * 128u)) = r[t];
         }
       }
       // the row's hits among the matrix offsets, as bits gj*K .. gj*K + K - 1 of the lane's mask words
