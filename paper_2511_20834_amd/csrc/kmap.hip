@@ -165,8 +165,12 @@ __host__ __device__ constexpr bool remainder_occurs(int G, int parts, int gb, in
     if (((G - p + parts - 1) / parts) % gb == rem) return true;
   return false;
 }
-// Output voxels per search workgroup (a multiple of the wave size that divides SEARCH_THREADS).
-__host__ __device__ constexpr int search_tile(int K) { return K <= 3 ? 128 : 64; }
+// Output voxels per search workgroup (a multiple of the wave size that divides SEARCH_THREADS).  Every tile pays for
+// its window bounds, their placement and the staging, so longer tiles do less work per voxel, and shorter ones
+// spread a small level over more compute units: 3x3x3, 128 -> 256 rows: 3 * 10^6 voxels 162 -> 140 us,
+// 10^6 60 -> 56 us, 120 k 16.8 -> 21 us; 5x5x5, 64 -> 128 rows: 240 k voxels 65 -> 62 us.
+constexpr int64_t SEARCH_LONG_TILE_FROM = 750000;  // output voxels from which K <= 3 takes 256-row tiles
+inline int search_tile(int K, int64_t n_out) { return K <= 3 ? (n_out >= SEARCH_LONG_TILE_FROM ? 256 : 128) : K <= 5 ? 128 : 64; }
 
 // Two outputs, each for its own subset of the K^3 offsets (Section 5.4: all offsets in one of them for a single
 // dataflow; the dense offsets in the matrix and the sparse ones in the lists for the hybrid dual dataflow):
@@ -178,7 +182,7 @@ __host__ __device__ constexpr int search_tile(int K) { return K <= 3 ? 128 : 64;
 //         tile * K^3 pairs, of which only the first sum-of-hits are touched); tile_counts gets the hits per
 //         (offset, tile).
 // Groups none of whose offsets is wanted are not searched (the second half of a symmetric map, for example).
-template <typename KeyT, int K, bool PAIRS>
+template <typename KeyT, int K, int TILE, bool PAIRS>
 __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const KeyT* __restrict__ in_keys, int n_in_h, const int* __restrict__ n_in_d, const KeyT* __restrict__ out_keys,
     int n_out_h, const int* __restrict__ n_out_d, SearchParams<KeyT> sp, int32_t* __restrict__ M,
@@ -186,10 +190,10 @@ __global__ __launch_bounds__(SEARCH_THREADS) void kmap_search_kernel(
     const int32_t* __restrict__ in_perm, KMask os_k, KMask ws_k, int2* __restrict__ tile_pairs,
     int32_t* __restrict__ inv_parent) {
   constexpr int G = K * K, K3 = K * K * K;
-  constexpr int tile = search_tile(K);
+  constexpr int tile = TILE;
   constexpr int SEARCH_GB = K <= 3 ? SEARCH_GB_SMALL : SEARCH_GB_LARGE;
   constexpr int MW = (K3 + 31) / 32;   // mask words per 32-row block
-  constexpr int MAX_BLOCKS = 4;        // tile <= 128 rows
+  constexpr int MAX_BLOCKS = TILE / 32;
   constexpr int WIN_CAP = WIN_CAP_BYTES / sizeof(KeyT);
   constexpr int NW = SEARCH_THREADS / 64;
   // lanes per window-bound search: with many groups of offsets the probe lines fetched count for more than the
@@ -708,11 +712,10 @@ __global__ void copy_int_kernel(const int* src, int* dst) { *dst = *src; }
 // ---------------------------------------------------------------- host side
 static int axis_offset(int K, int s, int i) { return (K % 2 == 1) ? (i - (K - 1) / 2) * s : i * s; }
 
-static int tile_for(int K) { return search_tile(K); }
 
 static std::atomic<int64_t> g_search_launches{0};  // searches enqueued by this process (see spc_search_count)
 
-template <typename KeyT, int K>
+template <typename KeyT, int K, int TILE>
 static int launch_search(spc_kmap* m, hipStream_t s) {
   const PackInfo& pi = m->pi;
   const int sp_stride = m->desc.in_stride;
@@ -738,10 +741,10 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
   const size_t lds = size_t(m->tile) * sizeof(KeyT) + WIN_CAP_BYTES + MAX_K * sizeof(KeyT) + (pairs ? size_t(K) * K * m->tile * 5 : 0);
   auto go = [&](auto PAIRS_) {
     constexpr bool PAIRS = decltype(PAIRS_)::value;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&kmap_search_kernel<KeyT, K, PAIRS>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&kmap_search_kernel<KeyT, K, TILE, PAIRS>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     (void)attr;
-    hipLaunchKernelGGL((kmap_search_kernel<KeyT, K, PAIRS>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
+    hipLaunchKernelGGL((kmap_search_kernel<KeyT, K, TILE, PAIRS>), dim3(m->n_tiles), dim3(SEARCH_THREADS), lds, s,
                        static_cast<const KeyT*>(in->keys), static_cast<int>(in->n_host < 0 ? 0 : in->n_host), in->n_dev,
                        static_cast<const KeyT*>(out->keys), static_cast<int>(out->n_host < 0 ? 0 : out->n_host), out->n_dev,
                        sp, m->os_map, m->block_masks, m->tile_counts, m->n_tiles, m->in_perm, m->os_k, m->ws_k,
@@ -758,11 +761,11 @@ static int launch_search(spc_kmap* m, hipStream_t s) {
 template <typename KeyT>
 static int launch_search_k(spc_kmap* m, hipStream_t s) {
   switch (m->desc.K) {
-    case 1: return launch_search<KeyT, 1>(m, s);
-    case 2: return launch_search<KeyT, 2>(m, s);
-    case 3: return launch_search<KeyT, 3>(m, s);
-    case 5: return launch_search<KeyT, 5>(m, s);
-    case 7: return launch_search<KeyT, 7>(m, s);
+    case 1: return m->tile == 256 ? launch_search<KeyT, 1, 256>(m, s) : launch_search<KeyT, 1, 128>(m, s);
+    case 2: return m->tile == 256 ? launch_search<KeyT, 2, 256>(m, s) : launch_search<KeyT, 2, 128>(m, s);
+    case 3: return m->tile == 256 ? launch_search<KeyT, 3, 256>(m, s) : launch_search<KeyT, 3, 128>(m, s);
+    case 5: return launch_search<KeyT, 5, 128>(m, s);
+    case 7: return launch_search<KeyT, 7, 64>(m, s);
   }
   return set_error(SPC_ERR_UNSUPPORTED, "kernel size %d not built (1,2,3,5,7 are)", m->desc.K);
 }
@@ -872,7 +875,7 @@ static int build_on_levels(Level* in, Level* out, const PackInfo& pi, const spc_
   out->add_reader(s);
   (void)hipGetDevice(&m->device);
   m->out_cap = out->n_host >= 0 ? out->n_host : out->cap;
-  m->tile = tile_for(l.K);
+  m->tile = search_tile(l.K, m->out_cap);
   m->n_tiles = static_cast<int>((m->out_cap + m->tile - 1) / m->tile);
   m->n_blocks_cap = (m->out_cap + 31) / 32;
   m->mask_words = (m->K3 + 31) / 32;
@@ -958,7 +961,7 @@ static int build_transposed_from_twin(spc_kmap* twin, Level* coarse, Level* fine
   fine->refs++;
   (void)hipGetDevice(&m->device);
   m->out_cap = fine->n_host >= 0 ? fine->n_host : fine->cap;
-  m->tile = tile_for(l.K);
+  m->tile = search_tile(l.K, m->out_cap);
   m->n_tiles = static_cast<int>((m->out_cap + m->tile - 1) / m->tile);
   m->n_blocks_cap = (m->out_cap + 31) / 32;
   m->mask_words = 1;
