@@ -10,9 +10,10 @@
 // What is different (CDNA4): a workgroup owns a contiguous tile of sorted output
 // voxels.  Because adding a constant keeps the order, all queries of a tile and group
 // fall into one contiguous window of the input array.  The 2 K^2 window bounds are found
-// by groups of lanes, 16-ary (4-ary for K >= 5) after a shared 64-ary first round (two or three
-// dependent loads for 2^18 keys instead of 18), the
-// windows are copied into LDS with coalesced loads, and every lane then searches in LDS.
+// by groups of lanes, 16-ary (4-ary for K >= 5), the first rounds on 256 probes shared by all
+// searches in LDS (one or two dependent loads for 2^18 keys instead of 18), the
+// windows are copied into LDS with coalesced loads, and every lane then searches in LDS
+// with the window state in scalar registers (the kernel is bound by instruction issue).
 // Windows that do not fit the LDS budget are searched in global memory, restricted to
 // the window, with the same code.
 #include <algorithm>
@@ -154,10 +155,9 @@ __device__ inline int lane_lower_bound(Ptr win, int wsz, KeyT q) {
   return lo;
 }
 
-// Groups whose LDS searches one lane keeps in flight together.  K <= 3 with 32-bit keys: five (one lane's share of
-// the nine groups in one go, 60 registers; with 64-bit keys that takes 82 registers, so three there as well: 10^6
-// voxels 95 -> 89 us).  Larger kernels: three; five cost the registers that hold eight waves per SIMD
-// (240 k voxels, 5x5x5: map build 90 us with five or seven, 75 us with two, three or four).
+// Groups whose LDS searches one lane keeps in flight together.  K <= 3: five (one lane's share of the nine groups
+// in one go; 44 registers with 32-bit keys, 64 with 64-bit keys).  Larger kernels: four (three and five measured
+// within 5 % on 240 k voxels, 5x5x5).
 constexpr int SEARCH_GB_SMALL = 5, SEARCH_GB_LARGE = 4;
 // Whether some part p < parts has `rem` groups left after whole batches of gb (its groups are p, p + parts, ... < G).
 __host__ __device__ constexpr bool remainder_occurs(int G, int parts, int gb, int rem) {
