@@ -522,6 +522,12 @@ def test_large_random_scene(n, key_bits):
         y = B.spc_conv_forward(km, Fs, Wt, df, variant)
         assert_close(y.cpu().double().numpy(), ref, 1e-2, (n, df, variant))
     km.destroy()
+    # 1x1x1: every voxel maps to itself
+    km1 = B.spc_build_kmap(keys, desc, 1, 1, 1, 0, B.LAYOUT_BOTH)
+    ident = np.stack([np.zeros(n, np.int32), np.arange(n, dtype=np.int32), np.arange(n, dtype=np.int32)], 1)
+    assert np.array_equal(km1.export_triples(B.LAYOUT_OS), ident)
+    assert np.array_equal(km1.export_triples(B.LAYOUT_WS), ident)
+    km1.destroy()
     B.spc_release_cache()
 
 
@@ -533,10 +539,15 @@ def test_large_random_scene_levels():
     keys, _ = gpu_pack(c, desc)
     cs, _ = oracle.sort_coords(c)
     maps = B.spc_build_kmaps_network(keys, desc, [(2, s, 2, 0, B.LAYOUT_OS) for s in (1, 2)])
+    levels = {1: cs}
     for m, stride in zip(maps, (2, 4)):
-        ref = oracle_keys(oracle.downsample(cs, stride), desc)
+        levels[stride] = oracle.downsample(cs, stride)
+        ref = oracle_keys(levels[stride], desc)
         assert m.n_out == len(ref)
         assert np.array_equal(m.out_keys(), ref), stride
+    # the strided 2x2x2 map onto the first level (long search tiles at this size)
+    ref_t = oracle.triples(oracle.kernel_map(levels[1], levels[2], 2, 1))
+    assert np.array_equal(maps[0].export_triples(B.LAYOUT_OS), ref_t)
     for m in maps:
         m.destroy()
     B.spc_release_cache()
