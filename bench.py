@@ -392,7 +392,9 @@ def main() -> int:
         roof["flop_per_byte"] = intensity
         roof["timed"] = "feature phase, HIP events on the launch stream, mean of %d steps" % n_prof
 
-    roof["traffic"] = _recorded_traffic(args.config, roof["kernel"])
+    # the counters were taken on the configuration's own cloud, dataflow and key width
+    own_workload = args.voxels <= 0 and dataflow == B.DATAFLOW_OS and args.hybrid_t is None and desc.key_bits == 32
+    roof["traffic"] = _recorded_traffic(args.config, roof["kernel"]) if own_workload else None
 
     result = {
         "metric": "SpC layer hot path (pack+sort, kmap build, feature computation) Mvoxel-offsets/s",
