@@ -350,6 +350,37 @@ def main() -> int:
     phase_ms = {p: float(np.mean([marks[i][j].elapsed_time(marks[i][j + 1]) for i in range(n_prof)]))
                 for j, p in enumerate(phases)}
 
+    # ---- each phase alone, 20 invocations back to back between two events (the launch of one hides under the
+    # kernels of the one before): the rate the phase sustains, beside the duration it has inside a step
+    def back_to_back(fn, reps=20, rounds=3):
+        best = float("inf")
+        for _ in range(rounds):
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b) / reps)
+        return best
+
+    def build_once():
+        if args.sym:
+            B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout).destroy()
+        else:
+            B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout, in_perm=perm).destroy()
+
+    B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+    km_b = (B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout) if args.sym
+            else B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout, in_perm=perm))
+    loop_ms = {
+        "pack_sort": back_to_back(lambda: B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)),
+        "kmap_build": back_to_back(build_once),
+        "conv": back_to_back(lambda: B.spc_conv_forward(km_b, F_sorted if args.sym else F_raw, Wp if use_packed else W, dataflow,
+                                                        conv_flags, out=out, hybrid_t=args.hybrid_t)),
+    }
+    km_b.destroy()
+
     voxel_offsets = n_out * K3
     flops = 2.0 * nnz * cin * cout
     value = voxel_offsets / (ms_per_step * 1e-3) / 1e6
@@ -407,7 +438,8 @@ def main() -> int:
                       ("OS" if dataflow == B.DATAFLOW_OS else "WS")),
                    "n_voxels": n, "n_out": n_out, "K": K, "cin": cin, "cout": cout, "nnz": nnz,
                    "key_bits": desc.key_bits},
-        "parts": {"phase_ms": phase_ms,
+        "parts": {"phase_ms": phase_ms, "phase_back_to_back_ms": loop_ms,
+                  "kmap_build_back_to_back_frac_of_hbm_peak": map_bytes / (loop_ms["kmap_build"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                   "kmap_build_Mvoxel_offsets_per_s": voxel_offsets / (phase_ms["kmap_build"] * 1e-3) / 1e6,
                   "kmap_build_algorithmic_GBps": kmap_gbs, "kmap_build_frac_of_hbm_peak": kmap_gbs / PEAK_HBM_GBS,
                   "conv_useful_TFLOPs": conv_tflops, "conv_frac_of_mfma_peak": conv_tflops / PEAK_MFMA_F16_TFLOPS,
