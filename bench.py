@@ -451,8 +451,8 @@ def main() -> int:
     # captured graph of the same step; replays go round-robin over the streams, so the latency-bound sort and
     # search kernels of one scene run next to the feature kernel of another.  Reported beside the headline, which
     # stays the one-scene-at-a-time number.
-    # (the step can be captured when the library's own sort runs: up to 2 Mi voxels, see include/spc.h)
-    capturable = n <= 2048 * 1024
+    # (the step can be captured when the library's own sort runs: up to 8 Mi voxels, see include/spc.h)
+    capturable = n <= 8192 * 1024
     if args.scene_streams > 1 and capturable and dataflow == B.DATAFLOW_OS and not args.sym and args.hybrid_t is None:
         class Scene:
             def __init__(self):

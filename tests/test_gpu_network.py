@@ -205,6 +205,66 @@ def test_capture_of_a_small_cloud_replays():
     km.destroy()
 
 
+def test_capture_above_the_eager_sort_crossover():
+    """Above 2 Mi keys an eager call sorts with the library sort; on a capturing stream the library's own sort is
+    taken instead (up to 8 Mi keys).  Pack + sort and a strided map (whose level is downsampled from 2.2 M voxels) are
+    recorded into a graph and replayed; every replay equals the eager result."""
+    n = 2_200_000
+    clouds = [synth.scaled_random_cloud(n), None]
+    rng = np.random.default_rng(synth.SEED_BASE + 710)
+    clouds[1] = clouds[0][rng.permutation(n)].copy()
+    clouds[1][:, 3] = np.where(clouds[1][:, 1] % 3 == 0, clouds[1][:, 3] ^ 1, clouds[1][:, 3])  # a different cloud of the same size
+    clouds[1] = np.unique(clouds[1], axis=0)
+    if len(clouds[1]) < n:  # top up with voxels outside the first cloud's z range
+        extra = clouds[0][: n - len(clouds[1])].copy()
+        extra[:, 3] += 400
+        clouds[1] = np.concatenate([clouds[1], extra])
+    lo = np.min([c[:, 1:].min(0) for c in clouds], axis=0)
+    hi = np.max([c[:, 1:].max(0) for c in clouds], axis=0)
+    desc = B.spc_pack_desc_fit(lo, hi, 1, 2, 1)
+    coords = torch.from_numpy(clouds[0]).cuda()
+    ws = torch.empty(B.spc_pack_workspace_bytes(n, desc), dtype=torch.uint8, device="cuda")
+    keys = torch.empty(n, dtype=torch.int32 if desc.key_bits == 32 else torch.int64, device="cuda")
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+
+    def eager(c):
+        k, p = B.spc_pack_coords(torch.from_numpy(c).cuda(), desc, True)
+        km = B.spc_build_kmap(k, desc, 2, 1, 2, 0, B.LAYOUT_OS)
+        t, ok = km.export_triples(B.LAYOUT_OS), km.out_keys()
+        km.destroy()
+        return k.clone(), p.clone(), t, ok
+
+    refs = [eager(c) for c in clouds]
+    cs, operm = oracle.sort_coords(clouds[0])
+    assert np.array_equal(refs[0][1].cpu().numpy(), operm)  # the eager reference itself against the oracle
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    # a first capture, thrown away, fills the block cache of the capturing stream with the sizes of the captured
+    # path (an eager call at this size takes the other sort and other scratch sizes)
+    warm = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(warm, stream=stream, capture_error_mode="relaxed"):
+        B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+        km = B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS)
+    km.destroy()
+    del warm
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream, capture_error_mode="relaxed"):
+        B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
+        km = B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS)
+    for rep, i in enumerate([0, 1, 0]):
+        coords.copy_(torch.from_numpy(clouds[i]).cuda())
+        keys.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(keys, refs[i][0]) and torch.equal(perm, refs[i][1]), rep
+        assert np.array_equal(km.out_keys(), refs[i][3]), rep
+        assert np.array_equal(km.export_triples(B.LAYOUT_OS), refs[i][2]), rep
+    km.destroy()
+    B.spc_release_cache()
+
+
 def test_network_build_searches_nine_maps():
     """Configuration 4 in its default (all output-stationary) setting: 25 layers, 13 distinct maps, 9 searches."""
     coords, cs, operm, layers, W, desc, keys, F0, Fs = _setup("lidar")
