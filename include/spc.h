@@ -285,12 +285,11 @@ void spc_kmap_destroy(spc_kmap* m);
  * stream), so a warmed-up call sequence can be captured into a HIP graph: spc_pack_coords
  * (without SPC_PACK_VALIDATE), spc_build_kmap(s_network), spc_conv_forward and
  * spc_permute_rows only enqueue kernels, event records and event waits — as long as every sort
- * is the library's own.  Outside capture that is the case up to 2 097 152 voxels (for strided layers:
- * of the level that is downsampled); above, the sort is rocPRIM's, which is faster there but also
- * enqueues memsets (replayed memset nodes are not reliable on the target systems, and a radix sort
- * that starts from stale counters writes out of bounds).  On a stream that is being captured the
- * library's own sort is taken up to 8 388 608 voxels instead, and beyond that spc_pack_coords and the
- * builders return SPC_ERR_UNSUPPORTED.  Maps built under
+ * is the library's own, i.e. the cloud (for strided layers: the level that is downsampled) has
+ * at most 8 388 608 voxels.  Above that the sort is rocPRIM's, which also
+ * enqueues memsets; under stream capture spc_pack_coords and the builders then return
+ * SPC_ERR_UNSUPPORTED instead of recording them (replayed memset nodes are not reliable on the
+ * target systems, and a radix sort that starts from stale counters writes out of bounds).  Maps built under
  * capture must stay alive as long as the graph; their accessors that wait (n_out, nnz,
  * export) drain the device and read the values of the latest replay.
  */

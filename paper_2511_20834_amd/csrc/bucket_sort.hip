@@ -147,7 +147,8 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
                                                              const int32_t* __restrict__ tot, KeyT* __restrict__ keys1,
                                                              int32_t* __restrict__ vals1, int2* __restrict__ win,
                                                              int32_t* __restrict__ n_part_keys, uint32_t* __restrict__ bits,
-                                                             int n_words, int32_t* __restrict__ ccnt, int n_chunks) {
+                                                             int n_words, int32_t* __restrict__ ccnt, int n_chunks,
+                                                             int32_t* __restrict__ rest_count) {
   extern __shared__ int lds_bins[];
   int* pos = lds_bins;                    // [n_bin + 1] this workgroup's running position in every bin
   int* bin_start = lds_bins + n_bin + 1;  // [n_bin + 1] where every bin starts
@@ -229,6 +230,7 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
   if (blockIdx.x == 0) {
     if (t < BS_PAD_KEYS) keys1[total + t] = ~KeyT(0);  // the rank kernels read whole steps
     if (t == 0 && n_part_keys) *n_part_keys = total;
+    if (t == 0) *rest_count = 0;  // windows left over by bs_rank_lds_kernel
   }
   const int part = blockIdx.x + t * gridDim.x;
   if (int64_t(part) * BS_PART < total) {
@@ -265,6 +267,9 @@ __global__ __launch_bounds__(BS_WIDE) void bs_scatter_kernel(const KeyT* __restr
 #ifndef BS_RANK_SOLO_N
 #define BS_RANK_SOLO_N 400000
 #endif
+#ifndef BS_RANK_LDS_N
+#define BS_RANK_LDS_N 600000  // keys from which the ranking splits its windows once more in LDS (bs_rank_lds_kernel)
+#endif
 constexpr int BS_RANK_STEP = BS_PAD_KEYS;  // positions; a window is a whole number of steps
 // 128 bytes of keys at a wave-uniform address in scalar registers.  The load is issued by hand and
 // its arrival awaited by hand, one compare step later: left to the compiler, the load of a step
@@ -272,8 +277,18 @@ constexpr int BS_RANK_STEP = BS_PAD_KEYS;  // positions; a window is a whole num
 typedef uint32_t bs_u32x16 __attribute__((ext_vector_type(16)));
 struct BsChunk {
   bs_u32x16 lo, hi;
+  // SCALAR: the caller's address is in scalar registers already (derived from blockIdx and kernel arguments);
+  // otherwise it is the same in every lane but arrives in vector registers (a part number read from a list)
+  template <bool SCALAR>
   __device__ void issue(const void* p) {
-    asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx16 %1, %2, 0x40" : "=&s"(lo), "=&s"(hi) : "s"(p) : "memory");
+    const void* q = p;
+    if constexpr (!SCALAR) {
+      const uint64_t a = reinterpret_cast<uint64_t>(p);
+      const uint32_t a_lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a));
+      const uint32_t a_hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
+      q = reinterpret_cast<const void*>((static_cast<uint64_t>(a_hi) << 32) | a_lo);
+    }
+    asm volatile("s_load_dwordx16 %0, %2, 0x0\n\ts_load_dwordx16 %1, %2, 0x40" : "=&s"(lo), "=&s"(hi) : "s"(q) : "memory");
   }
   // the counters are operands only to keep the compare step that runs under the load in front of the wait
   __device__ void arrive(int (&c)[4]) {
@@ -289,7 +304,7 @@ struct BsChunk {
 // keys k[a, b) that sort before (key, x): MODE 0 for positions below the workgroup's own 64 (equal
 // keys count), 2 for positions above (they do not), 1 for the own positions (full comparison).
 // a and b are multiples of BS_RANK_STEP.
-template <int MODE, typename KeyT>
+template <int MODE, bool SCALAR = true, typename KeyT>
 __device__ inline int bs_count_before(const KeyT* __restrict__ k, int a, int b, KeyT key, int x) {
   constexpr int C = 128 / sizeof(KeyT);  // keys per chunk
   static_assert(BS_RANK_STEP % C == 0, "a step of positions is a whole number of chunks");
@@ -307,14 +322,14 @@ __device__ inline int bs_count_before(const KeyT* __restrict__ k, int a, int b, 
     }
   };
   BsChunk A, B;
-  A.issue(k + a);
+  A.template issue<SCALAR>(k + a);
   A.arrive(c);
   for (int j = a; j < b; j += 2 * C) {  // the last chunk is fetched once more instead of running past b
-    B.issue(k + min(j + C, b - C));
+    B.template issue<SCALAR>(k + min(j + C, b - C));
     compare(A, j);
     B.arrive(c);
     if (j + C < b) {
-      A.issue(k + min(j + 2 * C, b - C));
+      A.template issue<SCALAR>(k + min(j + 2 * C, b - C));
       compare(B, j + C);
       A.arrive(c);
     }
@@ -322,18 +337,19 @@ __device__ inline int bs_count_before(const KeyT* __restrict__ k, int a, int b, 
   return (c[0] + c[1]) + (c[2] + c[3]);
 }
 
-template <typename KeyT, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void bs_rank_kernel(const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
-                                                             const int2* __restrict__ win, int n, KeyT* __restrict__ out_k,
-                                                             int32_t* __restrict__ out_v) {
+// (a device function of the part number: the kernel below ranks part blockIdx.x, bs_rank_rest_kernel the parts
+// of the windows that bs_rank_lds_kernel has left over)
+template <typename KeyT, int WAVES, bool LISTED = false>
+__device__ inline void bs_rank_part(int part, const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
+                                    const int2* __restrict__ win, int n, KeyT* __restrict__ out_k, int32_t* __restrict__ out_v) {
   static_assert(BS_PART == 64, "one key per lane");
   __shared__ int partial[WAVES][BS_PART];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
-  const int own0 = blockIdx.x * BS_PART;
+  const int own0 = part * BS_PART;
   const int x = own0 + lane;
   const bool act = x < n;
-  const int2 w = win[blockIdx.x];
+  const int2 w = win[part];
   const KeyT key = act ? keys1[x] : ~KeyT(0);
   const int32_t val = (act && out_v && wave == 0) ? vals1[x] : 0;
   const int n_pad = (n + BS_RANK_STEP - 1) & ~(BS_RANK_STEP - 1);  // positions n .. n_pad - 1 hold all-ones keys
@@ -349,11 +365,11 @@ __global__ __launch_bounds__(64 * WAVES) void bs_rank_kernel(const KeyT* __restr
   };
   int qa, qb;
   quarter(g0, own0, qa, qb);
-  int c = bs_count_before<0>(keys1, qa, qb, key, x);
+  int c = bs_count_before<0, !LISTED>(keys1, qa, qb, key, x);
   quarter(own0, own1, qa, qb);
-  c += bs_count_before<1>(keys1, qa, qb, key, x);
+  c += bs_count_before<1, !LISTED>(keys1, qa, qb, key, x);
   quarter(own1, g1, qa, qb);
-  c += bs_count_before<2>(keys1, qa, qb, key, x);
+  c += bs_count_before<2, !LISTED>(keys1, qa, qb, key, x);
   int r = g0 + c;
   if constexpr (WAVES > 1) {
     partial[wave][lane] = c;
@@ -368,6 +384,13 @@ __global__ __launch_bounds__(64 * WAVES) void bs_rank_kernel(const KeyT* __restr
   }
 }
 
+template <typename KeyT, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void bs_rank_kernel(const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
+                                                             const int2* __restrict__ win, int n, KeyT* __restrict__ out_k,
+                                                             int32_t* __restrict__ out_v) {
+  bs_rank_part<KeyT, WAVES>(blockIdx.x, keys1, vals1, win, n, out_k, out_v);
+}
+
 // ---------------------------------------------------------------- rank + compact (downsampling path)
 // The distinct masked keys in ascending order.  Ranking as above, on the key alone: equal keys get
 // equal positions, so position = window start + (number of window keys smaller than mine) leaves the
@@ -376,29 +399,26 @@ __global__ __launch_bounds__(64 * WAVES) void bs_rank_kernel(const KeyT* __restr
 // level).  A position is marked in a bitmap by whoever gets there first, and counted once in its
 // chunk of BS_CHUNK positions; bs_compact_kernel then closes the gaps.
 constexpr int BS_CHUNK = 1024;
-template <typename KeyT>
-__global__ __launch_bounds__(BS_THREADS) void bs_rank_unique_kernel(const KeyT* __restrict__ keys1, const int2* __restrict__ win,
-                                                                    const int32_t* __restrict__ n_kept,
-                                                                    KeyT* __restrict__ sorted, uint32_t* __restrict__ bits,
-                                                                    int32_t* __restrict__ ccnt) {
+template <typename KeyT, bool LISTED = false>
+__device__ inline void bs_rank_unique_part(int part, const KeyT* __restrict__ keys1, const int2* __restrict__ win, int n,
+                                           KeyT* __restrict__ sorted, uint32_t* __restrict__ bits, int32_t* __restrict__ ccnt) {
   constexpr int WAVES = BS_THREADS / 64;
   __shared__ int partial[WAVES][BS_PART];
   __shared__ uint32_t lbits[64];
-  const int n = *n_kept;  // the grid is sized for the level before the equal neighbours were dropped
-  const int own0 = blockIdx.x * BS_PART;
-  if (own0 >= n) return;
+  const int own0 = part * BS_PART;
+  if (own0 >= n) return;  // (the whole workgroup)
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
   const int x = own0 + lane;
   const bool act = x < n;
-  const int2 w = win[blockIdx.x];
+  const int2 w = win[part];
   const KeyT key = act ? keys1[x] : ~KeyT(0);
   const int n_pad = (n + BS_RANK_STEP - 1) & ~(BS_RANK_STEP - 1);  // positions n .. n_pad - 1 hold all-ones keys
   const int g0 = w.x & ~(BS_RANK_STEP - 1);
   const int g1 = min((w.y + BS_RANK_STEP - 1) & ~(BS_RANK_STEP - 1), n_pad);
   const int steps = (g1 - g0) / BS_RANK_STEP, per = (steps + WAVES - 1) / WAVES;
   const int qa = min(g0 + wave * per * BS_RANK_STEP, g1), qb = min(qa + per * BS_RANK_STEP, g1);
-  partial[wave][lane] = bs_count_before<2>(keys1, qa, qb, key, x);
+  partial[wave][lane] = bs_count_before<2, !LISTED>(keys1, qa, qb, key, x);
   __syncthreads();
   if (wave == 0) {
     int r = g0;
@@ -437,6 +457,15 @@ __global__ __launch_bounds__(BS_THREADS) void bs_rank_unique_kernel(const KeyT* 
       }
     }
   }
+}
+
+template <typename KeyT>
+__global__ __launch_bounds__(BS_THREADS) void bs_rank_unique_kernel(const KeyT* __restrict__ keys1, const int2* __restrict__ win,
+                                                                    const int32_t* __restrict__ n_kept,
+                                                                    KeyT* __restrict__ sorted, uint32_t* __restrict__ bits,
+                                                                    int32_t* __restrict__ ccnt) {
+  // (the grid is sized for the level before the equal neighbours were dropped)
+  bs_rank_unique_part<KeyT>(blockIdx.x, keys1, win, *n_kept, sorted, bits, ccnt);
 }
 
 // out = the marked positions of `sorted`, in order; their number to *n_out.  One workgroup per chunk
@@ -482,6 +511,205 @@ __global__ __launch_bounds__(BS_THREADS) void bs_compact_kernel(const KeyT* __re
   for (int j = 0; j < 4; ++j) {
     const int bit = 4 * sub + j;
     if ((word >> bit) & 1u) out[rank++] = sorted[b * BS_CHUNK + wi * 32 + bit];
+  }
+}
+
+// ---------------------------------------------------------------- rank in LDS (large inputs)
+// The ranking above compares every key with its whole window, which is quadratic in the bin size, and the bin
+// count is capped (an LDS histogram per workgroup in the count pass): from about half a million keys on that pass
+// sets the time of the sort.  Here a workgroup takes BS_LP scattered positions and the window of whole bins around
+// them (through the 64-position windows the scatter pass has written), and splits the window once more in LDS:
+//   * a thread owns eight consecutive window keys; a key's bin rank inside the window is a prefix sum of "the bin
+//     changes here" flags (the scattered array is ordered by bin), so the empty bins of a sparse key space cost
+//     nothing;
+//   * sub-bin = (bin rank, the next sb key bits below the bin bits), sb chosen per window so that all sub-bins fit
+//     the LDS histogram; histogram, exclusive scan, and the keys move, with their window index, to their sub-bin's
+//     slots (LDS atomics for the slot: the order inside a sub-bin does not matter);
+//   * a key's final position is window start + start of its sub-bin + the number of keys of the sub-bin that sort
+//     before it, in (key, window index) order for pack + sort and on the key alone for downsampling (equal keys
+//     then share a position; the one with the smallest window index marks the position and is counted for its chunk,
+//     which is the same on every workgroup that sees the bin, because all of a bin's keys lie in every window that
+//     touches it).
+// A window that does not fit (bins of thousands of keys: the floors and walls of dense indoor scenes) is left to
+// bs_rank_rest_kernel: the workgroup appends its number to a list, and the 64-position parts of the listed
+// workgroups are ranked by comparing against their own windows as above, spread over a fixed grid.
+constexpr int BS_LP = 2048;    // own positions per workgroup (a multiple of BS_PART)
+constexpr int BS_LW = 4096;    // window keys a workgroup holds
+constexpr int BS_LSUB = 4096;  // sub-bins
+constexpr int BS_LT = 512;     // threads: eight window keys each
+constexpr int BS_LK = BS_LW / BS_LT;
+static_assert(BS_LP % BS_PART == 0 && BS_LW >= BS_LP && BS_LK == 8, "window layout");
+
+template <typename KeyT, bool UNIQUE>
+__global__ __launch_bounds__(BS_LT) void bs_rank_lds_kernel(const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
+                                                            const int2* __restrict__ win, int n_h,
+                                                            const int32_t* __restrict__ n_d, int shift, int n_bin,
+                                                            KeyT* __restrict__ out_k, int32_t* __restrict__ out_v,
+                                                            uint32_t* __restrict__ bits, int32_t* __restrict__ ccnt,
+                                                            int32_t* __restrict__ rest_count, int32_t* __restrict__ rest) {
+  constexpr int WAVES = BS_LT / 64;
+  __shared__ KeyT skey[BS_LW];
+  __shared__ uint16_t sidx[BS_LW];
+  __shared__ int hist[BS_LSUB];
+  __shared__ KeyT s_last[BS_LT];
+  __shared__ int wave_tot[WAVES];
+  __shared__ uint32_t s_bits[BS_LW / 32 + 2];
+  __shared__ int s_cc[BS_LW / BS_CHUNK + 2];
+  const int n = n_d ? *n_d : n_h;
+  const int own0 = blockIdx.x * BS_LP;
+  if (own0 >= n) return;
+  const int own1 = min(own0 + BS_LP, n);
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int g0 = win[own0 / BS_PART].x, g1 = win[(own1 - 1) / BS_PART].y;
+  const int W = g1 - g0;
+  if (W > BS_LW) {  // the window does not fit: bs_rank_rest_kernel ranks these positions
+    if (t == 0) rest[atomicAdd(rest_count, 1)] = blockIdx.x;
+    return;
+  }
+  // ---- window keys, eight consecutive ones per thread
+  KeyT k[BS_LK];
+  const int j0 = t * BS_LK;
+#pragma unroll
+  for (int u = 0; u < BS_LK; ++u) k[u] = keys1[g0 + min(j0 + u, W - 1)];
+  for (int i = t; i < BS_LSUB; i += BS_LT) hist[i] = 0;
+  if (UNIQUE) {
+    for (int i = t; i < BS_LW / 32 + 2; i += BS_LT) s_bits[i] = 0u;
+    if (t < BS_LW / BS_CHUNK + 2) s_cc[t] = 0;
+  }
+  s_last[t] = k[BS_LK - 1];
+  __syncthreads();
+  // bin rank inside the window: inclusive prefix of the "bin changes" flags, minus one
+  int d[BS_LK], flags = 0;
+  {
+    int prev_bin = t > 0 ? bs_bin(s_last[t - 1], shift, n_bin) : -1;
+#pragma unroll
+    for (int u = 0; u < BS_LK; ++u) {
+      const int bin = bs_bin(k[u], shift, n_bin);
+      flags += (j0 + u < W && bin != prev_bin) ? 1 : 0;
+      d[u] = flags;
+      prev_bin = bin;
+    }
+  }
+  int x = flags;
+  for (int s = 1; s < 64; s <<= 1) {
+    const int y = __shfl_up(x, s, 64);
+    if (lane >= s) x += y;
+  }
+  if (lane == 63) wave_tot[wave] = x;
+  __syncthreads();
+  int base = x - flags, n_bins_here = 0;
+  for (int w = 0; w < WAVES; ++w) {
+    if (w < wave) base += wave_tot[w];
+    n_bins_here += wave_tot[w];
+  }
+  // sub-bin bits: as many as keep (bins in the window) << sb within the histogram, at most the key bits below the bins
+  int sb = 0;
+  while (sb < shift && sb < 12 && ((n_bins_here << (sb + 1)) <= BS_LSUB)) ++sb;
+  const KeyT sub_mask = (KeyT(1) << sb) - 1;
+  int id[BS_LK];
+#pragma unroll
+  for (int u = 0; u < BS_LK; ++u) {
+    id[u] = ((base + d[u] - 1) << sb) | static_cast<int>((k[u] >> (shift - sb)) & sub_mask);
+    if (j0 + u < W) atomicAdd(&hist[id[u]], 1);
+  }
+  __syncthreads();
+  // exclusive scan of the sub-bin counts, eight per thread (BS_LSUB = 8 * BS_LT)
+  static_assert(BS_LSUB == BS_LK * BS_LT, "eight sub-bins per thread");
+  {
+    int c[BS_LK], sum = 0;
+#pragma unroll
+    for (int u = 0; u < BS_LK; ++u) {
+      c[u] = hist[j0 + u];
+      sum += c[u];
+    }
+    int y = sum;
+    for (int s = 1; s < 64; s <<= 1) {
+      const int z = __shfl_up(y, s, 64);
+      if (lane >= s) y += z;
+    }
+    __syncthreads();  // everybody has read the counts and the wave totals of the flags
+    if (lane == 63) wave_tot[wave] = y;
+    __syncthreads();
+    int run = y - sum;
+    for (int w = 0; w < wave; ++w) run += wave_tot[w];
+#pragma unroll
+    for (int u = 0; u < BS_LK; ++u) {
+      hist[j0 + u] = run;  // becomes the sub-bin's cursor
+      run += c[u];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < BS_LK; ++u)
+    if (j0 + u < W) {
+      const int slot = atomicAdd(&hist[id[u]], 1);
+      skey[slot] = k[u];
+      sidx[slot] = static_cast<uint16_t>(j0 + u);
+    }
+  __syncthreads();
+  // after the moves hist[i] is the end of sub-bin i, i.e. the start of sub-bin i + 1
+  const int o0 = own0 - g0, o1 = own1 - g0;  // the own positions, as window indices
+#pragma unroll
+  for (int u = 0; u < BS_LK; ++u) {
+    const int j = j0 + u;
+    if (j < o0 || j >= o1) continue;
+    const int lo = id[u] > 0 ? hist[id[u] - 1] : 0, hi = hist[id[u]];
+    int c = lo;
+    bool first = true;  // UNIQUE: no equal key at a smaller window index
+    for (int s = lo; s < hi; ++s) {
+      const KeyT e = skey[s];
+      const int ej = sidx[s];
+      if constexpr (UNIQUE) {
+        c += e < k[u] ? 1 : 0;
+        first = first && !(e == k[u] && ej < j);
+      } else {
+        c += (e < k[u] || (e == k[u] && ej < j)) ? 1 : 0;
+      }
+    }
+    const int r = g0 + c;
+    out_k[r] = k[u];
+    if constexpr (!UNIQUE) {
+      if (out_v) out_v[r] = vals1[g0 + j];
+    } else if (first) {
+      const int rel = r - (g0 & ~31);
+      atomicOr(&s_bits[rel >> 5], 1u << (rel & 31));
+    }
+  }
+  if constexpr (UNIQUE) {
+    __syncthreads();
+    const int word0 = g0 >> 5, chunk0 = word0 / (BS_CHUNK / 32);
+    if (t < BS_LW / 32 + 2) {
+      const uint32_t word = s_bits[t];
+      if (word) {  // the marks of different workgroups in one word are different bits
+        atomicOr(&bits[word0 + t], word);
+        atomicAdd(&s_cc[(word0 + t) / (BS_CHUNK / 32) - chunk0], __popc(word));
+      }
+    }
+    __syncthreads();
+    if (t < BS_LW / BS_CHUNK + 2 && s_cc[t]) atomicAdd(&ccnt[chunk0 + t], s_cc[t]);
+  }
+}
+
+// The parts bs_rank_lds_kernel has listed (none for most clouds: the workgroups then read the count and leave).
+constexpr int BS_REST_WG = 2048;
+template <typename KeyT, bool UNIQUE>
+__global__ __launch_bounds__(BS_THREADS) void bs_rank_rest_kernel(const int32_t* __restrict__ rest_count,
+                                                                  const int32_t* __restrict__ rest,
+                                                                  const KeyT* __restrict__ keys1, const int32_t* __restrict__ vals1,
+                                                                  const int2* __restrict__ win, int n_h,
+                                                                  const int32_t* __restrict__ n_d, KeyT* __restrict__ out_k,
+                                                                  int32_t* __restrict__ out_v, uint32_t* __restrict__ bits,
+                                                                  int32_t* __restrict__ ccnt) {
+  constexpr int PER = BS_LP / BS_PART;  // 64-position parts per listed workgroup
+  const int n = n_d ? *n_d : n_h;
+  const int todo = *rest_count * PER;
+  for (int i = blockIdx.x; i < todo; i += gridDim.x) {
+    const int part = rest[i / PER] * PER + i % PER;
+    if (part * BS_PART >= n) continue;  // (uniform)
+    if constexpr (UNIQUE) bs_rank_unique_part<KeyT, true>(part, keys1, win, n, out_k, bits, ccnt);
+    else bs_rank_part<KeyT, BS_THREADS / 64, true>(part, keys1, vals1, win, n, out_k, out_v);
+    __syncthreads();  // the part functions' LDS is reused by the next part
   }
 }
 
@@ -657,6 +885,8 @@ struct Ws {
   int32_t* n_kept;
   int32_t* ccnt;
   uint32_t* bits;
+  int32_t* rest_count;  // workgroups of bs_rank_lds_kernel whose window did not fit, and their numbers
+  int32_t* rest;
   int n_words, n_chunks;
 };
 size_t words_for(int64_t n) { return static_cast<size_t>(n / 32 + 64); }    // bitmap words the downsampling path clears and reads
@@ -681,6 +911,8 @@ Ws<KeyT> carve(void* ws, int64_t n) {
   w.n_chunks = static_cast<int>(chunks_for(n));
   w.bits = reinterpret_cast<uint32_t*>(w.ccnt + w.n_chunks);
   w.n_words = static_cast<int>(words_for(n));
+  w.rest_count = w.n_kept + 1;
+  w.rest = reinterpret_cast<int32_t*>(w.bits + w.n_words);
   return w;
 }
 
@@ -698,7 +930,7 @@ void partition(const Src& src, int64_t n, const BucketPlan& p, const Ws<KeyT>& w
   hipLaunchKernelGGL((bs_scatter_kernel<KeyT, DEDUP>), dim3(p.n_wg), dim3(BS_WIDE), size_t(2 * p.n_bin + 2) * 4, s, w.keys0, n, p.per,
                      p.shift, p.n_bin, w.before,
                      w.fstart, w.keys1, w.vals1, w.win, DEDUP ? w.n_kept : static_cast<int32_t*>(nullptr), w.bits, w.n_words, w.ccnt,
-                     w.n_chunks);
+                     w.n_chunks, w.rest_count);
 }
 }  // namespace
 
@@ -707,7 +939,7 @@ size_t bucket_sort_ws_bytes(int key_bits, int64_t n) {
   const size_t k = ((nn + BS_PAD_KEYS) * (key_bits / 8) + 255) / 256 * 256, v = (nn * 4 + 255) / 256 * 256;
   const BucketPlan cap = bucket_plan(n, 64);
   const size_t tbl = (size_t(cap.n_wg) * cap.n_bin + 63) / 64 * 64;
-  return 2 * k + v + (2 * tbl + cap.n_bin + 64 + 2 * (nn / BS_PART + 2) + 2 + chunks_for(n) + words_for(n)) * 4;
+  return 2 * k + v + (2 * tbl + cap.n_bin + 64 + 2 * (nn / BS_PART + 2) + 2 + chunks_for(n) + words_for(n) + (nn / BS_LP + 2)) * 4;
 }
 
 template <typename KeyT>
@@ -722,7 +954,15 @@ static int pack_sort_t(const int4* coords, int64_t n, const PackParams& pp, int 
   // a CU has in flight, and one wave per part (no LDS, no barrier, four times the parts per CU) is
   // faster: 10^6 keys 32 -> 26 us, 2 * 10^6 keys 145 -> 129 us for the whole sort; at 240 k keys of
   // dense indoor scenes it was slower (37 -> 47 us).
-  if (n >= BS_RANK_SOLO_N)
+  if (n >= BS_RANK_LDS_N) {
+    hipLaunchKernelGGL((bs_rank_lds_kernel<KeyT, false>), dim3(static_cast<int>((n + BS_LP - 1) / BS_LP)), dim3(BS_LT), 0, s, w.keys1,
+                       w.vals1, w.win, static_cast<int>(n), static_cast<const int32_t*>(nullptr), p.shift, p.n_bin,
+                       static_cast<KeyT*>(keys_out), perm_out, static_cast<uint32_t*>(nullptr), static_cast<int32_t*>(nullptr),
+                       w.rest_count, w.rest);
+    hipLaunchKernelGGL((bs_rank_rest_kernel<KeyT, false>), dim3(BS_REST_WG), dim3(BS_THREADS), 0, s, w.rest_count, w.rest, w.keys1,
+                       w.vals1, w.win, static_cast<int>(n), static_cast<const int32_t*>(nullptr), static_cast<KeyT*>(keys_out),
+                       perm_out, static_cast<uint32_t*>(nullptr), static_cast<int32_t*>(nullptr));
+  } else if (n >= BS_RANK_SOLO_N)
     hipLaunchKernelGGL((bs_rank_kernel<KeyT, 1>), dim3(n_part), dim3(64), 0, s, w.keys1, w.vals1, w.win, static_cast<int>(n),
                        static_cast<KeyT*>(keys_out), perm_out);
   else
@@ -746,8 +986,16 @@ static int mask_unique_t(const void* keys_in, int64_t n, uint64_t mask, int used
   partition<KeyT, true>(SrcMask<KeyT>{static_cast<const KeyT*>(keys_in), static_cast<KeyT>(mask)}, n, p, w, s);
   // the sorted keys (with gaps) go to keys0, which is free again by now
   const int n_part = static_cast<int>((n + BS_PART - 1) / BS_PART), n_chunk = static_cast<int>((n + BS_CHUNK - 1) / BS_CHUNK);
-  hipLaunchKernelGGL(bs_rank_unique_kernel<KeyT>, dim3(n_part), dim3(BS_THREADS), 0, s, w.keys1, w.win, w.n_kept, w.keys0, w.bits,
-                     w.ccnt);
+  if (n >= BS_RANK_LDS_N) {
+    hipLaunchKernelGGL((bs_rank_lds_kernel<KeyT, true>), dim3(static_cast<int>((n + BS_LP - 1) / BS_LP)), dim3(BS_LT), 0, s, w.keys1,
+                       static_cast<const int32_t*>(nullptr), w.win, static_cast<int>(n), w.n_kept, p.shift, p.n_bin, w.keys0,
+                       static_cast<int32_t*>(nullptr), w.bits, w.ccnt, w.rest_count, w.rest);
+    hipLaunchKernelGGL((bs_rank_rest_kernel<KeyT, true>), dim3(BS_REST_WG), dim3(BS_THREADS), 0, s, w.rest_count, w.rest, w.keys1,
+                       static_cast<const int32_t*>(nullptr), w.win, static_cast<int>(n), w.n_kept, w.keys0,
+                       static_cast<int32_t*>(nullptr), w.bits, w.ccnt);
+  } else
+    hipLaunchKernelGGL(bs_rank_unique_kernel<KeyT>, dim3(n_part), dim3(BS_THREADS), 0, s, w.keys1, w.win, w.n_kept, w.keys0, w.bits,
+                       w.ccnt);
   hipLaunchKernelGGL(bs_compact_kernel<KeyT>, dim3(n_chunk), dim3(BS_THREADS), 0, s, w.keys0, w.bits, w.ccnt, w.n_kept,
                      static_cast<KeyT*>(keys_out), n_out);
   if (hipGetLastError() != hipSuccess) return set_error(SPC_ERR_HIP, "downsample launch failed");

@@ -18,7 +18,7 @@ static int refuse_if_capturing(hipStream_t s, int64_t n) {
   return set_error(SPC_ERR_UNSUPPORTED,
                    "%lld keys are sorted by the library sort, which cannot be recorded into a graph; "
                    "capture is supported up to %lld keys",
-                   static_cast<long long>(n), static_cast<long long>(BS_CAPTURE_MAX_N));
+                   static_cast<long long>(n), static_cast<long long>(BS_MAX_N));
 }
 
 template <typename KeyT>
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(UQ_THREADS) void unique_write_kernel(const KeyT* __
 
 template <typename KeyT>
 static int downsample_t(const void* src, int64_t n, const PackInfo& pi, int m, Level* lv, hipStream_t s) {
-  if (use_bucket_sort(n, stream_is_capturing(s))) {
+  if (use_bucket_sort(n)) {
     char* scratch = static_cast<char*>(pool_alloc(bucket_sort_ws_bytes(pi.key_bits, n), s));
     if (!scratch) return SPC_ERR_NOMEM;
     const int rc = bucket_mask_unique(pi.key_bits, src, n, level_mask(pi, m), pi.used_bits, lv->keys, lv->n_dev, scratch, s);
@@ -303,11 +303,9 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   const size_t off_iota = (nn * ksz + 255) / 256 * 256;
   const size_t off_status = off_iota + (nn * 4 + 255) / 256 * 256;
   const size_t off_temp = off_status + 256;
-  // sizes that take the own sort only under stream capture need room for either sort (the query does not know yet)
-  const bool own_always = use_bucket_sort(n, false), own_captured = use_bucket_sort(n, true);
-  const size_t tb_own = own_captured ? bucket_sort_ws_bytes(pi.key_bits, nn) : 0;
-  const size_t tb_lib = own_always ? 0 : std::max(sort_pairs_temp_bytes(pi.key_bits, nn), sort_keys_temp_bytes(pi.key_bits, nn));
-  const size_t tb = std::max(tb_own, tb_lib);
+  const bool bucket = use_bucket_sort(n);
+  const size_t tb = bucket ? bucket_sort_ws_bytes(pi.key_bits, nn)
+                           : std::max(sort_pairs_temp_bytes(pi.key_bits, nn), sort_keys_temp_bytes(pi.key_bits, nn));
   const size_t need = off_temp + tb + 256;
   if (!workspace) {
     *workspace_bytes = need;
@@ -317,7 +315,6 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
   if (!coords || !keys_out) return set_error(SPC_ERR_ARG, "NULL coords or keys_out");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool small = n > 0 && n < BS_MIN_N;
-  const bool bucket = use_bucket_sort(n, stream_is_capturing(s));
   if (!bucket && !small && n > 0) SPC_RETURN_IF(refuse_if_capturing(s, n));
   char* ws = static_cast<char*>(workspace);
   void* keys_tmp = ws;
@@ -355,8 +352,8 @@ extern "C" int spc_pack_coords(const int32_t* coords, int64_t n, const spc_pack_
                          static_cast<uint64_t*>(keys_tmp), perm_out ? iota : nullptr, status);
     // all-ones keys of rejected rows must keep their place at the end: sort every key bit then
     const int end_bit = (flags & SPC_PACK_VALIDATE) ? pi.key_bits : pi.used_bits;
-    if (perm_out) SPC_RETURN_IF(sort_pairs(pi.key_bits, keys_tmp, keys_out, iota, perm_out, n, end_bit, ws + off_temp, tb_lib, s));
-    else SPC_RETURN_IF(sort_keys(pi.key_bits, keys_tmp, keys_out, n, end_bit, ws + off_temp, tb_lib, s));
+    if (perm_out) SPC_RETURN_IF(sort_pairs(pi.key_bits, keys_tmp, keys_out, iota, perm_out, n, end_bit, ws + off_temp, tb, s));
+    else SPC_RETURN_IF(sort_keys(pi.key_bits, keys_tmp, keys_out, n, end_bit, ws + off_temp, tb, s));
     if (flags & SPC_PACK_VALIDATE) {
       if (pi.key_bits == 32)
         hipLaunchKernelGGL(dup_check_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint32_t*>(keys_out), n, status);

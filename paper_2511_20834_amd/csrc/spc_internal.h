@@ -140,15 +140,11 @@ __device__ inline KeyT pack_key(const int4 c, const PackParams& p, int32_t* stat
 constexpr int BS_MAX_WG = 128;      // workgroups of the count / scatter passes
 constexpr int BS_MAX_BIN_BITS = 14;
 constexpr int BS_MAX_BIN = 1 << BS_MAX_BIN_BITS;  // fine bins (top used key bits)
-constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 2048 * 1024;  // sizes of the partitioning sort; below: one workgroup in LDS; above: rocPRIM
-// While a stream is being captured the partitioning sort also takes larger inputs, up to this many keys: the
-// library sort cannot be recorded into a graph, and with at most 16384 bins the rank pass of the own sort grows with
-// the bin size (3 * 10^6 keys: pack + sort 245 us against 177 us, 5 * 10^6: 384 against 286), which is why it is
-// not taken there otherwise.
-constexpr int64_t BS_CAPTURE_MAX_N = 8192 * 1024;
-inline bool use_bucket_sort(int64_t n, bool capturing) {
-  return n >= BS_MIN_N && (n <= BS_MAX_N || (capturing && n <= BS_CAPTURE_MAX_N));
-}
+// Sizes of the partitioning sort; below: one workgroup in LDS; above: rocPRIM (with 16384 bins at most, the windows of
+// the rank pass outgrow its LDS beyond that).  3 * 10^6 keys: pack + sort 150 us against 177 us with rocPRIM,
+// 5 * 10^6: 234 against 286.
+constexpr int64_t BS_MIN_N = 4096, BS_MAX_N = 8192 * 1024;
+inline bool use_bucket_sort(int64_t n) { return n >= BS_MIN_N && n <= BS_MAX_N; }
 constexpr int BS_PART = 64;         // keys per rank workgroup
 constexpr int BS_PAD_KEYS = 32;     // all-ones keys kept behind the scattered keys
 struct BucketPlan {

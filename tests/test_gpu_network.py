@@ -205,10 +205,10 @@ def test_capture_of_a_small_cloud_replays():
     km.destroy()
 
 
-def test_capture_above_the_eager_sort_crossover():
-    """Above 2 Mi keys an eager call sorts with the library sort; on a capturing stream the library's own sort is
-    taken instead (up to 8 Mi keys).  Pack + sort and a strided map (whose level is downsampled from 2.2 M voxels) are
-    recorded into a graph and replayed; every replay equals the eager result."""
+def test_capture_of_a_large_cloud_replays():
+    """The library's own sort runs up to 8 Mi keys (from 600 k on with the ranking that splits its windows in LDS), so
+    steps of that size can be recorded: pack + sort and a strided map (whose level is downsampled from 2.2 M voxels) go
+    into a graph and are replayed; every replay equals the eager result."""
     n = 2_200_000
     clouds = [synth.scaled_random_cloud(n), None]
     rng = np.random.default_rng(synth.SEED_BASE + 710)
@@ -239,14 +239,9 @@ def test_capture_above_the_eager_sort_crossover():
     assert np.array_equal(refs[0][1].cpu().numpy(), operm)  # the eager reference itself against the oracle
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
-    # a first capture, thrown away, fills the block cache of the capturing stream with the sizes of the captured
-    # path (an eager call at this size takes the other sort and other scratch sizes)
-    warm = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(warm, stream=stream, capture_error_mode="relaxed"):
+    with torch.cuda.stream(stream):  # warm the block cache on the capturing stream
         B.spc_pack_coords(coords, desc, True, 0, None, ws, keys, perm)
-        km = B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS)
-    km.destroy()
-    del warm
+        B.spc_build_kmap(keys, desc, 2, 1, 2, 0, B.LAYOUT_OS).destroy()
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=stream, capture_error_mode="relaxed"):

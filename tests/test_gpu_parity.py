@@ -553,6 +553,24 @@ def test_large_random_scene_levels():
     B.spc_release_cache()
 
 
+def test_beyond_the_own_sort():
+    """Above 8 Mi keys pack + sort and the downsampling fall back on the library sort (eager calls only): keys,
+    permutation and the stride-2 level against the oracle at 8.5 million voxels."""
+    n = 8_500_000
+    c = synth.scaled_random_cloud(n)
+    desc = fit_desc(c, [(2, 2, 2)])
+    keys, perm = gpu_pack(c, desc)
+    cs, operm = oracle.sort_coords(c)
+    assert np.array_equal(perm.cpu().numpy(), operm)
+    assert np.array_equal(keys_to_u64(keys), oracle_keys(cs, desc))
+    m = B.spc_build_kmaps_network(keys, desc, [(2, 1, 2, 0, B.LAYOUT_OS)])[0]
+    ref = oracle_keys(oracle.downsample(cs, 2), desc)
+    assert m.n_out == len(ref)
+    assert np.array_equal(m.out_keys(), ref)
+    m.destroy()
+    B.spc_release_cache()
+
+
 def test_destroy_and_rebuild_while_another_stream_still_reads_the_map():
     """spc_kmap_destroy hands the map's arrays back to the build stream's block cache without waiting.  A
     feature layer enqueued on another stream must still see its map when the next build on the build
