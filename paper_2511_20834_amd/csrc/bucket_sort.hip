@@ -1,6 +1,7 @@
-// Sort of packed voxel keys for the cloud sizes of this workload (thousands to about two
-// million keys): one most-significant-digit split into fine bins, then every key is ranked by
-// counting inside the window of bins around it.  Short launches, no look-back spinning:
+// Sort of packed voxel keys for the cloud sizes of this workload (thousands to a few million
+// keys): one most-significant-digit split into fine bins, then every key is ranked by
+// counting inside the window of bins around it (from 600 k keys on after a second split of the
+// window in LDS, see bs_rank_lds_kernel).  Short launches, no look-back spinning:
 //
 //   count    each workgroup produces its share of the keys (packing coordinates, Section 5.3,
 //            or masking the keys of a finer level, Section 5.5), histograms the top `fb` used
