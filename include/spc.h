@@ -311,6 +311,27 @@ int spc_conv_forward_hybrid(spc_kmap* m, const void* feats_in, int64_t ld_in, co
                             void* stream);
 
 /*
+ * One-time tuning of the hybrid threshold of one layer (Section 5.4: the threshold is chosen per layer by timing
+ * it once on sample data).  Runs the layer's feature computation for every threshold t = 0 (all offsets
+ * weight-stationary) .. L1max + 1 (all output-stationary), one untimed call and `reps` (1..1000) timed ones each,
+ * between two events on `stream`, and waits for them: not capturable.
+ *   m              map holding both full layouts (SPC_LAYOUT_BOTH without a hybrid threshold of its own).
+ *   weights        [device] plain [K^3][cin][cout]; packed_weights [device] the same weights from
+ *                  spc_conv_prepare_weights, or NULL: used for the thresholds and shapes that take them.
+ *   flags          SPC_CONV_RELU and the OS kernel choice only.
+ *   ws_build_us    what the weight-stationary lists add to the build of this map (measured by the caller, may be
+ *                  0): added to every threshold that has a weight-stationary part.
+ *   us_per_t       [host] `cap` floats; receives microseconds per call for t = 0 .. *n_t - 1.  *n_t is set even
+ *                  when cap is too small (SPC_ERR_ARG), so a caller can size the array from a first call.
+ *   best_t         [host] the fastest threshold.  On return feats_out holds the layer's output computed with it.
+ * Feature and output arguments as spc_conv_forward.
+ */
+int spc_conv_tune_threshold(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights,
+                            const void* packed_weights, void* feats_out, int64_t ld_out, int32_t cin, int32_t cout,
+                            int32_t dtype, int32_t flags, int32_t reps, float ws_build_us, float* us_per_t, int32_t cap,
+                            int32_t* n_t, int32_t* best_t, void* stream);
+
+/*
  * Weights are constant during inference, so their re-layout into MFMA operand order can
  * be hoisted out of the layer call.  Writes K^3*cin*cout elements to packed_out [device]
  * (same dtype) for use with SPC_CONV_PACKED_WEIGHTS.  Returns SPC_ERR_UNSUPPORTED for the

@@ -41,7 +41,7 @@ EXPORTS = [
     "spc_pack_desc_fit", "spc_pack_coords", "spc_pack_coords_noalloc", "spc_build_kmap", "spc_build_kmap_perm", "spc_build_kmaps_network", "spc_kmap_n_in",
     "spc_kmap_n_out", "spc_kmap_kvol", "spc_kmap_copy_out_keys", "spc_kmap_out_keys", "spc_kmap_in_keys", "spc_kmap_os_map",
     "spc_kmap_ws_lists", "spc_kmap_nnz", "spc_kmap_search_info", "spc_search_count", "spc_kmap_export_triples", "spc_kmap_set_size_hint", "spc_kmap_destroy",
-    "spc_conv_forward", "spc_conv_forward_hybrid",
+    "spc_conv_forward", "spc_conv_forward_hybrid", "spc_conv_tune_threshold",
     "spc_conv_prepare_weights", "spc_permute_rows",
     "spc_probe_copy", "spc_probe_mfma",
     "spc_release_cache", "spc_last_error", "spc_version",
@@ -107,6 +107,8 @@ def lib():
         L.spc_conv_forward.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         L.spc_conv_forward_hybrid.argtypes = [vp, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, vp]
         L.spc_conv_prepare_weights.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+        L.spc_conv_tune_threshold.argtypes = [vp, vp, i64, vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_float,
+                                              ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
         L.spc_permute_rows.argtypes = [vp, i64, vp, i64, i64, vp, i64, vp]
         L.spc_probe_copy.argtypes = [vp, vp, i64, vp]
         L.spc_probe_mfma.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
@@ -317,6 +319,30 @@ def spc_conv_forward(kmap: KMap, feats_in: torch.Tensor, weights: torch.Tensor, 
     _check(lib().spc_conv_forward(kmap.handle, feats_in.data_ptr(), feats_in.stride(0), weights.data_ptr(), out.data_ptr(),
                                   out.stride(0), cin, cout, _TORCH_DTYPE[feats_in.dtype], dataflow, flags, _stream(stream)))
     return out
+
+
+def spc_conv_tune_threshold(kmap: KMap, feats_in: torch.Tensor, weights: torch.Tensor, packed: torch.Tensor | None = None,
+                            flags: int = 0, reps: int = 5, ws_build_us: float = 0.0, out: torch.Tensor | None = None,
+                            stream=None):
+    """One-time tuning of a layer's hybrid threshold (spc_conv_tune_threshold).  Returns (best t, [microseconds for
+    t = 0 .. L1max + 1], output computed with the best t)."""
+    assert feats_in.is_cuda and weights.is_cuda and weights.is_contiguous() and weights.dim() == 3
+    assert feats_in.dim() == 2 and feats_in.stride(1) == 1 and feats_in.dtype == weights.dtype and feats_in.dtype in _TORCH_DTYPE
+    cin, cout = weights.shape[1], weights.shape[2]
+    assert feats_in.shape[1] == cin and weights.shape[0] == kmap.kvol
+    assert packed is None or (packed.is_cuda and packed.is_contiguous() and packed.dtype == weights.dtype
+                              and packed.numel() == weights.numel())
+    if out is None:
+        out = torch.empty((kmap.n_out, cout), dtype=feats_in.dtype, device=feats_in.device)
+    assert out.dim() == 2 and out.stride(1) == 1 and out.shape[1] == cout and out.dtype == feats_in.dtype
+    cap = 64
+    us = (ctypes.c_float * cap)()
+    n_t, best = ctypes.c_int32(0), ctypes.c_int32(-1)
+    _check(lib().spc_conv_tune_threshold(kmap.handle, feats_in.data_ptr(), feats_in.stride(0), weights.data_ptr(),
+                                         packed.data_ptr() if packed is not None else None, out.data_ptr(), out.stride(0), cin,
+                                         cout, _TORCH_DTYPE[feats_in.dtype], flags, int(reps), float(ws_build_us), us, cap,
+                                         ctypes.byref(n_t), ctypes.byref(best), _stream(stream)))
+    return int(best.value), [float(us[i]) for i in range(n_t.value)], out
 
 
 def spc_conv_prepare_weights(weights: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:

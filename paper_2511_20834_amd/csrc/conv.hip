@@ -1159,6 +1159,61 @@ extern "C" int spc_conv_forward_hybrid(spc_kmap* m, const void* feats_in, int64_
   return spc::conv_entry(m, feats_in, ld_in, weights, feats_out, ld_out, cin, cout, dtype, t, flags, stream);
 }
 
+extern "C" int spc_conv_tune_threshold(spc_kmap* m, const void* feats_in, int64_t ld_in, const void* weights,
+                                       const void* packed_weights, void* feats_out, int64_t ld_out, int32_t cin, int32_t cout,
+                                       int32_t dtype, int32_t flags, int32_t reps, float ws_build_us, float* us_per_t,
+                                       int32_t cap, int32_t* n_t, int32_t* best_t, void* stream) {
+  using namespace spc;
+  if (!m || !us_per_t || !n_t || !best_t || !weights) return set_error(SPC_ERR_ARG, "NULL argument");
+  if (reps < 1 || reps > 1000) return set_error(SPC_ERR_ARG, "reps must be in 1..1000");
+  if (flags & SPC_CONV_PACKED_WEIGHTS) return set_error(SPC_ERR_ARG, "pass prepacked weights as packed_weights, not by flag");
+  if ((m->desc.layout & SPC_LAYOUT_BOTH) != SPC_LAYOUT_BOTH || m->hybrid_t)
+    return set_error(SPC_ERR_ARG, "tuning needs a map that holds both layouts for every offset");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  SPC_HIP_CHECK(hipStreamIsCapturing(s, &cs));
+  if (cs != hipStreamCaptureStatusNone) return set_error(SPC_ERR_UNSUPPORTED, "tuning waits for the device: not under stream capture");
+  int l1_max = 0;
+  for (int k = 0; k < m->K3; ++k) l1_max = std::max(l1_max, offset_l1(m->desc.K, k));
+  const int count = l1_max + 2;  // t = 0 (all offsets weight-stationary) .. l1_max + 1 (all output-stationary)
+  *n_t = count;
+  if (cap < count) return set_error(SPC_ERR_ARG, "us_per_t holds %d entries, the layer has %d thresholds", cap, count);
+  const bool mfma_shape = dtype != SPC_DTYPE_F32 && cin % 16 == 0 && cout % 32 == 0;
+  const bool ws_takes_packed = cout == 32 || cout == 64 || cout == 128 || cout == 256;
+  auto run = [&](int t) {
+    const bool ws_part = t <= l1_max;
+    const bool packed = packed_weights && mfma_shape && (!ws_part || ws_takes_packed);
+    return conv_entry(m, feats_in, ld_in, packed ? packed_weights : weights, feats_out, ld_out, cin, cout, dtype, t,
+                      flags | (packed ? SPC_CONV_PACKED_WEIGHTS : 0), stream);
+  };
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  SPC_HIP_CHECK(hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) {
+    hipEventDestroy(e0);
+    return set_error(SPC_ERR_HIP, "hipEventCreate failed");
+  }
+  int rc = SPC_OK, best = 0;
+  for (int t = 0; t < count && rc == SPC_OK; ++t) {
+    rc = run(t);  // untimed: fills the block cache for this shape
+    if (rc == SPC_OK && hipEventRecord(e0, s) != hipSuccess) rc = set_error(SPC_ERR_HIP, "hipEventRecord failed");
+    for (int r = 0; r < reps && rc == SPC_OK; ++r) rc = run(t);
+    if (rc != SPC_OK) break;
+    float ms = 0.f;
+    if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+      rc = set_error(SPC_ERR_HIP, "timing a threshold failed");
+      break;
+    }
+    us_per_t[t] = ms * 1e3f / float(reps) + (t <= l1_max ? ws_build_us : 0.f);
+    if (us_per_t[t] < us_per_t[best]) best = t;
+  }
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (rc != SPC_OK) return rc;
+  *best_t = best;
+  return run(best);  // feats_out holds the layer's output under the chosen threshold
+}
+
 extern "C" int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32_t cin, int32_t cout, int32_t dtype,
                                         void* packed_out, void* stream) {
   using namespace spc;

@@ -112,8 +112,9 @@ class SpcNetwork:
     def tune(self, v0_keys, desc, feats, reps=5):
         """One-time tuning of the hybrid dual dataflow (Section 5.4): on the sample cloud given, every
         layer's feature computation is timed for every threshold t = 0 (pure weight-stationary) ..
-        L1max + 1 (pure output-stationary), the extra kernel-map build time of the layouts a threshold
-        needs is added, and the fastest threshold is kept.  Returns one row per layer:
+        L1max + 1 (pure output-stationary) by the library (spc_conv_tune_threshold), with the extra
+        kernel-map build time of the layouts a threshold needs added, and the fastest threshold is
+        kept.  Returns one row per layer:
         (name, best t, {t: microseconds}).  Afterwards build_maps / forward use the chosen settings."""
         n = len(self.layers)
         ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -153,16 +154,9 @@ class SpcNetwork:
             wp = B.spc_conv_prepare_weights(w) if (w.dtype != torch.float32 and w.shape[1] % 16 == 0 and cout % 32 == 0) else None
             out = torch.empty((maps[j].n_out, cout), dtype=x.dtype, device=x.device)
             l1_max = 3 if l["K"] == 2 else 3 * (l["K"] - 1) // 2
-            times = {}
-            for t in range(0, l1_max + 2):
-                ws_part = t <= l1_max
-                use_packed = wp is not None and (not ws_part or cout in (32, 64, 128, 256))
-                flags = (B.CONV_RELU if l["relu"] else 0) | (B.CONV_PACKED_WEIGHTS if use_packed else 0)
-                ww = wp if use_packed else w
-                times[t] = timed(lambda: B.spc_conv_forward(maps[j], x, ww, flags=flags, out=out, hybrid_t=t))
-                if ws_part:
-                    times[t] += build_cost[geo]
-            best = min(times, key=times.get)
+            best, us, _ = B.spc_conv_tune_threshold(maps[j], x, w, wp, flags=B.CONV_RELU if l["relu"] else 0, reps=reps,
+                                                    ws_build_us=build_cost[geo], out=out)
+            times = dict(enumerate(us))
             rows.append((l["name"], best, times))
             if best == l1_max + 1:
                 self.dataflow[j], self.hybrid_t[j] = B.DATAFLOW_OS, None

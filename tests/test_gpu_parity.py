@@ -375,6 +375,49 @@ def test_conv_hybrid_dataflow_every_threshold(K, dtype, cin, cout):
     km.destroy()
 
 
+@pytest.mark.parametrize("name,K,s_l,dtype,cin,cout", [("rand_b3", 3, 1, torch.float16, 32, 64), ("tiny_neg", 2, 2, torch.bfloat16, 16, 32),
+                                                        ("tiny", 5, 1, torch.float32, 5, 7)])
+def test_threshold_tuning_entry_point(name, K, s_l, dtype, cin, cout):
+    """spc_conv_tune_threshold (Section 5.4, one-time tuning): one time per threshold, the fastest is reported
+    and the output left behind is Eq. (2) computed with it."""
+    import ctypes
+    c = _cloud(name)
+    desc = fit_desc(c, [(K, 1, s_l)])
+    keys, _ = gpu_pack(c, desc)
+    cs, _ = oracle.sort_coords(c)
+    ci, co, M = oracle_layer(cs, K, 1, s_l, 0)
+    np_dt = np.float32 if dtype == torch.float32 else np.float16
+    Ft, F64 = to_torch(synth.features(len(ci), cin, np_dt, seed=91), dtype)
+    Wt, W64 = to_torch(synth.weights(K ** 3, cin, cout, np_dt, seed=92), dtype)
+    ref = oracle.conv(M, F64, W64)
+    km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_BOTH)
+    l1_max = 3 if K == 2 else 3 * (K - 1) // 2
+    packed = B.spc_conv_prepare_weights(Wt) if dtype != torch.float32 else None
+    for pk in (None, packed):
+        best, us, y = B.spc_conv_tune_threshold(km, Ft, Wt, pk, reps=2, ws_build_us=0.5)
+        assert len(us) == l1_max + 2 and all(u > 0 for u in us)
+        assert 0 <= best <= l1_max + 1 and us[best] == min(us)
+        assert_close(y.cpu().to(torch.float64).numpy(), ref, TOL[dtype], (name, best))
+    # the array is too short: the count still comes back
+    n_t, b = ctypes.c_int32(0), ctypes.c_int32(0)
+    us1 = (ctypes.c_float * 1)()
+    out = torch.empty((km.n_out, cout), dtype=dtype, device="cuda")
+    rc = B.lib().spc_conv_tune_threshold(km.handle, Ft.data_ptr(), Ft.stride(0), Wt.data_ptr(), None, out.data_ptr(), out.stride(0),
+                                         cin, cout, B._TORCH_DTYPE[dtype], 0, 2, 0.0, us1, 1, ctypes.byref(n_t), ctypes.byref(b), None)
+    assert rc == B.ERR_ARG and n_t.value == l1_max + 2
+    with pytest.raises(B.SpcError):
+        B.spc_conv_tune_threshold(km, Ft, Wt, reps=0)
+    with pytest.raises(B.SpcError):  # prepacked weights go in their own argument
+        B.spc_conv_tune_threshold(km, Ft, Wt, flags=B.CONV_PACKED_WEIGHTS)
+    km.destroy()
+    for layout in (B.LAYOUT_OS, B.LAYOUT_WS) + ((B.LAYOUT_BOTH | B.LAYOUT_HYBRID_T(1),) if s_l == 1 else ()):
+        km = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, layout)
+        with pytest.raises(B.SpcError) as e:
+            B.spc_conv_tune_threshold(km, Ft, Wt)
+        assert e.value.code == B.ERR_ARG
+        km.destroy()
+
+
 @pytest.mark.parametrize("name,K,key_bits,with_os", [("tiny", 3, 0, False), ("tiny_neg", 5, 0, False), ("rand_b3", 3, 64, True),
                                                      ("ragged", 7, 0, False), ("grid", 3, 0, True)])
 def test_symmetric_half_map(name, K, key_bits, with_os):
