@@ -1189,7 +1189,7 @@ extern "C" int spc_conv_tune_threshold(spc_kmap* m, const void* feats_in, int64_
   hipEvent_t e0 = nullptr, e1 = nullptr;
   SPC_HIP_CHECK(hipEventCreate(&e0));
   if (hipEventCreate(&e1) != hipSuccess) {
-    hipEventDestroy(e0);
+    (void)hipEventDestroy(e0);
     return set_error(SPC_ERR_HIP, "hipEventCreate failed");
   }
   int rc = SPC_OK, best = 0;
@@ -1207,8 +1207,8 @@ extern "C" int spc_conv_tune_threshold(spc_kmap* m, const void* feats_in, int64_
     us_per_t[t] = ms * 1e3f / float(reps) + (t <= l1_max ? ws_build_us : 0.f);
     if (us_per_t[t] < us_per_t[best]) best = t;
   }
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (rc != SPC_OK) return rc;
   *best_t = best;
   return run(best);  // feats_out holds the layer's output under the chosen threshold
