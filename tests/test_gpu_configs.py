@@ -53,3 +53,14 @@ def test_config_full_size(cfg):
             else:
                 assert_close(y2, ref, tol, (cfg, df, "packed"))
     km.destroy()
+    # the step bench.py times: OS layout alone, the sort's permutation folded into the map, the caller's unsorted rows
+    kmp = B.spc_build_kmap(keys, desc, K, 1, s_l, 0, B.LAYOUT_OS, in_perm=perm)
+    ref_p = ref_t.copy()
+    ref_p[:, 1] = operm[ref_p[:, 1]]
+    got = kmp.export_triples(B.LAYOUT_OS)
+    assert np.array_equal(got[np.lexsort((got[:, 2], got[:, 1], got[:, 0]))], ref_p[np.lexsort((ref_p[:, 2], ref_p[:, 1], ref_p[:, 0]))])
+    Fu = torch.from_numpy(F).cuda()
+    flags = B.CONV_PACKED_WEIGHTS if packed is not None else 0
+    y = B.spc_conv_forward(kmp, Fu, packed if packed is not None else Wt, B.DATAFLOW_OS, flags).cpu().double().numpy()
+    assert_close(y, ref, tol, (cfg, "permutation folded"))
+    kmp.destroy()
