@@ -717,15 +717,17 @@ __global__ __launch_bounds__(BS_THREADS) void bs_rank_rest_kernel(const int32_t*
 // ---------------------------------------------------------------- small levels: one workgroup, one launch
 // Fewer than BS_MIN_N keys (the tiny cloud of a unit test, the coarsest levels of a network): the partitioning
 // scheme of the large path inside one workgroup and LDS.  The keys are produced (packed or masked) straight into
-// LDS and counted into 256 bins of their top used bits; a scan gives the bin starts; the keys move, with their source
+// LDS and counted into 1024 bins of their top used bits; a scan gives the bin starts; the keys move, with their source
 // index, to their bin's range; and every key's final place is its bin's start plus the number of (key, index)
 // pairs of the bin that sort before it (the index breaks ties, so equal keys of an invalid cloud still get distinct
 // places).  The downsampling form writes the sorted keys back to LDS and keeps the first key of every run of equal
 // keys (a scan over the head flags).  One launch of a few microseconds where the large path has four (five) and a
 // library sort more; nothing but kernels is enqueued, so it can be recorded into a graph.  Work is quadratic in the
-// bin sizes: a cloud whose keys all share their top 8 bits costs n^2 = 16 M comparisons at most.
+// bin sizes: a cloud whose keys all share their top 10 used bits costs n^2 = 16 M comparisons at most.
 constexpr int BS_SMALL_THREADS = 1024;
-constexpr int BS_SMALL_BINS = 256;
+constexpr int BS_SMALL_BIN_BITS = 10;
+constexpr int BS_SMALL_BINS = 1 << BS_SMALL_BIN_BITS;
+static_assert(BS_SMALL_BINS <= BS_SMALL_THREADS && BS_SMALL_BINS % 64 == 0, "one thread clears a bin; wave 0 scans whole groups");
 constexpr int BS_SMALL_MAX = 4096;  // >= BS_MIN_N - 1
 template <typename KeyT, typename Src, bool DEDUP>
 __global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src, int n, int shift, KeyT* __restrict__ out_k,
@@ -747,11 +749,12 @@ __global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src
   }
   src.report(bad);
   __syncthreads();
-  if (wave == 0) {  // exclusive scan of the 256 bin counts, four per lane
-    int c[4], sum = 0;
+  if (wave == 0) {  // exclusive scan of the bin counts, PL consecutive bins per lane
+    constexpr int PL = BS_SMALL_BINS / 64;
+    int c[PL], sum = 0;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      c[u] = s_cur[lane * 4 + u];
+    for (int u = 0; u < PL; ++u) {
+      c[u] = s_cur[lane * PL + u];
       sum += c[u];
     }
     int x = sum;
@@ -761,9 +764,9 @@ __global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src
     }
     int run = x - sum;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      s_start[lane * 4 + u] = run;
-      s_cur[lane * 4 + u] = run;
+    for (int u = 0; u < PL; ++u) {
+      s_start[lane * PL + u] = run;
+      s_cur[lane * PL + u] = run;
       run += c[u];
     }
     if (lane == 63) s_start[BS_SMALL_BINS] = run;
@@ -782,7 +785,21 @@ __global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src
     const int b = bs_bin(key, shift, BS_SMALL_BINS);
     const int a = s_start[b], e = s_start[b + 1];
     int r = a;
-    for (int y = a; y < e; ++y) {
+    int y = a;
+    // eight candidates per trip, read before any is compared: one LDS round trip per trip instead of one per key
+    // (a bin of the tiny test cloud holds a few hundred keys, and the loop was nine tenths of the kernel)
+    for (; y + 8 <= e; y += 8) {
+      KeyT ky[8];
+      int16_t vy[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        ky[u] = sk1[y + u];
+        vy[u] = sv1[y + u];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) r += (ky[u] < key || (ky[u] == key && vy[u] < vi)) ? 1 : 0;
+    }
+    for (; y < e; ++y) {
       const KeyT ky = sk1[y];
       r += (ky < key || (ky == key && sv1[y] < vi)) ? 1 : 0;
     }
@@ -824,7 +841,7 @@ __global__ __launch_bounds__(BS_SMALL_THREADS) void bs_small_sort_kernel(Src src
 template <typename KeyT, typename Src, bool DEDUP>
 static void launch_small_sort(const Src& src, int64_t n, int used_bits, void* out_k, int32_t* out_v, int32_t* n_out, hipStream_t s) {
   static_assert(BS_SMALL_MAX >= BS_MIN_N - 1, "the small path covers every size below the partitioning sort's");
-  const int shift = std::max(0, used_bits - 8);  // bins = the top 8 used key bits
+  const int shift = std::max(0, used_bits - BS_SMALL_BIN_BITS);  // bins = the top used key bits
   hipLaunchKernelGGL((bs_small_sort_kernel<KeyT, Src, DEDUP>), dim3(1), dim3(BS_SMALL_THREADS), 0, s, src, static_cast<int>(n), shift,
                      static_cast<KeyT*>(out_k), out_v, n_out);
 }
