@@ -333,11 +333,13 @@ int spc_conv_tune_threshold(spc_kmap* m, const void* feats_in, int64_t ld_in, co
 
 /*
  * Weights are constant during inference, so their re-layout into MFMA operand order can
- * be hoisted out of the layer call.  Writes K^3*cin*cout elements to packed_out [device]
- * (same dtype) for use with SPC_CONV_PACKED_WEIGHTS.  Returns SPC_ERR_UNSUPPORTED for the
- * shapes/dtypes that do not take prepacked weights (fp32, cin % 16 != 0, cout % 32 != 0);
- * those layers take the plain [K^3][cin][cout] weights only.  The WS dataflow accepts
- * prepacked weights for cout in {32,64,128,256}.
+ * be hoisted out of the layer call.  Writes K^3 * cin16 * cout elements to packed_out [device]
+ * (same dtype), cin16 = cin rounded up to a multiple of 16 (the padding channels are zeros; a
+ * layer with such a cin still copies its feature rows into a padded scratch buffer at every call),
+ * for use with SPC_CONV_PACKED_WEIGHTS.  Returns SPC_ERR_UNSUPPORTED for the shapes/dtypes
+ * that do not take prepacked weights (fp32, cout % 32 != 0); those layers take the plain
+ * [K^3][cin][cout] weights only.  The WS dataflow accepts prepacked weights for cout in
+ * {32,64,128,256}.
  */
 int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32_t cin, int32_t cout, int32_t dtype,
                              void* packed_out, void* stream);

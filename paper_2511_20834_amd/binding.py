@@ -306,8 +306,9 @@ def spc_conv_forward(kmap: KMap, feats_in: torch.Tensor, weights: torch.Tensor, 
     assert feats_in.is_cuda and weights.is_cuda and weights.is_contiguous()
     assert feats_in.dim() == 2 and feats_in.stride(1) == 1 and weights.dim() == 3
     assert feats_in.dtype == weights.dtype and feats_in.dtype in _TORCH_DTYPE
-    cin, cout = weights.shape[1], weights.shape[2]
-    assert feats_in.shape[1] == cin and weights.shape[0] == kmap.kvol
+    cin, cout = feats_in.shape[1], weights.shape[2]
+    # (prepacked weights hold their input channels padded to a multiple of 16)
+    assert weights.shape[1] == ((cin + 15) // 16 * 16 if flags & CONV_PACKED_WEIGHTS else cin) and weights.shape[0] == kmap.kvol
     if out is None:
         out = torch.empty((n_out if n_out is not None else kmap.n_out, cout), dtype=feats_in.dtype, device=feats_in.device)
     assert out.dim() == 2 and out.stride(1) == 1 and out.shape[1] == cout and out.dtype == feats_in.dtype
@@ -331,7 +332,7 @@ def spc_conv_tune_threshold(kmap: KMap, feats_in: torch.Tensor, weights: torch.T
     cin, cout = weights.shape[1], weights.shape[2]
     assert feats_in.shape[1] == cin and weights.shape[0] == kmap.kvol
     assert packed is None or (packed.is_cuda and packed.is_contiguous() and packed.dtype == weights.dtype
-                              and packed.numel() == weights.numel())
+                              and packed.numel() == weights.shape[0] * ((weights.shape[1] + 15) // 16 * 16) * weights.shape[2])
     if out is None:
         out = torch.empty((kmap.n_out, cout), dtype=feats_in.dtype, device=feats_in.device)
     assert out.dim() == 2 and out.stride(1) == 1 and out.shape[1] == cout and out.dtype == feats_in.dtype
@@ -348,8 +349,10 @@ def spc_conv_tune_threshold(kmap: KMap, feats_in: torch.Tensor, weights: torch.T
 def spc_conv_prepare_weights(weights: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
     """weights [K^3, cin, cout] fp16/bf16 -> the MFMA operand layout expected with CONV_PACKED_WEIGHTS."""
     assert weights.is_cuda and weights.is_contiguous() and weights.dim() == 3 and weights.dtype in _TORCH_DTYPE
+    cin16 = (weights.shape[1] + 15) // 16 * 16  # input channels are padded with zeros to a multiple of 16
     if out is None:
-        out = torch.empty_like(weights)
+        out = torch.empty((weights.shape[0], cin16, weights.shape[2]), dtype=weights.dtype, device=weights.device)
+    assert out.is_contiguous() and out.dtype == weights.dtype and out.numel() == weights.shape[0] * cin16 * weights.shape[2]
     _check(lib().spc_conv_prepare_weights(weights.data_ptr(), weights.shape[0], weights.shape[1], weights.shape[2],
                                           _TORCH_DTYPE[weights.dtype], out.data_ptr(), _stream(stream)))
     return out

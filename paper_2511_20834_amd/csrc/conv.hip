@@ -986,13 +986,13 @@ static int conv_typed(const ConvArgs& a0, bool allow_mfma) {
   const int K3 = a.m->K3;
   const int64_t out_elems = a.rows_cap * a.cout;
   const bool aligned = a.ld_in % 8 == 0 && reinterpret_cast<uintptr_t>(a.F) % 16 == 0;
-  if (a.packed && !(allow_mfma && mfma_shape(a.cin, a.cout, a.any_ws)))
-    return set_error(SPC_ERR_ARG, "packed weights given for a shape the MFMA kernels do not run");
-  if (a.packed && !aligned) return set_error(SPC_ERR_ARG, "packed weights need 16-byte aligned feature rows");
-  if (a.rows_cap <= 0) return SPC_OK;
   const int cin_pad = (a.cin + 15) / 16 * 16;
+  if (a.packed && !(allow_mfma && mfma_shape(cin_pad, a.cout, a.any_ws)))
+    return set_error(SPC_ERR_ARG, "packed weights given for a shape the MFMA kernels do not run");
+  if (a.rows_cap <= 0) return SPC_OK;
   // ragged input channel counts and unaligned rows go through a zero-padded copy of the features
-  const bool repack_rows = !a.packed && (cin_pad != a.cin || !aligned);
+  // (prepacked weights already hold zeros for the padding channels)
+  const bool repack_rows = cin_pad != a.cin || !aligned;
   const bool use_mfma = allow_mfma && mfma_shape(cin_pad, a.cout, a.any_ws);
   float* accum = nullptr;
   if (a.any_ws) {
@@ -1178,7 +1178,7 @@ extern "C" int spc_conv_tune_threshold(spc_kmap* m, const void* feats_in, int64_
   const int count = l1_max + 2;  // t = 0 (all offsets weight-stationary) .. l1_max + 1 (all output-stationary)
   *n_t = count;
   if (cap < count) return set_error(SPC_ERR_ARG, "us_per_t holds %d entries, the layer has %d thresholds", cap, count);
-  const bool mfma_shape = dtype != SPC_DTYPE_F32 && cin % 16 == 0 && cout % 32 == 0;
+  const bool mfma_shape = dtype != SPC_DTYPE_F32 && cout % 32 == 0;
   const bool ws_takes_packed = cout == 32 || cout == 64 || cout == 128 || cout == 256;
   auto run = [&](int t) {
     const bool ws_part = t <= l1_max;
@@ -1218,12 +1218,13 @@ extern "C" int spc_conv_prepare_weights(const void* weights, int32_t kvol, int32
                                         void* packed_out, void* stream) {
   using namespace spc;
   if (!weights || !packed_out || kvol < 1) return set_error(SPC_ERR_ARG, "NULL argument or kvol < 1");
-  if ((dtype != SPC_DTYPE_F16 && dtype != SPC_DTYPE_BF16) || cin < 16 || cin % 16 != 0 || cout < 32 || cout % 32 != 0)
+  if ((dtype != SPC_DTYPE_F16 && dtype != SPC_DTYPE_BF16) || cin < 1 || cout < 32 || cout % 32 != 0)
     return set_error(SPC_ERR_UNSUPPORTED, "no MFMA kernel for dtype %d, cin %d, cout %d", dtype, cin, cout);
-  const int64_t total = int64_t(kvol) * (cin / 16) * (cout / 32) * 64;
+  const int cin_pad = (cin + 15) / 16 * 16;  // the padding channels are written as zeros
+  const int64_t total = int64_t(kvol) * (cin_pad / 16) * (cout / 32) * 64;
   // both 16-bit types move as raw 2-byte elements
   hipLaunchKernelGGL(prepack_weights_kernel<_Float16>, dim3((total + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const _Float16*>(weights), static_cast<_Float16*>(packed_out), kvol, cin, cin, cout);
+                     static_cast<const _Float16*>(weights), static_cast<_Float16*>(packed_out), kvol, cin, cin_pad, cout);
   SPC_HIP_CHECK(hipGetLastError());
   return SPC_OK;
 }

@@ -70,7 +70,7 @@ class SpcNetwork:
         self._packed = []
         for w, df, t in zip(self.weights, self.dataflow, self.hybrid_t):
             cin, cout = w.shape[1], w.shape[2]
-            ok = w.dtype in (torch.float16, torch.bfloat16) and cin % 16 == 0 and cout % 32 == 0
+            ok = w.dtype in (torch.float16, torch.bfloat16) and cout % 32 == 0
             if df == B.DATAFLOW_WS or t is not None:
                 ok = ok and cout in (32, 64, 128, 256)
             self._packed.append(B.spc_conv_prepare_weights(w) if ok else None)
@@ -103,7 +103,7 @@ class SpcNetwork:
                 out = bufs[buf][:, col:col + l["cout"]]
             flags = B.CONV_RELU if l["relu"] else 0
             w = self.weights[j]
-            if self._packed[j] is not None and x.stride(0) % 8 == 0 and x.data_ptr() % 16 == 0:
+            if self._packed[j] is not None:
                 w, flags = self._packed[j], flags | B.CONV_PACKED_WEIGHTS
             y = B.spc_conv_forward(m, x, w, self.dataflow[j], flags, out=out, n_out=n_out, hybrid_t=self.hybrid_t[j])
             T[l["save"]] = y
@@ -151,7 +151,7 @@ class SpcNetwork:
                 x = torch.cat([T[l["src"]], T[l["skip"]]], dim=1)
             w = self.weights[j]
             cout = w.shape[2]
-            wp = B.spc_conv_prepare_weights(w) if (w.dtype != torch.float32 and w.shape[1] % 16 == 0 and cout % 32 == 0) else None
+            wp = B.spc_conv_prepare_weights(w) if (w.dtype != torch.float32 and cout % 32 == 0) else None
             out = torch.empty((maps[j].n_out, cout), dtype=x.dtype, device=x.device)
             l1_max = 3 if l["K"] == 2 else 3 * (l["K"] - 1) // 2
             best, us, _ = B.spc_conv_tune_threshold(maps[j], x, w, wp, flags=B.CONV_RELU if l["relu"] else 0, reps=reps,

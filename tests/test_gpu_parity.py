@@ -239,6 +239,17 @@ def _run_conv(c, K, s_l, transposed, cin, cout, dtype, seed=0, relu=False):
         assert_close(o, ref, TOL[dtype], (df, variant))
         outs[df] = o
         outs[(df, variant)] = o
+    # weights re-laid once (input channels padded to a multiple of 16 where needed): same kernels, same bits for OS
+    if dtype != torch.float32 and cout % 32 == 0:
+        packed = B.spc_conv_prepare_weights(Wt)
+        assert packed.shape == (K ** 3, (cin + 15) // 16 * 16, cout)
+        fl = (B.CONV_RELU if relu else 0) | B.CONV_PACKED_WEIGHTS
+        for variant in (B.CONV_OS_PHASE, B.CONV_OS_SPLITK, 0):
+            y = B.spc_conv_forward(km, Ft, packed, B.DATAFLOW_OS, fl | variant)
+            assert np.array_equal(y.cpu().to(torch.float64).numpy(), outs[(B.DATAFLOW_OS, variant)]), ("packed", variant)
+        if cout in (32, 64, 128, 256):
+            y = B.spc_conv_forward(km, Ft, packed, B.DATAFLOW_WS, fl)
+            assert_close(y.cpu().to(torch.float64).numpy(), ref, TOL[dtype], "packed ws")
     km.destroy()
     return outs, ref
 
@@ -476,9 +487,12 @@ def test_conv_unaligned_feature_rows():
     W = torch.from_numpy(synth.weights(27, 32, 64, np.float16, seed=19)).cuda()
     fin = wide_in[:, 3:35]
     ref = oracle.conv(M, fin.cpu().double().numpy(), W.cpu().double().numpy())
+    packed = B.spc_conv_prepare_weights(W)
     for df in (B.DATAFLOW_OS, B.DATAFLOW_WS):
         y = B.spc_conv_forward(km, fin, W, df)
         assert_close(y.cpu().double().numpy(), ref, 1e-2, df)
+        y = B.spc_conv_forward(km, fin, packed, df, B.CONV_PACKED_WEIGHTS)
+        assert_close(y.cpu().double().numpy(), ref, 1e-2, (df, "packed"))
     km.destroy()
 
 
